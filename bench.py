@@ -1,0 +1,329 @@
+#!/usr/bin/env python3
+"""Benchmark of the SSD layer core on one MI355X.
+
+A "step" is one pass of the whole hot path on one batch of synthetic input: ``ssd_prefill``
+over the prompt (segsum, intra-chunk masked product, chunk states, inter-chunk pass,
+state-to-output, final state) followed by one ``ssd_decode_step`` on the state it returned.
+Inputs are resident in HBM before the timed region.  The headline value is prefill
+throughput in TFLOP/s by the *algorithmic, causal-only* FLOP count at the configured chunk
+length (work the method must do: no per-head recomputation of C.B^T, no padding, no masked
+upper triangle); the dense-convention figure is printed beside it.  The decode workload
+(64 stacked layers, 1024 back-to-back steps, batch 16 and batch 1) is timed in a second
+region and reported as HBM GB/s under ``decode``.  One JSON line is printed last.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # dense bf16 MFMA, MI355X
+PEAK_VALU_F32_TFLOPS = 157.3     # fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+
+# ---- algorithmic work (stated in the design doc) ---------------------------------------------------
+def chunk_lengths(T, L):
+    L = min(L, T)
+    full, tail = divmod(T, L)
+    return [L] * full + ([tail] if tail else [])
+
+
+def prefill_flops(cfg, causal=True):
+    """FLOPs one prefill must perform, split by step of Alg. 1 (per call, all batch rows)."""
+    H, P, N, G = cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
+    out = dict(scores=0.0, intra=0.0, states=0.0, state_pass=0.0, state_out=0.0, skip=0.0)
+    for ln in chunk_lengths(cfg.seqlen, cfg.chunk):
+        k = (ln + 1) / (2.0 * ln) if causal else 1.0
+        out["scores"] += G * 2.0 * ln * ln * N * k          # C.B^T, once per group
+        out["intra"] += H * 2.0 * ln * ln * P * k           # (G o L).(dt o x)
+        out["states"] += H * 2.0 * ln * P * N               # chunk-end states
+        out["state_out"] += H * 2.0 * ln * N * P            # C.H_c
+        out["state_pass"] += H * 2.0 * P * N                # H_{c+1} = decay*H_c + S_c
+        out["skip"] += H * 2.0 * ln * P                     # + D x
+    return {k: v * cfg.batch for k, v in out.items()}
+
+
+def io_size(cfg):
+    return 4 if cfg.io_dtype == "f32" else 2
+
+
+def prefill_bytes(cfg):
+    """Compulsory HBM traffic of one prefill: every input read once, every output written once."""
+    Bt, T, H, P, N, G = cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
+    sz = io_size(cfg)
+    return 2 * Bt * T * H * P * sz + 4 * Bt * T * H + 2 * Bt * T * G * N * sz + 8 * H + 4 * Bt * H * P * N
+
+
+def decode_bytes(cfg, nlayers):
+    """Compulsory HBM traffic of one decode step over nlayers stacked layers."""
+    Bt, H, P, N, G = cfg.batch, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
+    sz = io_size(cfg)
+    per_layer = 2 * 4 * Bt * H * P * N + Bt * (2 * H * P * sz + 4 * H + 2 * G * N * sz) + 8 * H
+    return nlayers * per_layer
+
+
+def decode_flops(cfg, nlayers):
+    return nlayers * cfg.batch * cfg.nheads * cfg.headdim * (5.0 * cfg.dstate + 3.0)
+
+
+# Which algorithmic FLOPs each kernel of a prefill call is responsible for.
+KERNEL_WORK = {
+    # generic fp32 family
+    "chunk_cumsum": (),
+    "chunk_states": ("states",),
+    "state_pass": ("state_pass",),
+    "chunk_output": ("scores", "intra", "state_out", "skip"),
+    # MFMA family
+    "scores_bt": ("scores",),
+    "segment_states": (),          # re-computation: carries no algorithmic FLOPs of its own
+    "segment_pass": ("state_pass",),
+    "chunk_scan": ("intra", "states", "state_out", "skip"),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3_2p7b_long",
+                    help="prefill configuration of the timed step (see paper_2603_09555_amd.inputs.CONFIGS)")
+    ap.add_argument("--decode-steps", type=int, default=1024)
+    ap.add_argument("--decode-layers", type=int, default=64)
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-configs", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+                 "--gpus %d is not supported, use --gpus 1" % args.gpus)
+
+    import torch
+    from paper_2603_09555_amd import inputs, ssd
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+
+    def shape_of(cfg):
+        return ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups,
+                              cfg.chunk, cfg.torch_io_dtype)
+
+    def time_prefill(cfg, steps, warmup, with_decode=True):
+        """Times `steps` whole steps; then the same number of profiled steps for per-kernel times."""
+        inp = inputs.make_prefill_inputs(cfg, seed=0, device=dev)
+        nxt = inputs.make_decode_inputs(cfg, 1, seed=0, device=dev)
+        nxt = {k: v[0].contiguous() for k, v in nxt.items()}
+        y = torch.empty_like(inp["x"])
+        st = torch.empty((cfg.batch, cfg.nheads, cfg.headdim, cfg.dstate), dtype=torch.float32, device=dev)
+        yd = torch.empty_like(nxt["x"])
+        ws = torch.empty((max(ssd.prefill_workspace_bytes(shape_of(cfg)), 256),), dtype=torch.uint8, device=dev)
+
+        def step(profile=None):
+            ssd.ssd_prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], cfg.chunk, y=y,
+                            final_state=st, workspace=ws, profile=profile)
+            if with_decode:
+                ssd.ssd_decode_step(st, nxt["x"], nxt["dt"], inp["A"], nxt["B"], nxt["C"], inp["D"], y=yd)
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        kern = {}
+        for _ in range(steps):
+            prof = []
+            step(profile=prof)
+            for name, kms in prof:
+                kern.setdefault(name, []).append(kms)
+        torch.cuda.synchronize()
+        kern = {k: sum(v) / len(v) for k, v in kern.items()}
+        return ms, kern, inp
+
+    def prefill_report(cfg, ms, kern):
+        fl_c, fl_d = prefill_flops(cfg, True), prefill_flops(cfg, False)
+        tot_c, tot_d = sum(fl_c.values()), sum(fl_d.values())
+        path = ssd.prefill_path(shape_of(cfg))
+        peak = PEAK_MFMA_BF16_TFLOPS if path == "mfma_bf16" else PEAK_VALU_F32_TFLOPS
+        ai = tot_c / prefill_bytes(cfg)
+        attainable = min(peak, ai * PEAK_HBM_GBS / 1e3)
+        return dict(workload=cfg.name, path=path, ms=ms, tflops_causal=tot_c / ms / 1e9,
+                    tflops_dense=tot_d / ms / 1e9, frac_of_peak=tot_c / ms / 1e9 / peak, peak_tflops=peak,
+                    frac_of_attainable=tot_c / ms / 1e9 / attainable,
+                    hbm_gbs_compulsory=prefill_bytes(cfg) / ms / 1e6,
+                    kernels_ms={k: round(v, 5) for k, v in kern.items()})
+
+    # ---- headline: the timed step --------------------------------------------------------
+    cfg = inputs.CONFIGS[args.workload]
+    log("[bench] workload %s, path %s" % (cfg.name, ssd.prefill_path(shape_of(cfg))))
+    ms_step, kern, _ = time_prefill(cfg, args.steps, args.warmup)
+    head = prefill_report(cfg, ms_step, kern)
+    log("[bench] %s: %.3f ms/step, %.1f TFLOP/s (causal count), kernels %s" %
+        (cfg.name, ms_step, head["tflops_causal"], head["kernels_ms"]))
+
+    # roofline of the dominant kernel of the step
+    dom = max(kern, key=kern.get)
+    fl_c = prefill_flops(cfg, True)
+    dom_flops = sum(fl_c[k] for k in KERNEL_WORK.get(dom, ()))
+    if head["path"] == "mfma_bf16":
+        bound, peak = "mfma", PEAK_MFMA_BF16_TFLOPS
+    else:
+        bound, peak = "alu", PEAK_VALU_F32_TFLOPS
+    achieved = dom_flops / kern[dom] / 1e9
+    roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 3), peak=peak, unit="TFLOP/s",
+                    frac=round(achieved / peak, 5), traffic=None, kernel_ms=round(kern[dom], 5),
+                    flops_per_launch=dom_flops)
+
+    # ---- the other prefill configurations (reported, not the headline) -------------------------
+    extra = {}
+    if not args.no_extra_configs:
+        for name in ("c0_tiny_f32", "c1_130m", "c2_780m_b8", "c3_2p7b_long"):
+            if name == cfg.name:
+                continue
+            c = inputs.CONFIGS[name]
+            ms, k, _ = time_prefill(c, max(5, args.steps // 2), 2, with_decode=False)
+            extra[name] = prefill_report(c, ms, k)
+            log("[bench] %s: %.4f ms, %.1f TFLOP/s causal" % (name, ms, extra[name]["tflops_causal"]))
+            torch.cuda.empty_cache()
+
+    # ---- decode: 64 stacked layers, states seeded by a 2048-token prefill, 1024 steps ---------
+    decode = {}
+    if not args.no_decode:
+        for name in ("c4_decode_b16", "c4_decode_b1"):
+            c = inputs.CONFIGS[name]
+            Ly, nsteps = args.decode_layers, args.decode_steps
+            state = torch.empty((Ly, c.batch, c.nheads, c.headdim, c.dstate), dtype=torch.float32, device=dev)
+            A = torch.empty((Ly, c.nheads), dtype=torch.float32, device=dev)
+            D = torch.empty_like(A)
+            ws = torch.empty((max(ssd.prefill_workspace_bytes(shape_of(c)), 256),), dtype=torch.uint8,
+                             device=dev)
+            ytmp = None
+            for l in range(Ly):
+                inp = inputs.make_prefill_inputs(c, seed=0, layer=l, device=dev)
+                if ytmp is None:
+                    ytmp = torch.empty_like(inp["x"])
+                ssd.ssd_prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], c.chunk, y=ytmp,
+                                final_state=state[l], workspace=ws)
+                A[l], D[l] = inp["A"], inp["D"]
+            torch.cuda.synchronize()
+            del ytmp, ws, inp
+            # per-step inputs for all layers: (steps, Ly, Bt, ...)
+            g = torch.Generator(device=dev)
+            g.manual_seed(1234)
+            io = c.torch_io_dtype
+            xs = torch.randn((nsteps, Ly, c.batch, c.nheads, c.headdim), generator=g, device=dev,
+                             dtype=torch.float32).to(io) if c.batch == 1 else None
+            if xs is None:  # batch 16: 10.7 GB in bf16; draw per step block to bound the fp32 temporary
+                xs = torch.empty((nsteps, Ly, c.batch, c.nheads, c.headdim), dtype=io, device=dev)
+                for i in range(0, nsteps, 64):
+                    xs[i:i + 64] = torch.randn((min(64, nsteps - i),) + tuple(xs.shape[1:]), generator=g,
+                                               device=dev, dtype=torch.float32).to(io)
+            dts = torch.nn.functional.softplus(
+                0.5 * torch.randn((nsteps, Ly, c.batch, c.nheads), generator=g, device=dev) + inputs.DT_BIAS
+            ).clamp_(inputs.DT_MIN, inputs.DT_MAX)
+            Bs = (inputs.BC_SCALE * torch.randn((nsteps, Ly, c.batch, c.ngroups, c.dstate), generator=g,
+                                                device=dev)).to(io)
+            Cs = (inputs.BC_SCALE * torch.randn((nsteps, Ly, c.batch, c.ngroups, c.dstate), generator=g,
+                                                device=dev)).to(io)
+            yd = torch.empty((Ly, c.batch, c.nheads, c.headdim), dtype=io, device=dev)
+            for i in range(3):
+                ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=yd)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            marks = [torch.cuda.Event(enable_timing=True) for _ in range(9)]
+            e0.record()
+            for i in range(nsteps):
+                if i % (nsteps // 8 or 1) == 0 and i // (nsteps // 8 or 1) < 9:
+                    marks[i // (nsteps // 8 or 1)].record()
+                ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=yd)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / nsteps
+            nmarks = min(9, (nsteps + (nsteps // 8 or 1) - 1) // (nsteps // 8 or 1))
+            eighths = [marks[i].elapsed_time(marks[i + 1]) * 1e3 / (nsteps // 8 or 1) for i in range(nmarks - 1)]
+            bytes_step = decode_bytes(c, Ly)
+            gbs = bytes_step / us / 1e3
+            decode[name] = dict(layers=Ly, batch=c.batch, steps=nsteps, us_per_step=round(us, 3),
+                                bytes_per_step=bytes_step, hbm_gbs=round(gbs, 1),
+                                frac_of_hbm_peak=round(gbs / PEAK_HBM_GBS, 4),
+                                gflops=round(decode_flops(c, Ly) / us / 1e3, 1),
+                                us_per_step_by_eighth=[round(v, 3) for v in eighths],
+                                state_bytes=state.numel() * 4,
+                                note=("state (%.0f MB) fits the 256 MB Infinity Cache: not a pure HBM figure"
+                                      % (state.numel() * 4 / 1e6)) if state.numel() * 4 < 256e6 else
+                                "state streams from HBM")
+            log("[bench] decode %s: %.2f us/step, %.0f GB/s (%.1f%% of HBM peak)" %
+                (name, us, gbs, 100 * gbs / PEAK_HBM_GBS))
+            if c.batch == 1:
+                # per-layer launches (64 per step), the host-driven analogue
+                n2 = min(nsteps, 128)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(n2):
+                    for l in range(Ly):
+                        ssd.ssd_decode_step(state[l], xs[i, l], dts[i, l], A[l], Bs[i, l], Cs[i, l], D[l], y=yd[l])
+                e1.record()
+                torch.cuda.synchronize()
+                us2 = e0.elapsed_time(e1) * 1e3 / n2
+                decode[name]["per_layer_launch_us_per_step"] = round(us2, 2)
+                decode[name]["per_layer_launch_hbm_gbs"] = round(bytes_step / us2 / 1e3, 1)
+            del state, xs, dts, Bs, Cs, yd
+            torch.cuda.empty_cache()
+
+    # ---- CPU baseline: the oracle, as it stands, on a bounded sample of the headline workload --
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ssd_oracle
+        cores = ssd_oracle.max_threads()
+        hc = inputs.make_prefill_inputs(cfg, seed=0)  # host copy of the headline workload
+        flops_per_pair = sum(prefill_flops(cfg.with_(batch=1, nheads=1), True).values())
+        # nheads=1 would count C.B^T once per head; remove it and add the group's share
+        sc = prefill_flops(cfg.with_(batch=1, nheads=1), True)["scores"]
+        flops_per_pair = flops_per_pair - sc + sc * cfg.ngroups / cfg.nheads
+        all_pairs = [(b, h) for b in range(cfg.batch) for h in range(cfg.nheads)]
+        probe = all_pairs[:cores]
+        pa = ssd_oracle.gather_pairs(hc["x"], hc["dt"], hc["A"], hc["B"], hc["C"], hc["D"], None, probe)
+        t0 = time.perf_counter()
+        ssd_oracle.scan_pairs(*pa)
+        t_probe = time.perf_counter() - t0
+        rounds = int(max(1, min(len(all_pairs) // cores, args.cpu_seconds / max(t_probe, 1e-3))))
+        sample = all_pairs[:rounds * cores]
+        pa = ssd_oracle.gather_pairs(hc["x"], hc["dt"], hc["A"], hc["B"], hc["C"], hc["D"], None, sample)
+        t0 = time.perf_counter()
+        ssd_oracle.scan_pairs(*pa)
+        t_cpu = time.perf_counter() - t0
+        cpu = dict(value=round(flops_per_pair * len(sample) / t_cpu / 1e12, 6), unit="TFLOP/s", cores=cores,
+                   kind="oracle", seconds=round(t_cpu, 2),
+                   sample="%d of %d (batch,head) sequences of %s, all %d tokens each, fp64 token recurrence; "
+                          "same algorithmic FLOP count as the GPU figure" % (len(sample), len(all_pairs), cfg.name,
+                                                                           cfg.seqlen))
+        log("[bench] cpu oracle: %.4f TFLOP/s on %d threads (%.1f s)" % (cpu["value"], cores, t_cpu))
+
+    out = {
+        "metric": "ssd_prefill_tflops", "value": round(head["tflops_causal"], 3), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.io_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.batch, "seqlen": cfg.seqlen, "nheads": cfg.nheads,
+                   "headdim": cfg.headdim, "dstate": cfg.dstate, "ngroups": cfg.ngroups, "chunk": cfg.chunk,
+                   "step": "ssd_prefill + one ssd_decode_step", "flop_count": "algorithmic, causal-only"},
+        "prefill": head, "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "other_configs": extra,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

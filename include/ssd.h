@@ -1,0 +1,175 @@
+/*
+ * ssd.h -- C ABI of the MI355X (gfx950) SSD layer-core library.
+ *
+ * The library computes the Mamba-2 state-space-duality layer core of
+ * "Compiler-First State Space Duality and Portable O(1) Autoregressive
+ * Caching": the chunked-parallel prefill (Alg. 1, lines "Discretise" to
+ * "Store"; Eq. 3; appendix "Exact SSD Einsum Signatures") and the O(1) cached
+ * decode step (Alg. 2, "Discretise" and "SSM step"; Eq. 2 for the output).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *    allocates nothing, frees nothing, keeps no pointer after the call and
+ *    never synchronises: work is enqueued on `hip_stream` (a hipStream_t
+ *    passed as void*; NULL = the default stream) and the call returns.
+ *  - Tensors are dense, row-major (last index fastest), 16-byte aligned, in
+ *    the axis order of the paper's einsum signatures:
+ *        x, y           (batch, seqlen, nheads, headdim)      io dtype
+ *        B, C           (batch, seqlen, ngroups, dstate)      io dtype
+ *        dt             (batch, seqlen, nheads)               fp32, > 0: the final step
+ *                       size (softplus / bias / clamp are the caller's job)
+ *        A, D           (nheads)                              fp32; A <= 0 is the
+ *                       already negative per-head scalar, Abar = exp(dt*A)
+ *        state, h0      (batch, nheads, headdim, dstate)      fp32
+ *    Head h reads B/C group h / (nheads / ngroups).
+ *  - io dtype (x, B, C, y) is fp32 or bf16; bf16 values are the upper 16 bits
+ *    of the fp32 pattern.  y is rounded to the io dtype with round-to-nearest-
+ *    even.  All decay arithmetic (dt*A, its prefix sums, exp) and every
+ *    accumulation are fp32 (section "Mapping SSD onto JAX primitives",
+ *    precision rules).
+ *  - Arguments are validated on the host before any HIP call; an invalid call
+ *    returns a negative ssd_status and enqueues nothing.  Device data (the
+ *    sign of A, dt) is not inspected.  No C++ exception crosses this boundary.
+ *  - Results do not depend on `chunk` beyond floating-point summation order.
+ *    Runs are bitwise reproducible (no floating-point atomics).
+ */
+#ifndef SSD_H_
+#define SSD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define SSD_API __attribute__((visibility("default")))
+#else
+#define SSD_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SSD_F32 = 0, SSD_BF16 = 1 } ssd_dtype;
+
+typedef enum {
+  SSD_OK = 0,
+  SSD_ERR_NULL = -1,        /* a required pointer is NULL */
+  SSD_ERR_SHAPE = -2,       /* a dimension is < 1, nheads % ngroups != 0, or a size overflows */
+  SSD_ERR_DTYPE = -3,       /* io_dtype is not SSD_F32 / SSD_BF16 */
+  SSD_ERR_UNSUPPORTED = -4, /* valid but not implemented (see each entry point) */
+  SSD_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or smaller than required */
+  SSD_ERR_HIP = -6,         /* a HIP launch reported an error */
+  SSD_ERR_ALIGN = -7        /* a tensor pointer is not 16-byte aligned */
+} ssd_status;
+
+/* Plain data, filled by the caller; the library never keeps the pointer. */
+typedef struct {
+  int32_t batch;    /* Bt */
+  int32_t seqlen;   /* T  (ignored by the decode entry points) */
+  int32_t nheads;   /* H  */
+  int32_t headdim;  /* P  */
+  int32_t dstate;   /* N  */
+  int32_t ngroups;  /* G, divides H */
+  int32_t chunk;    /* L  (ignored by the decode entry points) */
+  int32_t io_dtype; /* ssd_dtype of x, B, C, y */
+} ssd_shape;
+
+/*
+ * Bytes of device scratch ssd_prefill needs for this shape (a multiple of
+ * 256); 0 if the shape is invalid.  Host-only, no HIP call.
+ */
+SSD_API size_t ssd_prefill_workspace_bytes(const ssd_shape *shape);
+
+/*
+ * Chunked-parallel prefill (Alg. 1; Eq. 3).  With cs_l the inclusive prefix
+ * sum of dt*A inside a chunk and H_c the state entering chunk c it evaluates
+ *     y[cL+l] = sum_{s<=l} (C_l.B_s) exp(cs_l - cs_s) dt_s x_s      (intra-chunk, Eq. 3)
+ *             + exp(cs_l) C_l.H_c                                     (state to output)
+ *             + D x_l
+ *     S_c     = sum_s exp(cs_{L-1} - cs_s) dt_s x_s (x) B_s           (chunk-end states)
+ *     H_{c+1} = exp(cs_{L-1}) H_c + S_c,  H_0 = h0 or 0               (inter-chunk pass)
+ * and stores H_{Nc} into final_state (Alg. 1, "Store").  This equals the
+ * token recurrence of Eq. 2 up to rounding order.
+ *
+ *  x, dt, A, B, C, D   inputs (device), layouts above
+ *  h0                  optional initial state (device) or NULL = zeros; may
+ *                      alias final_state
+ *  y                   output (device), same shape and dtype as x; must not
+ *                      alias an input
+ *  final_state         output (device), fp32 (batch, nheads, headdim, dstate)
+ *  workspace           device scratch of at least ssd_prefill_workspace_bytes()
+ *                      bytes, 256-byte aligned; contents are undefined afterwards
+ *  seqlen need not be a multiple of chunk (the last chunk is short).
+ *  Errors: SSD_ERR_NULL, _SHAPE, _DTYPE, _ALIGN, _WORKSPACE, _HIP.
+ */
+SSD_API ssd_status ssd_prefill(const ssd_shape *shape, const void *x, const float *dt,
+                       const float *A, const void *B, const void *C,
+                       const float *D, const float *h0, void *y,
+                       float *final_state, void *workspace,
+                       size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One cached decode step (Alg. 2, "Discretise" + "SSM step"; output per Eq. 2),
+ * for every (batch row, head):
+ *     dA      = exp(dt * A_h)
+ *     h[p][n] = dA * h[p][n] + (dt * x[p]) * B[n]        state updated IN PLACE
+ *     y[p]    = sum_n C[n] * h[p][n] + D_h * x[p]        (updated h)
+ *  state (batch, nheads, headdim, dstate) fp32 in/out; x, y (batch, nheads,
+ *  headdim) io dtype; dt (batch, nheads) fp32; B, C (batch, ngroups, dstate) io
+ *  dtype; A, D (nheads) fp32.  shape->seqlen and shape->chunk are ignored.
+ *  y must not alias an input; state must not alias anything else.
+ *  Errors: SSD_ERR_NULL, _SHAPE, _DTYPE, _ALIGN, _HIP.
+ */
+SSD_API ssd_status ssd_decode_step(const ssd_shape *shape, float *state, const void *x,
+                           const float *dt, const float *A, const void *B,
+                           const void *C, const float *D, void *y,
+                           void *hip_stream);
+
+/*
+ * The same step for `nlayers` independent layers in ONE launch: every array of
+ * ssd_decode_step gains a leading [nlayers] axis (A and D become
+ * (nlayers, nheads)).  Exists because one layer's state is far too small to
+ * amortise a kernel launch (the analogue of the paper's compiled on-device
+ * loop body, section "Mapping SSD onto JAX primitives").
+ */
+SSD_API ssd_status ssd_decode_step_layers(int32_t nlayers, const ssd_shape *shape,
+                                  float *state, const void *x, const float *dt,
+                                  const float *A, const void *B, const void *C,
+                                  const float *D, void *y, void *hip_stream);
+
+/*
+ * Measurement aid: ssd_prefill with a HIP event recorded on `hip_stream` after
+ * every kernel of the call (the prefill of Alg. 1 is several kernels).  Unlike
+ * every other entry point it creates and destroys HIP events and WAITS for the
+ * call to finish.  On return kernel_ms[i] (HOST array of max_kernels floats)
+ * holds the duration in milliseconds of the i-th kernel, kernel_names[i] (HOST
+ * array of max_kernels pointers) a static string naming it, *num_kernels their
+ * count.  The results in y / final_state are those of ssd_prefill.
+ */
+SSD_API ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, const float *dt,
+                               const float *A, const void *B, const void *C,
+                               const float *D, const float *h0, void *y,
+                               float *final_state, void *workspace,
+                               size_t workspace_bytes, void *hip_stream,
+                               int32_t max_kernels, float *kernel_ms,
+                               const char **kernel_names, int32_t *num_kernels);
+
+/*
+ * Name of the kernel family ssd_prefill would use for this shape:
+ * "mfma_bf16" (MFMA contractions over LDS-staged tiles), "generic_f32"
+ * (plain fp32 kernels, any shape), or "invalid".  Host-only.  The environment
+ * variable SSD_FORCE_GENERIC=1 forces "generic_f32" (debugging aid).
+ */
+SSD_API const char *ssd_prefill_path(const ssd_shape *shape);
+
+/* Human-readable name of a status code (static storage). */
+SSD_API const char *ssd_status_string(ssd_status status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+SSD_API int ssd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSD_H_ */

@@ -1,0 +1,174 @@
+// C ABI of the SSD library (declared in include/ssd.h): host-side validation and dispatch.
+// Every check runs before the first HIP call, so an invalid call enqueues nothing.
+#include <cstdlib>
+#include <cstring>
+#include <limits>
+
+#include "ssd_internal.hpp"
+
+namespace {
+
+using ssd::Dims;
+
+ssd_status make_dims(const ssd_shape *s, bool decode, Dims *out) {
+  if (!s) return SSD_ERR_NULL;
+  if (s->io_dtype != SSD_F32 && s->io_dtype != SSD_BF16) return SSD_ERR_DTYPE;
+  if (s->batch < 1 || s->nheads < 1 || s->headdim < 1 || s->dstate < 1 || s->ngroups < 1)
+    return SSD_ERR_SHAPE;
+  if (!decode && (s->seqlen < 1 || s->chunk < 1)) return SSD_ERR_SHAPE;
+  if (s->nheads % s->ngroups != 0) return SSD_ERR_SHAPE;
+  Dims d;
+  d.Bt = s->batch;
+  d.T = decode ? 1 : s->seqlen;
+  d.H = s->nheads;
+  d.P = s->headdim;
+  d.N = s->dstate;
+  d.G = s->ngroups;
+  d.L = decode ? 1 : s->chunk;
+  if (d.L > d.T) d.L = d.T;  // a chunk longer than the sequence is one short chunk
+  d.Nc = (d.T + d.L - 1) / d.L;
+  d.hpg = d.H / d.G;
+  d.bf16 = s->io_dtype == SSD_BF16;
+  // Every tensor must be addressable with comfortable head-room in size_t / 32-bit grids.
+  const long double lim = 1.0e15L;
+  const long double bt = d.Bt, t = d.T, h = d.H, p = d.P, n = d.N;
+  if (bt * t * h * p > lim || bt * h * p * n > lim || bt * t * d.G * n > lim) return SSD_ERR_SHAPE;
+  if (bt * h > 65535.0L && !decode) return SSD_ERR_UNSUPPORTED;  // grid y/z limit of the prefill kernels
+  if (d.Nc > 65535) return SSD_ERR_UNSUPPORTED;
+  *out = d;
+  return SSD_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool force_generic() {
+  const char *e = std::getenv("SSD_FORCE_GENERIC");
+  return e && e[0] == '1';
+}
+
+bool use_mfma(const Dims &d) { return !force_generic() && ssd::mfma_supported(d); }
+
+size_t workspace_bytes(const Dims &d) {
+  const size_t g = ssd::generic_workspace_bytes(d);
+  const size_t m = ssd::mfma_supported(d) ? ssd::mfma_workspace_bytes(d) : 0;
+  return g > m ? g : m;  // large enough for either family, so forcing the generic one stays valid
+}
+
+ssd_status prefill_impl(const ssd_shape *shape, const void *x, const float *dt, const float *A,
+                        const void *B, const void *C, const float *D, const float *h0, void *y,
+                        float *final_state, void *workspace, size_t workspace_bytes_given,
+                        void *hip_stream, ssd::KernelTrace *trace) {
+  Dims d;
+  const ssd_status st = make_dims(shape, false, &d);
+  if (st != SSD_OK) return st;
+  if (!x || !dt || !A || !B || !C || !D || !y || !final_state) return SSD_ERR_NULL;
+  if (!aligned16(x) || !aligned16(dt) || !aligned16(B) || !aligned16(C) || !aligned16(y) ||
+      !aligned16(final_state) || (h0 && !aligned16(h0)))
+    return SSD_ERR_ALIGN;
+  const size_t need = workspace_bytes(d);
+  if (!workspace || workspace_bytes_given < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SSD_ERR_WORKSPACE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (trace) (void)hipEventRecord(trace->ev[0], stream);
+  const hipError_t e =
+      use_mfma(d)
+          ? ssd::launch_prefill_mfma(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace)
+          : ssd::launch_prefill_generic(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream,
+                                        trace);
+  return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ssd_prefill_workspace_bytes(const ssd_shape *shape) {
+  Dims d;
+  if (make_dims(shape, false, &d) != SSD_OK) return 0;
+  return workspace_bytes(d);
+}
+
+const char *ssd_prefill_path(const ssd_shape *shape) {
+  Dims d;
+  if (make_dims(shape, false, &d) != SSD_OK) return "invalid";
+  return use_mfma(d) ? "mfma_bf16" : "generic_f32";
+}
+
+ssd_status ssd_prefill(const ssd_shape *shape, const void *x, const float *dt, const float *A,
+                       const void *B, const void *C, const float *D, const float *h0, void *y,
+                       float *final_state, void *workspace, size_t workspace_bytes_given,
+                       void *hip_stream) {
+  return prefill_impl(shape, x, dt, A, B, C, D, h0, y, final_state, workspace, workspace_bytes_given,
+                      hip_stream, nullptr);
+}
+
+ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, const float *dt, const float *A,
+                               const void *B, const void *C, const float *D, const float *h0, void *y,
+                               float *final_state, void *workspace, size_t workspace_bytes_given,
+                               void *hip_stream, int32_t max_kernels, float *kernel_ms,
+                               const char **kernel_names, int32_t *num_kernels) {
+  if (!kernel_ms || !kernel_names || !num_kernels || max_kernels < 1) return SSD_ERR_NULL;
+  *num_kernels = 0;
+  ssd::KernelTrace trace;
+  int made = 0;
+  for (; made <= ssd::KernelTrace::kMax; ++made)
+    if (hipEventCreate(&trace.ev[made]) != hipSuccess) break;
+  ssd_status st = SSD_ERR_HIP;
+  if (made == ssd::KernelTrace::kMax + 1) {
+    st = prefill_impl(shape, x, dt, A, B, C, D, h0, y, final_state, workspace, workspace_bytes_given,
+                      hip_stream, &trace);
+    if (st == SSD_OK) {
+      if (trace.n > 0 && hipEventSynchronize(trace.ev[trace.n]) != hipSuccess) st = SSD_ERR_HIP;
+      for (int i = 0; st == SSD_OK && i < trace.n && i < max_kernels; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, trace.ev[i], trace.ev[i + 1]) != hipSuccess) st = SSD_ERR_HIP;
+        kernel_ms[i] = ms;
+        kernel_names[i] = trace.names[i];
+        *num_kernels = i + 1;
+      }
+    }
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(trace.ev[i]);
+  return st;
+}
+
+ssd_status ssd_decode_step_layers(int32_t nlayers, const ssd_shape *shape, float *state, const void *x,
+                                  const float *dt, const float *A, const void *B, const void *C,
+                                  const float *D, void *y, void *hip_stream) {
+  Dims d;
+  const ssd_status st = make_dims(shape, true, &d);
+  if (st != SSD_OK) return st;
+  if (nlayers < 1) return SSD_ERR_SHAPE;
+  const long double pairs = static_cast<long double>(nlayers) * d.Bt * d.H;
+  if (pairs > 2.0e9L) return SSD_ERR_SHAPE;  // one workgroup per (layer, batch row, head)
+  if (!state || !x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
+  if (!aligned16(state) || !aligned16(x) || !aligned16(B) || !aligned16(C) || !aligned16(y))
+    return SSD_ERR_ALIGN;
+  const hipError_t e = ssd::launch_decode(nlayers, d, state, x, dt, A, B, C, D, y,
+                                          static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
+}
+
+ssd_status ssd_decode_step(const ssd_shape *shape, float *state, const void *x, const float *dt,
+                           const float *A, const void *B, const void *C, const float *D, void *y,
+                           void *hip_stream) {
+  return ssd_decode_step_layers(1, shape, state, x, dt, A, B, C, D, y, hip_stream);
+}
+
+const char *ssd_status_string(ssd_status status) {
+  switch (status) {
+    case SSD_OK: return "ok";
+    case SSD_ERR_NULL: return "a required pointer is NULL";
+    case SSD_ERR_SHAPE: return "invalid shape";
+    case SSD_ERR_DTYPE: return "invalid io dtype";
+    case SSD_ERR_UNSUPPORTED: return "shape not supported";
+    case SSD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SSD_ERR_HIP: return "HIP launch error";
+    case SSD_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+  }
+  return "unknown status";
+}
+
+int ssd_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,87 @@
+// Internal declarations shared by the translation units of the SSD library.
+// Nothing here is part of the C ABI (see include/ssd.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ssd.h"
+
+namespace ssd {
+
+// Validated problem dimensions (host side).
+struct Dims {
+  int Bt, T, H, P, N, G, L;
+  int Nc;     // number of chunks, ceil(T / L)
+  int hpg;    // heads per B/C group
+  bool bf16;  // io dtype of x, B, C, y
+};
+
+// ---- bf16 <-> fp32 (bf16 = upper half of the fp32 pattern, round-to-nearest-even) ----
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t v) {
+  return __uint_as_float(static_cast<uint32_t>(v) << 16);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+
+// Element access for the two io dtypes.
+struct IoF32 {
+  using type = float;
+  static __device__ __forceinline__ float load(const void *p, size_t i) {
+    return static_cast<const float *>(p)[i];
+  }
+  static __device__ __forceinline__ void store(void *p, size_t i, float v) {
+    static_cast<float *>(p)[i] = v;
+  }
+};
+struct IoBf16 {
+  using type = uint16_t;
+  static __device__ __forceinline__ float load(const void *p, size_t i) {
+    return bf16_bits_to_f32(static_cast<const uint16_t *>(p)[i]);
+  }
+  static __device__ __forceinline__ void store(void *p, size_t i, float v) {
+    static_cast<uint16_t *>(p)[i] = f32_to_bf16_bits(v);
+  }
+};
+
+// Optional per-kernel timing (used only by ssd_prefill_profile): an event is recorded on the
+// launch stream after every kernel of a prefill call.
+struct KernelTrace {
+  static constexpr int kMax = 8;
+  int n = 0;
+  hipEvent_t ev[kMax + 1];
+  const char *names[kMax];
+};
+inline void trace_mark(KernelTrace *t, hipStream_t s, const char *name) {
+  if (t && t->n < KernelTrace::kMax) {
+    (void)hipEventRecord(t->ev[t->n + 1], s);
+    t->names[t->n++] = name;
+  }
+}
+
+// ---- launchers (each returns the first HIP error it sees) ----
+hipError_t launch_decode(int nlayers, const Dims &d, float *state, const void *x, const float *dt,
+                         const float *A, const void *B, const void *C, const float *D, void *y,
+                         hipStream_t stream);
+
+size_t generic_workspace_bytes(const Dims &d);
+hipError_t launch_prefill_generic(const Dims &d, const void *x, const float *dt, const float *A,
+                                  const void *B, const void *C, const float *D, const float *h0,
+                                  void *y, float *final_state, void *workspace, hipStream_t stream,
+                                  KernelTrace *trace = nullptr);
+
+bool mfma_supported(const Dims &d);
+size_t mfma_workspace_bytes(const Dims &d);
+hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, const float *A,
+                               const void *B, const void *C, const float *D, const float *h0,
+                               void *y, float *final_state, void *workspace, hipStream_t stream,
+                               KernelTrace *trace = nullptr);
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace ssd

@@ -1,0 +1,317 @@
+// Generic fp32 prefill: the chunked SSD algorithm (Alg. 1; Eq. 3) for any shape and either
+// io dtype, in plain fp32 vector arithmetic.  It is the path for shapes the MFMA kernels do
+// not cover (and for fp32 inputs, whose 1e-4 tolerance bf16 matrix operands cannot meet).
+//
+// Four kernels, one per step of Alg. 1:
+//   1. chunk_cumsum   cs[l] = inclusive prefix sum of dt*A inside each chunk   ("Discretise")
+//   2. chunk_states   S_c = sum_s exp(cs_end - cs_s) dt_s x_s (x) B_s           ("State accumulate")
+//   3. state_pass     H_{c+1} = exp(cs_end) H_c + S_c, sequential over chunks   ("Inter-chunk scan")
+//   4. chunk_output   y = (C B^T o exp(segsum)) (dt o x) + exp(cs) C H_c + D x   ("Intra-chunk", "Combine")
+// The decay mask exp(cs_l - cs_s), s <= l, is generated on the fly from the prefix sums and
+// never stored; masked entries are set to zero without evaluating exp of a positive number.
+#include "ssd_internal.hpp"
+
+namespace ssd {
+namespace {
+
+constexpr int kThreads = 256;
+
+// ---- 1. per-chunk inclusive prefix sum of dt*A ------------------------------------------------
+// grid (Nc, Bt*H), one wave per chunk.  cs layout: (Bt, H, Nc, L).
+__global__ __launch_bounds__(64) void chunk_cumsum_kernel(const float *__restrict__ dt,
+                                                          const float *__restrict__ A,
+                                                          float *__restrict__ cs, int T, int H, int L,
+                                                          int Nc) {
+  const int c = blockIdx.x;
+  const int bh = blockIdx.y;
+  const int b = bh / H, h = bh % H;
+  const int lane = threadIdx.x;
+  const float Ah = A[h];
+  const int len = min(L, T - c * L);
+  float carry = 0.f;
+  float *out = cs + (static_cast<size_t>(bh) * Nc + c) * L;
+  for (int base = 0; base < len; base += 64) {
+    const int l = base + lane;
+    float v = 0.f;
+    if (l < len) v = dt[(static_cast<size_t>(b) * T + c * L + l) * H + h] * Ah;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const float up = __shfl_up(v, off, 64);
+      if (lane >= off) v += up;
+    }
+    v += carry;
+    if (l < len) out[l] = v;
+    carry = __shfl(v, 63, 64);
+  }
+}
+
+// ---- 2. chunk-end states -------------------------------------------------------------------
+// grid (ceil(P/64)*ceil(N/64), Nc, Bt*H); each workgroup owns a 64x64 (p, n) tile, each thread a
+// strided 4x4 micro-tile.  states layout: (Bt, H, Nc, P, N).
+template <typename Io>
+__global__ __launch_bounds__(kThreads) void chunk_states_kernel(
+    const void *__restrict__ x, const float *__restrict__ dt, const void *__restrict__ B,
+    const float *__restrict__ cs, float *__restrict__ states, int T, int H, int P, int N, int G,
+    int hpg, int L, int Nc) {
+  __shared__ float Xs[32][64 + 1];
+  __shared__ float Bs[32][64 + 1];
+  const int ntn = (N + 63) / 64;
+  const int p_base = (blockIdx.x / ntn) * 64;
+  const int n_base = (blockIdx.x % ntn) * 64;
+  const int c = blockIdx.y;
+  const int bh = blockIdx.z;
+  const int b = bh / H, h = bh % H, g = h / hpg;
+  const int len = min(L, T - c * L);
+  const float *csc = cs + (static_cast<size_t>(bh) * Nc + c) * L;
+  const float cs_end = csc[len - 1];
+  const int tp = threadIdx.x / 16, tn = threadIdx.x % 16;
+  float acc[4][4] = {};
+  for (int s0 = 0; s0 < len; s0 += 32) {
+    for (int i = threadIdx.x; i < 32 * 64; i += kThreads) {
+      const int s = s0 + i / 64, col = i % 64;
+      float xv = 0.f, bv = 0.f;
+      if (s < len) {
+        const size_t t = static_cast<size_t>(b) * T + c * L + s;
+        if (p_base + col < P) {
+          const float w = expf(cs_end - csc[s]) * dt[t * H + h];
+          xv = w * Io::load(x, (t * H + h) * P + p_base + col);
+        }
+        if (n_base + col < N) bv = Io::load(B, (t * G + g) * N + n_base + col);
+      }
+      Xs[i / 64][col] = xv;
+      Bs[i / 64][col] = bv;
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int s = 0; s < 32; ++s) {
+      float xv[4], bv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        xv[i] = Xs[s][tp + 16 * i];
+        bv[i] = Bs[s][tn + 16 * i];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += xv[i] * bv[j];
+    }
+    __syncthreads();
+  }
+  float *out = states + (static_cast<size_t>(bh) * Nc + c) * P * N;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int p = p_base + tp + 16 * i, n = n_base + tn + 16 * j;
+      if (p < P && n < N) out[static_cast<size_t>(p) * N + n] = acc[i][j];
+    }
+}
+
+// ---- 3. sequential inter-chunk pass ------------------------------------------------------------
+// grid (ceil(P*N/256), Bt*H); thread = one state element.  On return states[c] holds the state
+// ENTERING chunk c, and final_state the state after the last chunk.
+__global__ __launch_bounds__(kThreads) void state_pass_kernel(float *__restrict__ states,
+                                                              const float *__restrict__ cs,
+                                                              const float *__restrict__ h0,
+                                                              float *__restrict__ final_state, int T,
+                                                              int PN, int L, int Nc) {
+  const int e = blockIdx.x * kThreads + threadIdx.x;
+  const int bh = blockIdx.y;
+  if (e >= PN) return;
+  float run = h0 ? h0[static_cast<size_t>(bh) * PN + e] : 0.f;
+  for (int c = 0; c < Nc; ++c) {
+    const int len = min(L, T - c * L);
+    const float decay = expf(cs[(static_cast<size_t>(bh) * Nc + c) * L + len - 1]);
+    float *sp = states + (static_cast<size_t>(bh) * Nc + c) * PN + e;
+    const float s = *sp;
+    *sp = run;
+    run = decay * run + s;
+  }
+  final_state[static_cast<size_t>(bh) * PN + e] = run;
+}
+
+// ---- 4. chunk output -------------------------------------------------------------------------
+// grid (ceil(L/32)*ceil(P/64), Nc, Bt*H); each workgroup owns 32 rows l x 64 columns p of one
+// head-chunk; each thread a strided 2x4 micro-tile.
+template <typename Io>
+__global__ __launch_bounds__(kThreads) void chunk_output_kernel(
+    const void *__restrict__ x, const float *__restrict__ dt, const void *__restrict__ B,
+    const void *__restrict__ C, const float *__restrict__ D, const float *__restrict__ cs,
+    const float *__restrict__ states, void *__restrict__ y, int T, int H, int P, int N, int G, int hpg,
+    int L, int Nc) {
+  __shared__ float Cs[32][32 + 1];   // C[l][n] tile
+  __shared__ float Ts[64][32 + 1];   // H_c[p][n] tile, or B[s][n] tile (first 32 rows)
+  __shared__ float Ms[32][32 + 1];   // masked, decayed scores M[l][s]
+  __shared__ float Xs[32][64 + 1];   // x[s][p] tile
+  __shared__ float cs_l[32], cs_s[32], dt_s[32];
+
+  const int ntp = (P + 63) / 64;
+  const int l_base = (blockIdx.x / ntp) * 32;
+  const int p_base = (blockIdx.x % ntp) * 64;
+  const int c = blockIdx.y;
+  const int bh = blockIdx.z;
+  const int b = bh / H, h = bh % H, g = h / hpg;
+  const int len = min(L, T - c * L);
+  if (l_base >= len) return;
+  const float *csc = cs + (static_cast<size_t>(bh) * Nc + c) * L;
+  const size_t t0 = static_cast<size_t>(b) * T + static_cast<size_t>(c) * L;
+  const int tl = threadIdx.x / 16, tp = threadIdx.x % 16;  // rows tl, tl+16; cols tp+16j
+
+  if (threadIdx.x < 32) cs_l[threadIdx.x] = (l_base + threadIdx.x < len) ? csc[l_base + threadIdx.x] : 0.f;
+
+  // ---- state -> output: acc = C[l,:] . H_c[p,:], then scaled by exp(cs_l) ----
+  float acc[2][4] = {};
+  const float *Hc = states + (static_cast<size_t>(bh) * Nc + c) * P * N;
+  for (int n0 = 0; n0 < N; n0 += 32) {
+    for (int i = threadIdx.x; i < 32 * 32; i += kThreads) {
+      const int r = i / 32, n = n0 + i % 32;
+      float v = 0.f;
+      if (l_base + r < len && n < N) v = Io::load(C, ((t0 + l_base + r) * G + g) * N + n);
+      Cs[r][i % 32] = v;
+    }
+    for (int i = threadIdx.x; i < 64 * 32; i += kThreads) {
+      const int r = i / 32, n = n0 + i % 32;
+      float v = 0.f;
+      if (p_base + r < P && n < N) v = Hc[static_cast<size_t>(p_base + r) * N + n];
+      Ts[r][i % 32] = v;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int n = 0; n < 32; ++n) {
+      const float c0 = Cs[tl][n], c1 = Cs[tl + 16][n];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float hv = Ts[tp + 16 * j][n];
+        acc[0][j] += c0 * hv;
+        acc[1][j] += c1 * hv;
+      }
+    }
+    __syncthreads();
+  }
+  {
+    const float e0 = expf(cs_l[tl]), e1 = expf(cs_l[tl + 16]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      acc[0][j] *= e0;
+      acc[1][j] *= e1;
+    }
+  }
+
+  // ---- intra-chunk: acc += sum_{s<=l} (C_l.B_s) exp(cs_l - cs_s) dt_s x[s,p] ----
+  const int s_end = min(len, l_base + 32);  // causal: no column beyond the last row of this tile
+  const int ml = threadIdx.x / 8, ms = (threadIdx.x % 8) * 4;  // score micro-tile: row ml, cols ms..ms+3
+  for (int s0 = 0; s0 < s_end; s0 += 32) {
+    if (threadIdx.x < 32) {
+      const int s = s0 + threadIdx.x;
+      cs_s[threadIdx.x] = (s < len) ? csc[s] : 0.f;
+      dt_s[threadIdx.x] = (s < len) ? dt[(t0 + s) * H + h] : 0.f;
+    }
+    float sc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int n0 = 0; n0 < N; n0 += 32) {
+      for (int i = threadIdx.x; i < 32 * 32; i += kThreads) {
+        const int r = i / 32, n = n0 + i % 32;
+        float cv = 0.f, bv = 0.f;
+        if (n < N) {
+          if (l_base + r < len) cv = Io::load(C, ((t0 + l_base + r) * G + g) * N + n);
+          if (s0 + r < len) bv = Io::load(B, ((t0 + s0 + r) * G + g) * N + n);
+        }
+        Cs[r][i % 32] = cv;
+        Ts[r][i % 32] = bv;
+      }
+      __syncthreads();
+#pragma unroll 8
+      for (int n = 0; n < 32; ++n) {
+        const float cv = Cs[ml][n];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sc[j] += cv * Ts[ms + j][n];
+      }
+      __syncthreads();
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int l = l_base + ml, s = s0 + ms + j;
+      float m = 0.f;
+      if (s <= l && l < len) m = sc[j] * expf(cs_l[ml] - cs_s[ms + j]) * dt_s[ms + j];
+      Ms[ml][ms + j] = m;
+    }
+    for (int i = threadIdx.x; i < 32 * 64; i += kThreads) {
+      const int r = i / 64, col = i % 64;
+      float v = 0.f;
+      if (s0 + r < len && p_base + col < P) v = Io::load(x, ((t0 + s0 + r) * H + h) * P + p_base + col);
+      Xs[r][col] = v;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int s = 0; s < 32; ++s) {
+      const float m0 = Ms[tl][s], m1 = Ms[tl + 16][s];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float xv = Xs[s][tp + 16 * j];
+        acc[0][j] += m0 * xv;
+        acc[1][j] += m1 * xv;
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- skip connection and store ----
+  const float Dh = D[h];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int l = l_base + tl + 16 * i;
+    if (l >= len) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int p = p_base + tp + 16 * j;
+      if (p >= P) continue;
+      const size_t idx = ((t0 + l) * H + h) * P + p;
+      Io::store(y, idx, acc[i][j] + Dh * Io::load(x, idx));
+    }
+  }
+}
+
+template <typename Io>
+hipError_t launch_typed(const Dims &d, const void *x, const float *dt, const float *A, const void *B,
+                        const void *C, const float *D, const float *h0, void *y, float *final_state,
+                        void *workspace, hipStream_t stream, KernelTrace *trace) {
+  const size_t BH = static_cast<size_t>(d.Bt) * d.H;
+  float *cs = static_cast<float *>(workspace);
+  float *states = cs + round_up(BH * d.Nc * d.L, 64);
+  const int PN = d.P * d.N;
+
+  hipLaunchKernelGGL(chunk_cumsum_kernel, dim3(d.Nc, BH), dim3(64), 0, stream, dt, A, cs, d.T, d.H, d.L,
+                     d.Nc);
+  trace_mark(trace, stream, "chunk_cumsum");
+  const unsigned tiles_pn = ((d.P + 63) / 64) * ((d.N + 63) / 64);
+  hipLaunchKernelGGL((chunk_states_kernel<Io>), dim3(tiles_pn, d.Nc, BH), dim3(kThreads), 0, stream, x, dt,
+                     B, cs, states, d.T, d.H, d.P, d.N, d.G, d.hpg, d.L, d.Nc);
+  trace_mark(trace, stream, "chunk_states");
+  hipLaunchKernelGGL(state_pass_kernel, dim3((PN + kThreads - 1) / kThreads, BH), dim3(kThreads), 0, stream,
+                     states, cs, h0, final_state, d.T, PN, d.L, d.Nc);
+  trace_mark(trace, stream, "state_pass");
+  const unsigned tiles_lp = ((d.L + 31) / 32) * ((d.P + 63) / 64);
+  hipLaunchKernelGGL((chunk_output_kernel<Io>), dim3(tiles_lp, d.Nc, BH), dim3(kThreads), 0, stream, x, dt,
+                     B, C, D, cs, states, y, d.T, d.H, d.P, d.N, d.G, d.hpg, d.L, d.Nc);
+  trace_mark(trace, stream, "chunk_output");
+  return hipGetLastError();
+}
+
+}  // namespace
+
+size_t generic_workspace_bytes(const Dims &d) {
+  const size_t BH = static_cast<size_t>(d.Bt) * d.H;
+  const size_t cs = round_up(BH * d.Nc * d.L, 64);
+  const size_t st = BH * d.Nc * d.P * d.N;
+  return round_up((cs + st) * sizeof(float), 256);
+}
+
+hipError_t launch_prefill_generic(const Dims &d, const void *x, const float *dt, const float *A,
+                                  const void *B, const void *C, const float *D, const float *h0, void *y,
+                                  float *final_state, void *workspace, hipStream_t stream,
+                                  KernelTrace *trace) {
+  return d.bf16
+             ? launch_typed<IoBf16>(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace)
+             : launch_typed<IoF32>(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);
+}
+
+}  // namespace ssd

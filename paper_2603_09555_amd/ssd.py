@@ -1,0 +1,179 @@
+"""Python binding of the C-ABI SSD library (``include/ssd.h``): argument marshalling only.
+
+Every step of prefill and decode runs in the HIP kernels of ``libssd_hip.so``; this module
+turns torch tensors into device pointers, fills the ``ssd_shape`` struct, passes the current
+HIP stream and raises on a non-zero status.  There is no fallback: if the library has not
+been built (``python -m paper_2603_09555_amd.build``) importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libssd_hip.so")
+
+SSD_F32, SSD_BF16 = 0, 1
+SSD_OK = 0
+
+EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
+           "ssd_prefill_path", "ssd_status_string", "ssd_version"]
+
+
+class ssd_shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("batch", "seqlen", "nheads", "headdim", "dstate", "ngroups", "chunk", "io_dtype")]
+
+
+class SSDError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libssd_hip.so is missing: build it with `python -m paper_2603_09555_amd.build` "
+                      "(there is no CPU or PyTorch fallback)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+_vp, _sz = ctypes.c_void_p, ctypes.c_size_t
+_sp = ctypes.POINTER(ssd_shape)
+_lib.ssd_prefill_workspace_bytes.restype = _sz
+_lib.ssd_prefill_workspace_bytes.argtypes = [_sp]
+_lib.ssd_prefill.restype = ctypes.c_int
+_lib.ssd_prefill.argtypes = [_sp] + [_vp] * 10 + [_sz, _vp]
+_lib.ssd_prefill_profile.restype = ctypes.c_int
+_lib.ssd_prefill_profile.argtypes = [_sp] + [_vp] * 10 + [_sz, _vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_float),
+                                     ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_int32)]
+_lib.ssd_decode_step.restype = ctypes.c_int
+_lib.ssd_decode_step.argtypes = [_sp] + [_vp] * 9
+_lib.ssd_decode_step_layers.restype = ctypes.c_int
+_lib.ssd_decode_step_layers.argtypes = [ctypes.c_int32, _sp] + [_vp] * 9
+_lib.ssd_prefill_path.restype = ctypes.c_char_p
+_lib.ssd_prefill_path.argtypes = [_sp]
+_lib.ssd_status_string.restype = ctypes.c_char_p
+_lib.ssd_status_string.argtypes = [ctypes.c_int]
+_lib.ssd_version.restype = ctypes.c_int
+
+
+def raw():
+    """The ctypes handle, for callers that want to pass raw pointers (tests of error paths)."""
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return _lib.ssd_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(_lib.ssd_version())
+
+
+def make_shape(batch, seqlen, nheads, headdim, dstate, ngroups, chunk, io_dtype) -> ssd_shape:
+    if isinstance(io_dtype, torch.dtype):
+        io_dtype = {torch.float32: SSD_F32, torch.bfloat16: SSD_BF16}.get(io_dtype, -1)
+    return ssd_shape(batch, seqlen, nheads, headdim, dstate, ngroups, chunk, io_dtype)
+
+
+def prefill_workspace_bytes(shape: ssd_shape) -> int:
+    return int(_lib.ssd_prefill_workspace_bytes(ctypes.byref(shape)))
+
+
+def prefill_path(shape: ssd_shape) -> str:
+    return _lib.ssd_prefill_path(ctypes.byref(shape)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _check_dev(*ts):
+    for t in ts:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def _stream_ptr():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, workspace=None, profile=None):
+    """``ssd_prefill`` of the C ABI on torch device tensors.  Returns ``(y, final_state)``.
+
+    ``x (Bt,T,H,P)``, ``B, C (Bt,T,G,N)`` in fp32 or bf16; ``dt (Bt,T,H)``, ``A, D (H)``,
+    ``h0 (Bt,H,P,N)`` fp32.  Output and workspace tensors are allocated with torch unless given.
+    With ``profile`` a list, the call goes through ``ssd_prefill_profile`` (it waits for the
+    device) and ``(kernel name, milliseconds)`` pairs are appended to the list.
+    """
+    Bt, T, H, P = x.shape
+    G, N = B.shape[2], B.shape[3]
+    shape = make_shape(Bt, T, H, P, N, G, chunk, x.dtype)
+    if B.dtype != x.dtype or C.dtype != x.dtype:
+        raise ValueError("x, B and C must share one dtype")
+    for t in (dt, A, D, h0):
+        if t is not None and t.dtype != torch.float32:
+            raise ValueError("dt, A, D and h0 must be fp32")
+    if tuple(dt.shape) != (Bt, T, H) or tuple(A.shape) != (H,) or tuple(D.shape) != (H,) \
+            or tuple(C.shape) != tuple(B.shape) or tuple(B.shape[:2]) != (Bt, T) \
+            or (h0 is not None and tuple(h0.shape) != (Bt, H, P, N)):
+        raise ValueError("inconsistent tensor shapes")
+    if y is None:
+        y = torch.empty_like(x)
+    if final_state is None:
+        final_state = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device)
+    need = prefill_workspace_bytes(shape)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    _check_dev(x, dt, A, B, C, D, h0, y, final_state, workspace)
+    args = (ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(h0), _ptr(y),
+            _ptr(final_state), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_ptr())
+    if profile is None:
+        st = _lib.ssd_prefill(*args)
+    else:
+        ms = (ctypes.c_float * 8)()
+        names = (ctypes.c_char_p * 8)()
+        n = ctypes.c_int32(0)
+        st = _lib.ssd_prefill_profile(*args, 8, ms, names, ctypes.byref(n))
+        profile.extend((names[i].decode(), float(ms[i])) for i in range(n.value))
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_prefill")
+    return y, final_state
+
+
+def ssd_decode_step(state, x, dt, A, B, C, D, y=None):
+    """``ssd_decode_step``: updates ``state (Bt,H,P,N)`` in place, returns ``y (Bt,H,P)``."""
+    Bt, H, P, N = state.shape
+    G = B.shape[1]
+    shape = make_shape(Bt, 1, H, P, N, G, 1, x.dtype)
+    if y is None:
+        y = torch.empty_like(x)
+    if state.dtype != torch.float32 or tuple(x.shape) != (Bt, H, P) or tuple(dt.shape) != (Bt, H) \
+            or tuple(B.shape) != (Bt, G, N) or tuple(C.shape) != (Bt, G, N):
+        raise ValueError("inconsistent tensor shapes")
+    _check_dev(state, x, dt, A, B, C, D, y)
+    st = _lib.ssd_decode_step(ctypes.byref(shape), _ptr(state), _ptr(x), _ptr(dt), _ptr(A), _ptr(B),
+                              _ptr(C), _ptr(D), _ptr(y), _stream_ptr())
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_decode_step")
+    return y
+
+
+def ssd_decode_step_layers(state, x, dt, A, B, C, D, y=None):
+    """``ssd_decode_step_layers``: every tensor has a leading layer axis; one launch."""
+    Ly, Bt, H, P, N = state.shape
+    G = B.shape[2]
+    shape = make_shape(Bt, 1, H, P, N, G, 1, x.dtype)
+    if y is None:
+        y = torch.empty_like(x)
+    if state.dtype != torch.float32 or tuple(x.shape) != (Ly, Bt, H, P) or tuple(dt.shape) != (Ly, Bt, H) \
+            or tuple(A.shape) != (Ly, H) or tuple(D.shape) != (Ly, H) \
+            or tuple(B.shape) != (Ly, Bt, G, N) or tuple(C.shape) != (Ly, Bt, G, N):
+        raise ValueError("inconsistent tensor shapes")
+    _check_dev(state, x, dt, A, B, C, D, y)
+    st = _lib.ssd_decode_step_layers(Ly, ctypes.byref(shape), _ptr(state), _ptr(x), _ptr(dt), _ptr(A),
+                                     _ptr(B), _ptr(C), _ptr(D), _ptr(y), _stream_ptr())
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_decode_step_layers")
+    return y

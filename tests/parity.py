@@ -1,0 +1,41 @@
+"""Error metrics shared by the GPU parity tests.
+
+Tolerance: max relative error 1e-4 for fp32 inputs, 2e-2 for bf16 inputs with fp32
+accumulation.  "Relative" is made precise in two ways, and both are gated:
+  (i)  scale-normalised: max|g - o| / max|o| <= tol
+  (ii) element-wise, allclose-style (the form of the paper's own parity table):
+       |g - o| <= tol*|o| + tol*rms(o) for every element.
+"""
+import numpy as np
+import torch
+
+TOL = {"f32": 1e-4, "bf16": 2e-2, torch.float32: 1e-4, torch.bfloat16: 2e-2}
+
+
+def to_np64(t):
+    if isinstance(t, torch.Tensor):
+        return t.detach().float().cpu().numpy().astype(np.float64)
+    return np.asarray(t, dtype=np.float64)
+
+
+def errors(got, ref):
+    g, o = to_np64(got), to_np64(ref)
+    assert g.shape == o.shape, (g.shape, o.shape)
+    if o.size == 0:
+        return dict(norm=0.0, worst_allclose=0.0, max_ref=0.0)
+    assert np.all(np.isfinite(g)), "non-finite values in the GPU result"
+    d = np.abs(g - o)
+    mx = float(np.abs(o).max())
+    rms = float(np.sqrt(np.mean(o * o)))
+    norm = float(d.max() / mx) if mx > 0 else float(d.max())
+    denom = np.abs(o) + rms
+    worst = float((d / np.where(denom > 0, denom, 1.0)).max())
+    return dict(norm=norm, worst_allclose=worst, max_ref=mx)
+
+
+def assert_close(got, ref, tol, what=""):
+    e = errors(got, ref)
+    assert e["norm"] <= tol and e["worst_allclose"] <= tol, \
+        "%s: normalised max err %.3e, worst allclose ratio %.3e, tol %.1e" % (what, e["norm"],
+                                                                             e["worst_allclose"], tol)
+    return e

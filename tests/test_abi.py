@@ -1,0 +1,115 @@
+"""Host-side tests of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, and rejects invalid calls before any HIP call (so these run on a CPU machine)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ssd():
+    from paper_2603_09555_amd import build
+    build.build(force=False)
+    from paper_2603_09555_amd import ssd as binding
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ssd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"SSD_API\s+[\w\s\*]+?\b(ssd_\w+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(ssd):
+    names = declared_symbols()
+    assert len(names) >= 7, names
+    assert sorted(ssd.EXPORTS) == names
+    lib = ctypes.CDLL(ssd.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), "libssd_hip.so does not export %s" % n
+
+
+def test_version_and_status_strings(ssd):
+    assert ssd.version() >= 100
+    assert ssd.status_string(0) == "ok"
+    for code in range(-7, 0):
+        assert ssd.status_string(code) not in ("ok", "unknown status")
+    assert ssd.status_string(-99) == "unknown status"
+
+
+def shape(ssd, **kw):
+    d = dict(batch=1, seqlen=64, nheads=4, headdim=32, dstate=16, ngroups=1, chunk=16, io_dtype=0)
+    d.update(kw)
+    return ssd.make_shape(**d)
+
+
+def test_workspace_query(ssd):
+    assert ssd.prefill_workspace_bytes(shape(ssd)) > 0
+    assert ssd.prefill_workspace_bytes(shape(ssd)) % 256 == 0
+    for bad in (dict(batch=0), dict(seqlen=0), dict(nheads=0), dict(headdim=-1), dict(dstate=0),
+                dict(ngroups=0), dict(chunk=0), dict(nheads=6, ngroups=4), dict(io_dtype=2)):
+        assert ssd.prefill_workspace_bytes(shape(ssd, **bad)) == 0, bad
+        assert ssd.prefill_path(shape(ssd, **bad)) == "invalid"
+    # seqlen need not be a multiple of chunk, and chunk may exceed seqlen
+    assert ssd.prefill_workspace_bytes(shape(ssd, seqlen=65)) > 0
+    assert ssd.prefill_workspace_bytes(shape(ssd, seqlen=5, chunk=64)) > 0
+    assert ssd.prefill_path(shape(ssd)) in ("generic_f32", "mfma_bf16")
+
+
+def test_prefill_rejects_before_any_hip_call(ssd):
+    lib = ssd.raw()
+    fake = ctypes.c_void_p(4096)  # never dereferenced: validation fails first
+    ws = ctypes.c_void_p(4096)
+
+    def call(s, x=fake, dt=fake, A=fake, B=fake, C=fake, D=fake, h0=None, y=fake, st=fake, w=ws, wb=1 << 40):
+        return lib.ssd_prefill(ctypes.byref(s) if s is not None else None, x, dt, A, B, C, D, h0, y, st, w,
+                               wb, None)
+
+    assert call(None) == -1
+    assert call(shape(ssd, batch=0)) == -2
+    assert call(shape(ssd, nheads=6, ngroups=4)) == -2
+    assert call(shape(ssd, io_dtype=7)) == -3
+    assert call(shape(ssd), x=None) == -1
+    assert call(shape(ssd), st=None) == -1
+    assert call(shape(ssd), y=ctypes.c_void_p(4100)) == -7
+    assert call(shape(ssd), h0=ctypes.c_void_p(4104)) == -7
+    assert call(shape(ssd), w=None) == -5
+    assert call(shape(ssd), wb=16) == -5
+    assert call(shape(ssd), w=ctypes.c_void_p(4096 + 16)) == -5
+    assert call(shape(ssd, batch=70000)) == -4
+    assert call(shape(ssd, batch=2 ** 30, seqlen=2 ** 30)) == -2
+
+
+def test_decode_rejects_before_any_hip_call(ssd):
+    lib = ssd.raw()
+    fake = ctypes.c_void_p(4096)
+
+    def call(s, nl=1, state=fake, x=fake, dt=fake, A=fake, B=fake, C=fake, D=fake, y=fake):
+        return lib.ssd_decode_step_layers(nl, ctypes.byref(s) if s is not None else None, state, x, dt, A, B,
+                                          C, D, y, None)
+
+    assert call(None) == -1
+    assert call(shape(ssd), nl=0) == -2
+    assert call(shape(ssd, seqlen=0, chunk=0), state=None) == -1  # seqlen/chunk are ignored by decode
+    assert call(shape(ssd, dstate=0)) == -2
+    assert call(shape(ssd, io_dtype=-1)) == -3
+    assert call(shape(ssd), state=ctypes.c_void_p(4100)) == -7
+    assert call(shape(ssd), y=None) == -1
+    assert lib.ssd_decode_step(ctypes.byref(shape(ssd)), None, fake, fake, fake, fake, fake, fake, fake,
+                               None) == -1
+
+
+def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
+    """The product path has no fallback: with the .so absent the binding cannot be imported."""
+    import importlib.util
+    import shutil
+    src = os.path.join(ROOT, "paper_2603_09555_amd", "ssd.py")
+    dst = tmp_path / "ssd_copy.py"
+    shutil.copy(src, dst)
+    spec = importlib.util.spec_from_file_location("ssd_copy", str(dst))
+    mod = importlib.util.module_from_spec(spec)
+    with pytest.raises(ImportError):
+        spec.loader.exec_module(mod)

@@ -1,0 +1,212 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element,
+on the same seeded inputs.  Sizes here are ones the oracle finishes in seconds; they span
+several tiles and ragged tails.  Full-size configurations are in test_gpu_full_size.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ssd_oracle
+from paper_2603_09555_amd import inputs
+from parity import TOL, assert_close, to_np64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ssd():
+    from paper_2603_09555_amd import ssd as binding
+    return binding
+
+
+def cfg_of(Bt, T, H, P, N, G, L, io):
+    return inputs.SSDConfig("t", Bt, T, H, P, N, G, L, io)
+
+
+def run_prefill(ssd, cfg, seed=0, h0=None, chunk=None):
+    inp = inputs.make_prefill_inputs(cfg, seed=seed)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    h0d = None if h0 is None else h0.cuda()
+    print("prefill case", cfg, "seed", seed, "h0" if h0 is not None else "", flush=True)
+    y, st = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
+                            chunk if chunk is not None else cfg.chunk, h0=h0d)
+    torch.cuda.synchronize()
+    return inp, y, st
+
+
+def oracle_prefill(inp, h0=None, pairs=None):
+    return ssd_oracle.prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], h0=h0, pairs=pairs)
+
+
+PREFILL_CASES = [
+    # Bt, T, H, P, N, G, L
+    (1, 512, 4, 32, 16, 1, 64),     # configs[0]
+    (2, 100, 4, 32, 16, 2, 32),     # ragged tail (100 = 3*32 + 4)
+    (1, 1, 2, 8, 4, 1, 16),         # single token
+    (1, 65, 2, 16, 8, 1, 64),       # one full chunk + one token
+    (2, 37, 6, 24, 20, 3, 7),       # nothing is a multiple of any tile
+    (1, 48, 2, 64, 128, 1, 256),    # chunk longer than the sequence
+    (1, 300, 3, 72, 40, 1, 128),    # P and N beyond one 64-wide tile
+    (3, 129, 8, 64, 128, 2, 64),    # Mamba-2 head shape, small T
+]
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("case", PREFILL_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_prefill_matches_oracle(ssd, case, io):
+    cfg = cfg_of(*case, io)
+    inp, y, st = run_prefill(ssd, cfg, seed=1)
+    y_ref, st_ref = oracle_prefill(inp)
+    assert y.dtype == cfg.torch_io_dtype and st.dtype == torch.float32
+    assert_close(y, y_ref, TOL[io], "y")
+    assert_close(st, st_ref, TOL[io], "final state")
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_prefill_with_initial_state_and_aliasing(ssd, io):
+    cfg = cfg_of(2, 90, 4, 32, 16, 2, 32, io)
+    h0 = inputs.make_state(cfg, seed=3)
+    inp, y, st = run_prefill(ssd, cfg, seed=2, h0=h0)
+    y_ref, st_ref = oracle_prefill(inp, h0=h0)
+    assert_close(y, y_ref, TOL[io], "y with h0")
+    assert_close(st, st_ref, TOL[io], "state with h0")
+    # h0 may alias final_state
+    dev = {k: v.cuda() for k, v in inp.items()}
+    buf = h0.cuda().clone()
+    y2, st2 = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk, h0=buf,
+                              final_state=buf)
+    torch.cuda.synchronize()
+    assert st2.data_ptr() == buf.data_ptr()
+    assert torch.equal(y2, y) and torch.equal(st2, st)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_chunk_size_independence(ssd, io):
+    base = cfg_of(1, 200, 4, 32, 16, 1, 64, io)
+    inp = inputs.make_prefill_inputs(base, seed=5)
+    y_ref, st_ref = oracle_prefill(inp)
+    for L in (1, 3, 16, 64, 100, 200, 256, 1000):
+        _, y, st = run_prefill(ssd, base, seed=5, chunk=L)
+        assert_close(y, y_ref, TOL[io], "y chunk %d" % L)
+        assert_close(st, st_ref, TOL[io], "state chunk %d" % L)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_prefill_then_decode_equals_longer_prefill(ssd, io):
+    cfg = cfg_of(2, 97, 4, 32, 16, 2, 32, io)
+    inp = inputs.make_prefill_inputs(cfg, seed=7)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    y_all, st_all = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
+    cut = {k: (v[:, :-1].contiguous() if k in ("x", "dt", "B", "C") else v) for k, v in dev.items()}
+    y_pre, st_pre = ssd.ssd_prefill(cut["x"], cut["dt"], cut["A"], cut["B"], cut["C"], cut["D"], cfg.chunk)
+    y_last = ssd.ssd_decode_step(st_pre, dev["x"][:, -1].contiguous(), dev["dt"][:, -1].contiguous(), dev["A"],
+                                 dev["B"][:, -1].contiguous(), dev["C"][:, -1].contiguous(), dev["D"])
+    torch.cuda.synchronize()
+    y_ref, st_ref = oracle_prefill(inp)
+    assert_close(y_pre, y_ref[:, :-1], TOL[io], "prefix y")
+    assert_close(y_last, y_ref[:, -1], TOL[io], "decode y")
+    assert_close(st_pre, st_ref, TOL[io], "state after prefill+decode")
+    assert_close(st_pre, to_np64(st_all), TOL[io], "GPU prefill(T+1) vs GPU prefill(T)+decode")
+
+
+def test_split_prompt_with_carried_state(ssd):
+    cfg = cfg_of(1, 150, 4, 32, 16, 1, 64, "f32")
+    inp = inputs.make_prefill_inputs(cfg, seed=9)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    y_ref, st_ref = oracle_prefill(inp)
+    for cut in (1, 64, 77):
+        a = {k: (v[:, :cut].contiguous() if k in ("x", "dt", "B", "C") else v) for k, v in dev.items()}
+        b = {k: (v[:, cut:].contiguous() if k in ("x", "dt", "B", "C") else v) for k, v in dev.items()}
+        y1, s1 = ssd.ssd_prefill(a["x"], a["dt"], a["A"], a["B"], a["C"], a["D"], cfg.chunk)
+        y2, s2 = ssd.ssd_prefill(b["x"], b["dt"], b["A"], b["B"], b["C"], b["D"], cfg.chunk, h0=s1)
+        torch.cuda.synchronize()
+        assert_close(torch.cat([y1, y2], dim=1), y_ref, 1e-4, "split y at %d" % cut)
+        assert_close(s2, st_ref, 1e-4, "split state at %d" % cut)
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_bitwise_determinism_and_batch_invariance(ssd, io):
+    cfg = cfg_of(3, 130, 4, 32, 16, 2, 32, io)
+    inp, y1, s1 = run_prefill(ssd, cfg, seed=11)
+    _, y2, s2 = run_prefill(ssd, cfg, seed=11)
+    assert torch.equal(y1, y2) and torch.equal(s1, s2)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    row = {k: (v[1:2].contiguous() if k in ("x", "dt", "B", "C") else v) for k, v in dev.items()}
+    yr, sr = ssd.ssd_prefill(row["x"], row["dt"], row["A"], row["B"], row["C"], row["D"], cfg.chunk)
+    torch.cuda.synchronize()
+    assert torch.equal(yr, y1[1:2]) and torch.equal(sr, s1[1:2])
+
+
+def test_extreme_decay_stays_finite(ssd):
+    """Largest step size times the most negative A over a whole chunk: exponents reach -400,
+    masked entries must be exact zeros and nothing may overflow."""
+    cfg = cfg_of(1, 512, 2, 32, 16, 1, 256, "f32")
+    inp = inputs.make_prefill_inputs(cfg, seed=13)
+    inp["dt"] = torch.full_like(inp["dt"], 0.1)
+    inp["A"] = torch.tensor([-16.0, -1e-3])
+    dev = {k: v.cuda() for k, v in inp.items()}
+    y, st = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
+    torch.cuda.synchronize()
+    y_ref, st_ref = oracle_prefill(inp)
+    assert_close(y, y_ref, 1e-4, "extreme decay y")
+    assert_close(st, st_ref, 1e-4, "extreme decay state")
+
+
+# ---- decode ---------------------------------------------------------------------------------
+DECODE_CASES = [
+    # Ly, Bt, H, P, N, G
+    (1, 1, 4, 32, 16, 1),
+    (1, 3, 6, 24, 20, 3),     # N not a multiple of 4
+    (1, 2, 4, 16, 24, 2),     # N/4 = 6, not a power of two
+    (2, 2, 8, 64, 128, 1),    # Mamba-2 head shape
+    (3, 1, 5, 7, 4, 5),
+    (2, 1, 2, 40, 256, 1),
+    (1, 2, 3, 100, 64, 1),    # P beyond one unrolled pass
+]
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("case", DECODE_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_decode_matches_oracle(ssd, case, io):
+    Ly, Bt, H, P, N, G = case
+    iod = torch.float32 if io == "f32" else torch.bfloat16
+    g = torch.Generator().manual_seed(17)
+    state = torch.randn((Ly, Bt, H, P, N), generator=g)
+    x = torch.randn((Ly, Bt, H, P), generator=g).to(iod)
+    dt = torch.rand((Ly, Bt, H), generator=g) * 0.1 + 1e-3
+    A = -(torch.rand((Ly, H), generator=g) * 15 + 1)
+    D = torch.randn((Ly, H), generator=g)
+    B = (0.25 * torch.randn((Ly, Bt, G, N), generator=g)).to(iod)
+    C = (0.25 * torch.randn((Ly, Bt, G, N), generator=g)).to(iod)
+    print("decode case", case, io, flush=True)
+    sd = state.cuda().clone()
+    y = ssd.ssd_decode_step_layers(sd, x.cuda(), dt.cuda(), A.cuda(), B.cuda(), C.cuda(), D.cuda())
+    torch.cuda.synchronize()
+    y_ref, st_ref = ssd_oracle.decode_step_layers(state, x, dt, A, B, C, D)
+    assert_close(y, y_ref, TOL[io], "decode y")
+    assert_close(sd, st_ref, 1e-5, "decode state")  # the state is fp32 whatever the io dtype
+    if Ly == 1:
+        sd1 = state[0].cuda().clone()
+        y1 = ssd.ssd_decode_step(sd1, x[0].cuda(), dt[0].cuda(), A[0].cuda(), B[0].cuda(), C[0].cuda(),
+                                 D[0].cuda())
+        torch.cuda.synchronize()
+        assert torch.equal(y1, y[0]) and torch.equal(sd1, sd[0])
+
+
+def test_many_decode_steps_track_the_oracle(ssd):
+    """64 consecutive steps from a prefilled state (the generation loop of Alg. 2, SSM part)."""
+    cfg = cfg_of(2, 64, 8, 64, 128, 1, 64, "bf16")
+    inp = inputs.make_prefill_inputs(cfg, seed=19)
+    steps = inputs.make_decode_inputs(cfg, 64, seed=19)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    _, st = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
+    sdev = {k: v.cuda() for k, v in steps.items()}
+    ys = [ssd.ssd_decode_step(st, sdev["x"][i], sdev["dt"][i], dev["A"], sdev["B"][i], sdev["C"][i], dev["D"])
+          for i in range(64)]
+    torch.cuda.synchronize()
+    full = {"x": torch.cat([inp["x"], steps["x"].transpose(0, 1)], dim=1),
+            "dt": torch.cat([inp["dt"], steps["dt"].transpose(0, 1)], dim=1),
+            "B": torch.cat([inp["B"], steps["B"].transpose(0, 1)], dim=1),
+            "C": torch.cat([inp["C"], steps["C"].transpose(0, 1)], dim=1), "A": inp["A"], "D": inp["D"]}
+    y_ref, st_ref = oracle_prefill(full)
+    assert_close(torch.stack(ys, dim=1), y_ref[:, 64:], 2e-2, "decode y over 64 steps")
+    assert_close(st, st_ref, 2e-2, "state after 64 steps")
