@@ -25,7 +25,6 @@ ssd_status make_dims(const ssd_shape *s, bool decode, Dims *out) {
   d.N = s->dstate;
   d.G = s->ngroups;
   d.L = decode ? 1 : s->chunk;
-  if (d.L > d.T) d.L = d.T;  // a chunk longer than the sequence is one short chunk
   d.Nc = (d.T + d.L - 1) / d.L;
   d.hpg = d.H / d.G;
   d.bf16 = s->io_dtype == SSD_BF16;

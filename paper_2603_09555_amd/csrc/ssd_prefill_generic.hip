@@ -270,6 +270,13 @@ __global__ __launch_bounds__(kThreads) void chunk_output_kernel(
   }
 }
 
+// A chunk longer than the sequence is one short chunk.
+Dims clamp_chunk(Dims d) {
+  if (d.L > d.T) d.L = d.T;
+  d.Nc = (d.T + d.L - 1) / d.L;
+  return d;
+}
+
 template <typename Io>
 hipError_t launch_typed(const Dims &d, const void *x, const float *dt, const float *A, const void *B,
                         const void *C, const float *D, const float *h0, void *y, float *final_state,
@@ -298,17 +305,19 @@ hipError_t launch_typed(const Dims &d, const void *x, const float *dt, const flo
 
 }  // namespace
 
-size_t generic_workspace_bytes(const Dims &d) {
+size_t generic_workspace_bytes(const Dims &d_in) {
+  const Dims d = clamp_chunk(d_in);
   const size_t BH = static_cast<size_t>(d.Bt) * d.H;
   const size_t cs = round_up(BH * d.Nc * d.L, 64);
   const size_t st = BH * d.Nc * d.P * d.N;
   return round_up((cs + st) * sizeof(float), 256);
 }
 
-hipError_t launch_prefill_generic(const Dims &d, const void *x, const float *dt, const float *A,
+hipError_t launch_prefill_generic(const Dims &d_in, const void *x, const float *dt, const float *A,
                                   const void *B, const void *C, const float *D, const float *h0, void *y,
                                   float *final_state, void *workspace, hipStream_t stream,
                                   KernelTrace *trace) {
+  const Dims d = clamp_chunk(d_in);
   return d.bf16
              ? launch_typed<IoBf16>(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace)
              : launch_typed<IoF32>(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);

@@ -210,3 +210,61 @@ def test_many_decode_steps_track_the_oracle(ssd):
     y_ref, st_ref = oracle_prefill(full)
     assert_close(torch.stack(ys, dim=1), y_ref[:, 64:], 2e-2, "decode y over 64 steps")
     assert_close(st, st_ref, 2e-2, "state after 64 steps")
+
+
+# ---- MFMA path (headdim 64, dstate 128, bf16) --------------------------------------------------
+MFMA_CASES = [
+    # Bt, T, H, P, N, G, L, forced chunks per segment (0 = library's choice)
+    (1, 64, 2, 64, 128, 1, 64, 0),       # exactly one block
+    (1, 1, 1, 64, 128, 1, 64, 0),        # single token
+    (2, 300, 4, 64, 128, 1, 256, 0),     # ragged tail inside the second chunk
+    (1, 1000, 3, 64, 128, 1, 128, 1),    # one chunk per segment: 8 segments, ragged last block
+    (1, 1000, 3, 64, 128, 1, 128, 3),    # 3 chunks per segment
+    (2, 513, 8, 64, 128, 2, 64, 2),      # two groups, T = 8 blocks + 1 token
+    (1, 2048, 24, 64, 128, 1, 256, 0),   # configs[1]
+    (1, 777, 2, 64, 128, 1, 1024, 0),    # chunk longer than the sequence
+]
+
+
+@pytest.mark.parametrize("case", MFMA_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_mfma_prefill_matches_oracle(ssd, case, monkeypatch):
+    *dims, seg = case
+    cfg = cfg_of(*dims, "bf16")
+    sh = ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk,
+                        torch.bfloat16)
+    assert ssd.prefill_path(sh) == "mfma_bf16"
+    if seg:
+        monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+    else:
+        monkeypatch.delenv("SSD_SEG_CHUNKS", raising=False)
+    h0 = inputs.make_state(cfg, seed=4) if cfg.seqlen in (300, 1000) else None
+    inp, y, st = run_prefill(ssd, cfg, seed=23, h0=h0)
+    y_ref, st_ref = oracle_prefill(inp, h0=h0)
+    e = assert_close(y, y_ref, 2e-2, "mfma y")
+    assert_close(st, st_ref, 2e-2, "mfma final state")
+    print("errors", e, flush=True)
+
+
+def test_mfma_and_generic_paths_agree(ssd, monkeypatch):
+    cfg = cfg_of(2, 700, 4, 64, 128, 2, 128, "bf16")
+    inp, y, st = run_prefill(ssd, cfg, seed=29)
+    monkeypatch.setenv("SSD_FORCE_GENERIC", "1")
+    _, yg, stg = run_prefill(ssd, cfg, seed=29)
+    monkeypatch.delenv("SSD_FORCE_GENERIC")
+    assert_close(y, to_np64(yg), 2e-2, "mfma vs generic y")
+    assert_close(st, to_np64(stg), 2e-2, "mfma vs generic state")
+
+
+def test_mfma_extreme_decay_and_determinism(ssd):
+    cfg = cfg_of(1, 640, 2, 64, 128, 1, 256, "bf16")
+    inp = inputs.make_prefill_inputs(cfg, seed=31)
+    inp["dt"] = torch.full_like(inp["dt"], 0.1)
+    inp["A"] = torch.tensor([-16.0, -1e-3])
+    dev = {k: v.cuda() for k, v in inp.items()}
+    y, st = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
+    y2, st2 = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2) and torch.equal(st, st2)
+    y_ref, st_ref = oracle_prefill(inp)
+    assert_close(y, y_ref, 2e-2, "extreme decay y (mfma)")
+    assert_close(st, st_ref, 2e-2, "extreme decay state (mfma)")
