@@ -1,24 +1,33 @@
-// MFMA prefill for the Mamba-2 head shape (headdim 64, dstate 128, bf16 io, chunk % 64 == 0).
+// MFMA prefill for the Mamba-2 head shape (headdim 64, dstate 128, bf16 io, chunk % 64 == 0,
+// heads per group a multiple of 4).
 //
 // The chunked algorithm (Alg. 1; Eq. 3) is evaluated on 64-token blocks.  Below the diagonal
 // blocks the decay mask of Eq. 3 has rank one per block pair, so the off-diagonal part of the
-// masked product equals "C_l . (state entering the block)": one workgroup walks its blocks in
-// order with the fp32 state H (headdim x dstate) resident in MFMA accumulators -- the
+// masked product equals "C_l . (state entering the block)": a wave walks the blocks of its
+// head in order with the fp32 state H (headdim x dstate) resident in MFMA accumulators -- the
 // inter-chunk state pass happens in registers with no per-chunk launch -- and only the
-// diagonal 64x64 blocks need the mask.  Inside a diagonal block the mask is factorised around a
-// reference point per 32-token half (ref_0 = block start, ref_1 = token 31):
-//     exp(cs_l - cs_s) = exp(cs_l - ref_I) * exp(ref_I - ref_J) * exp(ref_J - cs_s),   J <= I
-// The last factor is folded into the input once per token (Xc = dt_s exp(ref_J - cs_s) x_s), the
-// middle one is a scalar applied to the accumulators between MFMA groups, the first one scales
-// output rows, and what remains of the mask -- the causal zero pattern -- is head independent
-// and baked into G = tril(C B^T), computed once per group.  So the mask is never materialised,
-// costs no per-element work per head, and every exponent that is evaluated is bounded by the
-// decay of 32 tokens (clamped at 2^100, far beyond dt*|A| = 1.6 per token).  Per block and head:
-//     Y^T  = H C^T                      (state -> output, K = dstate)          8 MFMA / wave
-//     Y^T += Xc^T G^T                   (intra-block, K <= 64)                 2-4 MFMA / wave
-//     y    = rowfactor o Y + D x                                               epilogue
-//     H^T  = d1 (d0 (H^T + Bt Xc[0:32]) + Bt Xc[32:64])                        8 MFMA / wave
-// all MFMAs v_mfma_f32_32x32x16_bf16 with fp32 accumulation; decay arithmetic is fp32.
+// diagonal 64x64 blocks need the mask.  Inside a diagonal block the mask is factorised around
+// the middle of the block (c31 = prefix sum at token 31):
+//     exp(cs_l - cs_s) = exp(cs_l - c31) * exp(c31 - cs_s)
+// The second factor is folded into the input once per token (Xm = dt_s exp(c31 - cs_s) x_s),
+// the first one scales output rows, and what remains of the mask -- the causal zero pattern --
+// is head independent and baked into G = tril(C B^T), computed once per group.  So the mask is
+// never materialised, costs no per-element work per head, and every exponent that is evaluated
+// is bounded by the decay of 32 tokens (clamped at 2^+-100, far beyond dt*|A| = 1.6 per token).
+// With Ht = exp(c31) * (state entering the block), per block and head:
+//     Y^T  = Ht C^T + Xm^T G^T            (state -> output, K = dstate; intra-block, K <= 64)
+//     y    = exp(cs_l - c31) o Y + D x     (epilogue)
+//     H'   = Ht + B^T Xm                   (chunk-state accumulation, K = 64)
+//     Ht_next = exp(c63 - c31) exp(c31_next) H'
+// all on v_mfma_f32_32x32x16_bf16 with fp32 accumulation (76 MFMAs per block and head); decay
+// arithmetic is fp32.
+//
+// Work decomposition: one WAVE per (head, half of headdim), four heads of one B/C group per
+// workgroup of eight waves, one workgroup per CU (two waves per SIMD).  A wave owns a 128 x 32
+// slice of the state and never exchanges data with another wave.  The C, B^T and G tiles are
+// staged once per workgroup in double-buffered LDS and shared by the four heads; each wave
+// stages its own slice of the scaled input.  Global loads for block j+2 are issued while block
+// j+1 is being computed, with one barrier per block.
 //
 // Kernels:
 //   scores_bt      per (batch, group, block): G = tril(C B^T) (diagonal blocks only, bf16) and a
@@ -149,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void scores_bt_kernel(const uint16_t *__r
 // ---- block_cumsum: per (batch, head, block) decay bookkeeping ----------------------------------
 // grid (NB, ceil(H/16), Bt).  For every head writes one 128-float record per block:
 //   [0,64)    cs_s  block-relative inclusive prefix sum of dt*A*log2(e)   (the "segsum" input)
-//   [64,128)  f_s = dt_s * exp2(min(ref - cs_s, 100)), ref = 0 for s < 32 and cs_31 otherwise
+//   [64,128)  f_s = dt_s * exp2(clamp(cs_31 - cs_s, -100, 100))
 // Tokens beyond the sequence get dt = 0 (state-neutral padding).  dt is read in its
 // (batch, token, head) layout and transposed through LDS.
 constexpr int kRec = 2 * kBlk;
@@ -179,11 +188,10 @@ __global__ __launch_bounds__(kThreads) void block_cumsum_kernel(const float *__r
       const float up = __shfl_up(v, off, 64);
       if (lane >= off) v += up;
     }
-    const float c31 = __shfl(v, 31, 64);  // executed by every lane: the source lane must be active
-    const float ref = (lane < 32) ? 0.f : c31;
+    const float c31 = __shfl(v, 31, 64);
     float *rec = prep + ((static_cast<size_t>(b) * H + h) * NB + jb) * kRec;
     rec[lane] = v;
-    rec[kBlk + lane] = dtv * fast_exp2(fminf(ref - v, kMaxExp));
+    rec[kBlk + lane] = dtv * fast_exp2(fminf(fmaxf(c31 - v, -kMaxExp), kMaxExp));
   }
 }
 
@@ -196,6 +204,7 @@ struct ScanParams {
   const uint16_t *Btr;
   const float *prep;
   uint16_t *y;
+  uint16_t *y_dump;        // 128 bytes of scratch: where the lanes of padded tokens store
   const float *Hin;        // state entering each segment, or nullptr = zeros
   size_t hin_bh_stride;    // elements between consecutive (b, h) in Hin
   float *final_state;      // (Bt, H, P, N): written by the last segment
@@ -204,278 +213,292 @@ struct ScanParams {
   int T, H, G, hpg, NB, seg_blocks, S;
 };
 
-// Register budget: two workgroups (8 waves) per CU for the full kernel, up to four for the
-// states-only one; pinned so that the compiler neither spills to reach a higher occupancy
-// nor exceeds what two resident workgroups allow.
-template <bool kStatesOnly>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, kStatesOnly ? 4 : 2)))
-void chunk_scan_kernel(const ScanParams p) {
-  __shared__ __align__(16) uint16_t sC[kStatesOnly ? 8 : kBlk * kCStride];  // C, n permuted per 16
-  __shared__ __align__(16) uint16_t sBt[kN * kBtStride];                    // B^T [n][s]
-  __shared__ __align__(16) uint16_t sXc[kP * kXStride];                     // Xc^T [p][s]
-  __shared__ __align__(16) u32x4 sExch[kStatesOnly ? 1 : 4][4][64];         // bf16 state operands
-  __shared__ __align__(16) float sCs[kBlk];  // block-relative inclusive prefix sum of dt*A*log2(e)
+constexpr int kHeadsPerWg = 4;
+constexpr int kScanThreads = 2 * 64 * kHeadsPerWg;  // two waves per head, one per half of headdim
+constexpr int kGStride = kBlk + 8;
 
-  const int h = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
-  const int g = h / p.hpg;
-  const size_t bh = static_cast<size_t>(b) * p.H + h;
-  const size_t bg = static_cast<size_t>(b) * p.G + g;
+// One wave per (head, half of headdim): the wave owns a 128 x 32 slice of the state (64
+// accumulator registers), a 64 x 32 output tile (32) and its input operands (16); with the next
+// block's data in flight it stays under 256 registers, so the eight waves of a workgroup run two
+// per SIMD and one wave's MFMAs overlap the other's vector work and memory waits.
+template <bool kStatesOnly>
+__global__ __launch_bounds__(kScanThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void chunk_scan_kernel(const ScanParams p) {
+  __shared__ __align__(16) uint16_t sC[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kBlk * kCStride];
+  __shared__ __align__(16) uint16_t sBt[2][kN * kBtStride];                   // B^T [n][s]
+  __shared__ __align__(16) uint16_t sG[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kBlk * kGStride];
+  __shared__ __align__(16) uint16_t sXm[kHeadsPerWg][kP * kXStride];          // Xm^T [p][s], per head
+
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wn = wave >> 1, wp = wave & 1;  // wn doubles as the row-block index of the outputs
+  const int hw = wave >> 1, ph = wave & 1;  // head inside the workgroup, half of headdim
+  const int h = blockIdx.x * kHeadsPerWg + hw, sg = blockIdx.y, b = blockIdx.z;
+  const int g = (blockIdx.x * kHeadsPerWg) / p.hpg;  // the four heads share one group
+  const size_t bh = static_cast<size_t>(b) * p.H + h;
+  const size_t bg = static_cast<size_t>(b) * p.G + g;
   const int r = lane & 31, kg = lane >> 5;
   const int jb0 = sg * p.seg_blocks;
   const int jb1 = min(p.NB, jb0 + p.seg_blocks);
-  const int pp = tid & 31, sq0 = tid >> 5;  // x staging: columns 2pp, 2pp+1; tokens 4sq..4sq+3
+  const int pq = lane & 7, sqb = lane >> 3;  // x staging: columns 32ph + 4pq..+3; tokens 4(sqb+8k)..+3
+  uint16_t *const myX = sXm[hw] + 32 * ph * kXStride;  // this wave's 32 rows of Xm^T
 
-  // Everything the workgroup needs for one block is held in registers while the previous block
-  // is being computed (global-load latency is hidden behind that block's MFMA work).
-  u32x4 r_c[4];          // C tile, 16-byte chunks
-  u32x4 r_bt[4] = {};    // B^T tile
-  uint32_t r_x[2][4];    // x: 2 tasks x 4 tokens x 2 columns
-  f32x4 r_f4[2];        // per-token input factors of the two tasks
-  f32x4 r_cs4 = {};     // threads 0..15: the block's prefix sums
-  u32x4 r_g[4];          // G rows in operand layout
+  // ---- data of a block in flight (registers) ----
+  u32x4 r_c[2], r_bt[2], r_g;  // shared tiles: this thread's 16-byte chunks
+  u32x2 r_x[2][4];             // own slice: 2 tasks x 4 tokens x 4 columns
+  f32x4 r_f[2];                // input factors of the 2 tasks' tokens
 
-  auto load_block = [&](int jb) {
+  auto load_tiles = [&](int jb) {
     const int tb = jb * kBlk;
+    const uint16_t *bp = p.Btr + (bg * p.NB + jb) * kN * kBlk;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) r_bt[k] = *reinterpret_cast<const u32x4 *>(bp + 8 * (tid + kScanThreads * k));
+    if constexpr (!kStatesOnly) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        // rows beyond the sequence are read from its last token (their outputs are never stored):
+        // no branch, so the loads of a block stay one uninterrupted burst
+        const int c = tid + kScanThreads * k, row = min(tb + (c >> 4), p.T - 1), ch = c & 15;
+        r_c[k] = *reinterpret_cast<const u32x4 *>(p.C + ((static_cast<size_t>(b) * p.T + row) * p.G + g) * kN +
+                                                  8 * ch);
+      }
+      r_g = *reinterpret_cast<const u32x4 *>(p.Gd + (bg * p.NB + jb) * kBlk * kBlk + 8 * tid);
+    }
     const float *rec = p.prep + (bh * p.NB + jb) * kRec;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
-      const int sq = sq0 + 8 * k;
-      r_f4[k] = *reinterpret_cast<const f32x4 *>(rec + kBlk + 4 * sq);
+      const int sq = sqb + 8 * k;
+      r_f[k] = *reinterpret_cast<const f32x4 *>(rec + kBlk + 4 * sq);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int t = tb + 4 * sq + i;
-        r_x[k][i] = 0;
-        if (t < p.T)
-          r_x[k][i] = *reinterpret_cast<const uint32_t *>(
-              p.x + ((static_cast<size_t>(b) * p.T + t) * p.H + h) * kP + 2 * pp);
+        // tokens beyond the sequence: the address is clamped and their factor f is 0 (dt = 0)
+        const int t = min(tb + 4 * sq + i, p.T - 1);
+        r_x[k][i] = *reinterpret_cast<const u32x2 *>(p.x + ((static_cast<size_t>(b) * p.T + t) * p.H + h) * kP +
+                                                     32 * ph + 4 * pq);
       }
-    }
-    if (tid < 16) r_cs4 = *reinterpret_cast<const f32x4 *>(rec + 4 * tid);
-    const uint16_t *bp = p.Btr + (bg * p.NB + jb) * kN * kBlk;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) r_bt[k] = *reinterpret_cast<const u32x4 *>(bp + 8 * (tid + kThreads * k));
-    if constexpr (!kStatesOnly) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int c = tid + kThreads * k, row = c >> 4, ch = c & 15;
-        r_c[k] = mk4(0, 0, 0, 0);
-        if (tb + row < p.T)
-          r_c[k] = *reinterpret_cast<const u32x4 *>(
-              p.C + ((static_cast<size_t>(b) * p.T + tb + row) * p.G + g) * kN + 8 * ch);
-      }
-      const uint16_t *gp = p.Gd + ((bg * p.NB + jb) * kBlk + 32 * wn + r) * kBlk + 8 * kg;
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (q <= 2 * wn + 1) r_g[q] = *reinterpret_cast<const u32x4 *>(gp + 16 * q);
     }
   };
 
-  auto store_block = [&]() {
-    if (tid < 16) *reinterpret_cast<f32x4 *>(&sCs[4 * tid]) = r_cs4;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int c = tid + kThreads * k, n = c >> 3, ch = c & 7;
-      *reinterpret_cast<u32x4 *>(sBt + n * kBtStride + 8 * ch) = r_bt[k];
-    }
+  auto store_tiles = [&](int buf) {
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
-      const int sq = sq0 + 8 * k;
-      const f32x4 f = r_f4[k];
-      const uint32_t v0 = r_x[k][0], v1 = r_x[k][1], v2 = r_x[k][2], v3 = r_x[k][3];
-      *reinterpret_cast<u32x2 *>(sXc + (2 * pp) * kXStride + 4 * sq) =
-          mk2(pack2(f.x * bf_lo(v0), f.y * bf_lo(v1)), pack2(f.z * bf_lo(v2), f.w * bf_lo(v3)));
-      *reinterpret_cast<u32x2 *>(sXc + (2 * pp + 1) * kXStride + 4 * sq) =
-          mk2(pack2(f.x * bf_hi(v0), f.y * bf_hi(v1)), pack2(f.z * bf_hi(v2), f.w * bf_hi(v3)));
+      const int c = tid + kScanThreads * k, n = c >> 3, ch = c & 7;
+      *reinterpret_cast<u32x4 *>(&sBt[buf][n * kBtStride + 8 * ch]) = r_bt[k];
     }
     if constexpr (!kStatesOnly) {
       // C columns are permuted inside each group of 16 so that one 16-byte read yields
       // n-offsets {4kg..4kg+3, 8+4kg..8+4kg+3}
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int c = tid + kThreads * k, row = c >> 4, ch = c & 15;
-        uint16_t *dst = sC + row * kCStride + 16 * (ch >> 1) + 4 * (ch & 1);
+      for (int k = 0; k < 2; ++k) {
+        const int c = tid + kScanThreads * k, row = c >> 4, ch = c & 15;
+        uint16_t *dst = &sC[buf][row * kCStride + 16 * (ch >> 1) + 4 * (ch & 1)];
         *reinterpret_cast<u32x2 *>(dst) = mk2(r_c[k].x, r_c[k].y);
         *reinterpret_cast<u32x2 *>(dst + 8) = mk2(r_c[k].z, r_c[k].w);
       }
+      *reinterpret_cast<u32x4 *>(&sG[buf][(tid >> 3) * kGStride + 8 * (tid & 7)]) = r_g;
+    }
+    // own slice: Xm^T[p][s] = f_s x[s][p], four tokens per 8-byte write
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      const int sq = sqb + 8 * k;
+      const f32x4 f = r_f[k];
+      uint16_t *dst = myX + (4 * pq) * kXStride + 4 * sq;
+      *reinterpret_cast<u32x2 *>(dst) =
+          mk2(pack2(f.x * bf_lo(r_x[k][0].x), f.y * bf_lo(r_x[k][1].x)),
+              pack2(f.z * bf_lo(r_x[k][2].x), f.w * bf_lo(r_x[k][3].x)));
+      *reinterpret_cast<u32x2 *>(dst + kXStride) =
+          mk2(pack2(f.x * bf_hi(r_x[k][0].x), f.y * bf_hi(r_x[k][1].x)),
+              pack2(f.z * bf_hi(r_x[k][2].x), f.w * bf_hi(r_x[k][3].x)));
+      *reinterpret_cast<u32x2 *>(dst + 2 * kXStride) =
+          mk2(pack2(f.x * bf_lo(r_x[k][0].y), f.y * bf_lo(r_x[k][1].y)),
+              pack2(f.z * bf_lo(r_x[k][2].y), f.w * bf_lo(r_x[k][3].y)));
+      *reinterpret_cast<u32x2 *>(dst + 3 * kXStride) =
+          mk2(pack2(f.x * bf_hi(r_x[k][0].y), f.y * bf_hi(r_x[k][1].y)),
+              pack2(f.z * bf_hi(r_x[k][2].y), f.w * bf_hi(r_x[k][3].y)));
     }
   };
 
-  // ---- state accumulators: Hacc[t][i] = H^T[n = 64wn + 32t + (i/4)*8 + 4kg + i%4][p = 32wp + r] ----
-  f32x16 Hacc[2];
-  if (!kStatesOnly && p.Hin != nullptr) {
-    const float *hp = p.Hin + bh * p.hin_bh_stride + static_cast<size_t>(sg) * kP * kN +
-                      static_cast<size_t>(32 * wp + r) * kN;
+  // Per-lane scalars of a block: cs at this lane's two output tokens (r, 32 + r), c31, c63.
+  struct BlockScalars {
+    float cs0, cs1, c31, c63;
+  };
+  auto load_scalars = [&](int jb) {
+    const float *rec = p.prep + (bh * p.NB + jb) * kRec;
+    BlockScalars v;
+    v.cs0 = rec[r];
+    v.cs1 = rec[32 + r];
+    v.c31 = rec[31];
+    v.c63 = rec[kBlk - 1];
+    return v;
+  };
+  // x in output layout for the skip term: token 32lt + r, columns 32ph + 8i4 + 4kg .. +3
+  u32x2 xepi[2][4];
+  auto load_xepi = [&](int jb) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int lt = 0; lt < 2; ++lt) {
+      const int t = min(jb * kBlk + 32 * lt + r, p.T - 1);
+      const uint16_t *xp = p.x + ((static_cast<size_t>(b) * p.T + t) * p.H + h) * kP + 32 * ph + 4 * kg;
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) xepi[lt][i4] = *reinterpret_cast<const u32x2 *>(xp + 8 * i4);
+    }
+  };
+
+  // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][p = 32ph + r] ----
+  f32x16 Hacc[4];
+  // scalars are fetched two blocks ahead: a load that is used right after it is issued would
+  // stall the wave for a full memory round trip (behind the output stores in front of it)
+  BlockScalars cur = {0.f, 0.f, 0.f, 0.f}, nxt = {0.f, 0.f, 0.f, 0.f};
+  if (jb0 < jb1) cur = load_scalars(jb0);
+  float Dh = kStatesOnly ? 0.f : p.D[h];
+  // Pin these values as "arrived" before the loop: otherwise the wait for them is placed at their
+  // first use inside the loop, where it also waits for every younger load of every iteration.
+  asm volatile("" : "+v"(Dh), "+v"(cur.cs0), "+v"(cur.cs1), "+v"(cur.c31), "+v"(cur.c63));
+  if (!kStatesOnly && p.Hin != nullptr) {
+    const float d0 = fast_exp2(cur.c31);
+    const float *hp = p.Hin + bh * p.hin_bh_stride + static_cast<size_t>(sg) * kP * kN +
+                      static_cast<size_t>(32 * ph + r) * kN;
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const f32x4 v = *reinterpret_cast<const f32x4 *>(hp + 64 * wn + 32 * t + i4 * 8 + 4 * kg);
-        Hacc[t][4 * i4 + 0] = v.x;
-        Hacc[t][4 * i4 + 1] = v.y;
-        Hacc[t][4 * i4 + 2] = v.z;
-        Hacc[t][4 * i4 + 3] = v.w;
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(hp + 32 * nt + 8 * i4 + 4 * kg);
+        Hacc[nt][4 * i4 + 0] = d0 * v.x;
+        Hacc[nt][4 * i4 + 1] = d0 * v.y;
+        Hacc[nt][4 * i4 + 2] = d0 * v.z;
+        Hacc[nt][4 * i4 + 3] = d0 * v.w;
       }
   } else {
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) Hacc[t][i] = 0.f;
+      for (int i = 0; i < 16; ++i) Hacc[nt][i] = 0.f;
   }
-
-  // bf16 copies of the state as MFMA operands: own[2t+u] covers n = 64wn + 32t + 16u + {4kg..4kg+3,
-  // 8+4kg..8+4kg+3}; the other n half comes from the partner wave through LDS.
-  Operand own[4], partner[4], Gop[4];
-  auto pack_state = [&]() {
+  // bf16 copy of a 16-column slice of Ht as an MFMA operand: slice 2nt+u covers n = 32nt + 16u +
+  // {4kg..4kg+3, 8+4kg..8+4kg+3} (the order in which sC stores each group of 16 columns).
+  // Converted right before use, so no second copy of the state is kept in registers.
+  auto state_operand = [&](int kk) {
+    Operand o;
+    const f32x16 &hv = Hacc[kk >> 1];
+    const int u = kk & 1;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-          own[2 * t + u].u[k] = pack2(Hacc[t][8 * u + 2 * k], Hacc[t][8 * u + 2 * k + 1]);
-  };
-  auto publish_state = [&]() {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) sExch[wave][k][lane] = own[k].q;
+    for (int k = 0; k < 4; ++k) o.u[k] = pack2(hv[8 * u + 2 * k], hv[8 * u + 2 * k + 1]);
+    return o;
   };
 
   float seg_total = 0.f;
-  if (jb0 < jb1) load_block(jb0);
-  if constexpr (!kStatesOnly) {
-    pack_state();
-    publish_state();
-  }
+  // The loop body below is free of branches around memory operations (indices are clamped to the
+  // segment instead, redundant work in the last two iterations is harmless): the hardware counts
+  // outstanding loads and stores in order, and only with straight-line code can the compiler wait
+  // for exactly the older ones and leave the newer ones in flight.
+  const int jlast = jb1 - 1;
   if (jb0 < jb1) {
-    store_block();
-    if constexpr (!kStatesOnly) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) Gop[q].q = r_g[q];
-    }
+    // ---- prologue: block jb0 into LDS buffer 0; block jb0+1 in flight ----
+    load_tiles(jb0);
+    store_tiles(0);
+    if constexpr (!kStatesOnly) load_xepi(jb0);
+    nxt = load_scalars(min(jb0 + 1, jlast));
+    load_tiles(min(jb0 + 1, jlast));
   }
   __syncthreads();
 
   for (int jb = jb0; jb < jb1; ++jb) {
+    const int buf = (jb - jb0) & 1;
     const int tb = jb * kBlk;
-    const bool more = jb + 1 < jb1;
-    // ---- issue the next block's global loads; they land while this block is computed ----
-    if (more) load_block(jb + 1);
-    const int l = 32 * wn + r;  // this lane's output token inside the block
-    const int t = tb + l;
-    u32x2 xepi[4];
-    size_t yrow = 0;
-    if constexpr (!kStatesOnly) {
-      // partner's state operands (published between the two barriers that end the previous block)
+    const bool more = jb < jlast;
+    if (kStatesOnly) seg_total += cur.c63;
+
+    Operand xo[4];  // Xm^T[p = 32ph + r][s = 16q + 8kg ..]
 #pragma unroll
-      for (int k = 0; k < 4; ++k) partner[k].q = sExch[wave ^ 2][k][lane];
-      yrow = ((static_cast<size_t>(b) * p.T + min(t, p.T - 1)) * p.H + h) * kP + 32 * wp + 4 * kg;
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) xepi[i4] = *reinterpret_cast<const u32x2 *>(p.x + yrow + 8 * i4);
-    }
-    const float c31 = sCs[31], c63 = sCs[kBlk - 1];
-    const float d0 = fast_exp2(c31);        // decay over tokens 0..31
-    const float d1 = fast_exp2(c63 - c31);  // decay over tokens 32..63
-    if (kStatesOnly) seg_total += c63;
-    const uint16_t *xrow = sXc + (32 * wp + r) * kXStride + 8 * kg;
-    Operand xo[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) xo[q].q = *reinterpret_cast<const u32x4 *>(xrow + 16 * q);
+    for (int q = 0; q < 4; ++q) xo[q].q = *reinterpret_cast<const u32x4 *>(myX + r * kXStride + 16 * q + 8 * kg);
 
     if constexpr (!kStatesOnly) {
-      // ---- state -> output: Y^T[p][l] = sum_n H[p][n] C[l][n] ----
-      f32x16 Y = {};
-      const uint16_t *crow = sC + l * kCStride + 8 * kg;
+      // ---- Y^T[p][l] = sum_n Ht[p][n] C[l][n]  +  sum_{s<=l} Xm[s][p] G[l][s] ----
+      f32x16 Y[2] = {};
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        Operand c;
-        c.q = *reinterpret_cast<const u32x4 *>(crow + 16 * (4 * wn + k));
-        Y = mfma(own[k], c, Y);
+      for (int kk = 0; kk < 8; ++kk) {
+        Operand c0, c1;
+        c0.q = *reinterpret_cast<const u32x4 *>(&sC[buf][r * kCStride + 16 * kk + 8 * kg]);
+        c1.q = *reinterpret_cast<const u32x4 *>(&sC[buf][(32 + r) * kCStride + 16 * kk + 8 * kg]);
+        const Operand ho = state_operand(kk);
+        Y[0] = mfma(ho, c0, Y[0]);
+        Y[1] = mfma(ho, c1, Y[1]);
       }
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        Operand c;
-        c.q = *reinterpret_cast<const u32x4 *>(crow + 16 * (4 * (wn ^ 1) + k));
-        Y = mfma(partner[k], c, Y);
-      }
-      // ---- intra-block: Y^T[p][l] += sum_{s<=l} Xc[s][p] G[l][s], half by half ----
-      Y = mfma(xo[0], Gop[0], Y);
-      Y = mfma(xo[1], Gop[1], Y);
-      float rowf = sCs[l];
-      if (wn == 1) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) Y[i] *= d0;
-        Y = mfma(xo[2], Gop[2], Y);
-        Y = mfma(xo[3], Gop[3], Y);
-        rowf -= c31;
-      }
-      rowf = fast_exp2(rowf);
-      // ---- epilogue: y[l][p] = rowf * Y + D x, four consecutive p per 8-byte store ----
-      if (t < p.T) {
-        const float Dh = p.D[h];
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const u32x2 xv = xepi[i4];
-          u32x2 o;
-          o.x = pack2(rowf * Y[4 * i4 + 0] + Dh * bf_lo(xv.x), rowf * Y[4 * i4 + 1] + Dh * bf_hi(xv.x));
-          o.y = pack2(rowf * Y[4 * i4 + 2] + Dh * bf_lo(xv.y), rowf * Y[4 * i4 + 3] + Dh * bf_hi(xv.y));
-          *reinterpret_cast<u32x2 *>(p.y + yrow + 8 * i4) = o;
-        }
-      }
-    }
-
-    // ---- state update: H^T = d1 (d0 (H^T + Bt Xc[0:32]) + Bt Xc[32:64]) ----
-    {
-      const uint16_t *btrow = sBt + (64 * wn + r) * kBtStride + 8 * kg;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        if (q == 2) {
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) Hacc[tt][i] *= d0;
+        Operand g0, g1;
+        g1.q = *reinterpret_cast<const u32x4 *>(&sG[buf][(32 + r) * kGStride + 16 * q + 8 * kg]);
+        if (q < 2) {
+          g0.q = *reinterpret_cast<const u32x4 *>(&sG[buf][r * kGStride + 16 * q + 8 * kg]);
+          Y[0] = mfma(xo[q], g0, Y[0]);
         }
-        Operand b0, b1;
-        b0.q = *reinterpret_cast<const u32x4 *>(btrow + 16 * q);
-        b1.q = *reinterpret_cast<const u32x4 *>(btrow + 32 * kBtStride + 16 * q);
-        Hacc[0] = mfma(b0, xo[q], Hacc[0]);
-        Hacc[1] = mfma(b1, xo[q], Hacc[1]);
+        Y[1] = mfma(xo[q], g1, Y[1]);
       }
+      // ---- epilogue: y[l][p] = exp2(cs_l - c31) Y + D x, four consecutive p per 8-byte store ----
+      const float rowf[2] = {fast_exp2(fminf(fmaxf(cur.cs0 - cur.c31, -kMaxExp), kMaxExp)),
+                             fast_exp2(fminf(fmaxf(cur.cs1 - cur.c31, -kMaxExp), kMaxExp))};
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
+      for (int lt = 0; lt < 2; ++lt) {
+        const int t = tb + 32 * lt + r;
+        // lanes of padded tokens store to a scratch row instead of branching around the store
+        uint16_t *yp = (t < p.T)
+                           ? p.y + ((static_cast<size_t>(b) * p.T + t) * p.H + h) * kP + 32 * ph + 4 * kg
+                           : p.y_dump + 4 * kg;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) Hacc[tt][i] *= d1;
-    }
-    if (!kStatesOnly) pack_state();
-    __syncthreads();  // ---- everyone is done reading this block's tiles and the published state ----
-    if (!kStatesOnly) publish_state();
-    if (more) {
-      store_block();
-      if constexpr (!kStatesOnly) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) Gop[q].q = r_g[q];
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const u32x2 xv = xepi[lt][i4];
+          const f32x16 &Yt = Y[lt];
+          const u32x2 o = mk2(pack2(rowf[lt] * Yt[4 * i4 + 0] + Dh * bf_lo(xv.x),
+                                    rowf[lt] * Yt[4 * i4 + 1] + Dh * bf_hi(xv.x)),
+                              pack2(rowf[lt] * Yt[4 * i4 + 2] + Dh * bf_lo(xv.y),
+                                    rowf[lt] * Yt[4 * i4 + 3] + Dh * bf_hi(xv.y)));
+          *reinterpret_cast<u32x2 *>(yp + 8 * i4) = o;
+        }
       }
     }
-    __syncthreads();  // ---- next block's tiles and the published state are visible ----
+
+    // ---- H'^T[n][p] = Ht^T[n][p] + sum_s B^T[n][s] Xm[s][p] ----
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        Operand bt;
+        bt.q = *reinterpret_cast<const u32x4 *>(&sBt[buf][(32 * nt + r) * kBtStride + 16 * q + 8 * kg]);
+        Hacc[nt] = mfma(bt, xo[q], Hacc[nt]);
+      }
+    }
+
+    // ---- next block: its tiles go to the other LDS buffer, its scalars become current, the
+    //      state moves to the next block's frame, and block jb+2 is requested ----
+    const float d1 = fast_exp2(cur.c63 - cur.c31);
+    store_tiles(buf ^ 1);
+    cur = nxt;
+    // after the last block the accumulators must hold the true state: no next-frame factor
+    const float scale = more ? d1 * fast_exp2(cur.c31) : d1;
+    const int j1 = min(jb + 1, jlast), j2 = min(jb + 2, jlast);
+    if constexpr (!kStatesOnly) load_xepi(j1);
+    nxt = load_scalars(j2);
+    load_tiles(j2);
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) Hacc[nt][i] *= scale;
+    __syncthreads();  // block jb's tiles may be overwritten; block jb+1's tiles are visible
   }
 
   // ---- write the state out (canonical (p, n) layout, four consecutive n per 16-byte store) ----
   float *out = nullptr;
   if (kStatesOnly) {
     out = p.seg_state + (bh * p.S + sg + 1) * kP * kN;
-    if (tid == 0) p.seg_decay[bh * p.S + sg] = seg_total;
+    if (lane == 0 && ph == 0) p.seg_decay[bh * p.S + sg] = seg_total;
   } else if (sg == p.S - 1) {
     out = p.final_state + bh * kP * kN;
   }
   if (out != nullptr) {
-    float *op = out + static_cast<size_t>(32 * wp + r) * kN;
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
+    for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4)
-        *reinterpret_cast<f32x4 *>(op + 64 * wn + 32 * tt + i4 * 8 + 4 * kg) =
-            f32x4{Hacc[tt][4 * i4 + 0], Hacc[tt][4 * i4 + 1], Hacc[tt][4 * i4 + 2], Hacc[tt][4 * i4 + 3]};
+        *reinterpret_cast<f32x4 *>(out + static_cast<size_t>(32 * ph + r) * kN + 32 * nt + 8 * i4 + 4 * kg) =
+            f32x4{Hacc[nt][4 * i4 + 0], Hacc[nt][4 * i4 + 1], Hacc[nt][4 * i4 + 2], Hacc[nt][4 * i4 + 3]};
   }
 }
 
@@ -496,19 +519,28 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
   }
 }
 
-// Blocks per segment: a whole number of chunks, as few segments as keep >= ~4 workgroups per CU.
+// Blocks per segment: a whole number of chunks.  One workgroup per CU is resident, so the cost of
+// a choice is (rounds of workgroups) x (blocks a workgroup walks, plus a fixed prologue), with the
+// extra states pass priced in when there is more than one segment.
+constexpr int kNumCUs = 256;
 int choose_seg_blocks(const Dims &d) {
   const int chunk_blocks = d.L / kBlk;
   const int nchunks = d.Nc;
   int k = 0;
   if (const char *e = std::getenv("SSD_SEG_CHUNKS")) k = std::atoi(e);
   if (k < 1) {
-    const long target = 1024;
-    const long bh = static_cast<long>(d.Bt) * d.H;
-    long want_segs = (target + bh - 1) / bh;       // segments needed to reach the target
-    if (want_segs < 1) want_segs = 1;
-    if (want_segs > nchunks) want_segs = nchunks;
-    k = static_cast<int>((nchunks + want_segs - 1) / want_segs);  // chunks per segment
+    const long groups = static_cast<long>(d.Bt) * (d.H / kHeadsPerWg);
+    double best = 0.0;
+    for (int cand = 1; cand <= nchunks; ++cand) {
+      const long segs = (nchunks + cand - 1) / cand;
+      if (cand > 1 && (nchunks + cand - 2) / (cand - 1) == segs) continue;  // same count, longer segments
+      const long rounds = (groups * segs + kNumCUs - 1) / kNumCUs;
+      const double cost = static_cast<double>(rounds) * (cand * chunk_blocks + 2) * (segs > 1 ? 1.35 : 1.0);
+      if (k == 0 || cost < best) {
+        best = cost;
+        k = cand;
+      }
+    }
   }
   if (k > nchunks) k = nchunks;
   if (k < 1) k = 1;
@@ -517,7 +549,7 @@ int choose_seg_blocks(const Dims &d) {
 
 struct Layout {
   int NB, S_max;
-  size_t off_G, off_Bt, off_prep, off_state, off_decay, total;
+  size_t off_G, off_Bt, off_prep, off_state, off_decay, off_dump, total;
 };
 
 Layout make_layout(const Dims &d) {
@@ -536,6 +568,8 @@ Layout make_layout(const Dims &d) {
   off += round_up(BH * w.S_max * kP * kN * sizeof(float), 256);
   w.off_decay = off;
   off += round_up(BH * w.S_max * sizeof(float), 256);
+  w.off_dump = off;
+  off += 256;
   w.total = off;
   return w;
 }
@@ -543,7 +577,8 @@ Layout make_layout(const Dims &d) {
 }  // namespace
 
 bool mfma_supported(const Dims &d) {
-  return d.bf16 && d.P == kP && d.N == kN && d.L % kBlk == 0 && d.Bt <= 65535 && d.H <= 65535;
+  return d.bf16 && d.P == kP && d.N == kN && d.L % kBlk == 0 && d.hpg % kHeadsPerWg == 0 && d.Bt <= 65535 &&
+         d.H <= 65535;
 }
 
 size_t mfma_workspace_bytes(const Dims &d) { return make_layout(d).total; }
@@ -577,6 +612,7 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
   p.Btr = Btr;
   p.prep = prep;
   p.y = static_cast<uint16_t *>(y);
+  p.y_dump = reinterpret_cast<uint16_t *>(ws + w.off_dump);
   p.final_state = final_state;
   p.seg_state = seg_state;
   p.seg_decay = seg_decay;
@@ -590,7 +626,7 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
   if (S > 1) {
     p.Hin = nullptr;
     p.hin_bh_stride = 0;
-    hipLaunchKernelGGL((chunk_scan_kernel<true>), dim3(d.H, S - 1, d.Bt), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL((chunk_scan_kernel<true>), dim3(d.H / kHeadsPerWg, S - 1, d.Bt), dim3(kScanThreads), 0, stream, p);
     trace_mark(trace, stream, "segment_states");
     hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / kThreads, d.Bt * d.H), dim3(kThreads), 0, stream,
                        seg_state, seg_decay, h0, S);
@@ -601,7 +637,7 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
     p.Hin = h0;
     p.hin_bh_stride = static_cast<size_t>(kP) * kN;
   }
-  hipLaunchKernelGGL((chunk_scan_kernel<false>), dim3(d.H, S, d.Bt), dim3(kThreads), 0, stream, p);
+  hipLaunchKernelGGL((chunk_scan_kernel<false>), dim3(d.H / kHeadsPerWg, S, d.Bt), dim3(kScanThreads), 0, stream, p);
   trace_mark(trace, stream, "chunk_scan");
   return hipGetLastError();
 }

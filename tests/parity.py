@@ -5,6 +5,11 @@ accumulation.  "Relative" is made precise in two ways, and both are gated:
   (i)  scale-normalised: max|g - o| / max|o| <= tol
   (ii) element-wise, allclose-style (the form of the paper's own parity table):
        |g - o| <= tol*|o| + tol*rms(o) for every element.
+Where the output is ill-conditioned with respect to rms(o) -- a large random initial state makes
+y a sum of big terms that cancel -- (ii) is replaced by the componentwise bound of rounding-error
+analysis, |g - o| <= tol * mag, with mag = the same recurrence evaluated by the oracle on the
+absolute values of x, B, C, D and h0 (every decay factor is positive, so mag is exactly the sum
+of the absolute values of the terms that make up each output).
 """
 import numpy as np
 import torch
@@ -33,9 +38,16 @@ def errors(got, ref):
     return dict(norm=norm, worst_allclose=worst, max_ref=mx)
 
 
-def assert_close(got, ref, tol, what=""):
+def assert_close(got, ref, tol, what="", mag=None):
     e = errors(got, ref)
-    assert e["norm"] <= tol and e["worst_allclose"] <= tol, \
-        "%s: normalised max err %.3e, worst allclose ratio %.3e, tol %.1e" % (what, e["norm"],
-                                                                             e["worst_allclose"], tol)
+    assert e["norm"] <= tol, "%s: normalised max err %.3e, tol %.1e" % (what, e["norm"], tol)
+    if mag is None:
+        assert e["worst_allclose"] <= tol, \
+            "%s: worst allclose ratio %.3e (normalised max err %.3e), tol %.1e" % (what, e["worst_allclose"],
+                                                                                  e["norm"], tol)
+    else:
+        g, o, m = to_np64(got), to_np64(ref), to_np64(mag)
+        worst = float((np.abs(g - o) / np.where(m > 0, m, 1.0)).max())
+        e["worst_componentwise"] = worst
+        assert np.all(np.abs(g - o) <= tol * m), "%s: worst |err|/mag %.3e, tol %.1e" % (what, worst, tol)
     return e

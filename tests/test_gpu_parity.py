@@ -215,14 +215,14 @@ def test_many_decode_steps_track_the_oracle(ssd):
 # ---- MFMA path (headdim 64, dstate 128, bf16) --------------------------------------------------
 MFMA_CASES = [
     # Bt, T, H, P, N, G, L, forced chunks per segment (0 = library's choice)
-    (1, 64, 2, 64, 128, 1, 64, 0),       # exactly one block
-    (1, 1, 1, 64, 128, 1, 64, 0),        # single token
+    (1, 64, 4, 64, 128, 1, 64, 0),       # exactly one block
+    (1, 1, 4, 64, 128, 1, 64, 0),        # single token
     (2, 300, 4, 64, 128, 1, 256, 0),     # ragged tail inside the second chunk
-    (1, 1000, 3, 64, 128, 1, 128, 1),    # one chunk per segment: 8 segments, ragged last block
-    (1, 1000, 3, 64, 128, 1, 128, 3),    # 3 chunks per segment
+    (1, 1000, 4, 64, 128, 1, 128, 1),    # one chunk per segment: 8 segments, ragged last block
+    (1, 1000, 12, 64, 128, 1, 128, 3),   # 3 chunks per segment
     (2, 513, 8, 64, 128, 2, 64, 2),      # two groups, T = 8 blocks + 1 token
     (1, 2048, 24, 64, 128, 1, 256, 0),   # configs[1]
-    (1, 777, 2, 64, 128, 1, 1024, 0),    # chunk longer than the sequence
+    (1, 777, 4, 64, 128, 1, 1024, 0),    # chunk longer than the sequence
 ]
 
 
@@ -237,16 +237,28 @@ def test_mfma_prefill_matches_oracle(ssd, case, monkeypatch):
         monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
     else:
         monkeypatch.delenv("SSD_SEG_CHUNKS", raising=False)
-    h0 = inputs.make_state(cfg, seed=4) if cfg.seqlen in (300, 1000) else None
+    # T = 300: an initial state of realistic size (what a prefill of similar inputs leaves behind);
+    # T = 1000: a large N(0,1) one, far bigger than anything the inputs build up, whose outputs are
+    # sums of large cancelling terms -> judged by the componentwise bound (see parity.py)
+    h0, mag_y, mag_st = None, None, None
+    if cfg.seqlen == 300:
+        warm = inputs.make_prefill_inputs(cfg, seed=77)
+        h0 = torch.from_numpy(oracle_prefill(warm)[1]).float()
+    inp, y, st = None, None, None
+    if cfg.seqlen == 1000:
+        h0 = inputs.make_state(cfg, seed=4)
     inp, y, st = run_prefill(ssd, cfg, seed=23, h0=h0)
     y_ref, st_ref = oracle_prefill(inp, h0=h0)
-    e = assert_close(y, y_ref, 2e-2, "mfma y")
-    assert_close(st, st_ref, 2e-2, "mfma final state")
+    if cfg.seqlen == 1000:
+        ab = {k: (v.abs() if k in ("x", "B", "C", "D") else v) for k, v in inp.items()}
+        mag_y, mag_st = oracle_prefill(ab, h0=h0.abs())
+    e = assert_close(y, y_ref, 2e-2, "mfma y", mag=mag_y)
+    assert_close(st, st_ref, 2e-2, "mfma final state", mag=mag_st)
     print("errors", e, flush=True)
 
 
 def test_mfma_and_generic_paths_agree(ssd, monkeypatch):
-    cfg = cfg_of(2, 700, 4, 64, 128, 2, 128, "bf16")
+    cfg = cfg_of(2, 700, 8, 64, 128, 2, 128, "bf16")
     inp, y, st = run_prefill(ssd, cfg, seed=29)
     monkeypatch.setenv("SSD_FORCE_GENERIC", "1")
     _, yg, stg = run_prefill(ssd, cfg, seed=29)
@@ -256,10 +268,10 @@ def test_mfma_and_generic_paths_agree(ssd, monkeypatch):
 
 
 def test_mfma_extreme_decay_and_determinism(ssd):
-    cfg = cfg_of(1, 640, 2, 64, 128, 1, 256, "bf16")
+    cfg = cfg_of(1, 640, 4, 64, 128, 1, 256, "bf16")
     inp = inputs.make_prefill_inputs(cfg, seed=31)
     inp["dt"] = torch.full_like(inp["dt"], 0.1)
-    inp["A"] = torch.tensor([-16.0, -1e-3])
+    inp["A"] = torch.tensor([-16.0, -1e-3, -4.0, -16.0])
     dev = {k: v.cuda() for k, v in inp.items()}
     y, st = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
     y2, st2 = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
