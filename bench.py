@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-configs", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also launch one plain device copy of this many MiB (counter calibration for "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -165,6 +168,15 @@ def main():
                     frac_of_attainable=tot_c / ms / 1e9 / attainable,
                     hbm_gbs_compulsory=prefill_bytes(cfg) / ms / 1e6,
                     kernels_ms={k: round(v, 5) for k, v in kern.items()})
+
+    if args.calibrate_copy_mib > 0:
+        # a copy of known size: its FETCH_SIZE / WRITE_SIZE readings give the counters' scale
+        src = torch.empty((args.calibrate_copy_mib << 20,), dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     # ---- headline: the timed step --------------------------------------------------------
     cfg = inputs.CONFIGS[args.workload]

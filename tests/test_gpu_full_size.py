@@ -1,0 +1,109 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration ``bench.py`` times.
+
+The oracle cannot evaluate every (batch row, head) sequence of these shapes in seconds, but
+sequences are independent (one scalar A and one state per head), so it evaluates a seeded
+sample of them completely -- every token, every channel, the final state -- and those are
+compared element by element.  Properties that hold at any size cover the rest: every output
+is finite, and a second run is bitwise identical.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ssd_oracle
+from paper_2603_09555_amd import inputs
+from parity import assert_close, to_np64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ssd():
+    from paper_2603_09555_amd import ssd as binding
+    return binding
+
+
+def sample_pairs(cfg, n, seed):
+    """n distinct (b, h) pairs: the first and the last sequence plus seeded random ones."""
+    rng = np.random.default_rng(seed)
+    total = cfg.batch * cfg.nheads
+    picks = {0, total - 1}
+    while len(picks) < min(n, total):
+        picks.add(int(rng.integers(total)))
+    return [(i // cfg.nheads, i % cfg.nheads) for i in sorted(picks)]
+
+
+@pytest.mark.parametrize("name,npairs", [("c1_130m", 24), ("c2_780m_b8", 8), ("c3_2p7b_long", 6)])
+def test_full_size_prefill_sampled_sequences(ssd, name, npairs):
+    cfg = inputs.CONFIGS[name]
+    print("full-size prefill", cfg, flush=True)
+    inp = inputs.make_prefill_inputs(cfg, seed=0)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    sh = ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk,
+                        cfg.torch_io_dtype)
+    assert ssd.prefill_path(sh) == "mfma_bf16"
+    y, st = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
+    y2, st2 = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y.float()).all() and torch.isfinite(st).all()
+    assert torch.equal(y, y2) and torch.equal(st, st2)
+    pairs = sample_pairs(cfg, npairs, seed=41)
+    y_ref, st_ref = ssd_oracle.prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], pairs=pairs)
+    bs = torch.tensor([b for b, _ in pairs], device="cuda")
+    hs = torch.tensor([h for _, h in pairs], device="cuda")
+    y_got = y[bs, :, hs, :]      # (n, T, P)
+    st_got = st[bs, hs]          # (n, P, N)
+    e = assert_close(y_got, y_ref, 2e-2, "%s y on sampled sequences" % name)
+    assert_close(st_got, st_ref, 2e-2, "%s final state on sampled sequences" % name)
+    print("errors", e, flush=True)
+
+
+@pytest.mark.parametrize("name", ["c4_decode_b1", "c4_decode_b16"])
+def test_full_size_stacked_decode_sampled_sequences(ssd, name):
+    """All 64 layers in one launch per step, states seeded by a 2048-token prefill per layer; the
+    oracle runs the token recurrence over prompt + generated steps for sampled (layer, row, head)."""
+    cfg = inputs.CONFIGS[name]
+    Ly, nsteps = cfg.nlayers, 24
+    print("full-size decode", cfg, "steps", nsteps, flush=True)
+    dev = "cuda"
+    rng = np.random.default_rng(43)
+    layers = sorted({0, Ly - 1, int(rng.integers(Ly))})
+    state = torch.empty((Ly, cfg.batch, cfg.nheads, cfg.headdim, cfg.dstate), dtype=torch.float32, device=dev)
+    A = torch.empty((Ly, cfg.nheads), dtype=torch.float32, device=dev)
+    D = torch.empty_like(A)
+    kept = {}
+    ytmp = None
+    for l in range(Ly):
+        inp = inputs.make_prefill_inputs(cfg, seed=0, layer=l, device=dev)
+        if ytmp is None:
+            ytmp = torch.empty_like(inp["x"])
+        ssd.ssd_prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], cfg.chunk, y=ytmp,
+                        final_state=state[l])
+        A[l], D[l] = inp["A"], inp["D"]
+        if l in layers:
+            kept[l] = {k: v.cpu() for k, v in inp.items()}
+    del ytmp, inp
+    steps = [inputs.make_decode_inputs(cfg, nsteps, seed=0, layer=l, device=dev) for l in range(Ly)]
+    xs = torch.stack([s["x"] for s in steps], dim=1)      # (steps, Ly, Bt, H, P)
+    dts = torch.stack([s["dt"] for s in steps], dim=1)
+    Bs = torch.stack([s["B"] for s in steps], dim=1)
+    Cs = torch.stack([s["C"] for s in steps], dim=1)
+    del steps
+    ys = torch.empty((nsteps, Ly, cfg.batch, cfg.nheads, cfg.headdim), dtype=xs.dtype, device=dev)
+    for i in range(nsteps):
+        ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=ys[i])
+    torch.cuda.synchronize()
+    assert torch.isfinite(ys.float()).all() and torch.isfinite(state).all()
+    for l in layers:
+        pairs = sample_pairs(cfg, 4, seed=47 + l)
+        p = kept[l]
+        full = {"x": torch.cat([p["x"], xs[:, l].transpose(0, 1).cpu()], dim=1),
+                "dt": torch.cat([p["dt"], dts[:, l].transpose(0, 1).cpu()], dim=1),
+                "B": torch.cat([p["B"], Bs[:, l].transpose(0, 1).cpu()], dim=1),
+                "C": torch.cat([p["C"], Cs[:, l].transpose(0, 1).cpu()], dim=1)}
+        y_ref, st_ref = ssd_oracle.prefill(full["x"], full["dt"], p["A"], full["B"], full["C"], p["D"], pairs=pairs)
+        bs = torch.tensor([b for b, _ in pairs], device=dev)
+        hs = torch.tensor([h for _, h in pairs], device=dev)
+        y_got = ys[:, l][:, bs, hs, :].transpose(0, 1)    # (n, steps, P)
+        assert_close(y_got, y_ref[:, cfg.seqlen:], 2e-2, "%s layer %d decode y" % (name, l))
+        assert_close(state[l][bs, hs], st_ref, 2e-2, "%s layer %d state after %d steps" % (name, l, nsteps))
