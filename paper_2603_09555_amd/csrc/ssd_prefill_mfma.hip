@@ -156,12 +156,17 @@ __global__ __launch_bounds__(kThreads) void scores_bt_kernel(const uint16_t *__r
 }
 
 // ---- block_cumsum: per (batch, head, block) decay bookkeeping ----------------------------------
-// grid (NB, ceil(H/16), Bt).  For every head writes one 128-float record per block:
-//   [0,64)    cs_s  block-relative inclusive prefix sum of dt*A*log2(e)   (the "segsum" input)
-//   [64,128)  f_s = dt_s * exp2(clamp(cs_31 - cs_s, -100, 100))
+// grid (NB, ceil(H/16), Bt).  With cs_s the block-relative inclusive prefix sum of dt*A*log2(e) (the
+// "segsum" input) and c31, c63 its values at tokens 31 and 63, every head gets one record of kRec
+// floats per block:
+//   [0,64)     rowf_l = exp2(clamp(cs_l - c31))            output-row factor of the decay mask
+//   [64,128)   f_s    = dt_s * exp2(clamp(c31 - cs_s))     input factor of the decay mask
+//   [128]      exp2(c63 - c31)     state: middle of the block -> end of the block
+//   [129]      exp2(c31)           state: start of the block -> middle of the block
+//   [130]      c63                 log2 of the block's total decay
 // Tokens beyond the sequence get dt = 0 (state-neutral padding).  dt is read in its
 // (batch, token, head) layout and transposed through LDS.
-constexpr int kRec = 2 * kBlk;
+constexpr int kRec = 2 * kBlk + 4;
 constexpr int kCumHeads = 16;
 constexpr float kMaxExp = 100.f;
 __global__ __launch_bounds__(kThreads) void block_cumsum_kernel(const float *__restrict__ dt,
@@ -189,22 +194,24 @@ __global__ __launch_bounds__(kThreads) void block_cumsum_kernel(const float *__r
       if (lane >= off) v += up;
     }
     const float c31 = __shfl(v, 31, 64);
+    const float c63 = __shfl(v, 63, 64);
     float *rec = prep + ((static_cast<size_t>(b) * H + h) * NB + jb) * kRec;
-    rec[lane] = v;
+    rec[lane] = fast_exp2(fminf(fmaxf(v - c31, -kMaxExp), kMaxExp));
     rec[kBlk + lane] = dtv * fast_exp2(fminf(fmaxf(c31 - v, -kMaxExp), kMaxExp));
+    if (lane < 4)
+      rec[2 * kBlk + lane] = lane == 0 ? fast_exp2(c63 - c31) : lane == 1 ? fast_exp2(c31) : lane == 2 ? c63 : 0.f;
   }
 }
 
 // ---- chunk_scan / segment_states ----------------------------------------------------------------
 struct ScanParams {
-  const uint16_t *x;
-  const uint16_t *C;
+  const uint8_t *x;
+  const uint8_t *C;
   const float *D;
-  const uint16_t *Gd;
-  const uint16_t *Btr;
+  const uint8_t *Gd;
+  const uint8_t *Btr;
   const float *prep;
-  uint16_t *y;
-  uint16_t *y_dump;        // 128 bytes of scratch: where the lanes of padded tokens store
+  uint8_t *y;
   const float *Hin;        // state entering each segment, or nullptr = zeros
   size_t hin_bh_stride;    // elements between consecutive (b, h) in Hin
   float *final_state;      // (Bt, H, P, N): written by the last segment
@@ -217,6 +224,26 @@ constexpr int kHeadsPerWg = 4;
 constexpr int kScanThreads = 2 * 64 * kHeadsPerWg;  // two waves per head, one per half of headdim
 constexpr int kGStride = kBlk + 8;
 
+// Buffer addressing: a 128-bit descriptor (base, size) in scalar registers plus a 32-bit byte offset
+// per lane.  The hardware checks the per-lane offset against the size: loads beyond it return zero
+// and stores beyond it are dropped, which is how the ragged last block is handled (a descriptor
+// that ends at the last token of the batch row) without clamps or branches.
+using Rsrc = __amdgpu_buffer_rsrc_t;
+__device__ __forceinline__ Rsrc make_rsrc(const void *base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(Rsrc r, uint32_t voff, uint32_t soff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+}
+__device__ __forceinline__ void buf_store16(Rsrc r, uint32_t voff, u32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, 0);
+}
+
+// The MFMA writes row m of a 32-row result to lane group kg = (m >> 2) & 1, element 4 (m >> 3) + (m & 3).
+// Giving MFMA row m the headdim column pi(m) = 16 kg + element makes every lane own 16 consecutive
+// columns of its token: 32 contiguous bytes of y per lane instead of four 8-byte pieces.
+__device__ __forceinline__ int pi_of_row(int m) { return 16 * ((m >> 2) & 1) + 4 * (m >> 3) + (m & 3); }
+
 // One wave per (head, half of headdim): the wave owns a 128 x 32 slice of the state (64
 // accumulator registers), a 64 x 32 output tile (32) and its input operands (16); with the next
 // block's data in flight it stays under 256 registers, so the eight waves of a workgroup run two
@@ -227,10 +254,11 @@ void chunk_scan_kernel(const ScanParams p) {
   __shared__ __align__(16) uint16_t sC[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kBlk * kCStride];
   __shared__ __align__(16) uint16_t sBt[2][kN * kBtStride];                   // B^T [n][s]
   __shared__ __align__(16) uint16_t sG[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kBlk * kGStride];
-  __shared__ __align__(16) uint16_t sXm[kHeadsPerWg][kP * kXStride];          // Xm^T [p][s], per head
+  __shared__ __align__(16) uint16_t sXm[kHeadsPerWg][kP * kXStride];          // Xm^T [row][s], per head
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: addresses derived from it stay scalar
   const int hw = wave >> 1, ph = wave & 1;  // head inside the workgroup, half of headdim
   const int h = blockIdx.x * kHeadsPerWg + hw, sg = blockIdx.y, b = blockIdx.z;
   const int g = (blockIdx.x * kHeadsPerWg) / p.hpg;  // the four heads share one group
@@ -239,123 +267,137 @@ void chunk_scan_kernel(const ScanParams p) {
   const int r = lane & 31, kg = lane >> 5;
   const int jb0 = sg * p.seg_blocks;
   const int jb1 = min(p.NB, jb0 + p.seg_blocks);
-  const int pq = lane & 7, sqb = lane >> 3;  // x staging: columns 32ph + 4pq..+3; tokens 4(sqb+8k)..+3
+  const int cg = lane & 3, tg = lane >> 2;  // x staging: columns 8cg..8cg+7 of the half, tokens 4tg..4tg+3
   uint16_t *const myX = sXm[hw] + 32 * ph * kXStride;  // this wave's 32 rows of Xm^T
 
+  // ---- addressing: scalar bases, per-lane byte offsets that never change ----
+  const uint32_t xrow = static_cast<uint32_t>(p.H) * (kP * 2);   // bytes per token of x / y
+  const uint32_t crow = static_cast<uint32_t>(p.G) * (kN * 2);   // bytes per token of C
+  const uint32_t xbytes = static_cast<uint32_t>(p.T) * xrow;     // one batch row of x / y
+  const uint32_t cbytes = static_cast<uint32_t>(p.T) * crow - static_cast<uint32_t>(g) * (kN * 2);
+  const uint8_t *const xb = p.x + static_cast<size_t>(b) * xbytes;
+  uint8_t *const yb = p.y + static_cast<size_t>(b) * xbytes;
+  const uint8_t *const cb = p.C + (static_cast<size_t>(b) * p.T * p.G + g) * (kN * 2);
+  const Rsrc rs_bt = make_rsrc(p.Btr + bg * p.NB * (kN * kBlk * 2), static_cast<uint32_t>(p.NB) * (kN * kBlk * 2));
+  const Rsrc rs_g = make_rsrc(p.Gd + bg * p.NB * (kBlk * kBlk * 2), static_cast<uint32_t>(p.NB) * (kBlk * kBlk * 2));
+  const float *const prep_bh = p.prep + bh * p.NB * kRec;
+  const Rsrc rs_prep = make_rsrc(prep_bh, static_cast<uint32_t>(p.NB) * (kRec * 4));
+  // descriptors of x, y and C start at the block and end at the batch row's last token
+  auto x_rsrc = [&](int jb) { return make_rsrc(xb + static_cast<size_t>(jb) * kBlk * xrow, xbytes - static_cast<uint32_t>(jb) * kBlk * xrow); };
+  auto y_rsrc = [&](int jb) { return make_rsrc(yb + static_cast<size_t>(jb) * kBlk * xrow, xbytes - static_cast<uint32_t>(jb) * kBlk * xrow); };
+  auto c_rsrc = [&](int jb) { return make_rsrc(cb + static_cast<size_t>(jb) * kBlk * crow, cbytes - static_cast<uint32_t>(jb) * kBlk * crow); };
+  const uint32_t vt = static_cast<uint32_t>(tid) * 16;  // shared tiles: 16 bytes per thread, tid-major
+  const uint32_t xcol = static_cast<uint32_t>(h) * (kP * 2) + 64 * ph;
+  uint32_t vx[4], vc[2], ve[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) vx[i] = static_cast<uint32_t>(4 * tg + i) * xrow + xcol + 16 * cg;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int c = tid + kScanThreads * k;
+    vc[k] = static_cast<uint32_t>(c >> 4) * crow + 16 * (c & 15);
+    ve[k] = static_cast<uint32_t>(r + 32 * k) * xrow + xcol + 32 * kg;  // output layout: token r + 32k, 32 bytes
+  }
+  const uint32_t vf = static_cast<uint32_t>(kBlk + 4 * tg) * 4;  // input factors of this thread's four tokens
+
   // ---- data of a block in flight (registers) ----
-  u32x4 r_c[2], r_bt[2], r_g;  // shared tiles: this thread's 16-byte chunks
-  u32x2 r_x[2][4];             // own slice: 2 tasks x 4 tokens x 4 columns
-  f32x4 r_f[2];                // input factors of the 2 tasks' tokens
+  u32x4 r_c[2], r_bt[2], r_g;  // shared tiles: this thread's 16-byte pieces
+  u32x4 r_x[4];                // own slice: 4 tokens x 8 columns
+  u32x4 r_f;                   // input factors of the 4 tokens (fp32 bits)
 
   auto load_tiles = [&](int jb) {
-    const int tb = jb * kBlk;
-    const uint16_t *bp = p.Btr + (bg * p.NB + jb) * kN * kBlk;
 #pragma unroll
-    for (int k = 0; k < 2; ++k) r_bt[k] = *reinterpret_cast<const u32x4 *>(bp + 8 * (tid + kScanThreads * k));
+    for (int k = 0; k < 2; ++k) r_bt[k] = buf_load16(rs_bt, vt, jb * (kN * kBlk * 2) + k * (kScanThreads * 16));
     if constexpr (!kStatesOnly) {
+      const Rsrc rc = c_rsrc(jb);
 #pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        // rows beyond the sequence are read from its last token (their outputs are never stored):
-        // no branch, so the loads of a block stay one uninterrupted burst
-        const int c = tid + kScanThreads * k, row = min(tb + (c >> 4), p.T - 1), ch = c & 15;
-        r_c[k] = *reinterpret_cast<const u32x4 *>(p.C + ((static_cast<size_t>(b) * p.T + row) * p.G + g) * kN +
-                                                  8 * ch);
-      }
-      r_g = *reinterpret_cast<const u32x4 *>(p.Gd + (bg * p.NB + jb) * kBlk * kBlk + 8 * tid);
+      for (int k = 0; k < 2; ++k) r_c[k] = buf_load16(rc, vc[k], 0);
+      r_g = buf_load16(rs_g, vt, jb * (kBlk * kBlk * 2));
     }
-    const float *rec = p.prep + (bh * p.NB + jb) * kRec;
+    r_f = buf_load16(rs_prep, vf, jb * (kRec * 4));
+    const Rsrc rx = x_rsrc(jb);
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-      const int sq = sqb + 8 * k;
-      r_f[k] = *reinterpret_cast<const f32x4 *>(rec + kBlk + 4 * sq);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        // tokens beyond the sequence: the address is clamped and their factor f is 0 (dt = 0)
-        const int t = min(tb + 4 * sq + i, p.T - 1);
-        r_x[k][i] = *reinterpret_cast<const u32x2 *>(p.x + ((static_cast<size_t>(b) * p.T + t) * p.H + h) * kP +
-                                                     32 * ph + 4 * pq);
-      }
-    }
+    for (int i = 0; i < 4; ++i) r_x[i] = buf_load16(rx, vx[i], 0);
   };
+
+  // LDS destinations of this thread's pieces (fixed)
+  uint32_t lds_bt[2], lds_c[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int c = tid + kScanThreads * k;
+    lds_bt[k] = (c >> 3) * kBtStride + 8 * (c & 7);
+    // C columns are permuted inside each group of 16 so that one 16-byte read yields
+    // n-offsets {4kg..4kg+3, 8+4kg..8+4kg+3}
+    lds_c[k] = (c >> 4) * kCStride + 16 * ((c & 15) >> 1) + 4 * (c & 1);
+  }
+  const uint32_t lds_g = (tid >> 3) * kGStride + 8 * (tid & 7);
+  // Xm^T: column 8cg + c of the half goes to row pi^-1(8cg + c) = 16 (cg & 1) + 4 (cg >> 1) + 8 (c >> 2) + (c & 3)
+  uint16_t *const xm_dst = myX + (16 * (cg & 1) + 4 * (cg >> 1)) * kXStride + 4 * tg;
 
   auto store_tiles = [&](int buf) {
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-      const int c = tid + kScanThreads * k, n = c >> 3, ch = c & 7;
-      *reinterpret_cast<u32x4 *>(&sBt[buf][n * kBtStride + 8 * ch]) = r_bt[k];
-    }
+    for (int k = 0; k < 2; ++k) *reinterpret_cast<u32x4 *>(&sBt[buf][lds_bt[k]]) = r_bt[k];
     if constexpr (!kStatesOnly) {
-      // C columns are permuted inside each group of 16 so that one 16-byte read yields
-      // n-offsets {4kg..4kg+3, 8+4kg..8+4kg+3}
 #pragma unroll
       for (int k = 0; k < 2; ++k) {
-        const int c = tid + kScanThreads * k, row = c >> 4, ch = c & 15;
-        uint16_t *dst = &sC[buf][row * kCStride + 16 * (ch >> 1) + 4 * (ch & 1)];
+        uint16_t *dst = &sC[buf][lds_c[k]];
         *reinterpret_cast<u32x2 *>(dst) = mk2(r_c[k].x, r_c[k].y);
         *reinterpret_cast<u32x2 *>(dst + 8) = mk2(r_c[k].z, r_c[k].w);
       }
-      *reinterpret_cast<u32x4 *>(&sG[buf][(tid >> 3) * kGStride + 8 * (tid & 7)]) = r_g;
+      *reinterpret_cast<u32x4 *>(&sG[buf][lds_g]) = r_g;
     }
-    // own slice: Xm^T[p][s] = f_s x[s][p], four tokens per 8-byte write
+    // own slice: Xm^T[row][s] = f_s x[s][col], four tokens per 8-byte write
+    const float f0 = __uint_as_float(r_f.x), f1 = __uint_as_float(r_f.y), f2 = __uint_as_float(r_f.z),
+                f3 = __uint_as_float(r_f.w);
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-      const int sq = sqb + 8 * k;
-      const f32x4 f = r_f[k];
-      uint16_t *dst = myX + (4 * pq) * kXStride + 4 * sq;
-      *reinterpret_cast<u32x2 *>(dst) =
-          mk2(pack2(f.x * bf_lo(r_x[k][0].x), f.y * bf_lo(r_x[k][1].x)),
-              pack2(f.z * bf_lo(r_x[k][2].x), f.w * bf_lo(r_x[k][3].x)));
-      *reinterpret_cast<u32x2 *>(dst + kXStride) =
-          mk2(pack2(f.x * bf_hi(r_x[k][0].x), f.y * bf_hi(r_x[k][1].x)),
-              pack2(f.z * bf_hi(r_x[k][2].x), f.w * bf_hi(r_x[k][3].x)));
-      *reinterpret_cast<u32x2 *>(dst + 2 * kXStride) =
-          mk2(pack2(f.x * bf_lo(r_x[k][0].y), f.y * bf_lo(r_x[k][1].y)),
-              pack2(f.z * bf_lo(r_x[k][2].y), f.w * bf_lo(r_x[k][3].y)));
-      *reinterpret_cast<u32x2 *>(dst + 3 * kXStride) =
-          mk2(pack2(f.x * bf_hi(r_x[k][0].y), f.y * bf_hi(r_x[k][1].y)),
-              pack2(f.z * bf_hi(r_x[k][2].y), f.w * bf_hi(r_x[k][3].y)));
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t a0 = r_x[0][w], a1 = r_x[1][w], a2 = r_x[2][w], a3 = r_x[3][w];
+      // columns c = 2w (low halves) and 2w + 1 (high halves)
+      uint16_t *dlo = xm_dst + (8 * ((2 * w) >> 2) + ((2 * w) & 3)) * kXStride;
+      *reinterpret_cast<u32x2 *>(dlo) =
+          mk2(pack2(f0 * bf_lo(a0), f1 * bf_lo(a1)), pack2(f2 * bf_lo(a2), f3 * bf_lo(a3)));
+      *reinterpret_cast<u32x2 *>(dlo + kXStride) =
+          mk2(pack2(f0 * bf_hi(a0), f1 * bf_hi(a1)), pack2(f2 * bf_hi(a2), f3 * bf_hi(a3)));
     }
   };
 
-  // Per-lane scalars of a block: cs at this lane's two output tokens (r, 32 + r), c31, c63.
+  // Per-block scalars: output-row factors of this lane's two tokens (r, 32 + r) and the state factors.
   struct BlockScalars {
-    float cs0, cs1, c31, c63;
+    float rowf0, rowf1, mid_to_end, start_to_mid, c63;
   };
   auto load_scalars = [&](int jb) {
-    const float *rec = p.prep + (bh * p.NB + jb) * kRec;
+    const float *rec = prep_bh + static_cast<size_t>(jb) * kRec;
     BlockScalars v;
-    v.cs0 = rec[r];
-    v.cs1 = rec[32 + r];
-    v.c31 = rec[31];
-    v.c63 = rec[kBlk - 1];
+    v.rowf0 = kStatesOnly ? 0.f : rec[r];
+    v.rowf1 = kStatesOnly ? 0.f : rec[32 + r];
+    const f32x4 s = *reinterpret_cast<const f32x4 *>(rec + 2 * kBlk);
+    v.mid_to_end = s.x;
+    v.start_to_mid = s.y;
+    v.c63 = s.z;
     return v;
   };
-  // x in output layout for the skip term: token 32lt + r, columns 32ph + 8i4 + 4kg .. +3
-  u32x2 xepi[2][4];
+  // x in output layout for the skip term: token r + 32lt, columns 32ph + 16kg .. +15
+  u32x4 xepi[2][2];
   auto load_xepi = [&](int jb) {
+    const Rsrc rx = x_rsrc(jb);
 #pragma unroll
-    for (int lt = 0; lt < 2; ++lt) {
-      const int t = min(jb * kBlk + 32 * lt + r, p.T - 1);
-      const uint16_t *xp = p.x + ((static_cast<size_t>(b) * p.T + t) * p.H + h) * kP + 32 * ph + 4 * kg;
+    for (int lt = 0; lt < 2; ++lt)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) xepi[lt][i4] = *reinterpret_cast<const u32x2 *>(xp + 8 * i4);
-    }
+      for (int c = 0; c < 2; ++c) xepi[lt][c] = buf_load16(rx, ve[lt] + 16 * c, 0);
   };
 
-  // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][p = 32ph + r] ----
+  // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][column of lane r] ----
+  const int pcol = 32 * ph + pi_of_row(r);  // headdim column of this lane's state column
   f32x16 Hacc[4];
-  // scalars are fetched two blocks ahead: a load that is used right after it is issued would
-  // stall the wave for a full memory round trip (behind the output stores in front of it)
-  BlockScalars cur = {0.f, 0.f, 0.f, 0.f}, nxt = {0.f, 0.f, 0.f, 0.f};
+  BlockScalars cur = {0.f, 0.f, 0.f, 0.f, 0.f}, nxt = {0.f, 0.f, 0.f, 0.f, 0.f};
   if (jb0 < jb1) cur = load_scalars(jb0);
   float Dh = kStatesOnly ? 0.f : p.D[h];
   // Pin these values as "arrived" before the loop: otherwise the wait for them is placed at their
   // first use inside the loop, where it also waits for every younger load of every iteration.
-  asm volatile("" : "+v"(Dh), "+v"(cur.cs0), "+v"(cur.cs1), "+v"(cur.c31), "+v"(cur.c63));
+  asm volatile("" : "+v"(Dh), "+v"(cur.rowf0), "+v"(cur.rowf1), "+v"(cur.mid_to_end), "+v"(cur.start_to_mid), "+v"(cur.c63));
   if (!kStatesOnly && p.Hin != nullptr) {
-    const float d0 = fast_exp2(cur.c31);
+    const float d0 = cur.start_to_mid;
     const float *hp = p.Hin + bh * p.hin_bh_stride + static_cast<size_t>(sg) * kP * kN +
-                      static_cast<size_t>(32 * ph + r) * kN;
+                      static_cast<size_t>(pcol) * kN;
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
@@ -385,10 +427,10 @@ void chunk_scan_kernel(const ScanParams p) {
   };
 
   float seg_total = 0.f;
-  // The loop body below is free of branches around memory operations (indices are clamped to the
-  // segment instead, redundant work in the last two iterations is harmless): the hardware counts
-  // outstanding loads and stores in order, and only with straight-line code can the compiler wait
-  // for exactly the older ones and leave the newer ones in flight.
+  // The loop body below is free of branches around memory operations (block indices are clamped to
+  // the segment instead, redundant loads in the last two iterations are harmless): the hardware
+  // counts outstanding loads and stores in order, and only with straight-line code can the compiler
+  // wait for exactly the older ones and leave the newer ones in flight.
   const int jlast = jb1 - 1;
   if (jb0 < jb1) {
     // ---- prologue: block jb0 into LDS buffer 0; block jb0+1 in flight ----
@@ -402,16 +444,15 @@ void chunk_scan_kernel(const ScanParams p) {
 
   for (int jb = jb0; jb < jb1; ++jb) {
     const int buf = (jb - jb0) & 1;
-    const int tb = jb * kBlk;
     const bool more = jb < jlast;
     if (kStatesOnly) seg_total += cur.c63;
 
-    Operand xo[4];  // Xm^T[p = 32ph + r][s = 16q + 8kg ..]
+    Operand xo[4];  // Xm^T[row r][s = 16q + 8kg ..]
 #pragma unroll
     for (int q = 0; q < 4; ++q) xo[q].q = *reinterpret_cast<const u32x4 *>(myX + r * kXStride + 16 * q + 8 * kg);
 
     if constexpr (!kStatesOnly) {
-      // ---- Y^T[p][l] = sum_n Ht[p][n] C[l][n]  +  sum_{s<=l} Xm[s][p] G[l][s] ----
+      // ---- Y^T[row][l] = sum_n Ht[row][n] C[l][n]  +  sum_{s<=l} Xm[s][row] G[l][s] ----
       f32x16 Y[2] = {};
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
@@ -432,30 +473,26 @@ void chunk_scan_kernel(const ScanParams p) {
         }
         Y[1] = mfma(xo[q], g1, Y[1]);
       }
-      // ---- epilogue: y[l][p] = exp2(cs_l - c31) Y + D x, four consecutive p per 8-byte store ----
-      const float rowf[2] = {fast_exp2(fminf(fmaxf(cur.cs0 - cur.c31, -kMaxExp), kMaxExp)),
-                             fast_exp2(fminf(fmaxf(cur.cs1 - cur.c31, -kMaxExp), kMaxExp))};
+      // ---- epilogue: y[l][col] = rowf_l Y + D x; element i of the lane is column 32ph + 16kg + i ----
+      const Rsrc ry = y_rsrc(jb);
+      const float rowf[2] = {cur.rowf0, cur.rowf1};
 #pragma unroll
       for (int lt = 0; lt < 2; ++lt) {
-        const int t = tb + 32 * lt + r;
-        // lanes of padded tokens store to a scratch row instead of branching around the store
-        uint16_t *yp = (t < p.T)
-                           ? p.y + ((static_cast<size_t>(b) * p.T + t) * p.H + h) * kP + 32 * ph + 4 * kg
-                           : p.y_dump + 4 * kg;
+        const f32x16 &Yt = Y[lt];
 #pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const u32x2 xv = xepi[lt][i4];
-          const f32x16 &Yt = Y[lt];
-          const u32x2 o = mk2(pack2(rowf[lt] * Yt[4 * i4 + 0] + Dh * bf_lo(xv.x),
-                                    rowf[lt] * Yt[4 * i4 + 1] + Dh * bf_hi(xv.x)),
-                              pack2(rowf[lt] * Yt[4 * i4 + 2] + Dh * bf_lo(xv.y),
-                                    rowf[lt] * Yt[4 * i4 + 3] + Dh * bf_hi(xv.y)));
-          *reinterpret_cast<u32x2 *>(yp + 8 * i4) = o;
+        for (int c = 0; c < 2; ++c) {
+          const u32x4 xv = xepi[lt][c];
+          u32x4 o;
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            o[w] = pack2(rowf[lt] * Yt[8 * c + 2 * w] + Dh * bf_lo(xv[w]),
+                         rowf[lt] * Yt[8 * c + 2 * w + 1] + Dh * bf_hi(xv[w]));
+          buf_store16(ry, ve[lt] + 16 * c, o);  // tokens beyond the sequence are beyond the descriptor: dropped
         }
       }
     }
 
-    // ---- H'^T[n][p] = Ht^T[n][p] + sum_s B^T[n][s] Xm[s][p] ----
+    // ---- H'^T[n][col] = Ht^T[n][col] + sum_s B^T[n][s] Xm[s][col] ----
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
 #pragma unroll
@@ -468,11 +505,11 @@ void chunk_scan_kernel(const ScanParams p) {
 
     // ---- next block: its tiles go to the other LDS buffer, its scalars become current, the
     //      state moves to the next block's frame, and block jb+2 is requested ----
-    const float d1 = fast_exp2(cur.c63 - cur.c31);
+    const float d1 = cur.mid_to_end;
     store_tiles(buf ^ 1);
     cur = nxt;
     // after the last block the accumulators must hold the true state: no next-frame factor
-    const float scale = more ? d1 * fast_exp2(cur.c31) : d1;
+    const float scale = more ? d1 * cur.start_to_mid : d1;
     const int j1 = min(jb + 1, jlast), j2 = min(jb + 2, jlast);
     if constexpr (!kStatesOnly) load_xepi(j1);
     nxt = load_scalars(j2);
@@ -497,7 +534,7 @@ void chunk_scan_kernel(const ScanParams p) {
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4)
-        *reinterpret_cast<f32x4 *>(out + static_cast<size_t>(32 * ph + r) * kN + 32 * nt + 8 * i4 + 4 * kg) =
+        *reinterpret_cast<f32x4 *>(out + static_cast<size_t>(pcol) * kN + 32 * nt + 8 * i4 + 4 * kg) =
             f32x4{Hacc[nt][4 * i4 + 0], Hacc[nt][4 * i4 + 1], Hacc[nt][4 * i4 + 2], Hacc[nt][4 * i4 + 3]};
   }
 }
@@ -549,7 +586,7 @@ int choose_seg_blocks(const Dims &d) {
 
 struct Layout {
   int NB, S_max;
-  size_t off_G, off_Bt, off_prep, off_state, off_decay, off_dump, total;
+  size_t off_G, off_Bt, off_prep, off_state, off_decay, total;
 };
 
 Layout make_layout(const Dims &d) {
@@ -568,8 +605,6 @@ Layout make_layout(const Dims &d) {
   off += round_up(BH * w.S_max * kP * kN * sizeof(float), 256);
   w.off_decay = off;
   off += round_up(BH * w.S_max * sizeof(float), 256);
-  w.off_dump = off;
-  off += 256;
   w.total = off;
   return w;
 }
@@ -577,8 +612,12 @@ Layout make_layout(const Dims &d) {
 }  // namespace
 
 bool mfma_supported(const Dims &d) {
+  // one batch row of x, C and the per-head block records must be addressable with 32-bit byte offsets
+  const unsigned long long lim = 0xFFFF0000ull;
+  const unsigned long long nb = (static_cast<unsigned long long>(d.T) + kBlk - 1) / kBlk;
   return d.bf16 && d.P == kP && d.N == kN && d.L % kBlk == 0 && d.hpg % kHeadsPerWg == 0 && d.Bt <= 65535 &&
-         d.H <= 65535;
+         d.H <= 65535 && static_cast<unsigned long long>(d.T) * d.H * (kP * 2) <= lim &&
+         static_cast<unsigned long long>(d.T) * d.G * (kN * 2) <= lim && nb * (kN * kBlk * 2) <= lim;
 }
 
 size_t mfma_workspace_bytes(const Dims &d) { return make_layout(d).total; }
@@ -605,14 +644,13 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
   trace_mark(trace, stream, "block_cumsum");
 
   ScanParams p;
-  p.x = static_cast<const uint16_t *>(x);
-  p.C = static_cast<const uint16_t *>(C);
+  p.x = static_cast<const uint8_t *>(x);
+  p.C = static_cast<const uint8_t *>(C);
   p.D = D;
-  p.Gd = Gd;
-  p.Btr = Btr;
+  p.Gd = reinterpret_cast<const uint8_t *>(Gd);
+  p.Btr = reinterpret_cast<const uint8_t *>(Btr);
   p.prep = prep;
-  p.y = static_cast<uint16_t *>(y);
-  p.y_dump = reinterpret_cast<uint16_t *>(ws + w.off_dump);
+  p.y = static_cast<uint8_t *>(y);
   p.final_state = final_state;
   p.seg_state = seg_state;
   p.seg_decay = seg_decay;
