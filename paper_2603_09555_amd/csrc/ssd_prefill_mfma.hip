@@ -248,13 +248,24 @@ __device__ __forceinline__ int pi_of_row(int m) { return 16 * ((m >> 2) & 1) + 4
 // accumulator registers), a 64 x 32 output tile (32) and its input operands (16); with the next
 // block's data in flight it stays under 256 registers, so the eight waves of a workgroup run two
 // per SIMD and one wave's MFMAs overlap the other's vector work and memory waits.
+//
+// What bounds the kernel is the memory path (every CU has to pull its share of x and push its share
+// of y, and a CU sustains only ~1/256 of the chip's bandwidth), so the loop is arranged to keep
+// requests outstanding all the time and to move no byte twice: the skip term D x reads x from a raw
+// copy that the staging step leaves in LDS instead of loading it again, the loads of the block after
+// next are issued in the middle of an iteration, as soon as their registers are free, and the stores
+// of y are spread over the second half.
+constexpr int kRawStride = 40;                       // raw x rows: 32 columns + 16 bytes, in bf16 elements
+constexpr int kGLowStride = 32 + 8;                  // G rows 0..31 keep only columns 0..31 (the rest is masked)
+constexpr int kGTile = 32 * kGLowStride + 32 * kGStride;  // elements of a compacted G tile
 template <bool kStatesOnly>
 __global__ __launch_bounds__(kScanThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void chunk_scan_kernel(const ScanParams p) {
   __shared__ __align__(16) uint16_t sC[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kBlk * kCStride];
   __shared__ __align__(16) uint16_t sBt[2][kN * kBtStride];                   // B^T [n][s]
-  __shared__ __align__(16) uint16_t sG[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kBlk * kGStride];
+  __shared__ __align__(16) uint16_t sG[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kGTile];
   __shared__ __align__(16) uint16_t sXm[kHeadsPerWg][kP * kXStride];          // Xm^T [row][s], per head
+  __shared__ __align__(16) uint16_t sRaw[kStatesOnly ? 1 : 2 * kHeadsPerWg][kStatesOnly ? 8 : kBlk * kRawStride];  // x [s][col], per wave
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -269,6 +280,7 @@ void chunk_scan_kernel(const ScanParams p) {
   const int jb1 = min(p.NB, jb0 + p.seg_blocks);
   const int cg = lane & 3, tg = lane >> 2;  // x staging: columns 8cg..8cg+7 of the half, tokens 4tg..4tg+3
   uint16_t *const myX = sXm[hw] + 32 * ph * kXStride;  // this wave's 32 rows of Xm^T
+  uint16_t *const myRaw = sRaw[kStatesOnly ? 0 : wave];
 
   // ---- addressing: scalar bases, per-lane byte offsets that never change ----
   const uint32_t xrow = static_cast<uint32_t>(p.H) * (kP * 2);   // bytes per token of x / y
@@ -298,25 +310,32 @@ void chunk_scan_kernel(const ScanParams p) {
     ve[k] = static_cast<uint32_t>(r + 32 * k) * xrow + xcol + 32 * kg;  // output layout: token r + 32k, 32 bytes
   }
   const uint32_t vf = static_cast<uint32_t>(kBlk + 4 * tg) * 4;  // input factors of this thread's four tokens
+  // G: thread -> (row, 16-byte piece); in rows 0..31 only pieces 0..3 are kept (s <= l < 32), the
+  // threads of the other pieces duplicate a kept one (same data to the same place)
+  const int g_row = tid >> 3, g_pc = (g_row < 32) ? (tid & 3) : (tid & 7);
+  const uint32_t vg = static_cast<uint32_t>(g_row * kBlk + 8 * g_pc) * 2;
 
   // ---- data of a block in flight (registers) ----
   u32x4 r_c[2], r_bt[2], r_g;  // shared tiles: this thread's 16-byte pieces
   u32x4 r_x[4];                // own slice: 4 tokens x 8 columns
   u32x4 r_f;                   // input factors of the 4 tokens (fp32 bits)
 
-  auto load_tiles = [&](int jb) {
+  // Global loads of block jb, in three portions so that they can be spread over the instruction stream.
+  auto load_part = [&](int part, int jb) {
+    if (part == 0) {
+      const Rsrc rx = x_rsrc(jb);
 #pragma unroll
-    for (int k = 0; k < 2; ++k) r_bt[k] = buf_load16(rs_bt, vt, jb * (kN * kBlk * 2) + k * (kScanThreads * 16));
-    if constexpr (!kStatesOnly) {
+      for (int i = 0; i < 4; ++i) r_x[i] = buf_load16(rx, vx[i], 0);
+      r_f = buf_load16(rs_prep, vf, jb * (kRec * 4));
+    } else if (part == 1) {
+#pragma unroll
+      for (int k = 0; k < 2; ++k) r_bt[k] = buf_load16(rs_bt, vt, jb * (kN * kBlk * 2) + k * (kScanThreads * 16));
+    } else if (!kStatesOnly) {
       const Rsrc rc = c_rsrc(jb);
 #pragma unroll
       for (int k = 0; k < 2; ++k) r_c[k] = buf_load16(rc, vc[k], 0);
-      r_g = buf_load16(rs_g, vt, jb * (kBlk * kBlk * 2));
+      r_g = buf_load16(rs_g, vg, jb * (kBlk * kBlk * 2));
     }
-    r_f = buf_load16(rs_prep, vf, jb * (kRec * 4));
-    const Rsrc rx = x_rsrc(jb);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) r_x[i] = buf_load16(rx, vx[i], 0);
   };
 
   // LDS destinations of this thread's pieces (fixed)
@@ -329,34 +348,43 @@ void chunk_scan_kernel(const ScanParams p) {
     // n-offsets {4kg..4kg+3, 8+4kg..8+4kg+3}
     lds_c[k] = (c >> 4) * kCStride + 16 * ((c & 15) >> 1) + 4 * (c & 1);
   }
-  const uint32_t lds_g = (tid >> 3) * kGStride + 8 * (tid & 7);
+  const uint32_t lds_g = (g_row < 32 ? g_row * kGLowStride : 32 * kGLowStride + (g_row - 32) * kGStride) + 8 * g_pc;
   // Xm^T: column 8cg + c of the half goes to row pi^-1(8cg + c) = 16 (cg & 1) + 4 (cg >> 1) + 8 (c >> 2) + (c & 3)
   uint16_t *const xm_dst = myX + (16 * (cg & 1) + 4 * (cg >> 1)) * kXStride + 4 * tg;
+  uint16_t *const raw_dst = myRaw + (4 * tg) * kRawStride + 8 * cg;
 
-  auto store_tiles = [&](int buf) {
-#pragma unroll
-    for (int k = 0; k < 2; ++k) *reinterpret_cast<u32x4 *>(&sBt[buf][lds_bt[k]]) = r_bt[k];
-    if constexpr (!kStatesOnly) {
-#pragma unroll
-      for (int k = 0; k < 2; ++k) {
-        uint16_t *dst = &sC[buf][lds_c[k]];
-        *reinterpret_cast<u32x2 *>(dst) = mk2(r_c[k].x, r_c[k].y);
-        *reinterpret_cast<u32x2 *>(dst + 8) = mk2(r_c[k].z, r_c[k].w);
-      }
-      *reinterpret_cast<u32x4 *>(&sG[buf][lds_g]) = r_g;
-    }
-    // own slice: Xm^T[row][s] = f_s x[s][col], four tokens per 8-byte write
+  // Registers -> LDS for the block in flight, in slices.  Slice c < 8 computes column c of the own
+  // slice, Xm^T[row][s] = f_s x[s][col] (four tokens per 8-byte write).
+  auto stage_column = [&](int c) {
     const float f0 = __uint_as_float(r_f.x), f1 = __uint_as_float(r_f.y), f2 = __uint_as_float(r_f.z),
                 f3 = __uint_as_float(r_f.w);
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const uint32_t a0 = r_x[0][w], a1 = r_x[1][w], a2 = r_x[2][w], a3 = r_x[3][w];
-      // columns c = 2w (low halves) and 2w + 1 (high halves)
-      uint16_t *dlo = xm_dst + (8 * ((2 * w) >> 2) + ((2 * w) & 3)) * kXStride;
-      *reinterpret_cast<u32x2 *>(dlo) =
-          mk2(pack2(f0 * bf_lo(a0), f1 * bf_lo(a1)), pack2(f2 * bf_lo(a2), f3 * bf_lo(a3)));
-      *reinterpret_cast<u32x2 *>(dlo + kXStride) =
+    const int w = c >> 1;
+    const uint32_t a0 = r_x[0][w], a1 = r_x[1][w], a2 = r_x[2][w], a3 = r_x[3][w];
+    uint16_t *dst = xm_dst + (8 * (c >> 2) + (c & 3)) * kXStride;
+    if (c & 1)
+      *reinterpret_cast<u32x2 *>(dst) =
           mk2(pack2(f0 * bf_hi(a0), f1 * bf_hi(a1)), pack2(f2 * bf_hi(a2), f3 * bf_hi(a3)));
+    else
+      *reinterpret_cast<u32x2 *>(dst) =
+          mk2(pack2(f0 * bf_lo(a0), f1 * bf_lo(a1)), pack2(f2 * bf_lo(a2), f3 * bf_lo(a3)));
+  };
+  auto stage_tile = [&](int piece, int buf) {  // pieces 0,1: B^T; 2,3: C; 4: G
+    if (piece < 2) {
+      *reinterpret_cast<u32x4 *>(&sBt[buf][lds_bt[piece]]) = r_bt[piece];
+    } else if constexpr (!kStatesOnly) {
+      if (piece < 4) {
+        uint16_t *d2 = &sC[buf][lds_c[piece - 2]];
+        *reinterpret_cast<u32x2 *>(d2) = mk2(r_c[piece - 2].x, r_c[piece - 2].y);
+        *reinterpret_cast<u32x2 *>(d2 + 8) = mk2(r_c[piece - 2].z, r_c[piece - 2].w);
+      } else {
+        *reinterpret_cast<u32x4 *>(&sG[buf][lds_g]) = r_g;
+      }
+    }
+  };
+  auto stage_raw = [&]() {  // the unscaled rows, for the skip term of the block's epilogue
+    if constexpr (!kStatesOnly) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(raw_dst + i * kRawStride) = r_x[i];
     }
   };
 
@@ -375,15 +403,6 @@ void chunk_scan_kernel(const ScanParams p) {
     v.c63 = s.z;
     return v;
   };
-  // x in output layout for the skip term: token r + 32lt, columns 32ph + 16kg .. +15
-  u32x4 xepi[2][2];
-  auto load_xepi = [&](int jb) {
-    const Rsrc rx = x_rsrc(jb);
-#pragma unroll
-    for (int lt = 0; lt < 2; ++lt)
-#pragma unroll
-      for (int c = 0; c < 2; ++c) xepi[lt][c] = buf_load16(rx, ve[lt] + 16 * c, 0);
-  };
 
   // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][column of lane r] ----
   const int pcol = 32 * ph + pi_of_row(r);  // headdim column of this lane's state column
@@ -395,7 +414,6 @@ void chunk_scan_kernel(const ScanParams p) {
   // first use inside the loop, where it also waits for every younger load of every iteration.
   asm volatile("" : "+v"(Dh), "+v"(cur.rowf0), "+v"(cur.rowf1), "+v"(cur.mid_to_end), "+v"(cur.start_to_mid), "+v"(cur.c63));
   if (!kStatesOnly && p.Hin != nullptr) {
-    const float d0 = cur.start_to_mid;
     const float *hp = p.Hin + bh * p.hin_bh_stride + static_cast<size_t>(sg) * kP * kN +
                       static_cast<size_t>(pcol) * kN;
 #pragma unroll
@@ -403,10 +421,10 @@ void chunk_scan_kernel(const ScanParams p) {
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         const f32x4 v = *reinterpret_cast<const f32x4 *>(hp + 32 * nt + 8 * i4 + 4 * kg);
-        Hacc[nt][4 * i4 + 0] = d0 * v.x;
-        Hacc[nt][4 * i4 + 1] = d0 * v.y;
-        Hacc[nt][4 * i4 + 2] = d0 * v.z;
-        Hacc[nt][4 * i4 + 3] = d0 * v.w;
+        Hacc[nt][4 * i4 + 0] = v.x;
+        Hacc[nt][4 * i4 + 1] = v.y;
+        Hacc[nt][4 * i4 + 2] = v.z;
+        Hacc[nt][4 * i4 + 3] = v.w;
       }
   } else {
 #pragma unroll
@@ -414,15 +432,21 @@ void chunk_scan_kernel(const ScanParams p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) Hacc[nt][i] = 0.f;
   }
-  // bf16 copy of a 16-column slice of Ht as an MFMA operand: slice 2nt+u covers n = 32nt + 16u +
-  // {4kg..4kg+3, 8+4kg..8+4kg+3} (the order in which sC stores each group of 16 columns).
-  // Converted right before use, so no second copy of the state is kept in registers.
-  auto state_operand = [&](int kk) {
+  // The accumulators hold the state up to a factor that is applied lazily: `pending` takes the state
+  // from where the previous block left it (the middle of that block) to the middle of the current
+  // block.  It is multiplied in eight elements at a time, right where those elements are converted
+  // to an MFMA operand, so the multiplies hide under the matrix instructions of the same loop.
+  float pending = cur.start_to_mid;
+
+  // LDS operand addresses of this lane (element offsets inside a tile)
+  const uint32_t a_c = r * kCStride + 8 * kg;    // + 32 rows for the second token half, + 16 kk
+  const uint32_t a_g0 = r * kGLowStride + 8 * kg;                     // token r, + 16 q (q < 2)
+  const uint32_t a_g1 = 32 * kGLowStride + r * kGStride + 8 * kg;     // token 32 + r, + 16 q
+  const uint32_t a_bt = r * kBtStride + 8 * kg;  // + 32 nt rows, + 16 q
+  const uint16_t *const raw_src = myRaw + r * kRawStride + 16 * kg;   // + 32 rows for the second half, + 8 c
+  auto lds16 = [](const uint16_t *ptr) {
     Operand o;
-    const f32x16 &hv = Hacc[kk >> 1];
-    const int u = kk & 1;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) o.u[k] = pack2(hv[8 * u + 2 * k], hv[8 * u + 2 * k + 1]);
+    o.q = *reinterpret_cast<const u32x4 *>(ptr);
     return o;
   };
 
@@ -431,95 +455,157 @@ void chunk_scan_kernel(const ScanParams p) {
   // the segment instead, redundant loads in the last two iterations are harmless): the hardware
   // counts outstanding loads and stores in order, and only with straight-line code can the compiler
   // wait for exactly the older ones and leave the newer ones in flight.
+  // It is written as an explicit software pipeline: every group of matrix instructions is preceded by
+  // the LDS reads of the NEXT group's operands and accompanied by independent vector work (state
+  // scaling and conversion and the staging of the next block in the first phase, the output epilogue
+  // in the second); the scheduling fences keep the compiler from undoing that order.
   const int jlast = jb1 - 1;
   if (jb0 < jb1) {
     // ---- prologue: block jb0 into LDS buffer 0; block jb0+1 in flight ----
-    load_tiles(jb0);
-    store_tiles(0);
-    if constexpr (!kStatesOnly) load_xepi(jb0);
+#pragma unroll
+    for (int part = 0; part < 3; ++part) load_part(part, jb0);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) stage_column(c);
+#pragma unroll
+    for (int piece = 0; piece < 5; ++piece) stage_tile(piece, 0);
+    stage_raw();
     nxt = load_scalars(min(jb0 + 1, jlast));
-    load_tiles(min(jb0 + 1, jlast));
+#pragma unroll
+    for (int part = 0; part < 3; ++part) load_part(part, min(jb0 + 1, jlast));
   }
   __syncthreads();
 
   for (int jb = jb0; jb < jb1; ++jb) {
     const int buf = (jb - jb0) & 1;
     const bool more = jb < jlast;
+    const int j2 = min(jb + 2, jlast);
     if (kStatesOnly) seg_total += cur.c63;
+    const uint16_t *const tC = sC[kStatesOnly ? 0 : buf], *const tG = sG[kStatesOnly ? 0 : buf], *const tBt = sBt[buf];
 
     Operand xo[4];  // Xm^T[row r][s = 16q + 8kg ..]
 #pragma unroll
-    for (int q = 0; q < 4; ++q) xo[q].q = *reinterpret_cast<const u32x4 *>(myX + r * kXStride + 16 * q + 8 * kg);
+    for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
+    Operand bto[2][4];  // operands of the state update, double buffered over q
+    f32x16 Y[2] = {};
+    u32x4 xepi[2][2];   // x in output layout for the skip term: token r + 32lt, columns 32ph + 16kg .. +15
 
     if constexpr (!kStatesOnly) {
-      // ---- Y^T[row][l] = sum_n Ht[row][n] C[l][n]  +  sum_{s<=l} Xm[s][row] G[l][s] ----
-      f32x16 Y[2] = {};
+      // ---- phase 1: Y^T[row][l] = sum_n Ht[row][n] C[l][n]  +  sum_{s<=l} Xm[s][row] G[l][s];
+      //      alongside, the next block moves from registers to the other LDS buffer, and as soon as
+      //      the registers of its shared tiles are free the tiles of block jb+2 are requested ----
+      Operand co[2][2], go[2][2];
+      co[0][0] = lds16(tC + a_c);
+      co[0][1] = lds16(tC + a_c + 32 * kCStride);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
-        Operand c0, c1;
-        c0.q = *reinterpret_cast<const u32x4 *>(&sC[buf][r * kCStride + 16 * kk + 8 * kg]);
-        c1.q = *reinterpret_cast<const u32x4 *>(&sC[buf][(32 + r) * kCStride + 16 * kk + 8 * kg]);
-        const Operand ho = state_operand(kk);
-        Y[0] = mfma(ho, c0, Y[0]);
-        Y[1] = mfma(ho, c1, Y[1]);
+        if (kk < 7) {
+          co[(kk + 1) & 1][0] = lds16(tC + a_c + 16 * (kk + 1));
+          co[(kk + 1) & 1][1] = lds16(tC + a_c + 32 * kCStride + 16 * (kk + 1));
+        } else {
+          go[0][1] = lds16(tG + a_g1);
+          go[0][0] = lds16(tG + a_g0);
+        }
+        // bf16 copy of a 16-column slice of Ht as an MFMA operand: slice 2nt+u covers n = 32nt + 16u +
+        // {4kg..4kg+3, 8+4kg..8+4kg+3} (the order in which sC stores each group of 16 columns)
+        f32x16 &hv = Hacc[kk >> 1];
+        const int u = kk & 1;
+        Operand ho;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          hv[8 * u + 2 * k] *= pending;
+          hv[8 * u + 2 * k + 1] *= pending;
+          ho.u[k] = pack2(hv[8 * u + 2 * k], hv[8 * u + 2 * k + 1]);
+        }
+        Y[0] = mfma(ho, co[kk & 1][0], Y[0]);
+        Y[1] = mfma(ho, co[kk & 1][1], Y[1]);
+        stage_column(kk);
+        if (kk < 5) stage_tile(kk, buf ^ 1);
+        if (kk == 5) load_part(1, j2);
+        if (kk == 6) load_part(2, j2);
+        __builtin_amdgcn_sched_barrier(0);
       }
+      // the masked product; alongside: x of this block leaves the raw copy, the raw rows of the next
+      // block replace it (LDS operations of a wave execute in order), and x of block jb+2 is requested
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        Operand g0, g1;
-        g1.q = *reinterpret_cast<const u32x4 *>(&sG[buf][(32 + r) * kGStride + 16 * q + 8 * kg]);
-        if (q < 2) {
-          g0.q = *reinterpret_cast<const u32x4 *>(&sG[buf][r * kGStride + 16 * q + 8 * kg]);
-          Y[0] = mfma(xo[q], g0, Y[0]);
+        if (q < 3) {
+          go[(q + 1) & 1][1] = lds16(tG + a_g1 + 16 * (q + 1));
+          if (q + 1 < 2) go[(q + 1) & 1][0] = lds16(tG + a_g0 + 16 * (q + 1));
+        } else {
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) bto[0][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride);
         }
-        Y[1] = mfma(xo[q], g1, Y[1]);
-      }
-      // ---- epilogue: y[l][col] = rowf_l Y + D x; element i of the lane is column 32ph + 16kg + i ----
-      const Rsrc ry = y_rsrc(jb);
-      const float rowf[2] = {cur.rowf0, cur.rowf1};
+        if (q < 2) Y[0] = mfma(xo[q], go[q & 1][0], Y[0]);
+        Y[1] = mfma(xo[q], go[q & 1][1], Y[1]);
+        if (q == 0) {
 #pragma unroll
-      for (int lt = 0; lt < 2; ++lt) {
-        const f32x16 &Yt = Y[lt];
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const u32x4 xv = xepi[lt][c];
-          u32x4 o;
-#pragma unroll
-          for (int w = 0; w < 4; ++w)
-            o[w] = pack2(rowf[lt] * Yt[8 * c + 2 * w] + Dh * bf_lo(xv[w]),
-                         rowf[lt] * Yt[8 * c + 2 * w + 1] + Dh * bf_hi(xv[w]));
-          buf_store16(ry, ve[lt] + 16 * c, o);  // tokens beyond the sequence are beyond the descriptor: dropped
+          for (int i = 0; i < 4; ++i) xepi[i >> 1][i & 1] = lds16(raw_src + 32 * (i >> 1) * kRawStride + 8 * (i & 1)).q;
         }
+        if (q == 1) stage_raw();
+        if (q == 2) load_part(0, j2);
+        __builtin_amdgcn_sched_barrier(0);
       }
+    } else {
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) bto[0][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride);
+      __builtin_amdgcn_sched_barrier(0);
     }
 
-    // ---- H'^T[n][col] = Ht^T[n][col] + sum_s B^T[n][s] Xm[s][col] ----
+    // ---- phase 2: H'^T[n][col] = Ht^T[n][col] + sum_s B^T[n][s] Xm[s][col]; alongside, the output
+    //      epilogue of the block (y[l][col] = rowf_l Y + D x; element i of the lane is column
+    //      32ph + 16kg + i), one quarter per group ----
+    const Rsrc ry = y_rsrc(jb);
+    const float rowf[2] = {cur.rowf0, cur.rowf1};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
+      if (q < 3) {
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) bto[(q + 1) & 1][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * (q + 1));
+      }
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt) {
-        Operand bt;
-        bt.q = *reinterpret_cast<const u32x4 *>(&sBt[buf][(32 * nt + r) * kBtStride + 16 * q + 8 * kg]);
-        Hacc[nt] = mfma(bt, xo[q], Hacc[nt]);
+        if (kStatesOnly && q == 0) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) Hacc[nt][i] *= pending;
+        }
+        Hacc[nt] = mfma(bto[q & 1][nt], xo[q], Hacc[nt]);
       }
+      if constexpr (!kStatesOnly) {
+        const int lt = q >> 1, c = q & 1;
+        const f32x16 &Yt = Y[lt];
+        const u32x4 xv = xepi[lt][c];
+        u32x4 o;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          o[w] = pack2(rowf[lt] * Yt[8 * c + 2 * w] + Dh * bf_lo(xv[w]),
+                       rowf[lt] * Yt[8 * c + 2 * w + 1] + Dh * bf_hi(xv[w]));
+        buf_store16(ry, ve[lt] + 16 * c, o);  // tokens beyond the sequence are beyond the descriptor: dropped
+      } else {
+        // states only: the next block is staged here (two columns per group), its successor requested last
+        stage_column(2 * q);
+        stage_column(2 * q + 1);
+        if (q < 2) stage_tile(q, buf ^ 1);
+        if (q == 3) {
+          load_part(0, j2);
+          load_part(1, j2);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
 
-    // ---- next block: its tiles go to the other LDS buffer, its scalars become current, the
-    //      state moves to the next block's frame, and block jb+2 is requested ----
+    // ---- next block's scalars become current ----
     const float d1 = cur.mid_to_end;
-    store_tiles(buf ^ 1);
     cur = nxt;
-    // after the last block the accumulators must hold the true state: no next-frame factor
-    const float scale = more ? d1 * cur.start_to_mid : d1;
-    const int j1 = min(jb + 1, jlast), j2 = min(jb + 2, jlast);
-    if constexpr (!kStatesOnly) load_xepi(j1);
+    // after the last block only the way to the end of that block is left: no next-block factor
+    pending = more ? d1 * cur.start_to_mid : d1;
     nxt = load_scalars(j2);
-    load_tiles(j2);
-#pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) Hacc[nt][i] *= scale;
     __syncthreads();  // block jb's tiles may be overwritten; block jb+1's tiles are visible
   }
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) Hacc[nt][i] *= pending;
 
   // ---- write the state out (canonical (p, n) layout, four consecutive n per 16-byte store) ----
   float *out = nullptr;
