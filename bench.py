@@ -81,7 +81,7 @@ KERNEL_WORK = {
     "state_pass": ("state_pass",),
     "chunk_output": ("scores", "intra", "state_out", "skip"),
     # MFMA family
-    "scores_bt": ("scores",),
+    "block_prep": ("scores",),
     "segment_states": (),          # re-computation: carries no algorithmic FLOPs of its own
     "segment_pass": ("state_pass",),
     "chunk_scan": ("intra", "states", "state_out", "skip"),

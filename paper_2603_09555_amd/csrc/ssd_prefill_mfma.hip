@@ -89,15 +89,11 @@ __device__ __forceinline__ f32x16 mfma(const Operand &a, const Operand &b, f32x1
 }
 
 // ---- scores_bt: G = tril(C B^T) on the diagonal blocks, and B transposed ------------------------------
-// grid (NB, Bt*G).  Gd: (Bt*G, NB, 64 l, 64 s) bf16.  Btr: (Bt*G, NB, 128 n, 64 s) bf16.
-__global__ __launch_bounds__(kThreads) void scores_bt_kernel(const uint16_t *__restrict__ B,
-                                                             const uint16_t *__restrict__ C,
-                                                             uint16_t *__restrict__ Gd,
-                                                             uint16_t *__restrict__ Btr, int T, int G,
-                                                             int NB) {
-  __shared__ __align__(16) uint16_t sB[kBlk * (kN + 2)];
-  const int jb = blockIdx.x;
-  const int bg = blockIdx.y;
+// One workgroup per (block jb, batch row x group bg).  Gd: (Bt*G, NB, 64 l, 64 s) bf16.
+// Btr: (Bt*G, NB, 128 n, 64 s) bf16.  sB: kBlk * (kN + 2) elements of LDS.
+__device__ __forceinline__ void scores_bt_block(uint16_t *sB, int jb, int bg, const uint16_t *__restrict__ B,
+                                                const uint16_t *__restrict__ C, uint16_t *__restrict__ Gd,
+                                                uint16_t *__restrict__ Btr, int T, int G, int NB) {
   const int b = bg / G, g = bg % G;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ws = wave >> 1, wl = wave & 1;
@@ -156,7 +152,8 @@ __global__ __launch_bounds__(kThreads) void scores_bt_kernel(const uint16_t *__r
 }
 
 // ---- block_cumsum: per (batch, head, block) decay bookkeeping ----------------------------------
-// grid (NB, ceil(H/16), Bt).  With cs_s the block-relative inclusive prefix sum of dt*A*log2(e) (the
+// One workgroup per (block jb, 16 heads starting at h0, batch row b).  With cs_s the block-relative
+// inclusive prefix sum of dt*A*log2(e) (the
 // "segsum" input) and c31, c63 its values at tokens 31 and 63, every head gets one record of kRec
 // floats per block:
 //   [0,64)     rowf_l = exp2(clamp(cs_l - c31))            output-row factor of the decay mask
@@ -164,21 +161,26 @@ __global__ __launch_bounds__(kThreads) void scores_bt_kernel(const uint16_t *__r
 //   [128]      exp2(c63 - c31)     state: middle of the block -> end of the block
 //   [129]      exp2(c31)           state: start of the block -> middle of the block
 //   [130]      c63                 log2 of the block's total decay
+//   [131]      [128] * [129] of the next block: middle of the block -> middle of the next block
 // Tokens beyond the sequence get dt = 0 (state-neutral padding).  dt is read in its
-// (batch, token, head) layout and transposed through LDS.
+// (batch, token, head) layout and transposed through LDS, 64 tokens of the block plus the first 32
+// of the next one (for [131]).
 constexpr int kRec = 2 * kBlk + 4;
 constexpr int kCumHeads = 16;
 constexpr float kMaxExp = 100.f;
-__global__ __launch_bounds__(kThreads) void block_cumsum_kernel(const float *__restrict__ dt,
-                                                                const float *__restrict__ A,
-                                                                float *__restrict__ prep, int T, int H,
-                                                                int NB) {
-  __shared__ float tile[kBlk][kCumHeads + 1];
-  const int jb = blockIdx.x, h0 = blockIdx.y * kCumHeads, b = blockIdx.z;
+__device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1], int jb, int h0, int b,
+                                                   const float *__restrict__ dt, const float *__restrict__ A,
+                                                   float *__restrict__ prep, int T, int H, int NB) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tb = jb * kBlk;
   for (int i = threadIdx.x; i < kBlk * kCumHeads; i += kThreads) {
     const int tok = i / kCumHeads, hh = i % kCumHeads;
+    float v = 0.f;
+    if (tb + tok < T && h0 + hh < H) v = dt[(static_cast<size_t>(b) * T + tb + tok) * H + h0 + hh];
+    tile[tok][hh] = v;
+  }
+  for (int i = threadIdx.x; i < (kBlk / 2) * kCumHeads; i += kThreads) {
+    const int tok = kBlk + i / kCumHeads, hh = i % kCumHeads;
     float v = 0.f;
     if (tb + tok < T && h0 + hh < H) v = dt[(static_cast<size_t>(b) * T + tb + tok) * H + h0 + hh];
     tile[tok][hh] = v;
@@ -195,11 +197,41 @@ __global__ __launch_bounds__(kThreads) void block_cumsum_kernel(const float *__r
     }
     const float c31 = __shfl(v, 31, 64);
     const float c63 = __shfl(v, 63, 64);
+    // prefix sum at token 31 of the next block: the sum of its first 32 terms
+    float nx = lane < kBlk / 2 ? tile[kBlk + lane][hh] * (A[h] * kLog2e) : 0.f;
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) nx += __shfl_xor(nx, m, 64);
     float *rec = prep + ((static_cast<size_t>(b) * H + h) * NB + jb) * kRec;
     rec[lane] = fast_exp2(fminf(fmaxf(v - c31, -kMaxExp), kMaxExp));
     rec[kBlk + lane] = dtv * fast_exp2(fminf(fmaxf(c31 - v, -kMaxExp), kMaxExp));
     if (lane < 4)
-      rec[2 * kBlk + lane] = lane == 0 ? fast_exp2(c63 - c31) : lane == 1 ? fast_exp2(c31) : lane == 2 ? c63 : 0.f;
+      rec[2 * kBlk + lane] = lane == 0   ? fast_exp2(c63 - c31)
+                             : lane == 1 ? fast_exp2(c31)
+                             : lane == 2 ? c63
+                                         : fast_exp2(c63 - c31) * fast_exp2(nx);
+  }
+}
+
+// Both preparation steps in one launch (they are independent of each other and each is far too
+// small to fill the chip): the first n_scores workgroups compute G and B^T, the others the decay
+// records.  grid (n_scores + NB * ceil(H/16) * Bt).
+__global__ __launch_bounds__(kThreads) void block_prep_kernel(const uint16_t *__restrict__ B,
+                                                              const uint16_t *__restrict__ C,
+                                                              uint16_t *__restrict__ Gd,
+                                                              uint16_t *__restrict__ Btr,
+                                                              const float *__restrict__ dt,
+                                                              const float *__restrict__ A,
+                                                              float *__restrict__ prep, int T, int H, int G,
+                                                              int NB, int n_scores) {
+  __shared__ __align__(16) uint16_t sB[kBlk * (kN + 2)];
+  __shared__ float tile[kBlk + kBlk / 2][kCumHeads + 1];
+  const int wg = blockIdx.x;
+  if (wg < n_scores) {
+    scores_bt_block(sB, wg % NB, wg / NB, B, C, Gd, Btr, T, G, NB);
+  } else {
+    const int i = wg - n_scores;
+    const int hgroups = (H + kCumHeads - 1) / kCumHeads;
+    block_cumsum_block(tile, i % NB, ((i / NB) % hgroups) * kCumHeads, i / (NB * hgroups), dt, A, prep, T, H, NB);
   }
 }
 
@@ -317,16 +349,19 @@ void chunk_scan_kernel(const ScanParams p) {
 
   // ---- data of a block in flight (registers) ----
   u32x4 r_c[2], r_bt[2], r_g;  // shared tiles: this thread's 16-byte pieces
-  u32x4 r_x[4];                // own slice: 4 tokens x 8 columns
-  u32x4 r_f;                   // input factors of the 4 tokens (fp32 bits)
+  // own slice: 4 tokens x 8 columns, and the input factors of the 4 tokens (fp32 bits).  The
+  // states-only kernel has registers to spare and keeps two blocks of them in flight.
+  constexpr int kSets = kStatesOnly ? 2 : 1;
+  u32x4 r_x[kSets][4];
+  u32x4 r_f[kSets];
 
   // Global loads of block jb, in three portions so that they can be spread over the instruction stream.
-  auto load_part = [&](int part, int jb) {
+  auto load_part = [&](int part, int jb, int set = 0) __attribute__((always_inline)) {
     if (part == 0) {
       const Rsrc rx = x_rsrc(jb);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) r_x[i] = buf_load16(rx, vx[i], 0);
-      r_f = buf_load16(rs_prep, vf, jb * (kRec * 4));
+      for (int i = 0; i < 4; ++i) r_x[set][i] = buf_load16(rx, vx[i], 0);
+      r_f[set] = buf_load16(rs_prep, vf, jb * (kRec * 4));
     } else if (part == 1) {
 #pragma unroll
       for (int k = 0; k < 2; ++k) r_bt[k] = buf_load16(rs_bt, vt, jb * (kN * kBlk * 2) + k * (kScanThreads * 16));
@@ -355,11 +390,11 @@ void chunk_scan_kernel(const ScanParams p) {
 
   // Registers -> LDS for the block in flight, in slices.  Slice c < 8 computes column c of the own
   // slice, Xm^T[row][s] = f_s x[s][col] (four tokens per 8-byte write).
-  auto stage_column = [&](int c) {
-    const float f0 = __uint_as_float(r_f.x), f1 = __uint_as_float(r_f.y), f2 = __uint_as_float(r_f.z),
-                f3 = __uint_as_float(r_f.w);
+  auto stage_column = [&](int c, int set = 0) __attribute__((always_inline)) {
+    const float f0 = __uint_as_float(r_f[set].x), f1 = __uint_as_float(r_f[set].y),
+                f2 = __uint_as_float(r_f[set].z), f3 = __uint_as_float(r_f[set].w);
     const int w = c >> 1;
-    const uint32_t a0 = r_x[0][w], a1 = r_x[1][w], a2 = r_x[2][w], a3 = r_x[3][w];
+    const uint32_t a0 = r_x[set][0][w], a1 = r_x[set][1][w], a2 = r_x[set][2][w], a3 = r_x[set][3][w];
     uint16_t *dst = xm_dst + (8 * (c >> 2) + (c & 3)) * kXStride;
     if (c & 1)
       *reinterpret_cast<u32x2 *>(dst) =
@@ -384,35 +419,34 @@ void chunk_scan_kernel(const ScanParams p) {
   auto stage_raw = [&]() {  // the unscaled rows, for the skip term of the block's epilogue
     if constexpr (!kStatesOnly) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(raw_dst + i * kRawStride) = r_x[i];
+      for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(raw_dst + i * kRawStride) = r_x[0][i];
     }
   };
 
-  // Per-block scalars: output-row factors of this lane's two tokens (r, 32 + r) and the state factors.
-  struct BlockScalars {
-    float rowf0, rowf1, mid_to_end, start_to_mid, c63;
+  // Per-block state factors {mid -> end, start -> mid, log2 of the total decay, mid -> next mid}:
+  // uniform over the wave and read-only for this kernel, so they are fetched with scalar loads (the
+  // constant address space tells the compiler so) and never touch the vector memory queue.
+  typedef const __attribute__((address_space(4))) f32x4 *ConstVec4;
+  auto state_factors = [&](int jb) {
+    return *reinterpret_cast<ConstVec4>(reinterpret_cast<uintptr_t>(prep_bh + static_cast<size_t>(jb) * kRec + 2 * kBlk));
   };
-  auto load_scalars = [&](int jb) {
-    const float *rec = prep_bh + static_cast<size_t>(jb) * kRec;
-    BlockScalars v;
-    v.rowf0 = kStatesOnly ? 0.f : rec[r];
-    v.rowf1 = kStatesOnly ? 0.f : rec[32 + r];
-    const f32x4 s = *reinterpret_cast<const f32x4 *>(rec + 2 * kBlk);
-    v.mid_to_end = s.x;
-    v.start_to_mid = s.y;
-    v.c63 = s.z;
-    return v;
+  // Output-row factors of this lane's two tokens (r, 32 + r) of block jb.
+  float rowf0 = 0.f, rowf1 = 0.f;
+  auto load_rowf = [&](int jb) __attribute__((always_inline)) {
+    if constexpr (!kStatesOnly) {
+      const float *rec = prep_bh + static_cast<size_t>(jb) * kRec;
+      rowf0 = rec[r];
+      rowf1 = rec[32 + r];
+    }
   };
 
   // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][column of lane r] ----
   const int pcol = 32 * ph + pi_of_row(r);  // headdim column of this lane's state column
   f32x16 Hacc[4];
-  BlockScalars cur = {0.f, 0.f, 0.f, 0.f, 0.f}, nxt = {0.f, 0.f, 0.f, 0.f, 0.f};
-  if (jb0 < jb1) cur = load_scalars(jb0);
   float Dh = kStatesOnly ? 0.f : p.D[h];
-  // Pin these values as "arrived" before the loop: otherwise the wait for them is placed at their
-  // first use inside the loop, where it also waits for every younger load of every iteration.
-  asm volatile("" : "+v"(Dh), "+v"(cur.rowf0), "+v"(cur.rowf1), "+v"(cur.mid_to_end), "+v"(cur.start_to_mid), "+v"(cur.c63));
+  // Pin the value as "arrived" before the loop: otherwise the wait for it is placed at its first use
+  // inside the loop, where it also waits for every younger load of every iteration.
+  asm volatile("" : "+v"(Dh));
   if (!kStatesOnly && p.Hin != nullptr) {
     const float *hp = p.Hin + bh * p.hin_bh_stride + static_cast<size_t>(sg) * kP * kN +
                       static_cast<size_t>(pcol) * kN;
@@ -436,7 +470,7 @@ void chunk_scan_kernel(const ScanParams p) {
   // from where the previous block left it (the middle of that block) to the middle of the current
   // block.  It is multiplied in eight elements at a time, right where those elements are converted
   // to an MFMA operand, so the multiplies hide under the matrix instructions of the same loop.
-  float pending = cur.start_to_mid;
+  float pending = jb0 < jb1 ? state_factors(jb0).y : 1.f;
 
   // LDS operand addresses of this lane (element offsets inside a tile)
   const uint32_t a_c = r * kCStride + 8 * kg;    // + 32 rows for the second token half, + 16 kk
@@ -460,7 +494,65 @@ void chunk_scan_kernel(const ScanParams p) {
   // scaling and conversion and the staging of the next block in the first phase, the output epilogue
   // in the second); the scheduling fences keep the compiler from undoing that order.
   const int jlast = jb1 - 1;
-  if (jb0 < jb1) {
+  if constexpr (kStatesOnly) {
+    // ---- states only: H' = Ht + B^T Xm per block, nothing else.  The kernel is a pure stream of x
+    //      (plus the shared B^T tile), so x is requested two blocks ahead: block k's iteration stages
+    //      block k+1 from one register set and then refills that set with block k+3.  Two iterations
+    //      are written out per loop trip so that the set index is a compile-time constant. ----
+    auto at = [&](int j) { return min(j, jlast); };
+    if (jb0 < jb1) {
+      load_part(0, jb0, 0);
+      load_part(1, jb0);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) stage_column(c, 0);
+      stage_tile(0, 0);
+      stage_tile(1, 0);
+      load_part(0, at(jb0 + 1), 1);
+      load_part(1, at(jb0 + 1));
+      load_part(0, at(jb0 + 2), 0);
+    }
+    __syncthreads();
+    auto body = [&](int par, int jb) __attribute__((always_inline)) {
+      const int buf = par, set = par ^ 1;  // block jb sits in LDS buffer `par`; block jb+1 in register set par^1
+      const f32x4 sf = state_factors(jb);
+      seg_total += sf.z;
+      const uint16_t *const tBt = sBt[buf];
+      Operand xo[4], bto[2][4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) bto[0][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (q < 3) {
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) bto[(q + 1) & 1][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * (q + 1));
+        }
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+          if (q == 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) Hacc[nt][i] *= pending;
+          }
+          Hacc[nt] = mfma(bto[q & 1][nt], xo[q], Hacc[nt]);
+        }
+        stage_column(2 * q, set);
+        stage_column(2 * q + 1, set);
+        if (q < 2) stage_tile(q, buf ^ 1);
+        if (q == 2) load_part(1, at(jb + 2));
+        if (q == 3) load_part(0, at(jb + 3), set);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      pending = jb < jlast ? sf.w : sf.x;  // to the middle of the next block, or to the end of the last one
+      __syncthreads();
+    };
+    for (int jb = jb0; jb < jb1; jb += 2) {
+      body(0, jb);
+      if (jb + 1 < jb1) body(1, jb + 1);
+    }
+  }
+  if (!kStatesOnly && jb0 < jb1) {
     // ---- prologue: block jb0 into LDS buffer 0; block jb0+1 in flight ----
 #pragma unroll
     for (int part = 0; part < 3; ++part) load_part(part, jb0);
@@ -469,17 +561,21 @@ void chunk_scan_kernel(const ScanParams p) {
 #pragma unroll
     for (int piece = 0; piece < 5; ++piece) stage_tile(piece, 0);
     stage_raw();
-    nxt = load_scalars(min(jb0 + 1, jlast));
-#pragma unroll
-    for (int part = 0; part < 3; ++part) load_part(part, min(jb0 + 1, jlast));
+    // block jb0+1 is requested in the order the loop requests blocks (shared tiles, own slice, row
+    // factors): the compiler derives its waits from the order of outstanding loads, and they stay
+    // exact only if the path into the loop and the path around it agree on that order
+    load_part(1, min(jb0 + 1, jlast));
+    load_part(2, min(jb0 + 1, jlast));
+    load_part(0, min(jb0 + 1, jlast));
+    load_rowf(jb0);
   }
   __syncthreads();
 
-  for (int jb = jb0; jb < jb1; ++jb) {
+  for (int jb = jb0; !kStatesOnly && jb < jb1; ++jb) {
     const int buf = (jb - jb0) & 1;
     const bool more = jb < jlast;
-    const int j2 = min(jb + 2, jlast);
-    if (kStatesOnly) seg_total += cur.c63;
+    const int j1 = min(jb + 1, jlast), j2 = min(jb + 2, jlast);
+    const f32x4 sf = state_factors(jb);
     const uint16_t *const tC = sC[kStatesOnly ? 0 : buf], *const tG = sG[kStatesOnly ? 0 : buf], *const tBt = sBt[buf];
 
     Operand xo[4];  // Xm^T[row r][s = 16q + 8kg ..]
@@ -519,10 +615,15 @@ void chunk_scan_kernel(const ScanParams p) {
         }
         Y[0] = mfma(ho, co[kk & 1][0], Y[0]);
         Y[1] = mfma(ho, co[kk & 1][1], Y[1]);
-        stage_column(kk);
+        // the shared tiles (requested first, a whole iteration ago) go first, the own slice (requested
+        // last) as late as possible: two columns per group in the second half
         if (kk < 5) stage_tile(kk, buf ^ 1);
         if (kk == 5) load_part(1, j2);
         if (kk == 6) load_part(2, j2);
+        if (kk >= 4) {
+          stage_column(2 * (kk - 4));
+          stage_column(2 * (kk - 4) + 1);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
       // the masked product; alongside: x of this block leaves the raw copy, the raw rows of the next
@@ -542,8 +643,10 @@ void chunk_scan_kernel(const ScanParams p) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) xepi[i >> 1][i & 1] = lds16(raw_src + 32 * (i >> 1) * kRawStride + 8 * (i & 1)).q;
         }
-        if (q == 1) stage_raw();
-        if (q == 2) load_part(0, j2);
+        if (q == 1) {
+          stage_raw();
+          load_part(0, j2);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     } else {
@@ -556,7 +659,7 @@ void chunk_scan_kernel(const ScanParams p) {
     //      epilogue of the block (y[l][col] = rowf_l Y + D x; element i of the lane is column
     //      32ph + 16kg + i), one quarter per group ----
     const Rsrc ry = y_rsrc(jb);
-    const float rowf[2] = {cur.rowf0, cur.rowf1};
+    const float rowf[2] = {rowf0, rowf1};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       if (q < 3) {
@@ -594,12 +697,9 @@ void chunk_scan_kernel(const ScanParams p) {
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    // ---- next block's scalars become current ----
-    const float d1 = cur.mid_to_end;
-    cur = nxt;
-    // after the last block only the way to the end of that block is left: no next-block factor
-    pending = more ? d1 * cur.start_to_mid : d1;
-    nxt = load_scalars(j2);
+    // to the middle of the next block; after the last block only the way to its end is left
+    pending = more ? sf.w : sf.x;
+    load_rowf(j1);  // after their last use: the registers are simply reused
     __syncthreads();  // block jb's tiles may be overwritten; block jb+1's tiles are visible
   }
 #pragma unroll
@@ -626,19 +726,38 @@ void chunk_scan_kernel(const ScanParams p) {
 }
 
 // ---- segment_pass: slot[0] = h0; slot[sg] = exp2(decay[sg-1]) * slot[sg-1] + local[sg-1] --------
-// grid (P*N/256, Bt*H).  seg_state slot sg (sg >= 1) holds the local end state of segment sg-1 on
-// entry and the state entering segment sg on exit.
+// grid (P*N/1024, Bt*H), four consecutive state elements per thread.  seg_state slot sg (sg >= 1)
+// holds the local end state of segment sg-1 on entry and the state entering segment sg on exit.
+// The chain over segments is serial, but the loads do not depend on it: they are issued eight
+// segments at a time before the chain consumes them, so the kernel pays a few memory round trips
+// instead of one per segment.
 __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restrict__ seg_state,
                                                                 const float *__restrict__ seg_decay,
                                                                 const float *__restrict__ h0, int S) {
-  const int e = blockIdx.x * kThreads + threadIdx.x;
+  constexpr int kAhead = 8;
+  const int e = (blockIdx.x * kThreads + threadIdx.x) * 4;
   const size_t bh = blockIdx.y;
-  float run = h0 ? h0[bh * kP * kN + e] : 0.f;
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+  if (h0) run = *reinterpret_cast<const f32x4 *>(h0 + bh * kP * kN + e);
   float *sp = seg_state + bh * S * kP * kN + e;
-  sp[0] = run;
-  for (int sg = 1; sg < S; ++sg) {
-    run = fast_exp2(seg_decay[bh * S + sg - 1]) * run + sp[static_cast<size_t>(sg) * kP * kN];
-    sp[static_cast<size_t>(sg) * kP * kN] = run;
+  *reinterpret_cast<f32x4 *>(sp) = run;
+  for (int s0 = 1; s0 < S; s0 += kAhead) {
+    f32x4 v[kAhead];
+    float d[kAhead];
+#pragma unroll
+    for (int k = 0; k < kAhead; ++k) {
+      const int sg = min(s0 + k, S - 1);  // clamped: the surplus loads of the last group are not used
+      v[k] = *reinterpret_cast<const f32x4 *>(sp + static_cast<size_t>(sg) * kP * kN);
+      d[k] = seg_decay[bh * S + sg - 1];
+    }
+#pragma unroll
+    for (int k = 0; k < kAhead; ++k) {
+      if (s0 + k < S) {
+        const float f = fast_exp2(d[k]);
+        run = f32x4{f * run.x + v[k].x, f * run.y + v[k].y, f * run.z + v[k].z, f * run.w + v[k].w};
+        *reinterpret_cast<f32x4 *>(sp + static_cast<size_t>(s0 + k) * kP * kN) = run;
+      }
+    }
   }
 }
 
@@ -721,13 +840,12 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
   const int seg_blocks = choose_seg_blocks(d);
   const int S = (w.NB + seg_blocks - 1) / seg_blocks;
 
-  hipLaunchKernelGGL(scores_bt_kernel, dim3(w.NB, d.Bt * d.G), dim3(kThreads), 0, stream,
-                     static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(C), Gd, Btr, d.T, d.G,
-                     w.NB);
-  trace_mark(trace, stream, "scores_bt");
-  hipLaunchKernelGGL(block_cumsum_kernel, dim3(w.NB, (d.H + kCumHeads - 1) / kCumHeads, d.Bt), dim3(kThreads),
-                     0, stream, dt, A, prep, d.T, d.H, w.NB);
-  trace_mark(trace, stream, "block_cumsum");
+  const int n_scores = w.NB * d.Bt * d.G;
+  const int n_cumsum = w.NB * ((d.H + kCumHeads - 1) / kCumHeads) * d.Bt;
+  hipLaunchKernelGGL(block_prep_kernel, dim3(n_scores + n_cumsum), dim3(kThreads), 0, stream,
+                     static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(C), Gd, Btr, dt, A, prep,
+                     d.T, d.H, d.G, w.NB, n_scores);
+  trace_mark(trace, stream, "block_prep");
 
   ScanParams p;
   p.x = static_cast<const uint8_t *>(x);
@@ -752,7 +870,7 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
     p.hin_bh_stride = 0;
     hipLaunchKernelGGL((chunk_scan_kernel<true>), dim3(d.H / kHeadsPerWg, S - 1, d.Bt), dim3(kScanThreads), 0, stream, p);
     trace_mark(trace, stream, "segment_states");
-    hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / kThreads, d.Bt * d.H), dim3(kThreads), 0, stream,
+    hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), d.Bt * d.H), dim3(kThreads), 0, stream,
                        seg_state, seg_decay, h0, S);
     trace_mark(trace, stream, "segment_pass");
     p.Hin = seg_state;
