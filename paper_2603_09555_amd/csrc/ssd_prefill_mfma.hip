@@ -271,6 +271,12 @@ __device__ __forceinline__ void buf_store16(Rsrc r, uint32_t voff, u32x4 v) {
   __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, 0);
 }
 
+// Waits until no vector memory operation of the wave is outstanding.  Used once, at the end of a
+// loop prologue: the compiler places its waits for the worst case over all paths into a loop, and the
+// order in which a prologue happened to request its loads would otherwise dictate (too strict) waits
+// to every iteration.  (vmcnt = 0, expcnt and lgkmcnt not waited for.)
+__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // The MFMA writes row m of a 32-row result to lane group kg = (m >> 2) & 1, element 4 (m >> 3) + (m & 3).
 // Giving MFMA row m the headdim column pi(m) = 16 kg + element makes every lane own 16 consecutive
 // columns of its token: 32 contiguous bytes of y per lane instead of four 8-byte pieces.
@@ -349,9 +355,9 @@ void chunk_scan_kernel(const ScanParams p) {
 
   // ---- data of a block in flight (registers) ----
   u32x4 r_c[2], r_bt[2], r_g;  // shared tiles: this thread's 16-byte pieces
-  // own slice: 4 tokens x 8 columns, and the input factors of the 4 tokens (fp32 bits).  The
-  // states-only kernel has registers to spare and keeps two blocks of them in flight.
-  constexpr int kSets = kStatesOnly ? 2 : 1;
+  // own slice: 4 tokens x 8 columns, and the input factors of the 4 tokens (fp32 bits); two blocks
+  // of them are in flight (x comes from HBM and is the stream that must never run dry)
+  constexpr int kSets = 2;
   u32x4 r_x[kSets][4];
   u32x4 r_f[kSets];
 
@@ -416,10 +422,10 @@ void chunk_scan_kernel(const ScanParams p) {
       }
     }
   };
-  auto stage_raw = [&]() {  // the unscaled rows, for the skip term of the block's epilogue
+  auto stage_raw = [&](int set = 0) __attribute__((always_inline)) {  // the unscaled rows, for the skip term of the block's epilogue
     if constexpr (!kStatesOnly) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(raw_dst + i * kRawStride) = r_x[0][i];
+      for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(raw_dst + i * kRawStride) = r_x[set][i];
     }
   };
 
@@ -478,6 +484,9 @@ void chunk_scan_kernel(const ScanParams p) {
   const uint32_t a_g1 = 32 * kGLowStride + r * kGStride + 8 * kg;     // token 32 + r, + 16 q
   const uint32_t a_bt = r * kBtStride + 8 * kg;  // + 32 nt rows, + 16 q
   const uint16_t *const raw_src = myRaw + r * kRawStride + 16 * kg;   // + 32 rows for the second half, + 8 c
+  uint16_t *const raw_rw = myRaw + r * kRawStride + 16 * kg;
+  const uint16_t *const raw_dst_row = myRaw + (lane >> 2) * kRawStride + 8 * (lane & 3);  // row layout: token lane/4 (+16k)
+  const uint32_t vy = static_cast<uint32_t>(lane >> 2) * xrow + xcol + 16 * (lane & 3);
   auto lds16 = [](const uint16_t *ptr) {
     Operand o;
     o.q = *reinterpret_cast<const u32x4 *>(ptr);
@@ -511,6 +520,7 @@ void chunk_scan_kernel(const ScanParams p) {
       load_part(1, at(jb0 + 1));
       load_part(0, at(jb0 + 2), 0);
     }
+    wait_all_loads();
     __syncthreads();
     auto body = [&](int par, int jb) __attribute__((always_inline)) {
       const int buf = par, set = par ^ 1;  // block jb sits in LDS buffer `par`; block jb+1 in register set par^1
@@ -547,45 +557,55 @@ void chunk_scan_kernel(const ScanParams p) {
       pending = jb < jlast ? sf.w : sf.x;  // to the middle of the next block, or to the end of the last one
       __syncthreads();
     };
-    for (int jb = jb0; jb < jb1; jb += 2) {
+    // pairs of blocks, then the odd one: with the test between the two halves of a pair the compiler
+    // would also have to allow for "first half, then first half again", where the set staged at the
+    // top has only just been requested, and would wait for the newest loads in every iteration
+    int jb = jb0;
+    for (; jb + 1 < jb1; jb += 2) {
       body(0, jb);
-      if (jb + 1 < jb1) body(1, jb + 1);
+      body(1, jb + 1);
     }
+    if (jb < jb1) body(0, jb);
   }
-  if (!kStatesOnly && jb0 < jb1) {
-    // ---- prologue: block jb0 into LDS buffer 0; block jb0+1 in flight ----
+  if constexpr (!kStatesOnly) {
+    auto at = [&](int j) { return min(j, jlast); };
+    if (jb0 < jb1) {
+      // ---- prologue: block jb0 into LDS buffer 0; blocks jb0+1 and jb0+2 in flight ----
 #pragma unroll
-    for (int part = 0; part < 3; ++part) load_part(part, jb0);
+      for (int part = 0; part < 3; ++part) load_part(part, jb0, 0);
 #pragma unroll
-    for (int c = 0; c < 8; ++c) stage_column(c);
+      for (int c = 0; c < 8; ++c) stage_column(c, 0);
 #pragma unroll
-    for (int piece = 0; piece < 5; ++piece) stage_tile(piece, 0);
-    stage_raw();
-    // block jb0+1 is requested in the order the loop requests blocks (shared tiles, own slice, row
-    // factors): the compiler derives its waits from the order of outstanding loads, and they stay
-    // exact only if the path into the loop and the path around it agree on that order
-    load_part(1, min(jb0 + 1, jlast));
-    load_part(2, min(jb0 + 1, jlast));
-    load_part(0, min(jb0 + 1, jlast));
-    load_rowf(jb0);
-  }
-  __syncthreads();
+      for (int piece = 0; piece < 5; ++piece) stage_tile(piece, 0);
+      stage_raw(0);
+      // the following blocks are requested in the order the loop requests blocks (shared tiles, own
+      // slices, row factors): the compiler derives its waits from the order of outstanding loads,
+      // and they stay exact only if the path into the loop and the path around it agree on it
+      load_part(1, at(jb0 + 1));
+      load_part(2, at(jb0 + 1));
+      load_part(0, at(jb0 + 1), 1);
+      load_part(0, at(jb0 + 2), 0);
+      load_rowf(jb0);
+    }
+    wait_all_loads();
+    __syncthreads();
 
-  for (int jb = jb0; !kStatesOnly && jb < jb1; ++jb) {
-    const int buf = (jb - jb0) & 1;
-    const bool more = jb < jlast;
-    const int j1 = min(jb + 1, jlast), j2 = min(jb + 2, jlast);
-    const f32x4 sf = state_factors(jb);
-    const uint16_t *const tC = sC[kStatesOnly ? 0 : buf], *const tG = sG[kStatesOnly ? 0 : buf], *const tBt = sBt[buf];
+    // One block.  `par` is the parity of the block inside the segment, a compile-time constant (two
+    // iterations are written out per loop trip): block jb sits in LDS buffer par, block jb+1 in
+    // register set par^1 (it is staged during this iteration, and the set then refilled with block
+    // jb+3), block jb+2 in register set par.
+    auto body = [&](int par, int jb) __attribute__((always_inline)) {
+      const int buf = par, setA = par ^ 1;
+      const bool more = jb < jlast;
+      const f32x4 sf = state_factors(jb);
+      const uint16_t *const tC = sC[buf], *const tG = sG[buf], *const tBt = sBt[buf];
 
-    Operand xo[4];  // Xm^T[row r][s = 16q + 8kg ..]
+      Operand xo[4];  // Xm^T[row r][s = 16q + 8kg ..]
 #pragma unroll
-    for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
-    Operand bto[2][4];  // operands of the state update, double buffered over q
-    f32x16 Y[2] = {};
-    u32x4 xepi[2][2];   // x in output layout for the skip term: token r + 32lt, columns 32ph + 16kg .. +15
+      for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
+      Operand bto[2][4];  // operands of the state update, double buffered over q
+      f32x16 Y[2] = {};
 
-    if constexpr (!kStatesOnly) {
       // ---- phase 1: Y^T[row][l] = sum_n Ht[row][n] C[l][n]  +  sum_{s<=l} Xm[s][row] G[l][s];
       //      alongside, the next block moves from registers to the other LDS buffer, and as soon as
       //      the registers of its shared tiles are free the tiles of block jb+2 are requested ----
@@ -615,19 +635,15 @@ void chunk_scan_kernel(const ScanParams p) {
         }
         Y[0] = mfma(ho, co[kk & 1][0], Y[0]);
         Y[1] = mfma(ho, co[kk & 1][1], Y[1]);
-        // the shared tiles (requested first, a whole iteration ago) go first, the own slice (requested
-        // last) as late as possible: two columns per group in the second half
         if (kk < 5) stage_tile(kk, buf ^ 1);
-        if (kk == 5) load_part(1, j2);
-        if (kk == 6) load_part(2, j2);
-        if (kk >= 4) {
-          stage_column(2 * (kk - 4));
-          stage_column(2 * (kk - 4) + 1);
-        }
+        if (kk == 5) load_part(1, at(jb + 2));
+        if (kk == 6) load_part(2, at(jb + 2));
+        stage_column(kk, setA);
         __builtin_amdgcn_sched_barrier(0);
       }
-      // the masked product; alongside: x of this block leaves the raw copy, the raw rows of the next
-      // block replace it (LDS operations of a wave execute in order), and x of block jb+2 is requested
+      // the masked product
+      u32x4 xe[2];  // x of the block in output layout (token r + 32lt, columns 32ph + 16kg + 8c ..), read
+                    // from the raw copy one epilogue quarter ahead of its use
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         if (q < 3) {
@@ -636,71 +652,69 @@ void chunk_scan_kernel(const ScanParams p) {
         } else {
 #pragma unroll
           for (int nt = 0; nt < 4; ++nt) bto[0][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride);
+          xe[0] = lds16(raw_src).q;
         }
         if (q < 2) Y[0] = mfma(xo[q], go[q & 1][0], Y[0]);
         Y[1] = mfma(xo[q], go[q & 1][1], Y[1]);
-        if (q == 0) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) xepi[i >> 1][i & 1] = lds16(raw_src + 32 * (i >> 1) * kRawStride + 8 * (i & 1)).q;
-        }
-        if (q == 1) {
-          stage_raw();
-          load_part(0, j2);
-        }
         __builtin_amdgcn_sched_barrier(0);
       }
-    } else {
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt) bto[0][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride);
-      __builtin_amdgcn_sched_barrier(0);
-    }
 
-    // ---- phase 2: H'^T[n][col] = Ht^T[n][col] + sum_s B^T[n][s] Xm[s][col]; alongside, the output
-    //      epilogue of the block (y[l][col] = rowf_l Y + D x; element i of the lane is column
-    //      32ph + 16kg + i), one quarter per group ----
-    const Rsrc ry = y_rsrc(jb);
-    const float rowf[2] = {rowf0, rowf1};
+      // ---- phase 2: H'^T[n][col] = Ht^T[n][col] + sum_s B^T[n][s] Xm[s][col]; alongside, the output
+      //      epilogue of the block (y[l][col] = rowf_l Y + D x; element i of the lane is column
+      //      32ph + 16kg + i), one quarter per group ----
+      const Rsrc ry = y_rsrc(jb);
+      const float rowf[2] = {rowf0, rowf1};
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (q < 3) {
+      for (int q = 0; q < 4; ++q) {
+        if (q < 3) {
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) bto[(q + 1) & 1][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * (q + 1));
-      }
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt) {
-        if (kStatesOnly && q == 0) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) Hacc[nt][i] *= pending;
+          for (int nt = 0; nt < 4; ++nt) bto[(q + 1) & 1][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * (q + 1));
+          xe[(q + 1) & 1] = lds16(raw_src + 32 * ((q + 1) >> 1) * kRawStride + 8 * ((q + 1) & 1)).q;
         }
-        Hacc[nt] = mfma(bto[q & 1][nt], xo[q], Hacc[nt]);
-      }
-      if constexpr (!kStatesOnly) {
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) Hacc[nt] = mfma(bto[q & 1][nt], xo[q], Hacc[nt]);
         const int lt = q >> 1, c = q & 1;
         const f32x16 &Yt = Y[lt];
-        const u32x4 xv = xepi[lt][c];
+        const u32x4 xv = xe[q & 1];
         u32x4 o;
 #pragma unroll
         for (int w = 0; w < 4; ++w)
           o[w] = pack2(rowf[lt] * Yt[8 * c + 2 * w] + Dh * bf_lo(xv[w]),
                        rowf[lt] * Yt[8 * c + 2 * w + 1] + Dh * bf_hi(xv[w]));
-        buf_store16(ry, ve[lt] + 16 * c, o);  // tokens beyond the sequence are beyond the descriptor: dropped
-      } else {
-        // states only: the next block is staged here (two columns per group), its successor requested last
-        stage_column(2 * q);
-        stage_column(2 * q + 1);
-        if (q < 2) stage_tile(q, buf ^ 1);
-        if (q == 3) {
-          load_part(0, j2);
-          load_part(1, j2);
-        }
+        // the quarter replaces, in place, the x it was computed from: y leaves through the raw copy
+        *reinterpret_cast<u32x4 *>(raw_rw + 32 * lt * kRawStride + 8 * c) = o;
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
-    }
 
-    // to the middle of the next block; after the last block only the way to its end is left
-    pending = more ? sf.w : sf.x;
-    load_rowf(j1);  // after their last use: the registers are simply reused
-    __syncthreads();  // block jb's tiles may be overwritten; block jb+1's tiles are visible
+      // ---- y goes out in row layout: lane i stores 16 bytes of token i/4 + 16k, four lanes cover the
+      //      wave's 64 bytes of a token, so every request is a whole 64-byte piece of a row (the
+      //      output layout of the MFMA would give 32-byte pieces, which the memory system handles much
+      //      worse next to the concurrent reads of x).  Tokens beyond the sequence are beyond the
+      //      descriptor and are dropped.  Then the raw rows of the next block replace this block's (LDS
+      //      operations of a wave execute in order), and its register set is refilled. ----
+      {
+        u32x4 yo[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) yo[k] = *reinterpret_cast<const u32x4 *>(raw_dst_row + 16 * k * kRawStride);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) buf_store16(ry, vy + static_cast<uint32_t>(16 * k) * xrow, yo[k]);
+      }
+      stage_raw(setA);
+      load_part(0, at(jb + 3), setA);
+      // to the middle of the next block; after the last block only the way to its end is left
+      pending = more ? sf.w : sf.x;
+      load_rowf(at(jb + 1));  // after their last use: the registers are simply reused
+      __syncthreads();  // block jb's tiles may be overwritten; block jb+1's tiles are visible
+    };
+    // pairs of blocks, then the odd one: with the test between the two halves of a pair the compiler
+    // would also have to allow for "first half, then first half again", where the set staged at the
+    // top has only just been requested, and would wait for the newest loads in every iteration
+    int jb = jb0;
+    for (; jb + 1 < jb1; jb += 2) {
+      body(0, jb);
+      body(1, jb + 1);
+    }
+    if (jb < jb1) body(0, jb);
   }
 #pragma unroll
   for (int nt = 0; nt < 4; ++nt)
