@@ -436,13 +436,16 @@ void chunk_scan_kernel(const ScanParams p) {
   auto state_factors = [&](int jb) {
     return *reinterpret_cast<ConstVec4>(reinterpret_cast<uintptr_t>(prep_bh + static_cast<size_t>(jb) * kRec + 2 * kBlk));
   };
-  // Output-row factors of this lane's two tokens (r, 32 + r) of block jb.
-  float rowf0 = 0.f, rowf1 = 0.f;
+  // Output-row factors of this lane's two tokens (r, 32 + r): of the current block, and of the next
+  // one.  The next block's are requested early in an iteration, BEFORE the stores of y and the loads
+  // of x: vector memory operations complete in order, so a small load issued after them could only be
+  // waited for together with them.
+  float rowf0 = 0.f, rowf1 = 0.f, rowf0n = 0.f, rowf1n = 0.f;
   auto load_rowf = [&](int jb) __attribute__((always_inline)) {
     if constexpr (!kStatesOnly) {
       const float *rec = prep_bh + static_cast<size_t>(jb) * kRec;
-      rowf0 = rec[r];
-      rowf1 = rec[32 + r];
+      rowf0n = rec[r];
+      rowf1n = rec[32 + r];
     }
   };
 
@@ -504,14 +507,29 @@ void chunk_scan_kernel(const ScanParams p) {
   // in the second); the scheduling fences keep the compiler from undoing that order.
   const int jlast = jb1 - 1;
   if constexpr (kStatesOnly) {
-    // ---- states only: H' = Ht + B^T Xm per block, nothing else.  The kernel is a pure stream of x
-    //      (plus the shared B^T tile), so x is requested two blocks ahead: block k's iteration stages
-    //      block k+1 from one register set and then refills that set with block k+3.  Two iterations
-    //      are written out per loop trip so that the set index is a compile-time constant. ----
+    // ---- states only: the segment's end state from a zero start, H = sum_s w_s x_s (x) B_s with
+    //      w_s = dt_s * (decay from token s to the END OF THE SEGMENT).  Taking the weights relative
+    //      to the segment end (every exponent <= 0: nothing overflows, what has decayed away
+    //      underflows to zero as it should) means the accumulators are never rescaled: per block only
+    //      H += B^T Xm.  w_s = f_s * (middle -> end of its block) * exp2(decay of the blocks after it).
+    //      The kernel is a pure stream of x (plus the shared B^T tile), so x is requested two blocks
+    //      ahead: block k's iteration stages block k+1 from one register set and then refills that set
+    //      with block k+3.  Two iterations are written out per loop trip so that the set index is a
+    //      compile-time constant. ----
     auto at = [&](int j) { return min(j, jlast); };
+    for (int j = jb0; j < jb1; ++j) seg_total += state_factors(j).z;
+    float rest = seg_total;  // log2 decay of the blocks after the one being staged
+    auto weigh = [&](int j, int set) __attribute__((always_inline)) {
+      const f32x4 sfj = state_factors(j);
+      rest -= sfj.z;
+      const float ws = sfj.x * fast_exp2(rest);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r_f[set][i] = __float_as_uint(__uint_as_float(r_f[set][i]) * ws);
+    };
     if (jb0 < jb1) {
       load_part(0, jb0, 0);
       load_part(1, jb0);
+      weigh(jb0, 0);
 #pragma unroll
       for (int c = 0; c < 8; ++c) stage_column(c, 0);
       stage_tile(0, 0);
@@ -524,8 +542,6 @@ void chunk_scan_kernel(const ScanParams p) {
     __syncthreads();
     auto body = [&](int par, int jb) __attribute__((always_inline)) {
       const int buf = par, set = par ^ 1;  // block jb sits in LDS buffer `par`; block jb+1 in register set par^1
-      const f32x4 sf = state_factors(jb);
-      seg_total += sf.z;
       const uint16_t *const tBt = sBt[buf];
       Operand xo[4], bto[2][4];
 #pragma unroll
@@ -540,13 +556,8 @@ void chunk_scan_kernel(const ScanParams p) {
           for (int nt = 0; nt < 4; ++nt) bto[(q + 1) & 1][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * (q + 1));
         }
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-          if (q == 0) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) Hacc[nt][i] *= pending;
-          }
-          Hacc[nt] = mfma(bto[q & 1][nt], xo[q], Hacc[nt]);
-        }
+        for (int nt = 0; nt < 4; ++nt) Hacc[nt] = mfma(bto[q & 1][nt], xo[q], Hacc[nt]);
+        if (q == 0) weigh(at(jb + 1), set);
         stage_column(2 * q, set);
         stage_column(2 * q + 1, set);
         if (q < 2) stage_tile(q, buf ^ 1);
@@ -554,7 +565,6 @@ void chunk_scan_kernel(const ScanParams p) {
         if (q == 3) load_part(0, at(jb + 3), set);
         __builtin_amdgcn_sched_barrier(0);
       }
-      pending = jb < jlast ? sf.w : sf.x;  // to the middle of the next block, or to the end of the last one
       __syncthreads();
     };
     // pairs of blocks, then the odd one: with the test between the two halves of a pair the compiler
@@ -588,6 +598,8 @@ void chunk_scan_kernel(const ScanParams p) {
       load_rowf(jb0);
     }
     wait_all_loads();
+    rowf0 = rowf0n;
+    rowf1 = rowf1n;
     __syncthreads();
 
     // One block.  `par` is the parity of the block inside the segment, a compile-time constant (two
@@ -636,6 +648,7 @@ void chunk_scan_kernel(const ScanParams p) {
         Y[0] = mfma(ho, co[kk & 1][0], Y[0]);
         Y[1] = mfma(ho, co[kk & 1][1], Y[1]);
         if (kk < 5) stage_tile(kk, buf ^ 1);
+        if (kk == 4) load_rowf(at(jb + 1));
         if (kk == 5) load_part(1, at(jb + 2));
         if (kk == 6) load_part(2, at(jb + 2));
         stage_column(kk, setA);
@@ -703,7 +716,8 @@ void chunk_scan_kernel(const ScanParams p) {
       load_part(0, at(jb + 3), setA);
       // to the middle of the next block; after the last block only the way to its end is left
       pending = more ? sf.w : sf.x;
-      load_rowf(at(jb + 1));  // after their last use: the registers are simply reused
+      rowf0 = rowf0n;
+      rowf1 = rowf1n;
       __syncthreads();  // block jb's tiles may be overwritten; block jb+1's tiles are visible
     };
     // pairs of blocks, then the odd one: with the test between the two halves of a pair the compiler
@@ -716,10 +730,12 @@ void chunk_scan_kernel(const ScanParams p) {
     }
     if (jb < jb1) body(0, jb);
   }
+  if constexpr (!kStatesOnly) {
 #pragma unroll
-  for (int nt = 0; nt < 4; ++nt)
+    for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) Hacc[nt][i] *= pending;
+      for (int i = 0; i < 16; ++i) Hacc[nt][i] *= pending;
+  }
 
   // ---- write the state out (canonical (p, n) layout, four consecutive n per 16-byte store) ----
   float *out = nullptr;
