@@ -296,21 +296,27 @@ __device__ __forceinline__ int pi_of_row(int m) { return 16 * ((m >> 2) & 1) + 4
 constexpr int kRawStride = 40;                       // raw x rows: 32 columns + 16 bytes, in bf16 elements
 constexpr int kGLowStride = 32 + 8;                  // G rows 0..31 keep only columns 0..31 (the rest is masked)
 constexpr int kGTile = 32 * kGLowStride + 32 * kGStride;  // elements of a compacted G tile
-template <bool kStatesOnly>
-__global__ __launch_bounds__(kScanThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// HPW = heads per workgroup (two waves each).  Both kernels take four heads: the full kernel's LDS tiles
+// fill the CU; the states-only kernel could run two smaller workgroups per CU, but its grid then no
+// longer divides evenly over the CUs and the measured time was worse.
+template <bool kStatesOnly, int HPW>
+__global__ __launch_bounds__(128 * HPW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void chunk_scan_kernel(const ScanParams p) {
+  static_assert(kStatesOnly || HPW == kHeadsPerWg, "the full kernel is written for four heads per workgroup");
+  constexpr int kThr = 128 * HPW;
+  constexpr int kBtPieces = kN * kBlk * 2 / 16 / kThr;  // 16-byte pieces of the B^T tile per thread
   __shared__ __align__(16) uint16_t sC[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kBlk * kCStride];
   __shared__ __align__(16) uint16_t sBt[2][kN * kBtStride];                   // B^T [n][s]
   __shared__ __align__(16) uint16_t sG[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kGTile];
-  __shared__ __align__(16) uint16_t sXm[kHeadsPerWg][kP * kXStride];          // Xm^T [row][s], per head
-  __shared__ __align__(16) uint16_t sRaw[kStatesOnly ? 1 : 2 * kHeadsPerWg][kStatesOnly ? 8 : kBlk * kRawStride];  // x [s][col], per wave
+  __shared__ __align__(16) uint16_t sXm[HPW][kP * kXStride];                  // Xm^T [row][s], per head
+  __shared__ __align__(16) uint16_t sRaw[kStatesOnly ? 1 : 2 * HPW][kStatesOnly ? 8 : kBlk * kRawStride];  // x [s][col], per wave
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: addresses derived from it stay scalar
   const int hw = wave >> 1, ph = wave & 1;  // head inside the workgroup, half of headdim
-  const int h = blockIdx.x * kHeadsPerWg + hw, sg = blockIdx.y, b = blockIdx.z;
-  const int g = (blockIdx.x * kHeadsPerWg) / p.hpg;  // the four heads share one group
+  const int h = blockIdx.x * HPW + hw, sg = blockIdx.y, b = blockIdx.z;
+  const int g = (blockIdx.x * HPW) / p.hpg;  // the heads of a workgroup share one group
   const size_t bh = static_cast<size_t>(b) * p.H + h;
   const size_t bg = static_cast<size_t>(b) * p.G + g;
   const int r = lane & 31, kg = lane >> 5;
@@ -343,7 +349,7 @@ void chunk_scan_kernel(const ScanParams p) {
   for (int i = 0; i < 4; ++i) vx[i] = static_cast<uint32_t>(4 * tg + i) * xrow + xcol + 16 * cg;
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
-    const int c = tid + kScanThreads * k;
+    const int c = tid + kThr * k;
     vc[k] = static_cast<uint32_t>(c >> 4) * crow + 16 * (c & 15);
     ve[k] = static_cast<uint32_t>(r + 32 * k) * xrow + xcol + 32 * kg;  // output layout: token r + 32k, 32 bytes
   }
@@ -354,7 +360,7 @@ void chunk_scan_kernel(const ScanParams p) {
   const uint32_t vg = static_cast<uint32_t>(g_row * kBlk + 8 * g_pc) * 2;
 
   // ---- data of a block in flight (registers) ----
-  u32x4 r_c[2], r_bt[2], r_g;  // shared tiles: this thread's 16-byte pieces
+  u32x4 r_c[2], r_bt[kBtPieces], r_g;  // shared tiles: this thread's 16-byte pieces
   // own slice: 4 tokens x 8 columns, and the input factors of the 4 tokens (fp32 bits); two blocks
   // of them are in flight (x comes from HBM and is the stream that must never run dry)
   constexpr int kSets = 2;
@@ -370,7 +376,7 @@ void chunk_scan_kernel(const ScanParams p) {
       r_f[set] = buf_load16(rs_prep, vf, jb * (kRec * 4));
     } else if (part == 1) {
 #pragma unroll
-      for (int k = 0; k < 2; ++k) r_bt[k] = buf_load16(rs_bt, vt, jb * (kN * kBlk * 2) + k * (kScanThreads * 16));
+      for (int k = 0; k < kBtPieces; ++k) r_bt[k] = buf_load16(rs_bt, vt, jb * (kN * kBlk * 2) + k * (kThr * 16));
     } else if (!kStatesOnly) {
       const Rsrc rc = c_rsrc(jb);
 #pragma unroll
@@ -380,11 +386,15 @@ void chunk_scan_kernel(const ScanParams p) {
   };
 
   // LDS destinations of this thread's pieces (fixed)
-  uint32_t lds_bt[2], lds_c[2];
+  uint32_t lds_bt[kBtPieces], lds_c[2];
+#pragma unroll
+  for (int k = 0; k < kBtPieces; ++k) {
+    const int c = tid + kThr * k;
+    lds_bt[k] = (c >> 3) * kBtStride + 8 * (c & 7);
+  }
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
-    const int c = tid + kScanThreads * k;
-    lds_bt[k] = (c >> 3) * kBtStride + 8 * (c & 7);
+    const int c = tid + kThr * k;
     // C columns are permuted inside each group of 16 so that one 16-byte read yields
     // n-offsets {4kg..4kg+3, 8+4kg..8+4kg+3}
     lds_c[k] = (c >> 4) * kCStride + 16 * ((c & 15) >> 1) + 4 * (c & 1);
@@ -532,8 +542,8 @@ void chunk_scan_kernel(const ScanParams p) {
       weigh(jb0, 0);
 #pragma unroll
       for (int c = 0; c < 8; ++c) stage_column(c, 0);
-      stage_tile(0, 0);
-      stage_tile(1, 0);
+#pragma unroll
+      for (int k = 0; k < kBtPieces; ++k) *reinterpret_cast<u32x4 *>(&sBt[0][lds_bt[k]]) = r_bt[k];
       load_part(0, at(jb0 + 1), 1);
       load_part(1, at(jb0 + 1));
       load_part(0, at(jb0 + 2), 0);
@@ -560,9 +570,15 @@ void chunk_scan_kernel(const ScanParams p) {
         if (q == 0) weigh(at(jb + 1), set);
         stage_column(2 * q, set);
         stage_column(2 * q + 1, set);
-        if (q < 2) stage_tile(q, buf ^ 1);
-        if (q == 2) load_part(1, at(jb + 2));
-        if (q == 3) load_part(0, at(jb + 3), set);
+        // the B^T pieces of block jb+1 spread over the groups; once the last one has left its
+        // register the tile of block jb+2 is requested, then the x of block jb+3
+#pragma unroll
+        for (int k = q * kBtPieces / 4; k < (q + 1) * kBtPieces / 4; ++k)
+          *reinterpret_cast<u32x4 *>(&sBt[buf ^ 1][lds_bt[k]]) = r_bt[k];
+        if (q == 3) {
+          load_part(1, at(jb + 2));
+          load_part(0, at(jb + 3), set);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
       __syncthreads();
@@ -898,7 +914,9 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
   if (S > 1) {
     p.Hin = nullptr;
     p.hin_bh_stride = 0;
-    hipLaunchKernelGGL((chunk_scan_kernel<true>), dim3(d.H / kHeadsPerWg, S - 1, d.Bt), dim3(kScanThreads), 0, stream, p);
+    constexpr int kStatesHeads = 4;  // heads per workgroup of the states-only kernel (2 was measured: slower)
+    hipLaunchKernelGGL((chunk_scan_kernel<true, kStatesHeads>), dim3(d.H / kStatesHeads, S - 1, d.Bt),
+                       dim3(128 * kStatesHeads), 0, stream, p);
     trace_mark(trace, stream, "segment_states");
     hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), d.Bt * d.H), dim3(kThreads), 0, stream,
                        seg_state, seg_decay, h0, S);
@@ -909,7 +927,8 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
     p.Hin = h0;
     p.hin_bh_stride = static_cast<size_t>(kP) * kN;
   }
-  hipLaunchKernelGGL((chunk_scan_kernel<false>), dim3(d.H / kHeadsPerWg, S, d.Bt), dim3(kScanThreads), 0, stream, p);
+  hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg>), dim3(d.H / kHeadsPerWg, S, d.Bt), dim3(kScanThreads), 0,
+                     stream, p);
   trace_mark(trace, stream, "chunk_scan");
   return hipGetLastError();
 }
