@@ -159,9 +159,9 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, int jb, int bg, co
 //   [0,64)     rowf_l = exp2(clamp(cs_l - c31))            output-row factor of the decay mask
 //   [64,128)   f_s    = dt_s * exp2(clamp(c31 - cs_s))     input factor of the decay mask
 //   [128]      exp2(c63 - c31)     state: middle of the block -> end of the block
-//   [129]      exp2(c31)           state: start of the block -> middle of the block
-//   [130]      c63                 log2 of the block's total decay
-//   [131]      [128] * [129] of the next block: middle of the block -> middle of the next block
+//   [129]      c63                 log2 of the block's total decay
+//   [130]      exp2(c31)           state: start of the block -> middle of the block
+//   [131]      [128] * [130] of the next block: middle of the block -> middle of the next block
 // Tokens beyond the sequence get dt = 0 (state-neutral padding).  dt is read in its
 // (batch, token, head) layout and transposed through LDS, 64 tokens of the block plus the first 32
 // of the next one (for [131]).
@@ -206,8 +206,8 @@ __device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1],
     rec[kBlk + lane] = dtv * fast_exp2(fminf(fmaxf(c31 - v, -kMaxExp), kMaxExp));
     if (lane < 4)
       rec[2 * kBlk + lane] = lane == 0   ? fast_exp2(c63 - c31)
-                             : lane == 1 ? fast_exp2(c31)
-                             : lane == 2 ? c63
+                             : lane == 1 ? c63
+                             : lane == 2 ? fast_exp2(c31)
                                          : fast_exp2(c63 - c31) * fast_exp2(nx);
   }
 }
@@ -439,13 +439,11 @@ void chunk_scan_kernel(const ScanParams p) {
     }
   };
 
-  // Per-block state factors {mid -> end, start -> mid, log2 of the total decay, mid -> next mid}:
-  // uniform over the wave and read-only for this kernel, so they are fetched with scalar loads (the
-  // constant address space tells the compiler so) and never touch the vector memory queue.
-  typedef const __attribute__((address_space(4))) f32x4 *ConstVec4;
-  auto state_factors = [&](int jb) {
-    return *reinterpret_cast<ConstVec4>(reinterpret_cast<uintptr_t>(prep_bh + static_cast<size_t>(jb) * kRec + 2 * kBlk));
-  };
+  // Per-block state factors (record entries 128..131): uniform over the wave, but fetched with
+  // ordinary (broadcast) vector loads and requested well ahead of their use.  A scalar load would share
+  // its counter with the LDS operations and, returning out of order, turn every LDS wait into a wait
+  // for everything including the scalar load's trip to memory.
+  auto factor_ptr = [&](int jb) { return prep_bh + static_cast<size_t>(jb) * kRec + 2 * kBlk; };
   // Output-row factors of this lane's two tokens (r, 32 + r): of the current block, and of the next
   // one.  The next block's are requested early in an iteration, BEFORE the stores of y and the loads
   // of x: vector memory operations complete in order, so a small load issued after them could only be
@@ -489,7 +487,8 @@ void chunk_scan_kernel(const ScanParams p) {
   // from where the previous block left it (the middle of that block) to the middle of the current
   // block.  It is multiplied in eight elements at a time, right where those elements are converted
   // to an MFMA operand, so the multiplies hide under the matrix instructions of the same loop.
-  float pending = jb0 < jb1 ? state_factors(jb0).y : 1.f;
+  float pending = jb0 < jb1 && !kStatesOnly ? factor_ptr(jb0)[2] : 1.f;
+  asm volatile("" : "+v"(pending));  // arrived before the loop (see Dh above)
 
   // LDS operand addresses of this lane (element offsets inside a tile)
   const uint32_t a_c = r * kCStride + 8 * kg;    // + 32 rows for the second token half, + 16 kk
@@ -527,19 +526,33 @@ void chunk_scan_kernel(const ScanParams p) {
     //      with block k+3.  Two iterations are written out per loop trip so that the set index is a
     //      compile-time constant. ----
     auto at = [&](int j) { return min(j, jlast); };
-    for (int j = jb0; j < jb1; ++j) seg_total += state_factors(j).z;
+    for (int j = jb0; j < jb1; j += 64) {  // the segment's total log2 decay: one lane per block
+      float v = j + lane < jb1 ? factor_ptr(j + lane)[1] : 0.f;
+#pragma unroll
+      for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+      seg_total += v;
+    }
     float rest = seg_total;  // log2 decay of the blocks after the one being staged
-    auto weigh = [&](int j, int set) __attribute__((always_inline)) {
-      const f32x4 sfj = state_factors(j);
-      rest -= sfj.z;
-      const float ws = sfj.x * fast_exp2(rest);
+    // {middle -> end, log2 of the total decay} of the block to be staged next, fetched one iteration
+    // before it is used
+    f32x2 sf_stage = {1.f, 0.f};
+    float ws = 0.f;
+    auto next_weight = [&]() __attribute__((always_inline)) {
+      rest -= sf_stage.y;
+      ws = sf_stage.x * fast_exp2(rest);
+    };
+    auto load_factors = [&](int j) { return *reinterpret_cast<const f32x2 *>(factor_ptr(j)); };
+    auto weigh = [&](int set) __attribute__((always_inline)) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) r_f[set][i] = __float_as_uint(__uint_as_float(r_f[set][i]) * ws);
     };
     if (jb0 < jb1) {
       load_part(0, jb0, 0);
       load_part(1, jb0);
-      weigh(jb0, 0);
+      sf_stage = load_factors(jb0);
+      next_weight();
+      weigh(0);
+      sf_stage = load_factors(at(jb0 + 1));
 #pragma unroll
       for (int c = 0; c < 8; ++c) stage_column(c, 0);
 #pragma unroll
@@ -553,21 +566,24 @@ void chunk_scan_kernel(const ScanParams p) {
     auto body = [&](int par, int jb) __attribute__((always_inline)) {
       const int buf = par, set = par ^ 1;  // block jb sits in LDS buffer `par`; block jb+1 in register set par^1
       const uint16_t *const tBt = sBt[buf];
-      Operand xo[4], bto[2][4];
+      next_weight();                          // weight of block jb+1 from the factors fetched an iteration ago
+      sf_stage = load_factors(at(jb + 2));    // for the next iteration
+      // all twenty operands of the block are requested up front (this kernel has the registers): with
+      // eight waves reading at once an LDS read takes a few hundred cycles to come back, far more than
+      // the four matrix instructions of one group cover
+      Operand xo[4], bto[4][4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) bto[0][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride);
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) bto[q][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * q);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        if (q < 3) {
 #pragma unroll
-          for (int nt = 0; nt < 4; ++nt) bto[(q + 1) & 1][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * (q + 1));
-        }
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) Hacc[nt] = mfma(bto[q & 1][nt], xo[q], Hacc[nt]);
-        if (q == 0) weigh(at(jb + 1), set);
+        for (int nt = 0; nt < 4; ++nt) Hacc[nt] = mfma(bto[q][nt], xo[q], Hacc[nt]);
+        if (q == 0) weigh(set);
         stage_column(2 * q, set);
         stage_column(2 * q + 1, set);
         // the B^T pieces of block jb+1 spread over the groups; once the last one has left its
@@ -625,7 +641,7 @@ void chunk_scan_kernel(const ScanParams p) {
     auto body = [&](int par, int jb) __attribute__((always_inline)) {
       const int buf = par, setA = par ^ 1;
       const bool more = jb < jlast;
-      const f32x4 sf = state_factors(jb);
+      float pend_next = 0.f;
       const uint16_t *const tC = sC[buf], *const tG = sG[buf], *const tBt = sBt[buf];
 
       Operand xo[4];  // Xm^T[row r][s = 16q + 8kg ..]
@@ -664,15 +680,19 @@ void chunk_scan_kernel(const ScanParams p) {
         Y[0] = mfma(ho, co[kk & 1][0], Y[0]);
         Y[1] = mfma(ho, co[kk & 1][1], Y[1]);
         if (kk < 5) stage_tile(kk, buf ^ 1);
-        if (kk == 4) load_rowf(at(jb + 1));
+        if (kk == 4) {
+          load_rowf(at(jb + 1));
+          // to the middle of the next block; after the last block only the way to its end is left
+          pend_next = factor_ptr(jb)[more ? 3 : 0];
+        }
         if (kk == 5) load_part(1, at(jb + 2));
         if (kk == 6) load_part(2, at(jb + 2));
         stage_column(kk, setA);
         __builtin_amdgcn_sched_barrier(0);
       }
       // the masked product
-      u32x4 xe[2];  // x of the block in output layout (token r + 32lt, columns 32ph + 16kg + 8c ..), read
-                    // from the raw copy one epilogue quarter ahead of its use
+      u32x4 xe;  // x of the block in output layout (token r + 32lt, columns 32ph + 16kg + 8c ..), read from
+                 // the raw copy at the start of the group whose end uses it
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         if (q < 3) {
@@ -681,7 +701,6 @@ void chunk_scan_kernel(const ScanParams p) {
         } else {
 #pragma unroll
           for (int nt = 0; nt < 4; ++nt) bto[0][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride);
-          xe[0] = lds16(raw_src).q;
         }
         if (q < 2) Y[0] = mfma(xo[q], go[q & 1][0], Y[0]);
         Y[1] = mfma(xo[q], go[q & 1][1], Y[1]);
@@ -698,13 +717,13 @@ void chunk_scan_kernel(const ScanParams p) {
         if (q < 3) {
 #pragma unroll
           for (int nt = 0; nt < 4; ++nt) bto[(q + 1) & 1][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * (q + 1));
-          xe[(q + 1) & 1] = lds16(raw_src + 32 * ((q + 1) >> 1) * kRawStride + 8 * ((q + 1) & 1)).q;
         }
+        xe = lds16(raw_src + 32 * (q >> 1) * kRawStride + 8 * (q & 1)).q;
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) Hacc[nt] = mfma(bto[q & 1][nt], xo[q], Hacc[nt]);
         const int lt = q >> 1, c = q & 1;
         const f32x16 &Yt = Y[lt];
-        const u32x4 xv = xe[q & 1];
+        const u32x4 xv = xe;
         u32x4 o;
 #pragma unroll
         for (int w = 0; w < 4; ++w)
@@ -730,8 +749,7 @@ void chunk_scan_kernel(const ScanParams p) {
       }
       stage_raw(setA);
       load_part(0, at(jb + 3), setA);
-      // to the middle of the next block; after the last block only the way to its end is left
-      pending = more ? sf.w : sf.x;
+      pending = pend_next;
       rowf0 = rowf0n;
       rowf1 = rowf1n;
       __syncthreads();  // block jb's tiles may be overwritten; block jb+1's tiles are visible
