@@ -825,32 +825,35 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
   }
 }
 
-// Blocks per segment: a whole number of chunks.  One workgroup per CU is resident, so the cost of
-// a choice is (rounds of workgroups) x (blocks a workgroup walks, plus a fixed prologue), with the
-// extra states pass priced in when there is more than one segment.
+// Blocks per segment.  One workgroup per CU is resident, so the cost of a choice is (rounds of
+// workgroups) x (blocks a workgroup walks, plus a fixed prologue), with the extra states pass priced
+// in when there is more than one segment.  A segment is any whole number of 64-token blocks but at
+// least one chunk long (which bounds the number of segments, and with it the workspace, by the
+// number of chunks).  SSD_SEG_CHUNKS=k forces k chunks per segment (tests).
 constexpr int kNumCUs = 256;
 int choose_seg_blocks(const Dims &d) {
   const int chunk_blocks = d.L / kBlk;
-  const int nchunks = d.Nc;
-  int k = 0;
-  if (const char *e = std::getenv("SSD_SEG_CHUNKS")) k = std::atoi(e);
-  if (k < 1) {
-    const long groups = static_cast<long>(d.Bt) * (d.H / kHeadsPerWg);
-    double best = 0.0;
-    for (int cand = 1; cand <= nchunks; ++cand) {
-      const long segs = (nchunks + cand - 1) / cand;
-      if (cand > 1 && (nchunks + cand - 2) / (cand - 1) == segs) continue;  // same count, longer segments
-      const long rounds = (groups * segs + kNumCUs - 1) / kNumCUs;
-      const double cost = static_cast<double>(rounds) * (cand * chunk_blocks + 2) * (segs > 1 ? 1.35 : 1.0);
-      if (k == 0 || cost < best) {
-        best = cost;
-        k = cand;
-      }
+  const int nblocks = (d.T + kBlk - 1) / kBlk;
+  if (const char *e = std::getenv("SSD_SEG_CHUNKS")) {
+    const int k = std::atoi(e);
+    if (k >= 1) return (k > d.Nc ? d.Nc : k) * chunk_blocks;
+  }
+  const long groups = static_cast<long>(d.Bt) * (d.H / kHeadsPerWg);
+  int best_blocks = nblocks > chunk_blocks ? nblocks : chunk_blocks;
+  double best = 0.0;
+  bool have = false;
+  for (int cand = chunk_blocks; cand <= (nblocks > chunk_blocks ? nblocks : chunk_blocks); ++cand) {
+    const long segs = (nblocks + cand - 1) / cand;
+    if (cand > chunk_blocks && (nblocks + cand - 2) / (cand - 1) == segs) continue;  // same count, longer segments
+    const long rounds = (groups * segs + kNumCUs - 1) / kNumCUs;
+    const double cost = static_cast<double>(rounds) * (cand + 2) * (segs > 1 ? 1.35 : 1.0);
+    if (!have || cost < best) {
+      have = true;
+      best = cost;
+      best_blocks = cand;
     }
   }
-  if (k > nchunks) k = nchunks;
-  if (k < 1) k = 1;
-  return k * chunk_blocks;
+  return best_blocks;
 }
 
 struct Layout {
