@@ -250,7 +250,25 @@ struct ScanParams {
   float *seg_state;        // states-only: (Bt, H, S, P, N); local end state of segment sg -> slot sg+1
   float *seg_decay;        // states-only: (Bt, H, S) log2 of the segment's total decay
   int T, H, G, hpg, NB, seg_blocks, S;
+  int cols, segs, total, per_xcd;  // workgroup mapping, see wg_coords
 };
+
+// Workgroup -> (head group, segment, batch row).  The chip dispatches consecutive workgroup ids to
+// its eight XCDs in turn, and each XCD has its own L2.  The workgroups that share C / B^T / G tiles
+// (all head groups of one segment of one batch row) are therefore given ids that are congruent
+// modulo 8, so that they run on one XCD and the tiles are fetched into one L2 instead of eight:
+// XCD k owns the contiguous range [k * per_xcd, (k + 1) * per_xcd) of the (batch, segment, head
+// group) list, head group fastest.  Ids beyond the list (the grid is rounded up to 8 * per_xcd) idle.
+constexpr int kXcds = 8;
+__device__ __forceinline__ bool wg_coords(const ScanParams &p, int &col, int &sg, int &b) {
+  const int id = blockIdx.x;
+  const int w = (id % kXcds) * p.per_xcd + id / kXcds;
+  if (w >= p.total) return false;
+  col = w % p.cols;
+  sg = (w / p.cols) % p.segs;
+  b = w / (p.cols * p.segs);
+  return true;
+}
 
 constexpr int kHeadsPerWg = 4;
 constexpr int kScanThreads = 2 * 64 * kHeadsPerWg;  // two waves per head, one per half of headdim
@@ -315,8 +333,10 @@ void chunk_scan_kernel(const ScanParams p) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: addresses derived from it stay scalar
   const int hw = wave >> 1, ph = wave & 1;  // head inside the workgroup, half of headdim
-  const int h = blockIdx.x * HPW + hw, sg = blockIdx.y, b = blockIdx.z;
-  const int g = (blockIdx.x * HPW) / p.hpg;  // the heads of a workgroup share one group
+  int col, sg, b;
+  if (!wg_coords(p, col, sg, b)) return;  // uniform over the workgroup
+  const int h = col * HPW + hw;
+  const int g = (col * HPW) / p.hpg;  // the heads of a workgroup share one group
   const size_t bh = static_cast<size_t>(b) * p.H + h;
   const size_t bg = static_cast<size_t>(b) * p.G + g;
   const int r = lane & 31, kg = lane >> 5;
@@ -936,8 +956,12 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
     p.Hin = nullptr;
     p.hin_bh_stride = 0;
     constexpr int kStatesHeads = 4;  // heads per workgroup of the states-only kernel (2 was measured: slower)
-    hipLaunchKernelGGL((chunk_scan_kernel<true, kStatesHeads>), dim3(d.H / kStatesHeads, S - 1, d.Bt),
-                       dim3(128 * kStatesHeads), 0, stream, p);
+    p.cols = d.H / kStatesHeads;
+    p.segs = S - 1;
+    p.total = p.cols * p.segs * d.Bt;
+    p.per_xcd = (p.total + kXcds - 1) / kXcds;
+    hipLaunchKernelGGL((chunk_scan_kernel<true, kStatesHeads>), dim3(kXcds * p.per_xcd), dim3(128 * kStatesHeads), 0,
+                       stream, p);
     trace_mark(trace, stream, "segment_states");
     hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), d.Bt * d.H), dim3(kThreads), 0, stream,
                        seg_state, seg_decay, h0, S);
@@ -948,8 +972,11 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
     p.Hin = h0;
     p.hin_bh_stride = static_cast<size_t>(kP) * kN;
   }
-  hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg>), dim3(d.H / kHeadsPerWg, S, d.Bt), dim3(kScanThreads), 0,
-                     stream, p);
+  p.cols = d.H / kHeadsPerWg;
+  p.segs = S;
+  p.total = p.cols * p.segs * d.Bt;
+  p.per_xcd = (p.total + kXcds - 1) / kXcds;
+  hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0, stream, p);
   trace_mark(trace, stream, "chunk_scan");
   return hipGetLastError();
 }
