@@ -845,12 +845,24 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
   }
 }
 
-// Blocks per segment.  One workgroup per CU is resident, so the cost of a choice is (rounds of
-// workgroups) x (blocks a workgroup walks, plus a fixed prologue), with the extra states pass priced
-// in when there is more than one segment.  A segment is any whole number of 64-token blocks but at
-// least one chunk long (which bounds the number of segments, and with it the workspace, by the
-// number of chunks).  SSD_SEG_CHUNKS=k forces k chunks per segment (tests).
+// Blocks per segment.  A segment is any whole number of 64-token blocks but at least one chunk long
+// (which bounds the number of segments, and with it the workspace, by the number of chunks).  The
+// choice minimises a small cost model fitted to measurements on MI355X (microseconds): one workgroup
+// per CU is resident, workgroups run in rounds of 256, a workgroup walks its blocks (plus a prologue
+// worth about two) at a per-block time that grows with the number of workgroups competing for
+// memory, and more than one segment costs the states pass (same structure, cheaper blocks), the
+// serial pass over segment states (traffic proportional to segments x sequences) and two launches.
+// SSD_SEG_CHUNKS=k forces k chunks per segment (tests), SSD_SEG_BLOCKS=k forces k blocks (tuning).
 constexpr int kNumCUs = 256;
+double rounds_time(long wgs, int blocks, double t_idle, double t_busy) {
+  double t = 0.0;
+  for (long left = wgs; left > 0; left -= kNumCUs) {
+    const double n = static_cast<double>(left < kNumCUs ? left : kNumCUs);
+    const double load = n < 192.0 ? n / 192.0 : 1.0;
+    t += (blocks + 2) * (t_idle + (t_busy - t_idle) * load);
+  }
+  return t;
+}
 int choose_seg_blocks(const Dims &d) {
   const int chunk_blocks = d.L / kBlk;
   const int nblocks = (d.T + kBlk - 1) / kBlk;
@@ -858,15 +870,21 @@ int choose_seg_blocks(const Dims &d) {
     const int k = std::atoi(e);
     if (k >= 1) return (k > d.Nc ? d.Nc : k) * chunk_blocks;
   }
+  if (const char *e = std::getenv("SSD_SEG_BLOCKS")) {
+    const int k = std::atoi(e);
+    if (k >= chunk_blocks) return k;
+  }
   const long groups = static_cast<long>(d.Bt) * (d.H / kHeadsPerWg);
-  int best_blocks = nblocks > chunk_blocks ? nblocks : chunk_blocks;
+  const double seqs = static_cast<double>(d.Bt) * d.H;
+  const int hi = nblocks > chunk_blocks ? nblocks : chunk_blocks;
+  int best_blocks = hi;
   double best = 0.0;
   bool have = false;
-  for (int cand = chunk_blocks; cand <= (nblocks > chunk_blocks ? nblocks : chunk_blocks); ++cand) {
+  for (int cand = chunk_blocks; cand <= hi; ++cand) {
     const long segs = (nblocks + cand - 1) / cand;
     if (cand > chunk_blocks && (nblocks + cand - 2) / (cand - 1) == segs) continue;  // same count, longer segments
-    const long rounds = (groups * segs + kNumCUs - 1) / kNumCUs;
-    const double cost = static_cast<double>(rounds) * (cand + 2) * (segs > 1 ? 1.35 : 1.0);
+    double cost = rounds_time(groups * segs, cand, 3.2, 4.0);
+    if (segs > 1) cost += rounds_time(groups * (segs - 1), cand, 1.6, 2.2) + 3.5 + 0.0089 * segs * seqs + 8.0;
     if (!have || cost < best) {
       have = true;
       best = cost;
