@@ -599,24 +599,22 @@ void chunk_scan_kernel(const ScanParams p) {
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) bto[q][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * q);
       __builtin_amdgcn_sched_barrier(0);
+      // While the operands are on their way (the LDS serves the eight waves' 160 reads for roughly a
+      // thousand cycles, and nothing of this block can start before), the NEXT block is staged: that
+      // work needs registers only.  Then its registers are refilled (tile of block jb+2, x of block
+      // jb+3), and only then come the matrix instructions.
+      weigh(set);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+      for (int c = 0; c < 8; ++c) stage_column(c, set);
+#pragma unroll
+      for (int k = 0; k < kBtPieces; ++k) *reinterpret_cast<u32x4 *>(&sBt[buf ^ 1][lds_bt[k]]) = r_bt[k];
+      load_part(1, at(jb + 2));
+      load_part(0, at(jb + 3), set);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) Hacc[nt] = mfma(bto[q][nt], xo[q], Hacc[nt]);
-        if (q == 0) weigh(set);
-        stage_column(2 * q, set);
-        stage_column(2 * q + 1, set);
-        // the B^T pieces of block jb+1 spread over the groups; once the last one has left its
-        // register the tile of block jb+2 is requested, then the x of block jb+3
-#pragma unroll
-        for (int k = q * kBtPieces / 4; k < (q + 1) * kBtPieces / 4; ++k)
-          *reinterpret_cast<u32x4 *>(&sBt[buf ^ 1][lds_bt[k]]) = r_bt[k];
-        if (q == 3) {
-          load_part(1, at(jb + 2));
-          load_part(0, at(jb + 3), set);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
       __syncthreads();
     };
     // pairs of blocks, then the odd one: with the test between the two halves of a pair the compiler
