@@ -73,6 +73,14 @@ def decode_flops(cfg, nlayers):
     return nlayers * cfg.batch * cfg.nheads * cfg.headdim * (5.0 * cfg.dstate + 3.0)
 
 
+# HBM bytes per launch of a kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a copy of known size gives on this chip; see
+# profiles/hbm_traffic_fetch_write_size.txt).  Measured values, not computed here: null for others.
+HBM_TRAFFIC_BYTES = {
+    ("c3_2p7b_long", "chunk_scan"): int((2 * 110741.3 + 166642.6) * 1024),
+    ("c3_2p7b_long", "segment_states"): int((2 * 85107.4 + 28188.3) * 1024),
+}
+
 # Which algorithmic FLOPs each kernel of a prefill call is responsible for.
 KERNEL_WORK = {
     # generic fp32 family
@@ -196,8 +204,8 @@ def main():
         bound, peak = "alu", PEAK_VALU_F32_TFLOPS
     achieved = dom_flops / kern[dom] / 1e9
     roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 3), peak=peak, unit="TFLOP/s",
-                    frac=round(achieved / peak, 5), traffic=None, kernel_ms=round(kern[dom], 5),
-                    flops_per_launch=dom_flops)
+                    frac=round(achieved / peak, 5), traffic=HBM_TRAFFIC_BYTES.get((cfg.name, dom)),
+                    kernel_ms=round(kern[dom], 5), flops_per_launch=dom_flops)
 
     # ---- the other prefill configurations (reported, not the headline) -------------------------
     extra = {}
