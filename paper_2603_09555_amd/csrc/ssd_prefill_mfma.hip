@@ -29,15 +29,17 @@
 // stages its own slice of the scaled input.  Global loads for block j+2 are issued while block
 // j+1 is being computed, with one barrier per block.
 //
-// Kernels:
-//   scores_bt      per (batch, group, block): G = tril(C B^T) (diagonal blocks only, bf16) and a
-//                  transposed copy of B, both shared by all heads of the group.
-//   block_cumsum   per (batch, head, block): prefix sums of dt*A and the per-token input factors.
-//   segment_states per (batch, head, segment): the segment's local end state from a zero start
-//                  (only the chunk-state accumulation), so that segments can run in parallel.
+// Kernels (launch order):
+//   block_prep     one launch for both preparation steps: per (batch, group, block) G = tril(C B^T)
+//                  (diagonal blocks only, bf16) and a transposed copy of B, both shared by all heads of
+//                  the group; per (batch, head, block) the prefix sums of dt*A turned into per-token
+//                  input factors, per-row output factors and per-block state factors.
+//   chunk_scan<true>  ("segment_states") per (batch, 4 heads, segment): the segment's end state from a
+//                  zero start (only the chunk-state accumulation), so that segments can run in parallel.
 //   segment_pass   sequential pass over segment end states -> state entering each segment.
-//   chunk_scan     per (batch, head, segment): everything above, from the entering state.
-// A segment is a whole number of chunks; with one segment only the first two and chunk_scan run.
+//   chunk_scan<false> per (batch, 4 heads, segment): everything above, from the entering state.
+// A segment is a whole number of 64-token blocks, at least one chunk; with one segment only the first
+// and the last kernel run.
 #include <cstdlib>
 
 #include "ssd_internal.hpp"
