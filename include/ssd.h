@@ -139,6 +139,27 @@ SSD_API ssd_status ssd_decode_step_layers(int32_t nlayers, const ssd_shape *shap
                                   const float *D, void *y, void *hip_stream);
 
 /*
+ * `nsteps` consecutive decode steps of `nlayers` independent layers in ONE
+ * launch, for callers that know the inputs of all steps up front (a short
+ * continuation of a cached prompt, draft tokens to be verified): the analogue
+ * of the paper's compiled on-device decode loop (section "Mapping SSD onto JAX
+ * primitives"; Alg. 2 applied nsteps times).  Every per-step array of
+ * ssd_decode_step_layers gains a leading [nsteps] axis:
+ *     x, y (nsteps, nlayers, batch, nheads, headdim);  dt (nsteps, nlayers, batch, nheads);
+ *     B, C (nsteps, nlayers, batch, ngroups, dstate);  A, D (nlayers, nheads);
+ *     state (nlayers, batch, nheads, headdim, dstate) in/out: the state after the last step.
+ * The result equals nsteps calls of ssd_decode_step_layers up to the order of
+ * the fp32 summation over dstate.  For
+ * the common head shapes the state stays on chip between the steps and moves
+ * through memory once per call instead of once per step.
+ * Errors: as ssd_decode_step_layers (only the base pointers need 16-byte alignment).
+ */
+SSD_API ssd_status ssd_decode_steps_layers(int32_t nsteps, int32_t nlayers, const ssd_shape *shape,
+                                   float *state, const void *x, const float *dt,
+                                   const float *A, const void *B, const void *C,
+                                   const float *D, void *y, void *hip_stream);
+
+/*
  * Measurement aid: ssd_prefill with a HIP event recorded on `hip_stream` after
  * every kernel of the call (the prefill of Alg. 1 is several kernels).  Unlike
  * every other entry point it creates and destroys HIP events and WAITS for the

@@ -198,3 +198,16 @@ def decode_step_layers(state, x, dt, A, B, C, D, nthreads: int = 0):
         ys.append(y)
         sts.append(s)
     return np.stack(ys), np.stack(sts)
+
+
+def decode_steps_layers(state, x, dt, A, B, C, D, nthreads: int = 0):
+    """``nsteps`` consecutive decode steps (Alg. 2 applied once per leading index of the
+    per-step arrays): ``x (S,Ly,Bt,H,P)``, ``dt (S,Ly,Bt,H)``, ``B, C (S,Ly,Bt,G,N)``,
+    ``A, D (Ly,H)``, ``state (Ly,Bt,H,P,N)``.  Returns ``(y (S,Ly,Bt,H,P), state after the last step)``."""
+    st = _f64(state)
+    xs, dts, Bs, Cs = _f64(x), _f64(dt), _f64(B), _f64(C)
+    ys = []
+    for s in range(xs.shape[0]):
+        y, st = decode_step_layers(st, xs[s], dts[s], A, Bs[s], Cs[s], D, nthreads=nthreads)
+        ys.append(y)
+    return np.stack(ys), st

@@ -148,6 +148,23 @@ ssd_status ssd_decode_step_layers(int32_t nlayers, const ssd_shape *shape, float
   return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
 }
 
+ssd_status ssd_decode_steps_layers(int32_t nsteps, int32_t nlayers, const ssd_shape *shape, float *state,
+                                   const void *x, const float *dt, const float *A, const void *B, const void *C,
+                                   const float *D, void *y, void *hip_stream) {
+  Dims d;
+  const ssd_status st = make_dims(shape, true, &d);
+  if (st != SSD_OK) return st;
+  if (nlayers < 1 || nsteps < 1) return SSD_ERR_SHAPE;
+  const long double pairs = static_cast<long double>(nlayers) * d.Bt * d.H;
+  if (pairs > 2.0e9L || pairs * d.P * nsteps > 1.0e15L) return SSD_ERR_SHAPE;
+  if (!state || !x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
+  if (!aligned16(state) || !aligned16(x) || !aligned16(B) || !aligned16(C) || !aligned16(y))
+    return SSD_ERR_ALIGN;
+  const hipError_t e = ssd::launch_decode_steps(nsteps, nlayers, d, state, x, dt, A, B, C, D, y,
+                                                static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
+}
+
 ssd_status ssd_decode_step(const ssd_shape *shape, float *state, const void *x, const float *dt,
                            const float *A, const void *B, const void *C, const float *D, void *y,
                            void *hip_stream) {

@@ -9,6 +9,8 @@
 // the N/4 lanes of a row with wave shuffles; nothing but the state round-trips memory.
 #include "ssd_internal.hpp"
 
+// Multiply-adds are written as explicit fmaf so that the single-step and the multi-step kernels
+// round identically (the compiler's own choice of what to fuse differs between kernels).
 namespace ssd {
 namespace {
 
@@ -73,15 +75,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_vec_kernel(
       if (p < P) {
         const float ux = dtv * xv[u];
         float4 v = hv[u];
-        v.x = dA * v.x + ux * Bv.x;
-        v.y = dA * v.y + ux * Bv.y;
-        v.z = dA * v.z + ux * Bv.z;
-        v.w = dA * v.w + ux * Bv.w;
+        v.x = fmaf(dA, v.x, ux * Bv.x);
+        v.y = fmaf(dA, v.y, ux * Bv.y);
+        v.z = fmaf(dA, v.z, ux * Bv.z);
+        v.w = fmaf(dA, v.w, ux * Bv.w);
         *reinterpret_cast<float4 *>(hbase + static_cast<size_t>(p) * N) = v;
-        float part = Cv.x * v.x + Cv.y * v.y + Cv.z * v.z + Cv.w * v.w;
+        float part = fmaf(Cv.w, v.w, fmaf(Cv.z, v.z, fmaf(Cv.y, v.y, Cv.x * v.x)));
 #pragma unroll
         for (int m = LPR / 2; m >= 1; m >>= 1) part += __shfl_xor(part, m, 64);
-        if (lane_n == 0) Io::store(y, pair * P + p, part + Dh * xv[u]);
+        if (lane_n == 0) Io::store(y, pair * P + p, fmaf(Dh, xv[u], part));
       }
     }
   }
@@ -109,14 +111,127 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_any_kernel(
     float *hp = state + (pair * P + p) * static_cast<size_t>(N);
     float part = 0.f;
     for (int n = lane; n < N; n += 64) {
-      const float v = dA * hp[n] + ux * Io::load(B, bc + n);
+      const float v = fmaf(dA, hp[n], ux * Io::load(B, bc + n));
       hp[n] = v;
-      part += Io::load(C, bc + n) * v;
+      part = fmaf(Io::load(C, bc + n), v, part);
     }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) part += __shfl_xor(part, m, 64);
-    if (lane == 0) Io::store(y, pair * P + p, part + Dh * xv);
+    if (lane == 0) Io::store(y, pair * P + p, fmaf(Dh, xv, part));
   }
+}
+
+// Several steps in one launch (inputs of all steps known up front, e.g. a short continuation of a
+// cached prompt): the state of a (layer, batch row, head) stays in registers across the steps, so
+// it is read and written once instead of once per step, and the per-step traffic shrinks to the
+// step's inputs and its output row.  What then bounds the kernel is the vector ALU, so the layout
+// minimises instructions per state element: LPR (<= 16) lanes share a row, each lane owns NV groups
+// of four consecutive n (group v covers n = 4 (v LPR + lane) ..), so a row's C.h is reduced inside a
+// 16-lane DPP row by four single add-with-lane-permute instructions, without LDS traffic.
+// ROWS = rows per lane = P / (256 / LPR).  The inputs of step s+1 are requested before step s is
+// computed.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+// Sum over the LPR lanes of a row (LPR a power of two <= 16, rows aligned to LPR lanes); every lane
+// of the row receives the sum.  Lane permutations: swap neighbours, swap pairs, mirror inside 8,
+// mirror inside 16 (after the first two steps the mirrors act like swaps of quads and of halves).
+template <int LPR>
+__device__ __forceinline__ float row_sum(float v) {
+  if (LPR >= 2) v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+  if (LPR >= 4) v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+  if (LPR >= 8) v += dpp_mov<0x141>(v);  // row_half_mirror
+  if (LPR >= 16) v += dpp_mov<0x140>(v); // row_mirror
+  return v;
+}
+
+template <typename Io, int LPR, int NV, int ROWS>
+__global__ __launch_bounds__(kDecodeThreads) void decode_steps_kernel(
+    float *__restrict__ state, const void *__restrict__ x, const float *__restrict__ dt,
+    const float *__restrict__ A, const void *__restrict__ B, const void *__restrict__ C,
+    const float *__restrict__ D, void *__restrict__ y, int nsteps, size_t npairs, size_t nbc, int BtH,
+    int H, int G, int hpg) {
+  constexpr int N = LPR * 4 * NV;
+  constexpr int RPP = kDecodeThreads / LPR;
+  constexpr int P = ROWS * RPP;
+  const size_t pair = blockIdx.x;
+  const int h = static_cast<int>(pair % H);
+  const size_t lb = pair / H;
+  const int layer = static_cast<int>(pair / BtH);
+  const int lane_n = threadIdx.x % LPR;
+  const int row0 = threadIdx.x / LPR;
+  const float Ah = A[static_cast<size_t>(layer) * H + h];
+  const float Dh = D[static_cast<size_t>(layer) * H + h];
+  const size_t bc = (lb * G + h / hpg) * N + lane_n * 4;
+  const size_t bc_step = nbc * N;  // elements of B (or C) per step
+
+  float *hbase = state + pair * static_cast<size_t>(P) * N + lane_n * 4;
+  float4 hv[ROWS][NV];
+#pragma unroll
+  for (int u = 0; u < ROWS; ++u)
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+      hv[u][v] = *reinterpret_cast<const float4 *>(hbase + static_cast<size_t>(row0 + u * RPP) * N + v * (4 * LPR));
+
+  float dt_n = dt[pair];
+  float4 B_n[NV], C_n[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    B_n[v] = load4<Io>(B, bc + v * (4 * LPR));
+    C_n[v] = load4<Io>(C, bc + v * (4 * LPR));
+  }
+  float x_n[ROWS];
+#pragma unroll
+  for (int u = 0; u < ROWS; ++u) x_n[u] = Io::load(x, pair * P + row0 + u * RPP);
+
+  // (Writing two steps per loop trip with alternating input sets saves the register copies below but
+  // costs registers, hence resident waves; it measured 10 % slower.)
+  for (int s = 0; s < nsteps; ++s) {
+    const float dtv = dt_n;
+    float4 Bv[NV], Cv[NV];
+    float xv[ROWS];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      Bv[v] = B_n[v];
+      Cv[v] = C_n[v];
+    }
+#pragma unroll
+    for (int u = 0; u < ROWS; ++u) xv[u] = x_n[u];
+    const int sn = s + 1 < nsteps ? s + 1 : s;  // the surplus loads of the last step are not used
+    dt_n = dt[sn * npairs + pair];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      B_n[v] = load4<Io>(B, sn * bc_step + bc + v * (4 * LPR));
+      C_n[v] = load4<Io>(C, sn * bc_step + bc + v * (4 * LPR));
+    }
+#pragma unroll
+    for (int u = 0; u < ROWS; ++u) x_n[u] = Io::load(x, (sn * npairs + pair) * P + row0 + u * RPP);
+
+    const float dA = expf(dtv * Ah);
+#pragma unroll
+    for (int u = 0; u < ROWS; ++u) {
+      const float ux = dtv * xv[u];
+      float part = 0.f;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        float4 w = hv[u][v];
+        w.x = fmaf(dA, w.x, ux * Bv[v].x);
+        w.y = fmaf(dA, w.y, ux * Bv[v].y);
+        w.z = fmaf(dA, w.z, ux * Bv[v].z);
+        w.w = fmaf(dA, w.w, ux * Bv[v].w);
+        hv[u][v] = w;
+        part = fmaf(Cv[v].w, w.w, fmaf(Cv[v].z, w.z, fmaf(Cv[v].y, w.y, fmaf(Cv[v].x, w.x, part))));
+      }
+      part = row_sum<LPR>(part);
+      if (lane_n == 0) Io::store(y, (s * npairs + pair) * P + row0 + u * RPP, fmaf(Dh, xv[u], part));
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < ROWS; ++u)
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+      *reinterpret_cast<float4 *>(hbase + static_cast<size_t>(row0 + u * RPP) * N + v * (4 * LPR)) = hv[u][v];
 }
 
 template <typename Io>
@@ -152,6 +267,33 @@ hipError_t launch_typed(int nlayers, const Dims &d, float *state, const void *x,
   return hipGetLastError();
 }
 
+// Register-resident multi-step kernel for the shapes whose state fits (at most 64 values per lane); returns false for any other shape.
+template <typename Io>
+bool launch_steps_resident(int nsteps, int nlayers, const Dims &d, float *state, const void *x, const float *dt,
+                           const float *A, const void *B, const void *C, const float *D, void *y,
+                           hipStream_t stream) {
+  const size_t npairs = static_cast<size_t>(nlayers) * d.Bt * d.H;
+  const size_t nbc = static_cast<size_t>(nlayers) * d.Bt * d.G;
+  const dim3 grid(static_cast<unsigned>(npairs)), block(kDecodeThreads);
+  const int BtH = d.Bt * d.H;
+#define SSD_STEPS_CASE(LPR_, NV_, ROWS_)                                                                      \
+  if (d.N == 4 * LPR_ * NV_ && d.P == ROWS_ * (kDecodeThreads / LPR_)) {                                      \
+    hipLaunchKernelGGL((decode_steps_kernel<Io, LPR_, NV_, ROWS_>), grid, block, 0, stream, state, x, dt, A, B, \
+                       C, D, y, nsteps, npairs, nbc, BtH, d.H, d.G, d.hpg);                                    \
+    return true;                                                                                              \
+  }
+  SSD_STEPS_CASE(16, 2, 4)  // P 64,  N 128
+  SSD_STEPS_CASE(16, 2, 8)  // P 128, N 128
+  SSD_STEPS_CASE(16, 2, 2)  // P 32,  N 128
+  SSD_STEPS_CASE(16, 1, 4)  // P 64,  N 64
+  SSD_STEPS_CASE(16, 1, 8)  // P 128, N 64
+  SSD_STEPS_CASE(16, 4, 4)  // P 64,  N 256
+  SSD_STEPS_CASE(4, 1, 1)   // P 64,  N 16
+  SSD_STEPS_CASE(4, 1, 2)   // P 128, N 16
+#undef SSD_STEPS_CASE
+  return false;
+}
+
 }  // namespace
 
 hipError_t launch_decode(int nlayers, const Dims &d, float *state, const void *x, const float *dt,
@@ -159,6 +301,27 @@ hipError_t launch_decode(int nlayers, const Dims &d, float *state, const void *x
                          hipStream_t stream) {
   return d.bf16 ? launch_typed<IoBf16>(nlayers, d, state, x, dt, A, B, C, D, y, stream)
                 : launch_typed<IoF32>(nlayers, d, state, x, dt, A, B, C, D, y, stream);
+}
+
+hipError_t launch_decode_steps(int nsteps, int nlayers, const Dims &d, float *state, const void *x,
+                               const float *dt, const float *A, const void *B, const void *C, const float *D,
+                               void *y, hipStream_t stream) {
+  const bool resident =
+      d.bf16 ? launch_steps_resident<IoBf16>(nsteps, nlayers, d, state, x, dt, A, B, C, D, y, stream)
+             : launch_steps_resident<IoF32>(nsteps, nlayers, d, state, x, dt, A, B, C, D, y, stream);
+  if (resident) return hipGetLastError();
+  // any other shape: one single-step launch per step
+  const size_t esz = d.bf16 ? 2 : 4;
+  const size_t npairs = static_cast<size_t>(nlayers) * d.Bt * d.H;
+  const size_t nbc = static_cast<size_t>(nlayers) * d.Bt * d.G;
+  for (int s = 0; s < nsteps; ++s) {
+    const hipError_t e = launch_decode(
+        nlayers, d, state, static_cast<const char *>(x) + s * npairs * d.P * esz, dt + s * npairs, A,
+        static_cast<const char *>(B) + s * nbc * d.N * esz, static_cast<const char *>(C) + s * nbc * d.N * esz, D,
+        static_cast<char *>(y) + s * npairs * d.P * esz, stream);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace ssd

@@ -69,6 +69,10 @@ hipError_t launch_decode(int nlayers, const Dims &d, float *state, const void *x
                          const float *A, const void *B, const void *C, const float *D, void *y,
                          hipStream_t stream);
 
+hipError_t launch_decode_steps(int nsteps, int nlayers, const Dims &d, float *state, const void *x,
+                               const float *dt, const float *A, const void *B, const void *C, const float *D,
+                               void *y, hipStream_t stream);
+
 size_t generic_workspace_bytes(const Dims &d);
 hipError_t launch_prefill_generic(const Dims &d, const void *x, const float *dt, const float *A,
                                   const void *B, const void *C, const float *D, const float *h0,

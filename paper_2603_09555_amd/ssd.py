@@ -19,6 +19,7 @@ SSD_F32, SSD_BF16 = 0, 1
 SSD_OK = 0
 
 EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
+           "ssd_decode_steps_layers",
            "ssd_prefill_path", "ssd_status_string", "ssd_version"]
 
 
@@ -51,6 +52,8 @@ _lib.ssd_decode_step.restype = ctypes.c_int
 _lib.ssd_decode_step.argtypes = [_sp] + [_vp] * 9
 _lib.ssd_decode_step_layers.restype = ctypes.c_int
 _lib.ssd_decode_step_layers.argtypes = [ctypes.c_int32, _sp] + [_vp] * 9
+_lib.ssd_decode_steps_layers.restype = ctypes.c_int
+_lib.ssd_decode_steps_layers.argtypes = [ctypes.c_int32, ctypes.c_int32, _sp] + [_vp] * 9
 _lib.ssd_prefill_path.restype = ctypes.c_char_p
 _lib.ssd_prefill_path.argtypes = [_sp]
 _lib.ssd_status_string.restype = ctypes.c_char_p
@@ -176,4 +179,25 @@ def ssd_decode_step_layers(state, x, dt, A, B, C, D, y=None):
                                      _ptr(B), _ptr(C), _ptr(D), _ptr(y), _stream_ptr())
     if st != SSD_OK:
         raise SSDError(st, "ssd_decode_step_layers")
+    return y
+
+
+def ssd_decode_steps_layers(state, x, dt, A, B, C, D, y=None):
+    """``ssd_decode_steps_layers``: ``x (steps,Ly,Bt,H,P)``, ``dt (steps,Ly,Bt,H)``,
+    ``B, C (steps,Ly,Bt,G,N)``, ``A, D (Ly,H)``; ``state (Ly,Bt,H,P,N)`` updated in place to the
+    state after the last step.  Returns ``y (steps,Ly,Bt,H,P)``.  One launch."""
+    Ly, Bt, H, P, N = state.shape
+    S, G = x.shape[0], B.shape[3]
+    shape = make_shape(Bt, 1, H, P, N, G, 1, x.dtype)
+    if y is None:
+        y = torch.empty_like(x)
+    if state.dtype != torch.float32 or tuple(x.shape) != (S, Ly, Bt, H, P) or tuple(dt.shape) != (S, Ly, Bt, H) \
+            or tuple(A.shape) != (Ly, H) or tuple(D.shape) != (Ly, H) \
+            or tuple(B.shape) != (S, Ly, Bt, G, N) or tuple(C.shape) != (S, Ly, Bt, G, N):
+        raise ValueError("inconsistent tensor shapes")
+    _check_dev(state, x, dt, A, B, C, D, y)
+    st = _lib.ssd_decode_steps_layers(S, Ly, ctypes.byref(shape), _ptr(state), _ptr(x), _ptr(dt), _ptr(A),
+                                      _ptr(B), _ptr(C), _ptr(D), _ptr(y), _stream_ptr())
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_decode_steps_layers")
     return y

@@ -102,6 +102,22 @@ def test_decode_rejects_before_any_hip_call(ssd):
                                None) == -1
 
 
+def test_decode_steps_rejects_before_any_hip_call(ssd):
+    lib = ssd.raw()
+    fake = ctypes.c_void_p(4096)
+
+    def call(s, ns=2, nl=1, state=fake, x=fake, y=fake):
+        return lib.ssd_decode_steps_layers(ns, nl, ctypes.byref(s) if s is not None else None, state, x, fake,
+                                           fake, fake, fake, fake, y, None)
+
+    assert call(None) == -1
+    assert call(shape(ssd), ns=0) == -2
+    assert call(shape(ssd), nl=0) == -2
+    assert call(shape(ssd, headdim=0)) == -2
+    assert call(shape(ssd), state=None) == -1
+    assert call(shape(ssd), y=ctypes.c_void_p(4100)) == -7
+
+
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     """The product path has no fallback: with the .so absent the binding cannot be imported."""
     import importlib.util

@@ -107,3 +107,27 @@ def test_full_size_stacked_decode_sampled_sequences(ssd, name):
         y_got = ys[:, l][:, bs, hs, :].transpose(0, 1)    # (n, steps, P)
         assert_close(y_got, y_ref[:, cfg.seqlen:], 2e-2, "%s layer %d decode y" % (name, l))
         assert_close(state[l][bs, hs], st_ref, 2e-2, "%s layer %d state after %d steps" % (name, l, nsteps))
+
+
+def test_full_size_multi_step_decode_equals_single_steps(ssd):
+    """Config 4 at batch 16, all 64 layers: 8 steps in one launch against 8 stacked launches,
+    from a random state (y up to summation order, the state bitwise)."""
+    cfg = inputs.CONFIGS["c4_decode_b16"]
+    Ly, S = cfg.nlayers, 8
+    print("full-size multi-step decode", cfg, "steps", S, flush=True)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(53)
+    state = torch.randn((Ly, cfg.batch, cfg.nheads, cfg.headdim, cfg.dstate), generator=g, device="cuda")
+    x = torch.randn((S, Ly, cfg.batch, cfg.nheads, cfg.headdim), generator=g, device="cuda").bfloat16()
+    dt = torch.rand((S, Ly, cfg.batch, cfg.nheads), generator=g, device="cuda") * 0.1 + 1e-3
+    A = -(torch.rand((Ly, cfg.nheads), generator=g, device="cuda") * 15 + 1)
+    D = torch.randn((Ly, cfg.nheads), generator=g, device="cuda")
+    B = (0.25 * torch.randn((S, Ly, cfg.batch, cfg.ngroups, cfg.dstate), generator=g, device="cuda")).bfloat16()
+    C = (0.25 * torch.randn((S, Ly, cfg.batch, cfg.ngroups, cfg.dstate), generator=g, device="cuda")).bfloat16()
+    s1 = state.clone()
+    y = ssd.ssd_decode_steps_layers(state, x, dt, A, B, C, D)
+    y1 = torch.stack([ssd.ssd_decode_step_layers(s1, x[i], dt[i], A, B[i], C[i], D) for i in range(S)])
+    torch.cuda.synchronize()
+    assert torch.isfinite(y.float()).all()
+    assert_close(y, to_np64(y1), 2e-2, "multi-step y vs single steps")
+    assert torch.equal(state, s1)  # the state update involves no sum: identical bits

@@ -212,6 +212,82 @@ def test_many_decode_steps_track_the_oracle(ssd):
     assert_close(st, st_ref, 2e-2, "state after 64 steps")
 
 
+STEPS_CASES = [
+    # steps, Ly, Bt, H, P, N, G
+    (5, 2, 2, 8, 64, 128, 1),    # Mamba-2 head shape: state stays in registers
+    (1, 1, 1, 4, 64, 128, 2),    # a single step
+    (7, 1, 2, 4, 128, 128, 1),
+    (4, 2, 1, 4, 64, 64, 2),
+    (3, 1, 2, 4, 64, 16, 1),
+    (6, 1, 2, 4, 64, 256, 1),
+    (4, 2, 2, 6, 24, 20, 3),     # no register-resident variant: one launch per step
+    (3, 1, 1, 3, 100, 64, 1),
+]
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("case", STEPS_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_multi_step_decode_matches_oracle_and_single_steps(ssd, case, io):
+    S, Ly, Bt, H, P, N, G = case
+    iod = torch.float32 if io == "f32" else torch.bfloat16
+    g = torch.Generator().manual_seed(23)
+    state = torch.randn((Ly, Bt, H, P, N), generator=g)
+    x = torch.randn((S, Ly, Bt, H, P), generator=g).to(iod)
+    dt = torch.rand((S, Ly, Bt, H), generator=g) * 0.1 + 1e-3
+    A = -(torch.rand((Ly, H), generator=g) * 15 + 1)
+    D = torch.randn((Ly, H), generator=g)
+    B = (0.25 * torch.randn((S, Ly, Bt, G, N), generator=g)).to(iod)
+    C = (0.25 * torch.randn((S, Ly, Bt, G, N), generator=g)).to(iod)
+    print("multi-step decode case", case, io, flush=True)
+    dev = [t.cuda() for t in (x, dt, A, B, C, D)]
+    sd = state.cuda().clone()
+    y = ssd.ssd_decode_steps_layers(sd, dev[0], dev[1], dev[2], dev[3], dev[4], dev[5])
+    torch.cuda.synchronize()
+    y_ref, st_ref = ssd_oracle.decode_steps_layers(state, x, dt, A, B, C, D)
+    assert_close(y, y_ref, TOL[io], "multi-step y")
+    assert_close(sd, st_ref, 1e-5, "multi-step state")
+    # the same steps one launch at a time: the same values up to the order of the sum over dstate
+    s1 = state.cuda().clone()
+    # (slices are copied: the single-step entry point wants 16-byte aligned pointers)
+    y1 = torch.stack([ssd.ssd_decode_step_layers(s1, dev[0][i].clone(), dev[1][i].clone(), dev[2], dev[3][i].clone(),
+                                                 dev[4][i].clone(), dev[5]) for i in range(S)])
+    torch.cuda.synchronize()
+    assert_close(y, to_np64(y1), TOL[io], "multi-step y vs single steps")
+    assert torch.equal(s1, sd)  # the state update involves no sum: identical bits
+
+
+def test_decode_steps_replayed_from_a_hip_graph(ssd):
+    """Stacked decode launches captured into a HIP graph: every replay (with eager work and
+    synchronisations in between) continues the recurrence exactly as eager launches do."""
+    S, Ly, Bt, H, P, N, G = 4, 3, 2, 8, 64, 128, 1
+    g = torch.Generator().manual_seed(29)
+    state = torch.randn((Ly, Bt, H, P, N), generator=g).cuda()
+    x = torch.randn((S, Ly, Bt, H, P), generator=g).bfloat16().cuda()
+    dt = (torch.rand((S, Ly, Bt, H), generator=g) * 0.1 + 1e-3).cuda()
+    A = (-(torch.rand((Ly, H), generator=g) * 15 + 1)).cuda()
+    D = torch.randn((Ly, H), generator=g).cuda()
+    B = (0.25 * torch.randn((S, Ly, Bt, G, N), generator=g)).bfloat16().cuda()
+    C = (0.25 * torch.randn((S, Ly, Bt, G, N), generator=g)).bfloat16().cuda()
+    sg, se = state.clone(), state.clone()
+    yg = torch.empty_like(x)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    keep = sg.clone()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(S):
+                ssd.ssd_decode_step_layers(sg, x[i], dt[i], A, B[i], C[i], D, y=yg[i])
+    torch.cuda.current_stream().wait_stream(side)
+    sg.copy_(keep)  # capture does not execute, but make the start state explicit
+    for rep in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        ye = torch.stack([ssd.ssd_decode_step_layers(se, x[i], dt[i], A, B[i], C[i], D) for i in range(S)])
+        torch.cuda.synchronize()
+        assert torch.equal(yg, ye) and torch.equal(sg, se), "replay %d differs from eager" % rep
+
+
 # ---- MFMA path (headdim 64, dstate 128, bf16) --------------------------------------------------
 MFMA_CASES = [
     # Bt, T, H, P, N, G, L, forced chunks per segment (0 = library's choice)

@@ -159,6 +159,27 @@ def test_decode_layers_equals_per_layer():
         np.testing.assert_array_equal(s2[l], sl)
 
 
+def test_decode_steps_equal_the_scan_over_the_same_tokens():
+    """Several decode steps (the step routine applied repeatedly) against the scan routine run
+    over the same tokens from the same initial state: two separate C functions."""
+    r = np.random.default_rng(5)
+    S, Ly, Bt, H, P, N, G = 6, 2, 2, 4, 3, 5, 2
+    st = r.standard_normal((Ly, Bt, H, P, N))
+    x = r.standard_normal((S, Ly, Bt, H, P))
+    dt = r.uniform(0.01, 0.1, (S, Ly, Bt, H))
+    A = -r.uniform(1, 16, (Ly, H))
+    D = r.standard_normal((Ly, H))
+    B = r.standard_normal((S, Ly, Bt, G, N))
+    C = r.standard_normal((S, Ly, Bt, G, N))
+    y, s2 = ssd_oracle.decode_steps_layers(st, x, dt, A, B, C, D)
+    assert y.shape == (S, Ly, Bt, H, P) and s2.shape == st.shape
+    for l in range(Ly):
+        yl, sl = ssd_oracle.prefill(x[:, l].transpose(1, 0, 2, 3), dt[:, l].transpose(1, 0, 2), A[l],
+                                    B[:, l].transpose(1, 0, 2, 3), C[:, l].transpose(1, 0, 2, 3), D[l], h0=st[l])
+        np.testing.assert_allclose(y[:, l].transpose(1, 0, 2, 3), yl, rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(s2[l], sl, rtol=1e-12, atol=1e-12)
+
+
 def test_bf16_decay_would_be_visible():
     """The paper's decay-precision ablation: rounding exp(dt*A) to bf16 shows up far above the
     fp32 tolerance (1e-4), so a parity test at that tolerance can tell the two apart."""
