@@ -110,6 +110,37 @@ SSD_API ssd_status ssd_prefill(const ssd_shape *shape, const void *x, const floa
                        size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Prefill of a packed, variable-length batch: `batch` independent sequences
+ * laid back to back along the token axis (ragged prompt batches, prompts fed in
+ * pieces with their cached state as h0 -- section "The O(1) state cache":
+ * prefill initialises the cache, later calls continue from it).  Each sequence
+ * is an ssd_prefill of its own: the recurrence of Eq. 2 restarts from h0[q] (or
+ * zero) at every boundary and nothing crosses it.
+ *   shape->batch      number of sequences (nseq); shape->seqlen = total tokens
+ *   cu_seqlens        DEVICE array of nseq + 1 int32: sequence q owns tokens
+ *                     [cu_seqlens[q], cu_seqlens[q+1]); must be non-decreasing
+ *                     within [0, seqlen].  Empty sequences are allowed (their
+ *                     final state is h0[q] or zero).  The array is read on the
+ *                     device only; boundaries violating the rule make the call
+ *                     a no-op (nothing is written, nothing faults).
+ *   x, y  (seqlen, nheads, headdim);  dt (seqlen, nheads);  B, C (seqlen, ngroups, dstate)
+ *   h0 (nullable), final_state   (nseq, nheads, headdim, dstate) fp32
+ *   workspace         at least ssd_prefill_varlen_workspace_bytes() bytes, 256-byte aligned
+ * Tokens outside every sequence are left untouched in y.
+ * Implemented for the MFMA kernel family (bf16 io, headdim 64, dstate 128,
+ * chunk a multiple of 64, heads per group a multiple of 4); any other shape
+ * returns SSD_ERR_UNSUPPORTED and ssd_prefill_varlen_workspace_bytes returns 0.
+ * Errors: SSD_ERR_NULL, _SHAPE, _DTYPE, _ALIGN, _UNSUPPORTED, _WORKSPACE, _HIP.
+ */
+SSD_API size_t ssd_prefill_varlen_workspace_bytes(const ssd_shape *shape);
+SSD_API ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_seqlens,
+                              const void *x, const float *dt, const float *A,
+                              const void *B, const void *C, const float *D,
+                              const float *h0, void *y, float *final_state,
+                              void *workspace, size_t workspace_bytes,
+                              void *hip_stream);
+
+/*
  * One cached decode step (Alg. 2, "Discretise" + "SSM step"; output per Eq. 2),
  * for every (batch row, head):
  *     dA      = exp(dt * A_h)

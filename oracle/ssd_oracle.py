@@ -211,3 +211,30 @@ def decode_steps_layers(state, x, dt, A, B, C, D, nthreads: int = 0):
         y, st = decode_step_layers(st, xs[s], dts[s], A, Bs[s], Cs[s], D, nthreads=nthreads)
         ys.append(y)
     return np.stack(ys), st
+
+
+def prefill_varlen(x, dt, A, B, C, D, cu_seqlens, h0=None, nthreads: int = 0):
+    """Packed variable-length batch: sequence q owns tokens ``[cu[q], cu[q+1])`` of
+    ``x (tokens,H,P)``, ``dt (tokens,H)``, ``B, C (tokens,G,N)`` and is scanned on its own from
+    ``h0[q]`` (or zero): the recurrence of Eq. 2 restarted at every boundary.
+    Returns ``y (tokens,H,P)`` (zeros outside every sequence) and ``state (nseq,H,P,N)``."""
+    tonp = lambda a: a.detach().cpu().float().numpy() if hasattr(a, "detach") else np.asarray(a)
+    xn, dtn, Bn, Cn = tonp(x), tonp(dt), tonp(B), tonp(C)
+    cu = [int(v) for v in np.asarray(tonp(cu_seqlens)).reshape(-1)]
+    T, H, P = xn.shape
+    N = Bn.shape[2]
+    nseq = len(cu) - 1
+    y = np.zeros((T, H, P), dtype=np.float64)
+    state = np.zeros((nseq, H, P, N), dtype=np.float64)
+    h0n = None if h0 is None else _f64(h0)
+    for q in range(nseq):
+        a, b = cu[q], cu[q + 1]
+        if b == a:  # no token: the state is untouched
+            if h0n is not None:
+                state[q] = h0n[q]
+            continue
+        yq, sq = prefill(xn[None, a:b], dtn[None, a:b], A, Bn[None, a:b], Cn[None, a:b], D,
+                         h0=None if h0n is None else h0n[q:q + 1], nthreads=nthreads)
+        y[a:b] = yq[0]
+        state[q] = sq[0]
+    return y, state

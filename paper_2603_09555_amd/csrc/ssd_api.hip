@@ -131,6 +131,32 @@ ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, const floa
   return st;
 }
 
+size_t ssd_prefill_varlen_workspace_bytes(const ssd_shape *shape) {
+  Dims d;
+  if (make_dims(shape, false, &d) != SSD_OK || force_generic() || !ssd::mfma_varlen_supported(d)) return 0;
+  return ssd::mfma_varlen_workspace_bytes(d);
+}
+
+ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_seqlens, const void *x, const float *dt,
+                              const float *A, const void *B, const void *C, const float *D, const float *h0,
+                              void *y, float *final_state, void *workspace, size_t workspace_bytes_given,
+                              void *hip_stream) {
+  Dims d;  // batch = number of sequences, seqlen = total tokens
+  const ssd_status st = make_dims(shape, false, &d);
+  if (st != SSD_OK) return st;
+  if (!cu_seqlens || !x || !dt || !A || !B || !C || !D || !y || !final_state) return SSD_ERR_NULL;
+  if (!aligned16(x) || !aligned16(dt) || !aligned16(B) || !aligned16(C) || !aligned16(y) ||
+      !aligned16(final_state) || (h0 && !aligned16(h0)) || (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u))
+    return SSD_ERR_ALIGN;
+  if (force_generic() || !ssd::mfma_varlen_supported(d)) return SSD_ERR_UNSUPPORTED;
+  const size_t need = ssd::mfma_varlen_workspace_bytes(d);
+  if (!workspace || workspace_bytes_given < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SSD_ERR_WORKSPACE;
+  const hipError_t e = ssd::launch_prefill_mfma_varlen(d, cu_seqlens, x, dt, A, B, C, D, h0, y, final_state,
+                                                       workspace, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
+}
+
 ssd_status ssd_decode_step_layers(int32_t nlayers, const ssd_shape *shape, float *state, const void *x,
                                   const float *dt, const float *A, const void *B, const void *C,
                                   const float *D, void *y, void *hip_stream) {

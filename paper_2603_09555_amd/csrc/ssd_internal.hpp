@@ -86,6 +86,14 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
                                void *y, float *final_state, void *workspace, hipStream_t stream,
                                KernelTrace *trace = nullptr);
 
+// Packed variable-length batch (d.Bt sequences, d.T tokens in total, cu_seqlens on the device).
+bool mfma_varlen_supported(const Dims &d);
+size_t mfma_varlen_workspace_bytes(const Dims &d);
+hipError_t launch_prefill_mfma_varlen(const Dims &d, const int32_t *cu_seqlens, const void *x, const float *dt,
+                                      const float *A, const void *B, const void *C, const float *D, const float *h0,
+                                      void *y, float *final_state, void *workspace, hipStream_t stream,
+                                      KernelTrace *trace = nullptr);
+
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace ssd

@@ -90,33 +90,118 @@ __device__ __forceinline__ f32x16 mfma(const Operand &a, const Operand &b, f32x1
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, c, 0, 0, 0);
 }
 
+// ---- tables of a variable-length call -----------------------------------------------------------
+// A packed batch (sequences back to back along the token axis, boundaries in a device array of
+// cumulative lengths) is handled as a batch whose rows differ in length: every sequence gets whole
+// 64-token blocks of its own (the ragged last block of each is masked by the buffer descriptors, as
+// for a plain batch) and one or more segments.  Two tiny kernels turn the boundaries into tables:
+//   tok0[q], len[q]      first token and length of sequence q
+//   blk0[q], item0[q]    number of blocks / segments of the sequences before q (entry nseq: totals)
+//   blk_seq[i], item_seq[i]   sequence that block i / segment i belongs to
+// Blocks and segments are numbered over the whole batch; workspace arrays are indexed by those
+// numbers (capacities nb_cap, item_cap are upper bounds that the host can compute from the token
+// count and the number of sequences alone).  Boundaries that are not non-decreasing within
+// [0, total] give empty tables: every later kernel then finds nothing to do.
+struct VarPlan {
+  const int32_t *tok0, *len, *blk0, *item0, *blk_seq, *item_seq;
+  int nseq, nb_cap, item_cap;
+};
+
+__global__ __launch_bounds__(256) void varlen_scan_kernel(const int32_t *__restrict__ cu, int nseq, int total,
+                                                          int seg_blocks, int32_t *__restrict__ tok0,
+                                                          int32_t *__restrict__ len, int32_t *__restrict__ blk0,
+                                                          int32_t *__restrict__ item0) {
+  __shared__ int sblk[256], sitem[256];
+  __shared__ int bad;
+  const int tid = threadIdx.x;
+  const int per = (nseq + 255) / 256;
+  const int q0 = min(nseq, tid * per), q1 = min(nseq, q0 + per);
+  if (tid == 0) bad = 0;
+  __syncthreads();
+  int nb = 0, ni = 0;
+  bool mine_bad = false;
+  for (int q = q0; q < q1; ++q) {
+    const int a = cu[q], b = cu[q + 1];
+    if (a < 0 || b < a || b > total) mine_bad = true;
+    const int n = (b - a + 63) / 64;
+    nb += n;
+    ni += max(1, (n + seg_blocks - 1) / seg_blocks);
+  }
+  if (mine_bad) atomicOr(&bad, 1);
+  sblk[tid] = nb;
+  sitem[tid] = ni;
+  __syncthreads();
+  if (tid == 0) {  // exclusive prefix over the 256 partial sums
+    int a = 0, b = 0;
+    for (int i = 0; i < 256; ++i) {
+      const int t = sblk[i], u = sitem[i];
+      sblk[i] = a;
+      sitem[i] = b;
+      a += t;
+      b += u;
+    }
+    blk0[nseq] = bad ? 0 : a;
+    item0[nseq] = bad ? 0 : b;
+  }
+  __syncthreads();
+  int rb = sblk[tid], ri = sitem[tid];
+  for (int q = q0; q < q1; ++q) {
+    const int a = cu[q], l = cu[q + 1] - a;
+    const int n = (l + 63) / 64;
+    tok0[q] = bad ? 0 : a;
+    len[q] = bad ? 0 : l;
+    blk0[q] = bad ? 0 : rb;
+    item0[q] = bad ? 0 : ri;
+    rb += n;
+    ri += max(1, (n + seg_blocks - 1) / seg_blocks);
+  }
+}
+
+// Largest q in [0, nseq) with first[q] <= i: the sequence that contains block (or segment) i.
+__device__ __forceinline__ int owner_of(const int32_t *__restrict__ first, int nseq, int i) {
+  int lo = 0, hi = nseq;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (first[mid] <= i) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+__global__ __launch_bounds__(256) void varlen_fill_kernel(const int32_t *__restrict__ blk0,
+                                                          const int32_t *__restrict__ item0, int nseq,
+                                                          int32_t *__restrict__ blk_seq,
+                                                          int32_t *__restrict__ item_seq) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < blk0[nseq]) blk_seq[i] = owner_of(blk0, nseq, i);
+  if (i < item0[nseq]) item_seq[i] = owner_of(item0, nseq, i);
+}
+
 // ---- scores_bt: G = tril(C B^T) on the diagonal blocks, and B transposed ------------------------------
-// One workgroup per (block jb, batch row x group bg).  Gd: (Bt*G, NB, 64 l, 64 s) bf16.
-// Btr: (Bt*G, NB, 128 n, 64 s) bf16.  sB: kBlk * (kN + 2) elements of LDS.
-__device__ __forceinline__ void scores_bt_block(uint16_t *sB, int jb, int bg, const uint16_t *__restrict__ B,
-                                                const uint16_t *__restrict__ C, uint16_t *__restrict__ Gd,
-                                                uint16_t *__restrict__ Btr, int T, int G, int NB) {
-  const int b = bg / G, g = bg % G;
+// One workgroup per (block, group).  The block covers rows [row0, row0 + 64) of the (tokens, G, N)
+// arrays B and C, of which only rows below row_end belong to its sequence; its results go to tile
+// number `tile` of Gd (64 l x 64 s, bf16) and of Btr (128 n x 64 s, bf16).  sB: kBlk * (kN + 2)
+// elements of LDS.
+__device__ __forceinline__ void scores_bt_block(uint16_t *sB, size_t row0, size_t row_end, size_t tile, int g,
+                                                const uint16_t *__restrict__ B, const uint16_t *__restrict__ C,
+                                                uint16_t *__restrict__ Gd, uint16_t *__restrict__ Btr, int G) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ws = wave >> 1, wl = wave & 1;
   const int r = lane & 31, kg = lane >> 5;
-  const int t0 = jb * kBlk;
 
   // G^T tile (rows s, columns l): lane ends up with four consecutive s for its l.
-  const int srow = t0 + 32 * ws + r, lrow = t0 + 32 * wl + r;
-  const uint16_t *Bp = B + ((static_cast<size_t>(b) * T + srow) * G + g) * kN + 8 * kg;
-  const uint16_t *Cp = C + ((static_cast<size_t>(b) * T + lrow) * G + g) * kN + 8 * kg;
+  const size_t srow = row0 + 32 * ws + r, lrow = row0 + 32 * wl + r;
+  const uint16_t *Bp = B + (srow * G + g) * kN + 8 * kg;
+  const uint16_t *Cp = C + (lrow * G + g) * kN + 8 * kg;
   f32x16 acc = {};
 #pragma unroll
   for (int q = 0; q < kN / 16; ++q) {
     Operand a, c;
     a.q = mk4(0, 0, 0, 0);
     c.q = mk4(0, 0, 0, 0);
-    if (srow < T) a.q = *reinterpret_cast<const u32x4 *>(Bp + 16 * q);
-    if (lrow < T) c.q = *reinterpret_cast<const u32x4 *>(Cp + 16 * q);
+    if (srow < row_end) a.q = *reinterpret_cast<const u32x4 *>(Bp + 16 * q);
+    if (lrow < row_end) c.q = *reinterpret_cast<const u32x4 *>(Cp + 16 * q);
     acc = mfma(a, c, acc);
   }
-  uint16_t *Gout = Gd + (static_cast<size_t>(bg) * NB + jb) * kBlk * kBlk;
+  uint16_t *Gout = Gd + tile * kBlk * kBlk;
   const int l = 32 * wl + r;
 #pragma unroll
   for (int i4 = 0; i4 < 4; ++i4) {
@@ -131,8 +216,7 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, int jb, int bg, co
   for (int c = threadIdx.x; c < kBlk * (kN / 8); c += kThreads) {
     const int row = c / (kN / 8), ch = c % (kN / 8);
     u32x4 v = mk4(0, 0, 0, 0);
-    if (t0 + row < T)
-      v = *reinterpret_cast<const u32x4 *>(B + ((static_cast<size_t>(b) * T + t0 + row) * G + g) * kN + 8 * ch);
+    if (row0 + row < row_end) v = *reinterpret_cast<const u32x4 *>(B + ((row0 + row) * G + g) * kN + 8 * ch);
     uint32_t *dst = reinterpret_cast<uint32_t *>(sB + row * (kN + 2) + 8 * ch);
     dst[0] = v.x;
     dst[1] = v.y;
@@ -140,7 +224,7 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, int jb, int bg, co
     dst[3] = v.w;
   }
   __syncthreads();
-  uint16_t *Bout = Btr + (static_cast<size_t>(bg) * NB + jb) * kN * kBlk;
+  uint16_t *Bout = Btr + tile * kN * kBlk;
   for (int c = threadIdx.x; c < kN * (kBlk / 8); c += kThreads) {
     const int n = c / (kBlk / 8), s0 = (c % (kBlk / 8)) * 8;
     uint32_t w[4];
@@ -153,38 +237,37 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, int jb, int bg, co
   }
 }
 
-// ---- block_cumsum: per (batch, head, block) decay bookkeeping ----------------------------------
-// One workgroup per (block jb, 16 heads starting at h0, batch row b).  With cs_s the block-relative
-// inclusive prefix sum of dt*A*log2(e) (the
-// "segsum" input) and c31, c63 its values at tokens 31 and 63, every head gets one record of kRec
-// floats per block:
+// ---- block_cumsum: per (head, block) decay bookkeeping ------------------------------------------
+// One workgroup per (block, 16 heads starting at h0).  With cs_s the block-relative inclusive prefix
+// sum of dt*A*log2(e) (the "segsum" input) and c31, c63 its values at tokens 31 and 63, every head
+// gets one record of kRec floats per block:
 //   [0,64)     rowf_l = exp2(clamp(cs_l - c31))            output-row factor of the decay mask
 //   [64,128)   f_s    = dt_s * exp2(clamp(c31 - cs_s))     input factor of the decay mask
 //   [128]      exp2(c63 - c31)     state: middle of the block -> end of the block
 //   [129]      c63                 log2 of the block's total decay
 //   [130]      exp2(c31)           state: start of the block -> middle of the block
 //   [131]      [128] * [130] of the next block: middle of the block -> middle of the next block
-// Tokens beyond the sequence get dt = 0 (state-neutral padding).  dt is read in its
-// (batch, token, head) layout and transposed through LDS, 64 tokens of the block plus the first 32
-// of the next one (for [131]).
+// The block covers rows [row0, row0 + 64) of dt (tokens, H); rows from row_end on are not part of
+// the sequence and count as dt = 0 (state-neutral padding).  dt is transposed through LDS, 64 tokens
+// of the block plus the first 32 of the next one (for [131]).  Head h's record goes to record number
+// h * rec_stride + rec_off.
 constexpr int kRec = 2 * kBlk + 4;
 constexpr int kCumHeads = 16;
 constexpr float kMaxExp = 100.f;
-__device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1], int jb, int h0, int b,
-                                                   const float *__restrict__ dt, const float *__restrict__ A,
-                                                   float *__restrict__ prep, int T, int H, int NB) {
+__device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1], size_t row0, size_t row_end, int h0,
+                                                   size_t rec_stride, size_t rec_off, const float *__restrict__ dt,
+                                                   const float *__restrict__ A, float *__restrict__ prep, int H) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int tb = jb * kBlk;
   for (int i = threadIdx.x; i < kBlk * kCumHeads; i += kThreads) {
     const int tok = i / kCumHeads, hh = i % kCumHeads;
     float v = 0.f;
-    if (tb + tok < T && h0 + hh < H) v = dt[(static_cast<size_t>(b) * T + tb + tok) * H + h0 + hh];
+    if (row0 + tok < row_end && h0 + hh < H) v = dt[(row0 + tok) * H + h0 + hh];
     tile[tok][hh] = v;
   }
   for (int i = threadIdx.x; i < (kBlk / 2) * kCumHeads; i += kThreads) {
     const int tok = kBlk + i / kCumHeads, hh = i % kCumHeads;
     float v = 0.f;
-    if (tb + tok < T && h0 + hh < H) v = dt[(static_cast<size_t>(b) * T + tb + tok) * H + h0 + hh];
+    if (row0 + tok < row_end && h0 + hh < H) v = dt[(row0 + tok) * H + h0 + hh];
     tile[tok][hh] = v;
   }
   __syncthreads();
@@ -203,7 +286,7 @@ __device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1],
     float nx = lane < kBlk / 2 ? tile[kBlk + lane][hh] * (A[h] * kLog2e) : 0.f;
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) nx += __shfl_xor(nx, m, 64);
-    float *rec = prep + ((static_cast<size_t>(b) * H + h) * NB + jb) * kRec;
+    float *rec = prep + (static_cast<size_t>(h) * rec_stride + rec_off) * kRec;
     rec[lane] = fast_exp2(fminf(fmaxf(v - c31, -kMaxExp), kMaxExp));
     rec[kBlk + lane] = dtv * fast_exp2(fminf(fmaxf(c31 - v, -kMaxExp), kMaxExp));
     if (lane < 4)
@@ -216,7 +299,10 @@ __device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1],
 
 // Both preparation steps in one launch (they are independent of each other and each is far too
 // small to fill the chip): the first n_scores workgroups compute G and B^T, the others the decay
-// records.  grid (n_scores + NB * ceil(H/16) * Bt).
+// records.  NB = blocks per batch row (plain batch) or the block capacity (variable-length batch,
+// where workgroups beyond the actual number of blocks have nothing to do).
+// grid (n_scores + NB * ceil(H/16) * Bt), n_scores = NB * Bt * G; Bt = 1 for a variable-length batch.
+// Workspace tiles are numbered (b * G + g) * NB + block, records (b * H + h) * NB + block.
 __global__ __launch_bounds__(kThreads) void block_prep_kernel(const uint16_t *__restrict__ B,
                                                               const uint16_t *__restrict__ C,
                                                               uint16_t *__restrict__ Gd,
@@ -224,16 +310,36 @@ __global__ __launch_bounds__(kThreads) void block_prep_kernel(const uint16_t *__
                                                               const float *__restrict__ dt,
                                                               const float *__restrict__ A,
                                                               float *__restrict__ prep, int T, int H, int G,
-                                                              int NB, int n_scores) {
+                                                              int NB, int n_scores, const VarPlan vp) {
   __shared__ __align__(16) uint16_t sB[kBlk * (kN + 2)];
   __shared__ float tile[kBlk + kBlk / 2][kCumHeads + 1];
   const int wg = blockIdx.x;
-  if (wg < n_scores) {
-    scores_bt_block(sB, wg % NB, wg / NB, B, C, Gd, Btr, T, G, NB);
+  const bool scores = wg < n_scores;
+  const int i = scores ? wg : wg - n_scores;
+  const int jb = i % NB;  // block inside the batch row, or block of the packed batch
+  size_t row0, row_end;
+  if (vp.tok0 != nullptr) {
+    if (jb >= vp.blk0[vp.nseq]) return;
+    const int q = vp.blk_seq[jb];
+    row0 = static_cast<size_t>(vp.tok0[q]) + static_cast<size_t>(jb - vp.blk0[q]) * kBlk;
+    row_end = static_cast<size_t>(vp.tok0[q]) + vp.len[q];
+  }
+  if (scores) {
+    const int bg = i / NB;
+    if (vp.tok0 == nullptr) {
+      row0 = static_cast<size_t>(bg / G) * T + static_cast<size_t>(jb) * kBlk;
+      row_end = static_cast<size_t>(bg / G) * T + T;
+    }
+    scores_bt_block(sB, row0, row_end, static_cast<size_t>(bg) * NB + jb, bg % G, B, C, Gd, Btr, G);
   } else {
-    const int i = wg - n_scores;
     const int hgroups = (H + kCumHeads - 1) / kCumHeads;
-    block_cumsum_block(tile, i % NB, ((i / NB) % hgroups) * kCumHeads, i / (NB * hgroups), dt, A, prep, T, H, NB);
+    const int b = i / (NB * hgroups);
+    if (vp.tok0 == nullptr) {
+      row0 = static_cast<size_t>(b) * T + static_cast<size_t>(jb) * kBlk;
+      row_end = static_cast<size_t>(b) * T + T;
+    }
+    block_cumsum_block(tile, row0, row_end, ((i / NB) % hgroups) * kCumHeads, NB,
+                       static_cast<size_t>(b) * H * NB + jb, dt, A, prep, H);
   }
 }
 
@@ -246,29 +352,67 @@ struct ScanParams {
   const uint8_t *Btr;
   const float *prep;
   uint8_t *y;
-  const float *Hin;        // state entering each segment, or nullptr = zeros
-  size_t hin_bh_stride;    // elements between consecutive (b, h) in Hin
-  float *final_state;      // (Bt, H, P, N): written by the last segment
-  float *seg_state;        // states-only: (Bt, H, S, P, N); local end state of segment sg -> slot sg+1
-  float *seg_decay;        // states-only: (Bt, H, S) log2 of the segment's total decay
+  const float *Hin;        // state entering each segment (see slot numbering below), or nullptr = zeros
+  float *final_state;      // (sequences, H, P, N): written by the last segment of each sequence
+  float *seg_state;        // states-only: local end state of a segment -> the slot of the NEXT segment
+  float *seg_decay;        // states-only: log2 of the segment's total decay, one per slot
   int T, H, G, hpg, NB, seg_blocks, S;
   int cols, segs, total, per_xcd;  // workgroup mapping, see wg_coords
+  VarPlan vp;              // tok0 == nullptr: plain batch
 };
 
-// Workgroup -> (head group, segment, batch row).  The chip dispatches consecutive workgroup ids to
+// Where a workgroup works: head group `col`, segment `sg` of `S` of sequence `b`, whose `nb` blocks
+// start at token `tok0` of the packed token axis (`len` tokens), at workspace tile / record number
+// `blk0` (per group / per head: stride `blk_stride`), and whose state slots (one per segment, per
+// head: stride `slot_stride`) start at `slot0`.
+struct SeqView {
+  int col, sg, S, b, nb;
+  size_t tok0, blk0, blk_stride, slot0, slot_stride;
+  uint32_t len;
+};
+
+// Workgroup -> (head group, segment, sequence).  The chip dispatches consecutive workgroup ids to
 // its eight XCDs in turn, and each XCD has its own L2.  The workgroups that share C / B^T / G tiles
-// (all head groups of one segment of one batch row) are therefore given ids that are congruent
+// (all head groups of one segment of one sequence) are therefore given ids that are congruent
 // modulo 8, so that they run on one XCD and the tiles are fetched into one L2 instead of eight:
-// XCD k owns the contiguous range [k * per_xcd, (k + 1) * per_xcd) of the (batch, segment, head
+// XCD k owns the contiguous range [k * per_xcd, (k + 1) * per_xcd) of the (sequence, segment, head
 // group) list, head group fastest.  Ids beyond the list (the grid is rounded up to 8 * per_xcd) idle.
+// `last_too`: whether the last segment of a sequence is in the list (the states-only pass skips it).
 constexpr int kXcds = 8;
-__device__ __forceinline__ bool wg_coords(const ScanParams &p, int &col, int &sg, int &b) {
+__device__ __forceinline__ bool wg_coords(const ScanParams &p, bool last_too, SeqView &v) {
   const int id = blockIdx.x;
   const int w = (id % kXcds) * p.per_xcd + id / kXcds;
   if (w >= p.total) return false;
-  col = w % p.cols;
-  sg = (w / p.cols) % p.segs;
-  b = w / (p.cols * p.segs);
+  v.col = w % p.cols;
+  if (p.vp.tok0 == nullptr) {
+    v.sg = (w / p.cols) % p.segs;
+    v.b = w / (p.cols * p.segs);
+    v.S = p.S;
+    v.nb = p.NB;
+    v.tok0 = static_cast<size_t>(v.b) * p.T;
+    v.len = static_cast<uint32_t>(p.T);
+    v.blk0 = static_cast<size_t>(v.b) * p.NB;   // times G (tiles) or H (records) in the caller's stride
+    v.blk_stride = p.NB;
+    v.slot0 = static_cast<size_t>(v.b) * p.S;
+    v.slot_stride = p.S;
+    return true;
+  }
+  // variable-length batch: one list entry per segment of the whole batch
+  const int item = w / p.cols;
+  if (item >= p.vp.item0[p.vp.nseq]) return false;
+  const int q = p.vp.item_seq[item];
+  const int first = p.vp.item0[q];
+  v.b = q;
+  v.sg = item - first;
+  v.S = p.vp.item0[q + 1] - first;
+  if (!last_too && v.sg == v.S - 1) return false;
+  v.len = static_cast<uint32_t>(p.vp.len[q]);
+  v.nb = static_cast<int>((v.len + kBlk - 1) / kBlk);
+  v.tok0 = static_cast<size_t>(p.vp.tok0[q]);
+  v.blk0 = static_cast<size_t>(p.vp.blk0[q]);
+  v.blk_stride = static_cast<size_t>(p.vp.nb_cap);
+  v.slot0 = static_cast<size_t>(first);
+  v.slot_stride = static_cast<size_t>(p.vp.item_cap);
   return true;
 }
 
@@ -335,15 +479,21 @@ void chunk_scan_kernel(const ScanParams p) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: addresses derived from it stay scalar
   const int hw = wave >> 1, ph = wave & 1;  // head inside the workgroup, half of headdim
-  int col, sg, b;
-  if (!wg_coords(p, col, sg, b)) return;  // uniform over the workgroup
+  SeqView sv;
+  if (!wg_coords(p, !kStatesOnly, sv)) return;  // uniform over the workgroup
+  const int col = sv.col, sg = sv.sg;
   const int h = col * HPW + hw;
   const int g = (col * HPW) / p.hpg;  // the heads of a workgroup share one group
-  const size_t bh = static_cast<size_t>(b) * p.H + h;
-  const size_t bg = static_cast<size_t>(b) * p.G + g;
+  // workspace numbering: tiles (b, g, block), records (b, h, block), state slots (b, h, segment) for a
+  // plain batch; (g, block), (h, block), (h, segment) with batch-wide block / segment numbers otherwise
+  const bool plain = p.vp.tok0 == nullptr;
+  const size_t tile0 = plain ? (sv.blk0 * p.G + static_cast<size_t>(g) * sv.blk_stride) : (g * sv.blk_stride + sv.blk0);
+  const size_t rec0 = plain ? (sv.blk0 * p.H + static_cast<size_t>(h) * sv.blk_stride) : (h * sv.blk_stride + sv.blk0);
+  const size_t slot0 = plain ? (sv.slot0 * p.H + static_cast<size_t>(h) * sv.slot_stride) : (h * sv.slot_stride + sv.slot0);
+  const size_t bh = static_cast<size_t>(sv.b) * p.H + h;  // row of final_state
   const int r = lane & 31, kg = lane >> 5;
-  const int jb0 = sg * p.seg_blocks;
-  const int jb1 = min(p.NB, jb0 + p.seg_blocks);
+  const int jb0 = min(sv.nb, sg * p.seg_blocks);
+  const int jb1 = min(sv.nb, jb0 + p.seg_blocks);
   const int cg = lane & 3, tg = lane >> 2;  // x staging: columns 8cg..8cg+7 of the half, tokens 4tg..4tg+3
   uint16_t *const myX = sXm[hw] + 32 * ph * kXStride;  // this wave's 32 rows of Xm^T
   uint16_t *const myRaw = sRaw[kStatesOnly ? 0 : wave];
@@ -351,16 +501,16 @@ void chunk_scan_kernel(const ScanParams p) {
   // ---- addressing: scalar bases, per-lane byte offsets that never change ----
   const uint32_t xrow = static_cast<uint32_t>(p.H) * (kP * 2);   // bytes per token of x / y
   const uint32_t crow = static_cast<uint32_t>(p.G) * (kN * 2);   // bytes per token of C
-  const uint32_t xbytes = static_cast<uint32_t>(p.T) * xrow;     // one batch row of x / y
-  const uint32_t cbytes = static_cast<uint32_t>(p.T) * crow - static_cast<uint32_t>(g) * (kN * 2);
-  const uint8_t *const xb = p.x + static_cast<size_t>(b) * xbytes;
-  uint8_t *const yb = p.y + static_cast<size_t>(b) * xbytes;
-  const uint8_t *const cb = p.C + (static_cast<size_t>(b) * p.T * p.G + g) * (kN * 2);
-  const Rsrc rs_bt = make_rsrc(p.Btr + bg * p.NB * (kN * kBlk * 2), static_cast<uint32_t>(p.NB) * (kN * kBlk * 2));
-  const Rsrc rs_g = make_rsrc(p.Gd + bg * p.NB * (kBlk * kBlk * 2), static_cast<uint32_t>(p.NB) * (kBlk * kBlk * 2));
-  const float *const prep_bh = p.prep + bh * p.NB * kRec;
-  const Rsrc rs_prep = make_rsrc(prep_bh, static_cast<uint32_t>(p.NB) * (kRec * 4));
-  // descriptors of x, y and C start at the block and end at the batch row's last token
+  const uint32_t xbytes = sv.len * xrow;                         // the sequence's rows of x / y
+  const uint32_t cbytes = sv.len > 0 ? sv.len * crow - static_cast<uint32_t>(g) * (kN * 2) : 0;
+  const uint8_t *const xb = p.x + sv.tok0 * xrow;
+  uint8_t *const yb = p.y + sv.tok0 * xrow;
+  const uint8_t *const cb = p.C + (sv.tok0 * p.G + g) * (kN * 2);
+  const Rsrc rs_bt = make_rsrc(p.Btr + tile0 * (kN * kBlk * 2), static_cast<uint32_t>(sv.nb) * (kN * kBlk * 2));
+  const Rsrc rs_g = make_rsrc(p.Gd + tile0 * (kBlk * kBlk * 2), static_cast<uint32_t>(sv.nb) * (kBlk * kBlk * 2));
+  const float *const prep_bh = p.prep + rec0 * kRec;
+  const Rsrc rs_prep = make_rsrc(prep_bh, static_cast<uint32_t>(sv.nb) * (kRec * 4));
+  // descriptors of x, y and C start at the block and end at the sequence's last token
   auto x_rsrc = [&](int jb) { return make_rsrc(xb + static_cast<size_t>(jb) * kBlk * xrow, xbytes - static_cast<uint32_t>(jb) * kBlk * xrow); };
   auto y_rsrc = [&](int jb) { return make_rsrc(yb + static_cast<size_t>(jb) * kBlk * xrow, xbytes - static_cast<uint32_t>(jb) * kBlk * xrow); };
   auto c_rsrc = [&](int jb) { return make_rsrc(cb + static_cast<size_t>(jb) * kBlk * crow, cbytes - static_cast<uint32_t>(jb) * kBlk * crow); };
@@ -487,8 +637,7 @@ void chunk_scan_kernel(const ScanParams p) {
   // inside the loop, where it also waits for every younger load of every iteration.
   asm volatile("" : "+v"(Dh));
   if (!kStatesOnly && p.Hin != nullptr) {
-    const float *hp = p.Hin + bh * p.hin_bh_stride + static_cast<size_t>(sg) * kP * kN +
-                      static_cast<size_t>(pcol) * kN;
+    const float *hp = p.Hin + (slot0 + sg) * (kP * kN) + static_cast<size_t>(pcol) * kN;
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
@@ -794,9 +943,9 @@ void chunk_scan_kernel(const ScanParams p) {
   // ---- write the state out (canonical (p, n) layout, four consecutive n per 16-byte store) ----
   float *out = nullptr;
   if (kStatesOnly) {
-    out = p.seg_state + (bh * p.S + sg + 1) * kP * kN;
-    if (lane == 0 && ph == 0) p.seg_decay[bh * p.S + sg] = seg_total;
-  } else if (sg == p.S - 1) {
+    out = p.seg_state + (slot0 + sg + 1) * (kP * kN);
+    if (lane == 0 && ph == 0) p.seg_decay[slot0 + sg] = seg_total;
+  } else if (sg == sv.S - 1) {
     out = p.final_state + bh * kP * kN;
   }
   if (out != nullptr) {
@@ -810,20 +959,31 @@ void chunk_scan_kernel(const ScanParams p) {
 }
 
 // ---- segment_pass: slot[0] = h0; slot[sg] = exp2(decay[sg-1]) * slot[sg-1] + local[sg-1] --------
-// grid (P*N/1024, Bt*H), four consecutive state elements per thread.  seg_state slot sg (sg >= 1)
+// grid (P*N/1024, sequences*H), four consecutive state elements per thread.  seg_state slot sg (sg >= 1)
 // holds the local end state of segment sg-1 on entry and the state entering segment sg on exit.
 // The chain over segments is serial, but the loads do not depend on it: they are issued eight
 // segments at a time before the chain consumes them, so the kernel pays a few memory round trips
 // instead of one per segment.
 __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restrict__ seg_state,
                                                                 const float *__restrict__ seg_decay,
-                                                                const float *__restrict__ h0, int S) {
+                                                                const float *__restrict__ h0, int S_plain, int H,
+                                                                const VarPlan vp) {
   constexpr int kAhead = 8;
   const int e = (blockIdx.x * kThreads + threadIdx.x) * 4;
-  const size_t bh = blockIdx.y;
+  const size_t bh = blockIdx.y;  // (sequence, head)
+  int S = S_plain;
+  size_t slot0 = bh * S_plain;
+  if (vp.tok0 != nullptr) {
+    const int q = static_cast<int>(bh / H), h = static_cast<int>(bh % H);
+    const int first = vp.item0[q];
+    S = vp.item0[q + 1] - first;
+    slot0 = static_cast<size_t>(h) * vp.item_cap + first;
+    if (S < 1) return;  // rejected boundaries: empty tables
+  }
   f32x4 run = {0.f, 0.f, 0.f, 0.f};
   if (h0) run = *reinterpret_cast<const f32x4 *>(h0 + bh * kP * kN + e);
-  float *sp = seg_state + bh * S * kP * kN + e;
+  float *sp = seg_state + slot0 * (kP * kN) + e;
+  const float *dp = seg_decay + slot0;
   *reinterpret_cast<f32x4 *>(sp) = run;
   for (int s0 = 1; s0 < S; s0 += kAhead) {
     f32x4 v[kAhead];
@@ -832,7 +992,7 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
     for (int k = 0; k < kAhead; ++k) {
       const int sg = min(s0 + k, S - 1);  // clamped: the surplus loads of the last group are not used
       v[k] = *reinterpret_cast<const f32x4 *>(sp + static_cast<size_t>(sg) * kP * kN);
-      d[k] = seg_decay[bh * S + sg - 1];
+      d[k] = dp[sg - 1];
     }
 #pragma unroll
     for (int k = 0; k < kAhead; ++k) {
@@ -894,16 +1054,22 @@ int choose_seg_blocks(const Dims &d) {
   return best_blocks;
 }
 
+// Workspace.  Plain batch: rows = Bt sequences of NB blocks each.  Variable-length batch: one "row" whose
+// NB is the block capacity ceil(total / 64) + nseq (every sequence may end in a partial block) and
+// whose segment capacity is NB / (blocks per chunk) + nseq (a segment is at least a chunk, and every
+// sequence has at least one segment), followed by the int32 tables of VarPlan.
 struct Layout {
   int NB, S_max;
-  size_t off_G, off_Bt, off_prep, off_state, off_decay, total;
+  size_t off_G, off_Bt, off_prep, off_state, off_decay, off_tables, total;
 };
 
-Layout make_layout(const Dims &d) {
+Layout make_layout(const Dims &d, bool varlen) {
   Layout w;
-  w.NB = (d.T + kBlk - 1) / kBlk;
-  w.S_max = d.Nc;  // a segment is at least one chunk
-  const size_t BG = static_cast<size_t>(d.Bt) * d.G, BH = static_cast<size_t>(d.Bt) * d.H;
+  const int rows = varlen ? 1 : d.Bt;
+  const int nseq = varlen ? d.Bt : 0;
+  w.NB = (d.T + kBlk - 1) / kBlk + nseq;
+  w.S_max = varlen ? w.NB / (d.L / kBlk) + nseq + 1 : d.Nc;  // a segment is at least one chunk
+  const size_t BG = static_cast<size_t>(rows) * d.G, BH = static_cast<size_t>(rows) * d.H;
   size_t off = 0;
   w.off_G = off;
   off += round_up(BG * w.NB * kBlk * kBlk * sizeof(uint16_t), 256);
@@ -915,41 +1081,62 @@ Layout make_layout(const Dims &d) {
   off += round_up(BH * w.S_max * kP * kN * sizeof(float), 256);
   w.off_decay = off;
   off += round_up(BH * w.S_max * sizeof(float), 256);
+  w.off_tables = off;
+  if (varlen) off += round_up((4 * (static_cast<size_t>(nseq) + 1) + w.NB + w.S_max) * sizeof(int32_t), 256);
   w.total = off;
   return w;
 }
 
-}  // namespace
-
-bool mfma_supported(const Dims &d) {
-  // one batch row of x, C and the per-head block records must be addressable with 32-bit byte offsets
+bool shape_ok(const Dims &d, unsigned long long tokens, unsigned long long nb) {
+  // one sequence of x, C and the per-head block records must be addressable with 32-bit byte offsets
   const unsigned long long lim = 0xFFFF0000ull;
-  const unsigned long long nb = (static_cast<unsigned long long>(d.T) + kBlk - 1) / kBlk;
   return d.bf16 && d.P == kP && d.N == kN && d.L % kBlk == 0 && d.hpg % kHeadsPerWg == 0 && d.Bt <= 65535 &&
-         d.H <= 65535 && static_cast<unsigned long long>(d.T) * d.H * (kP * 2) <= lim &&
-         static_cast<unsigned long long>(d.T) * d.G * (kN * 2) <= lim && nb * (kN * kBlk * 2) <= lim;
+         d.H <= 65535 && tokens * d.H * (kP * 2) <= lim && tokens * d.G * (kN * 2) <= lim &&
+         nb * (kN * kBlk * 2) <= lim;
 }
 
-size_t mfma_workspace_bytes(const Dims &d) { return make_layout(d).total; }
-
-hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, const float *A, const void *B,
-                               const void *C, const float *D, const float *h0, void *y, float *final_state,
-                               void *workspace, hipStream_t stream, KernelTrace *trace) {
-  const Layout w = make_layout(d);
+// d: plain batch (cu == nullptr), or Bt = number of sequences and T = total tokens of a packed batch.
+hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *dt, const float *A, const void *B,
+                  const void *C, const float *D, const float *h0, void *y, float *final_state, void *workspace,
+                  hipStream_t stream, KernelTrace *trace) {
+  const bool varlen = cu != nullptr;
+  const Layout w = make_layout(d, varlen);
   char *ws = static_cast<char *>(workspace);
   uint16_t *Gd = reinterpret_cast<uint16_t *>(ws + w.off_G);
   uint16_t *Btr = reinterpret_cast<uint16_t *>(ws + w.off_Bt);
   float *prep = reinterpret_cast<float *>(ws + w.off_prep);
   float *seg_state = reinterpret_cast<float *>(ws + w.off_state);
   float *seg_decay = reinterpret_cast<float *>(ws + w.off_decay);
-  const int seg_blocks = choose_seg_blocks(d);
-  const int S = (w.NB + seg_blocks - 1) / seg_blocks;
+  const int rows = varlen ? 1 : d.Bt;
+  Dims one = d;  // the segment length of a packed batch is chosen as for one sequence of all its tokens
+  if (varlen) one.Bt = 1;
+  const int seg_blocks = choose_seg_blocks(one);
 
-  const int n_scores = w.NB * d.Bt * d.G;
-  const int n_cumsum = w.NB * ((d.H + kCumHeads - 1) / kCumHeads) * d.Bt;
+  VarPlan vp = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
+  int S = (w.NB + seg_blocks - 1) / seg_blocks;  // plain batch: segments per sequence
+  int items = S * d.Bt;                          // segments of the whole batch (varlen: upper bound)
+  if (varlen) {
+    int32_t *t = reinterpret_cast<int32_t *>(ws + w.off_tables);
+    const int n1 = d.Bt + 1;
+    int32_t *tok0 = t, *len = t + n1, *blk0 = t + 2 * n1, *item0 = t + 3 * n1, *blk_seq = t + 4 * n1,
+            *item_seq = blk_seq + w.NB;
+    items = w.NB / seg_blocks + d.Bt + 1;
+    if (items > w.S_max) items = w.S_max;
+    S = 0;  // per sequence, from the tables
+    hipLaunchKernelGGL(varlen_scan_kernel, dim3(1), dim3(256), 0, stream, cu, d.Bt, d.T, seg_blocks, tok0, len, blk0,
+                       item0);
+    const int cap = w.NB > items ? w.NB : items;
+    hipLaunchKernelGGL(varlen_fill_kernel, dim3((cap + 255) / 256), dim3(256), 0, stream, blk0, item0, d.Bt, blk_seq,
+                       item_seq);
+    vp = VarPlan{tok0, len, blk0, item0, blk_seq, item_seq, d.Bt, w.NB, w.S_max};
+    trace_mark(trace, stream, "varlen_tables");
+  }
+
+  const int n_scores = w.NB * rows * d.G;
+  const int n_cumsum = w.NB * ((d.H + kCumHeads - 1) / kCumHeads) * rows;
   hipLaunchKernelGGL(block_prep_kernel, dim3(n_scores + n_cumsum), dim3(kThreads), 0, stream,
                      static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(C), Gd, Btr, dt, A, prep,
-                     d.T, d.H, d.G, w.NB, n_scores);
+                     d.T, d.H, d.G, w.NB, n_scores, vp);
   trace_mark(trace, stream, "block_prep");
 
   ScanParams p;
@@ -970,33 +1157,62 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
   p.NB = w.NB;
   p.seg_blocks = seg_blocks;
   p.S = S;
-  if (S > 1) {
+  p.vp = vp;
+  if (varlen || S > 1) {
+    // (a packed batch always takes this route: whether any sequence has more than one segment is
+    // known on the device only; workgroups of last segments leave the states-only pass at once)
     p.Hin = nullptr;
-    p.hin_bh_stride = 0;
     constexpr int kStatesHeads = 4;  // heads per workgroup of the states-only kernel (2 was measured: slower)
     p.cols = d.H / kStatesHeads;
     p.segs = S - 1;
-    p.total = p.cols * p.segs * d.Bt;
+    p.total = varlen ? p.cols * items : p.cols * p.segs * d.Bt;
     p.per_xcd = (p.total + kXcds - 1) / kXcds;
     hipLaunchKernelGGL((chunk_scan_kernel<true, kStatesHeads>), dim3(kXcds * p.per_xcd), dim3(128 * kStatesHeads), 0,
                        stream, p);
     trace_mark(trace, stream, "segment_states");
     hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), d.Bt * d.H), dim3(kThreads), 0, stream,
-                       seg_state, seg_decay, h0, S);
+                       seg_state, seg_decay, h0, S, d.H, vp);
     trace_mark(trace, stream, "segment_pass");
     p.Hin = seg_state;
-    p.hin_bh_stride = static_cast<size_t>(S) * kP * kN;
   } else {
     p.Hin = h0;
-    p.hin_bh_stride = static_cast<size_t>(kP) * kN;
   }
   p.cols = d.H / kHeadsPerWg;
   p.segs = S;
-  p.total = p.cols * p.segs * d.Bt;
+  p.total = varlen ? p.cols * items : p.cols * p.segs * d.Bt;
   p.per_xcd = (p.total + kXcds - 1) / kXcds;
   hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0, stream, p);
   trace_mark(trace, stream, "chunk_scan");
   return hipGetLastError();
+}
+
+}  // namespace
+
+bool mfma_supported(const Dims &d) {
+  return shape_ok(d, static_cast<unsigned long long>(d.T), (static_cast<unsigned long long>(d.T) + kBlk - 1) / kBlk);
+}
+
+size_t mfma_workspace_bytes(const Dims &d) { return make_layout(d, false).total; }
+
+hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, const float *A, const void *B,
+                               const void *C, const float *D, const float *h0, void *y, float *final_state,
+                               void *workspace, hipStream_t stream, KernelTrace *trace) {
+  return launch(d, nullptr, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);
+}
+
+// Packed variable-length batch: d.Bt sequences, d.T tokens in total, boundaries in the device array cu.
+bool mfma_varlen_supported(const Dims &d) {
+  const unsigned long long nb = (static_cast<unsigned long long>(d.T) + kBlk - 1) / kBlk + d.Bt;
+  return shape_ok(d, static_cast<unsigned long long>(d.T), nb) && nb <= 0x7fffffffull / 64;
+}
+
+size_t mfma_varlen_workspace_bytes(const Dims &d) { return make_layout(d, true).total; }
+
+hipError_t launch_prefill_mfma_varlen(const Dims &d, const int32_t *cu_seqlens, const void *x, const float *dt,
+                                      const float *A, const void *B, const void *C, const float *D, const float *h0,
+                                      void *y, float *final_state, void *workspace, hipStream_t stream,
+                                      KernelTrace *trace) {
+  return launch(d, cu_seqlens, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);
 }
 
 }  // namespace ssd

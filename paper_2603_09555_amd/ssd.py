@@ -19,7 +19,7 @@ SSD_F32, SSD_BF16 = 0, 1
 SSD_OK = 0
 
 EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
-           "ssd_decode_steps_layers",
+           "ssd_decode_steps_layers", "ssd_prefill_varlen_workspace_bytes", "ssd_prefill_varlen",
            "ssd_prefill_path", "ssd_status_string", "ssd_version"]
 
 
@@ -52,6 +52,10 @@ _lib.ssd_decode_step.restype = ctypes.c_int
 _lib.ssd_decode_step.argtypes = [_sp] + [_vp] * 9
 _lib.ssd_decode_step_layers.restype = ctypes.c_int
 _lib.ssd_decode_step_layers.argtypes = [ctypes.c_int32, _sp] + [_vp] * 9
+_lib.ssd_prefill_varlen_workspace_bytes.restype = _sz
+_lib.ssd_prefill_varlen_workspace_bytes.argtypes = [_sp]
+_lib.ssd_prefill_varlen.restype = ctypes.c_int
+_lib.ssd_prefill_varlen.argtypes = [_sp] + [_vp] * 11 + [_sz, _vp]
 _lib.ssd_decode_steps_layers.restype = ctypes.c_int
 _lib.ssd_decode_steps_layers.argtypes = [ctypes.c_int32, ctypes.c_int32, _sp] + [_vp] * 9
 _lib.ssd_prefill_path.restype = ctypes.c_char_p
@@ -201,3 +205,34 @@ def ssd_decode_steps_layers(state, x, dt, A, B, C, D, y=None):
     if st != SSD_OK:
         raise SSDError(st, "ssd_decode_steps_layers")
     return y
+
+
+def ssd_prefill_varlen(x, dt, A, B, C, D, cu_seqlens, chunk, h0=None, y=None, final_state=None, workspace=None):
+    """``ssd_prefill_varlen``: packed batch ``x (tokens,H,P)``, ``dt (tokens,H)``, ``B, C (tokens,G,N)``,
+    ``cu_seqlens (nseq+1)`` int32 on the device, ``h0 (nseq,H,P,N)`` optional.
+    Returns ``(y (tokens,H,P), final_state (nseq,H,P,N))``."""
+    T, H, P = x.shape
+    G, N = B.shape[1], B.shape[2]
+    nseq = cu_seqlens.numel() - 1
+    if cu_seqlens.dtype != torch.int32 or nseq < 1:
+        raise ValueError("cu_seqlens must hold nseq + 1 int32 values")
+    shape = make_shape(nseq, T, H, P, N, G, chunk, x.dtype)
+    if B.dtype != x.dtype or C.dtype != x.dtype:
+        raise ValueError("x, B and C must share one dtype")
+    if tuple(dt.shape) != (T, H) or tuple(A.shape) != (H,) or tuple(D.shape) != (H,) or tuple(B.shape) != (T, G, N) \
+            or tuple(C.shape) != (T, G, N) or (h0 is not None and tuple(h0.shape) != (nseq, H, P, N)):
+        raise ValueError("inconsistent tensor shapes")
+    if y is None:
+        y = torch.empty_like(x)
+    if final_state is None:
+        final_state = torch.empty((nseq, H, P, N), dtype=torch.float32, device=x.device)
+    need = int(_lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(shape)))
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    _check_dev(x, dt, A, B, C, D, h0, y, final_state, workspace, cu_seqlens)
+    st = _lib.ssd_prefill_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C),
+                                 _ptr(D), _ptr(h0), _ptr(y), _ptr(final_state), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream_ptr())
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_prefill_varlen")
+    return y, final_state

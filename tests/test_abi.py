@@ -102,6 +102,31 @@ def test_decode_rejects_before_any_hip_call(ssd):
                                None) == -1
 
 
+def test_varlen_rejects_before_any_hip_call(ssd):
+    lib = ssd.raw()
+    fake = ctypes.c_void_p(4096)
+    ok = dict(batch=3, seqlen=1000, nheads=8, headdim=64, dstate=128, ngroups=1, chunk=256, io_dtype=1)
+
+    def call(s, cu=fake, x=fake, h0=None, w=fake, wb=1 << 40):
+        return lib.ssd_prefill_varlen(ctypes.byref(s) if s is not None else None, cu, x, fake, fake, fake, fake, fake,
+                                      h0, fake, fake, w, ctypes.c_size_t(wb), None)
+
+    need = lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(shape(ssd, **ok)))
+    assert need > 0 and need % 256 == 0
+    assert call(None) == -1
+    assert call(shape(ssd, **ok), cu=None) == -1
+    assert call(shape(ssd, **ok), x=None) == -1
+    assert call(shape(ssd, **ok), cu=ctypes.c_void_p(4098)) == -7
+    assert call(shape(ssd, **ok), h0=ctypes.c_void_p(4100)) == -7
+    assert call(shape(ssd, **ok), wb=need - 1) == -5
+    assert call(shape(ssd, **ok), w=None) == -5
+    assert call(shape(ssd, **dict(ok, seqlen=0))) == -2
+    # outside the MFMA kernel family: fp32 io, other head shapes, chunk not a multiple of 64
+    for bad in (dict(io_dtype=0), dict(headdim=32), dict(dstate=64), dict(chunk=100), dict(ngroups=4)):
+        assert call(shape(ssd, **dict(ok, **bad))) == -4
+        assert lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(shape(ssd, **dict(ok, **bad)))) == 0
+
+
 def test_decode_steps_rejects_before_any_hip_call(ssd):
     lib = ssd.raw()
     fake = ctypes.c_void_p(4096)

@@ -356,3 +356,77 @@ def test_mfma_extreme_decay_and_determinism(ssd):
     y_ref, st_ref = oracle_prefill(inp)
     assert_close(y, y_ref, 2e-2, "extreme decay y (mfma)")
     assert_close(st, st_ref, 2e-2, "extreme decay state (mfma)")
+
+
+# ---- packed variable-length batches (MFMA kernel family) ----------------------------------------
+VARLEN_CASES = [
+    # lengths (a tuple marks a filler sequence), H, G, L, forced chunks per segment, with h0
+    ([64], 4, 1, 64, 0, False),                                  # one sequence, one block
+    ([1, 63, 64, 65, 0, 300, 129], 4, 1, 64, 0, False),          # ragged ends, an empty sequence
+    ([1, 63, 64, 65, 0, 300, 129], 8, 2, 64, 1, True),           # two groups, one chunk per segment, h0
+    ([700, 5, 0, 0, 1000, 64], 4, 1, 128, 1, True),              # several segments per sequence
+    ([(3,), 200, (70,), 130, (1,)], 4, 1, 256, 0, True),         # short fillers between long sequences
+    ([1000, 1048], 12, 1, 256, 2, False),
+    ([17] * 40, 4, 1, 64, 0, True),                              # many short sequences
+]
+
+
+@pytest.mark.parametrize("case", VARLEN_CASES, ids=lambda c: "-".join(str(v) for v in c[1:]) + "-n%d" % len(c[0]))
+def test_varlen_prefill_matches_oracle(ssd, case, monkeypatch):
+    lengths, H, G, L, seg_chunks, with_h0 = case
+    lens = [v[0] if isinstance(v, tuple) else v for v in lengths]   # gaps are simply more sequences
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T, nseq = int(cu[-1]), len(lens)
+    if seg_chunks:
+        monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg_chunks))
+    cfg = cfg_of(1, T, H, 64, 128, G, L, "bf16")
+    inp = inputs.make_prefill_inputs(cfg, seed=31)
+    pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
+    h0 = inputs.make_state(cfg_of(nseq, 1, H, 64, 128, G, L, "bf16"), seed=31) if with_h0 else None
+    print("varlen case", lens, "H", H, "G", G, "L", L, "seg_chunks", seg_chunks, "h0", with_h0, flush=True)
+    dev = {k: v.cuda() for k, v in pk.items()}
+    y = torch.full_like(dev["x"], 7.0)
+    y, st = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
+                                   torch.from_numpy(cu).cuda(), L, h0=None if h0 is None else h0.cuda(), y=y)
+    torch.cuda.synchronize()
+    y_ref, st_ref = ssd_oracle.prefill_varlen(pk["x"], pk["dt"], pk["A"], pk["B"], pk["C"], pk["D"], cu, h0=h0)
+    assert_close(y, y_ref, 2e-2, "varlen y")
+    assert_close(st, st_ref, 2e-2, "varlen final states")
+    # every sequence on its own through the plain entry point: same kernels, same values
+    for q in range(nseq):
+        a, b = int(cu[q]), int(cu[q + 1])
+        if b == a:
+            continue
+        yq, sq = ssd.ssd_prefill(dev["x"][None, a:b].contiguous(), dev["dt"][None, a:b].contiguous(), dev["A"],
+                                 dev["B"][None, a:b].contiguous(), dev["C"][None, a:b].contiguous(), dev["D"], L,
+                                 h0=None if h0 is None else h0[q:q + 1].cuda())
+        torch.cuda.synchronize()
+        assert_close(y[a:b], to_np64(yq[0]), 2e-2, "varlen y vs single sequence %d" % q)
+        assert_close(st[q], to_np64(sq[0]), 2e-2, "varlen state vs single sequence %d" % q)
+
+
+def test_varlen_leaves_unowned_tokens_alone_and_rejects_bad_boundaries(ssd):
+    H, L = 4, 64
+    T = 400
+    cfg = cfg_of(1, T, H, 64, 128, 1, L, "bf16")
+    inp = inputs.make_prefill_inputs(cfg, seed=37)
+    dev = {k: (v[0] if k in ("x", "dt", "B", "C") else v).cuda() for k, v in inp.items()}
+    # tokens [0, 10) and [300, 400) belong to no sequence
+    cu = torch.tensor([10, 100, 300], dtype=torch.int32).cuda()
+    y = torch.full_like(dev["x"], 7.0)
+    y, st = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cu, L, y=y)
+    torch.cuda.synchronize()
+    assert (y[:10] == 7.0).all() and (y[300:] == 7.0).all()
+    pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
+    y_ref, st_ref = ssd_oracle.prefill_varlen(pk["x"], pk["dt"], pk["A"], pk["B"], pk["C"], pk["D"],
+                                              np.array([10, 100, 300], dtype=np.int32))
+    assert_close(y[10:300], y_ref[10:300], 2e-2, "varlen y with unowned tokens")
+    assert_close(st, st_ref, 2e-2, "varlen states with unowned tokens")
+    # boundaries that decrease, or run past the token count: the call is a no-op
+    for bad in ([0, 200, 100], [0, 100, 401], [-1, 100, 300]):
+        y2 = torch.full_like(dev["x"], 7.0)
+        st2 = torch.full((2, H, 64, 128), 5.0, device="cuda")
+        ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
+                               torch.tensor(bad, dtype=torch.int32).cuda(), L, y=y2, final_state=st2)
+        torch.cuda.synchronize()
+        assert (y2 == 7.0).all() and (st2 == 5.0).all(), bad

@@ -180,6 +180,81 @@ def test_decode_steps_equal_the_scan_over_the_same_tokens():
         np.testing.assert_allclose(s2[l], sl, rtol=1e-12, atol=1e-12)
 
 
+def packed_kernel_form(x, dt, A, B, C, D, cu, h0=None):
+    """The O(T^2) form of Eq. 3 over the PACKED token axis with a block-diagonal mask:
+    y_t = sum_{s<=t, seq(s)=seq(t)} (C_t.B_s) exp(sum_{j=s+1..t} dt_j A) dt_s x_s + D x_t
+    (+ the h0 term decayed from the start of t's sequence).  No slicing per sequence."""
+    T, H, P = x.shape
+    G, N = B.shape[1], B.shape[2]
+    hpg = H // G
+    seq = np.full(T, -1)
+    for q in range(len(cu) - 1):
+        seq[cu[q]:cu[q + 1]] = q
+    y = np.zeros((T, H, P))
+    st = np.zeros((len(cu) - 1, H, P, N)) if h0 is None else np.array(h0, dtype=np.float64)
+    for h in range(H):
+        g = h // hpg
+        a = dt[:, h] * A[h]
+        ca = np.concatenate([[0.0], np.cumsum(a)])          # ca[t+1] = sum_{j<=t} a_j
+        for t in range(T):
+            if seq[t] < 0:
+                continue
+            acc = np.zeros(P)
+            for s in range(t + 1):
+                if seq[s] == seq[t]:
+                    acc += np.dot(C[t, g], B[s, g]) * np.exp(ca[t + 1] - ca[s + 1]) * dt[s, h] * x[s, h]
+            if h0 is not None:
+                acc += np.exp(ca[t + 1] - ca[cu[seq[t]]]) * (h0[seq[t], h] @ C[t, g])
+            y[t, h] = acc + D[h] * x[t, h]
+        for q in range(len(cu) - 1):
+            e = cu[q + 1]
+            if e == cu[q]:
+                continue
+            acc = np.zeros((P, N))
+            for s in range(cu[q], e):
+                acc += np.exp(ca[e] - ca[s + 1]) * dt[s, h] * np.outer(x[s, h], B[s, g])
+            if h0 is not None:
+                acc += np.exp(ca[e] - ca[cu[q]]) * h0[q, h]
+            st[q, h] = acc
+    return y, st
+
+
+def test_varlen_oracle_against_block_diagonal_kernel_form():
+    r = np.random.default_rng(11)
+    T, H, P, N, G = 23, 4, 3, 5, 2
+    cu = [2, 2, 9, 10, 10, 21]      # leading gap, empty sequences, a single token, trailing gap
+    x = r.standard_normal((T, H, P))
+    dt = r.uniform(0.01, 0.3, (T, H))
+    A = -r.uniform(0.5, 4, H)
+    D = r.standard_normal(H)
+    B = r.standard_normal((T, G, N))
+    C = r.standard_normal((T, G, N))
+    for h0 in (None, r.standard_normal((len(cu) - 1, H, P, N))):
+        y, st = ssd_oracle.prefill_varlen(x, dt, A, B, C, D, np.array(cu, dtype=np.int32), h0=h0)
+        y_ref, st_ref = packed_kernel_form(x, dt, A, B, C, D, cu, h0=h0)
+        np.testing.assert_allclose(y, y_ref, rtol=1e-11, atol=1e-12)
+        np.testing.assert_allclose(st, st_ref, rtol=1e-11, atol=1e-12)
+        assert not y[:2].any() and not y[21:].any()
+
+
+def test_varlen_oracle_equal_lengths_is_the_batched_prefill():
+    r = np.random.default_rng(12)
+    Bt, T, H, P, N, G = 3, 6, 4, 2, 3, 1
+    x = r.standard_normal((Bt, T, H, P))
+    dt = r.uniform(0.01, 0.3, (Bt, T, H))
+    A = -r.uniform(0.5, 4, H)
+    D = r.standard_normal(H)
+    B = r.standard_normal((Bt, T, G, N))
+    C = r.standard_normal((Bt, T, G, N))
+    h0 = r.standard_normal((Bt, H, P, N))
+    y, st = ssd_oracle.prefill(x, dt, A, B, C, D, h0=h0)
+    cu = np.arange(Bt + 1, dtype=np.int32) * T
+    yv, stv = ssd_oracle.prefill_varlen(x.reshape(Bt * T, H, P), dt.reshape(Bt * T, H), A, B.reshape(Bt * T, G, N),
+                                        C.reshape(Bt * T, G, N), D, cu, h0=h0)
+    np.testing.assert_array_equal(yv.reshape(Bt, T, H, P), y)
+    np.testing.assert_array_equal(stv, st)
+
+
 def test_bf16_decay_would_be_visible():
     """The paper's decay-precision ablation: rounding exp(dt*A) to bf16 shows up far above the
     fp32 tolerance (1e-4), so a parity test at that tolerance can tell the two apart."""
