@@ -108,6 +108,7 @@ def main():
     ap.add_argument("--decode-block", type=int, default=64,
                     help="steps per HIP graph and per multi-step launch in the decode comparison")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-varlen", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-configs", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -220,6 +221,73 @@ def main():
             extra[name] = prefill_report(c, ms, k)
             log("[bench] %s: %.4f ms, %.1f TFLOP/s causal" % (name, ms, extra[name]["tflops_causal"]))
             torch.cuda.empty_cache()
+
+    # ---- ragged batches and piecewise prompts (same token count and head shape as the headline) -----
+    varlen = {}
+    if not args.no_varlen and head["path"] == "mfma_bf16" and cfg.batch == 1:
+        import numpy as np
+        inp = inputs.make_prefill_inputs(cfg, seed=0, device=dev)
+        pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
+        T = cfg.seqlen
+        y = torch.empty_like(pk["x"])
+
+        def ragged_lengths(nseq, seed):
+            """nseq lengths summing to T: log-uniform over a 64x range, rounded, the rest to the longest."""
+            r = np.random.default_rng(seed)
+            w = np.exp(r.uniform(0.0, np.log(64.0), nseq))
+            ln = np.maximum(1, np.floor(w / w.sum() * T).astype(np.int64))
+            ln[np.argmax(ln)] += T - ln.sum()
+            return ln
+
+        for label, lens in (("1x%d" % T, np.array([T])), ("16_ragged", ragged_lengths(16, 7)),
+                            ("64_ragged", ragged_lengths(64, 8)), ("256x64", np.full(T // 64, 64))):
+            cu = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).to(dev)
+            nseq = len(lens)
+            st = torch.empty((nseq, cfg.nheads, cfg.headdim, cfg.dstate), dtype=torch.float32, device=dev)
+            shp = ssd.make_shape(nseq, T, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk,
+                                 cfg.torch_io_dtype)
+            ws = torch.empty((ssd.raw().ssd_prefill_varlen_workspace_bytes(shp),), dtype=torch.uint8, device=dev)
+            run = lambda: ssd.ssd_prefill_varlen(pk["x"], pk["dt"], pk["A"], pk["B"], pk["C"], pk["D"], cu, cfg.chunk,
+                                                 y=y, final_state=st, workspace=ws)
+            for _ in range(3):
+                run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                run()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            fl = sum(sum(prefill_flops(cfg.with_(seqlen=int(n)), True).values()) for n in lens if n > 0)
+            varlen[label] = dict(nseq=nseq, min_len=int(lens.min()), max_len=int(lens.max()), ms=round(ms, 5),
+                                 tflops_causal=round(fl / ms / 1e9, 1))
+            log("[bench] varlen %s: %.4f ms, %.1f TFLOP/s causal" % (label, ms, fl / ms / 1e9))
+            del ws, st
+        # the headline prompt fed in four pieces, each continuing from the state the previous one left
+        pieces = 4
+        Tp = T // pieces
+        st = torch.zeros((1, cfg.nheads, cfg.headdim, cfg.dstate), dtype=torch.float32, device=dev)
+        cfgp = cfg.with_(seqlen=Tp)
+        ws = torch.empty((max(ssd.prefill_workspace_bytes(shape_of(cfgp)), 256),), dtype=torch.uint8, device=dev)
+        sl = [{k: inp[k][:, i * Tp:(i + 1) * Tp].contiguous() for k in ("x", "dt", "B", "C")} for i in range(pieces)]
+        yp = torch.empty_like(sl[0]["x"])
+
+        def run_pieces():
+            for i in range(pieces):
+                ssd.ssd_prefill(sl[i]["x"], sl[i]["dt"], inp["A"], sl[i]["B"], sl[i]["C"], inp["D"], cfg.chunk,
+                                h0=None if i == 0 else st, y=yp, final_state=st, workspace=ws)
+        for _ in range(3):
+            run_pieces()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run_pieces()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        varlen["continuation_4x%d" % Tp] = dict(pieces=pieces, ms=round(ms, 5),
+                                                tflops_causal=round(sum(prefill_flops(cfg, True).values()) / ms / 1e9, 1))
+        log("[bench] prompt in %d pieces with carried state: %.4f ms" % (pieces, ms))
+        del inp, pk, y, sl, yp, ws, st
+        torch.cuda.empty_cache()
 
     # ---- decode: 64 stacked layers, states seeded by a 2048-token prefill, 1024 steps ---------
     decode = {}
@@ -393,6 +461,7 @@ def main():
                    "headdim": cfg.headdim, "dstate": cfg.dstate, "ngroups": cfg.ngroups, "chunk": cfg.chunk,
                    "step": "ssd_prefill + one ssd_decode_step", "flop_count": "algorithmic, causal-only"},
         "prefill": head, "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "other_configs": extra,
+        "varlen": varlen,
     }
     print(json.dumps(out))
 

@@ -10,7 +10,7 @@ namespace {
 
 using ssd::Dims;
 
-ssd_status make_dims(const ssd_shape *s, bool decode, Dims *out) {
+ssd_status make_dims(const ssd_shape *s, bool decode, Dims *out, bool packed = false) {
   if (!s) return SSD_ERR_NULL;
   if (s->io_dtype != SSD_F32 && s->io_dtype != SSD_BF16) return SSD_ERR_DTYPE;
   if (s->batch < 1 || s->nheads < 1 || s->headdim < 1 || s->dstate < 1 || s->ngroups < 1)
@@ -32,7 +32,7 @@ ssd_status make_dims(const ssd_shape *s, bool decode, Dims *out) {
   const long double lim = 1.0e15L;
   const long double bt = d.Bt, t = d.T, h = d.H, p = d.P, n = d.N;
   if (bt * t * h * p > lim || bt * h * p * n > lim || bt * t * d.G * n > lim) return SSD_ERR_SHAPE;
-  if (bt * h > 65535.0L && !decode) return SSD_ERR_UNSUPPORTED;  // grid y/z limit of the prefill kernels
+  if (bt * h > 65535.0L && !decode && !packed) return SSD_ERR_UNSUPPORTED;  // grid y/z limit of the prefill kernels
   if (d.Nc > 65535) return SSD_ERR_UNSUPPORTED;
   *out = d;
   return SSD_OK;
@@ -133,7 +133,7 @@ ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, const floa
 
 size_t ssd_prefill_varlen_workspace_bytes(const ssd_shape *shape) {
   Dims d;
-  if (make_dims(shape, false, &d) != SSD_OK || force_generic() || !ssd::mfma_varlen_supported(d)) return 0;
+  if (make_dims(shape, false, &d, true) != SSD_OK || force_generic() || !ssd::mfma_varlen_supported(d)) return 0;
   return ssd::mfma_varlen_workspace_bytes(d);
 }
 
@@ -142,7 +142,7 @@ ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_seqlens,
                               void *y, float *final_state, void *workspace, size_t workspace_bytes_given,
                               void *hip_stream) {
   Dims d;  // batch = number of sequences, seqlen = total tokens
-  const ssd_status st = make_dims(shape, false, &d);
+  const ssd_status st = make_dims(shape, false, &d, true);
   if (st != SSD_OK) return st;
   if (!cu_seqlens || !x || !dt || !A || !B || !C || !D || !y || !final_state) return SSD_ERR_NULL;
   if (!aligned16(x) || !aligned16(dt) || !aligned16(B) || !aligned16(C) || !aligned16(y) ||

@@ -97,63 +97,74 @@ __device__ __forceinline__ f32x16 mfma(const Operand &a, const Operand &b, f32x1
 // for a plain batch) and one or more segments.  Two tiny kernels turn the boundaries into tables:
 //   tok0[q], len[q]      first token and length of sequence q
 //   blk0[q], item0[q]    number of blocks / segments of the sequences before q (entry nseq: totals)
-//   blk_seq[i], item_seq[i]   sequence that block i / segment i belongs to
+//   slot0[q]             number of state slots before q: a sequence of several segments has one slot
+//                        per segment, a sequence of one segment needs none
+//   blk_seq[i], item_seq[i]   sequence that block i / entry i of the segment list belongs to
 // Blocks and segments are numbered over the whole batch; workspace arrays are indexed by those
-// numbers (capacities nb_cap, item_cap are upper bounds that the host can compute from the token
+// numbers (capacities nb_cap, slot_cap are upper bounds that the host can compute from the token
 // count and the number of sequences alone).  Boundaries that are not non-decreasing within
 // [0, total] give empty tables: every later kernel then finds nothing to do.
 struct VarPlan {
-  const int32_t *tok0, *len, *blk0, *item0, *blk_seq, *item_seq;
-  int nseq, nb_cap, item_cap;
+  const int32_t *tok0, *len, *blk0, *item0, *slot0, *blk_seq, *item_seq;
+  int nseq, nb_cap, slot_cap;
 };
 
 __global__ __launch_bounds__(256) void varlen_scan_kernel(const int32_t *__restrict__ cu, int nseq, int total,
                                                           int seg_blocks, int32_t *__restrict__ tok0,
                                                           int32_t *__restrict__ len, int32_t *__restrict__ blk0,
-                                                          int32_t *__restrict__ item0) {
-  __shared__ int sblk[256], sitem[256];
+                                                          int32_t *__restrict__ item0, int32_t *__restrict__ slot0) {
+  __shared__ int sblk[256], sitem[256], sslot[256];
   __shared__ int bad;
   const int tid = threadIdx.x;
   const int per = (nseq + 255) / 256;
   const int q0 = min(nseq, tid * per), q1 = min(nseq, q0 + per);
   if (tid == 0) bad = 0;
   __syncthreads();
-  int nb = 0, ni = 0;
+  int nb = 0, ni = 0, ns = 0;
   bool mine_bad = false;
   for (int q = q0; q < q1; ++q) {
     const int a = cu[q], b = cu[q + 1];
     if (a < 0 || b < a || b > total) mine_bad = true;
     const int n = (b - a + 63) / 64;
+    const int segs = max(1, (n + seg_blocks - 1) / seg_blocks);
     nb += n;
-    ni += max(1, (n + seg_blocks - 1) / seg_blocks);
+    ni += segs;
+    ns += segs > 1 ? segs : 0;
   }
   if (mine_bad) atomicOr(&bad, 1);
   sblk[tid] = nb;
   sitem[tid] = ni;
+  sslot[tid] = ns;
   __syncthreads();
   if (tid == 0) {  // exclusive prefix over the 256 partial sums
-    int a = 0, b = 0;
+    int a = 0, b = 0, c = 0;
     for (int i = 0; i < 256; ++i) {
-      const int t = sblk[i], u = sitem[i];
+      const int t = sblk[i], u = sitem[i], v = sslot[i];
       sblk[i] = a;
       sitem[i] = b;
+      sslot[i] = c;
       a += t;
       b += u;
+      c += v;
     }
     blk0[nseq] = bad ? 0 : a;
     item0[nseq] = bad ? 0 : b;
+    slot0[nseq] = bad ? 0 : c;
   }
   __syncthreads();
-  int rb = sblk[tid], ri = sitem[tid];
+  int rb = sblk[tid], ri = sitem[tid], rs = sslot[tid];
   for (int q = q0; q < q1; ++q) {
     const int a = cu[q], l = cu[q + 1] - a;
     const int n = (l + 63) / 64;
+    const int segs = max(1, (n + seg_blocks - 1) / seg_blocks);
     tok0[q] = bad ? 0 : a;
     len[q] = bad ? 0 : l;
     blk0[q] = bad ? 0 : rb;
     item0[q] = bad ? 0 : ri;
+    slot0[q] = bad ? 0 : rs;
     rb += n;
-    ri += max(1, (n + seg_blocks - 1) / seg_blocks);
+    ri += segs;
+    rs += segs > 1 ? segs : 0;
   }
 }
 
@@ -166,13 +177,49 @@ __device__ __forceinline__ int owner_of(const int32_t *__restrict__ first, int n
   }
   return lo;
 }
+// Segments are listed with every sequence's non-last segments first (all of them are full length,
+// seg_blocks blocks) and the last segment of every sequence after them (any length from empty to
+// full), longest first while the batch has at most kSortMax sequences (rank by counting, quadratic
+// but tiny): workgroups are dispatched in list order, so the long ones start first and the short
+// ones fill the gaps; and the states-only pass, which needs no last segment, takes a prefix of the
+// list.  Sequence q has item0[q] - q non-last segments before it.
+constexpr int kSortMax = 2048;
 __global__ __launch_bounds__(256) void varlen_fill_kernel(const int32_t *__restrict__ blk0,
                                                           const int32_t *__restrict__ item0, int nseq,
-                                                          int32_t *__restrict__ blk_seq,
+                                                          int seg_blocks, int32_t *__restrict__ blk_seq,
                                                           int32_t *__restrict__ item_seq) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < blk0[nseq]) blk_seq[i] = owner_of(blk0, nseq, i);
-  if (i < item0[nseq]) item_seq[i] = owner_of(item0, nseq, i);
+  const int n_items = item0[nseq], n_full = n_items - nseq;
+  if (i < n_full) {
+    int lo = 0, hi = nseq;
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (item0[mid] - mid <= i) lo = mid; else hi = mid;
+    }
+    item_seq[i] = lo;
+  }
+  // (no early return above: the barrier below is reached by every thread)
+  __shared__ int16_t last_blocks[kSortMax];  // blocks in the last segment of every sequence (<= seg_blocks)
+  const bool sort = nseq <= kSortMax && seg_blocks < 32768;
+  const bool ranks_here = static_cast<int>(blockIdx.x) * 256 < n_items && static_cast<int>(blockIdx.x) * 256 + 256 > n_full;
+  if (sort && ranks_here)
+    for (int k = threadIdx.x; k < nseq; k += 256)
+      last_blocks[k] = static_cast<int16_t>((blk0[k + 1] - blk0[k]) - (item0[k + 1] - item0[k] - 1) * seg_blocks);
+  __syncthreads();
+  if (i >= n_full && i < n_items) {
+    const int q = i - n_full;
+    int rank = q;
+    if (sort) {
+      const int mine = last_blocks[q];
+      rank = 0;
+      for (int k = 0; k < nseq; ++k) {
+        const int other = last_blocks[k];
+        rank += (other > mine || (other == mine && k < q)) ? 1 : 0;
+      }
+    }
+    item_seq[n_full + rank] = q;
+  }
 }
 
 // ---- scores_bt: G = tril(C B^T) on the diagonal blocks, and B transposed ------------------------------
@@ -352,7 +399,8 @@ struct ScanParams {
   const uint8_t *Btr;
   const float *prep;
   uint8_t *y;
-  const float *Hin;        // state entering each segment (see slot numbering below), or nullptr = zeros
+  const float *h0;         // (sequences, H, P, N) initial states, or nullptr = zeros (read by one-segment sequences)
+  const float *Hin;        // state entering each segment of a sequence of several: one slot per segment
   float *final_state;      // (sequences, H, P, N): written by the last segment of each sequence
   float *seg_state;        // states-only: local end state of a segment -> the slot of the NEXT segment
   float *seg_decay;        // states-only: log2 of the segment's total decay, one per slot
@@ -377,42 +425,64 @@ struct SeqView {
 // modulo 8, so that they run on one XCD and the tiles are fetched into one L2 instead of eight:
 // XCD k owns the contiguous range [k * per_xcd, (k + 1) * per_xcd) of the (sequence, segment, head
 // group) list, head group fastest.  Ids beyond the list (the grid is rounded up to 8 * per_xcd) idle.
-// `last_too`: whether the last segment of a sequence is in the list (the states-only pass skips it).
+// `last_too`: whether the last segment of a sequence is in the list (not for the states-only pass).
 constexpr int kXcds = 8;
+__device__ __forceinline__ bool wg_coords_varlen(const ScanParams &p, bool last_too, SeqView &v);
 __device__ __forceinline__ bool wg_coords(const ScanParams &p, bool last_too, SeqView &v) {
+  if (p.vp.tok0 != nullptr) return wg_coords_varlen(p, last_too, v);
   const int id = blockIdx.x;
   const int w = (id % kXcds) * p.per_xcd + id / kXcds;
   if (w >= p.total) return false;
   v.col = w % p.cols;
-  if (p.vp.tok0 == nullptr) {
-    v.sg = (w / p.cols) % p.segs;
-    v.b = w / (p.cols * p.segs);
-    v.S = p.S;
-    v.nb = p.NB;
-    v.tok0 = static_cast<size_t>(v.b) * p.T;
-    v.len = static_cast<uint32_t>(p.T);
-    v.blk0 = static_cast<size_t>(v.b) * p.NB;   // times G (tiles) or H (records) in the caller's stride
-    v.blk_stride = p.NB;
-    v.slot0 = static_cast<size_t>(v.b) * p.S;
-    v.slot_stride = p.S;
-    return true;
+  v.sg = (w / p.cols) % p.segs;
+  v.b = w / (p.cols * p.segs);
+  v.S = p.S;
+  v.nb = p.NB;
+  v.tok0 = static_cast<size_t>(v.b) * p.T;
+  v.len = static_cast<uint32_t>(p.T);
+  v.blk0 = static_cast<size_t>(v.b) * p.NB;   // times G (tiles) or H (records) in the caller's stride
+  v.blk_stride = p.NB;
+  v.slot0 = static_cast<size_t>(v.b) * p.S;
+  v.slot_stride = p.S;
+  return true;
+}
+// Variable-length batch: the list (see varlen_fill_kernel) and with it the split over the XCDs come
+// from the device-side tables; the grid was sized for the host's upper bound on its length.
+__device__ __forceinline__ bool wg_coords_varlen(const ScanParams &p, bool last_too, SeqView &v) {
+  const int n_items = p.vp.item0[p.vp.nseq];
+  const int n_full = n_items - p.vp.nseq;
+  const int n_list = last_too ? n_items : n_full;
+  // The same contiguous split over the XCDs as for a plain batch, so that every XCD gets the same
+  // number of workgroups.  The list is sorted by length; for the full pass (whose entries differ in
+  // length) it is first dealt into eight hands, hand k holding entries k, k + 8, ..., and the hands
+  // are laid end to end: every XCD then works on the same mix of long and short entries, long first.
+  const int total = n_list * p.cols;
+  const int per_xcd = (total + kXcds - 1) / kXcds;
+  const int id = blockIdx.x;
+  if (id / kXcds >= per_xcd) return false;
+  const int w = (id % kXcds) * per_xcd + id / kXcds;
+  if (w >= total) return false;
+  v.col = w % p.cols;
+  int item = w / p.cols;
+  if (last_too) {
+    const int base = n_list / kXcds, rem = n_list % kXcds;  // hands 0..rem-1 hold base + 1 entries
+    const int big = rem * (base + 1);
+    const int hand = item < big ? item / (base + 1) : rem + (item - big) / base;
+    const int pos = item < big ? item % (base + 1) : (item - big) % base;
+    item = pos * kXcds + hand;
   }
-  // variable-length batch: one list entry per segment of the whole batch
-  const int item = w / p.cols;
-  if (item >= p.vp.item0[p.vp.nseq]) return false;
   const int q = p.vp.item_seq[item];
   const int first = p.vp.item0[q];
   v.b = q;
-  v.sg = item - first;
   v.S = p.vp.item0[q + 1] - first;
-  if (!last_too && v.sg == v.S - 1) return false;
+  v.sg = item < n_full ? item - (first - q) : v.S - 1;
   v.len = static_cast<uint32_t>(p.vp.len[q]);
   v.nb = static_cast<int>((v.len + kBlk - 1) / kBlk);
   v.tok0 = static_cast<size_t>(p.vp.tok0[q]);
   v.blk0 = static_cast<size_t>(p.vp.blk0[q]);
   v.blk_stride = static_cast<size_t>(p.vp.nb_cap);
-  v.slot0 = static_cast<size_t>(first);
-  v.slot_stride = static_cast<size_t>(p.vp.item_cap);
+  v.slot0 = static_cast<size_t>(p.vp.slot0[q]);
+  v.slot_stride = static_cast<size_t>(p.vp.slot_cap);
   return true;
 }
 
@@ -636,8 +706,17 @@ void chunk_scan_kernel(const ScanParams p) {
   // Pin the value as "arrived" before the loop: otherwise the wait for it is placed at its first use
   // inside the loop, where it also waits for every younger load of every iteration.
   asm volatile("" : "+v"(Dh));
-  if (!kStatesOnly && p.Hin != nullptr) {
-    const float *hp = p.Hin + (slot0 + sg) * (kP * kN) + static_cast<size_t>(pcol) * kN;
+  const float *hp = nullptr;
+  if (!kStatesOnly) {
+    // A sequence of one segment starts from h0 itself (this workgroup reads it here and is the only
+    // one to write final_state, so the two may share memory); with several segments every segment,
+    // the first included, starts from the slot that the pass over segment states has filled.
+    if (sv.S > 1)
+      hp = p.Hin + (slot0 + sg) * (kP * kN) + static_cast<size_t>(pcol) * kN;
+    else if (p.h0 != nullptr)
+      hp = p.h0 + bh * (kP * kN) + static_cast<size_t>(pcol) * kN;
+  }
+  if (hp != nullptr) {
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
@@ -959,7 +1038,7 @@ void chunk_scan_kernel(const ScanParams p) {
 }
 
 // ---- segment_pass: slot[0] = h0; slot[sg] = exp2(decay[sg-1]) * slot[sg-1] + local[sg-1] --------
-// grid (P*N/1024, sequences*H), four consecutive state elements per thread.  seg_state slot sg (sg >= 1)
+// grid (P*N/1024, rows <= sequences*H), four consecutive state elements per thread.  seg_state slot sg (sg >= 1)
 // holds the local end state of segment sg-1 on entry and the state entering segment sg on exit.
 // The chain over segments is serial, but the loads do not depend on it: they are issued eight
 // segments at a time before the chain consumes them, so the kernel pays a few memory round trips
@@ -967,19 +1046,20 @@ void chunk_scan_kernel(const ScanParams p) {
 __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restrict__ seg_state,
                                                                 const float *__restrict__ seg_decay,
                                                                 const float *__restrict__ h0, int S_plain, int H,
-                                                                const VarPlan vp) {
+                                                                int rows, const VarPlan vp) {
   constexpr int kAhead = 8;
   const int e = (blockIdx.x * kThreads + threadIdx.x) * 4;
-  const size_t bh = blockIdx.y;  // (sequence, head)
+  if (vp.tok0 != nullptr && vp.slot0[vp.nseq] == 0) return;  // no sequence has more than one segment
+  for (size_t bh = blockIdx.y; bh < static_cast<size_t>(rows); bh += gridDim.y) {  // (sequence, head)
   int S = S_plain;
   size_t slot0 = bh * S_plain;
   if (vp.tok0 != nullptr) {
     const int q = static_cast<int>(bh / H), h = static_cast<int>(bh % H);
     const int first = vp.item0[q];
     S = vp.item0[q + 1] - first;
-    slot0 = static_cast<size_t>(h) * vp.item_cap + first;
-    if (S < 1) return;  // rejected boundaries: empty tables
+    slot0 = static_cast<size_t>(h) * vp.slot_cap + vp.slot0[q];
   }
+  if (S < 2) continue;  // a single segment starts from h0 itself
   f32x4 run = {0.f, 0.f, 0.f, 0.f};
   if (h0) run = *reinterpret_cast<const f32x4 *>(h0 + bh * kP * kN + e);
   float *sp = seg_state + slot0 * (kP * kN) + e;
@@ -1002,6 +1082,7 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
         *reinterpret_cast<f32x4 *>(sp + static_cast<size_t>(s0 + k) * kP * kN) = run;
       }
     }
+  }
   }
 }
 
@@ -1055,11 +1136,13 @@ int choose_seg_blocks(const Dims &d) {
 }
 
 // Workspace.  Plain batch: rows = Bt sequences of NB blocks each.  Variable-length batch: one "row" whose
-// NB is the block capacity ceil(total / 64) + nseq (every sequence may end in a partial block) and
-// whose segment capacity is NB / (blocks per chunk) + nseq (a segment is at least a chunk, and every
-// sequence has at least one segment), followed by the int32 tables of VarPlan.
+// NB is the block capacity ceil(total / 64) + nseq (every sequence may end in a partial block), whose
+// segment list holds at most NB / (blocks per chunk) + nseq + 1 entries (a segment is at least a
+// chunk, and every sequence has at least one segment) and whose state slots -- needed only by
+// sequences of several segments, which are longer than a segment and so cannot be many -- number at
+// most min(that, 4 ceil(total / 64) / (blocks per chunk) + 4); then the int32 tables of VarPlan.
 struct Layout {
-  int NB, S_max;
+  int NB, S_max, items_max;
   size_t off_G, off_Bt, off_prep, off_state, off_decay, off_tables, total;
 };
 
@@ -1068,7 +1151,13 @@ Layout make_layout(const Dims &d, bool varlen) {
   const int rows = varlen ? 1 : d.Bt;
   const int nseq = varlen ? d.Bt : 0;
   w.NB = (d.T + kBlk - 1) / kBlk + nseq;
-  w.S_max = varlen ? w.NB / (d.L / kBlk) + nseq + 1 : d.Nc;  // a segment is at least one chunk
+  const int cb = d.L / kBlk;  // a segment is at least one chunk
+  w.items_max = varlen ? w.NB / cb + nseq + 1 : d.Nc;
+  w.S_max = w.items_max;      // state slots per head
+  if (varlen) {
+    const long tight = 4L * ((d.T + kBlk - 1) / kBlk) / cb + 4;
+    if (tight < w.S_max) w.S_max = static_cast<int>(tight);
+  }
   const size_t BG = static_cast<size_t>(rows) * d.G, BH = static_cast<size_t>(rows) * d.H;
   size_t off = 0;
   w.off_G = off;
@@ -1082,7 +1171,7 @@ Layout make_layout(const Dims &d, bool varlen) {
   w.off_decay = off;
   off += round_up(BH * w.S_max * sizeof(float), 256);
   w.off_tables = off;
-  if (varlen) off += round_up((4 * (static_cast<size_t>(nseq) + 1) + w.NB + w.S_max) * sizeof(int32_t), 256);
+  if (varlen) off += round_up((5 * (static_cast<size_t>(nseq) + 1) + w.NB + w.items_max) * sizeof(int32_t), 256);
   w.total = off;
   return w;
 }
@@ -1112,23 +1201,23 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
   if (varlen) one.Bt = 1;
   const int seg_blocks = choose_seg_blocks(one);
 
-  VarPlan vp = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
+  VarPlan vp = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
   int S = (w.NB + seg_blocks - 1) / seg_blocks;  // plain batch: segments per sequence
   int items = S * d.Bt;                          // segments of the whole batch (varlen: upper bound)
   if (varlen) {
     int32_t *t = reinterpret_cast<int32_t *>(ws + w.off_tables);
     const int n1 = d.Bt + 1;
-    int32_t *tok0 = t, *len = t + n1, *blk0 = t + 2 * n1, *item0 = t + 3 * n1, *blk_seq = t + 4 * n1,
-            *item_seq = blk_seq + w.NB;
+    int32_t *tok0 = t, *len = t + n1, *blk0 = t + 2 * n1, *item0 = t + 3 * n1, *slot0 = t + 4 * n1,
+            *blk_seq = t + 5 * n1, *item_seq = blk_seq + w.NB;
     items = w.NB / seg_blocks + d.Bt + 1;
-    if (items > w.S_max) items = w.S_max;
+    if (items > w.items_max) items = w.items_max;
     S = 0;  // per sequence, from the tables
     hipLaunchKernelGGL(varlen_scan_kernel, dim3(1), dim3(256), 0, stream, cu, d.Bt, d.T, seg_blocks, tok0, len, blk0,
-                       item0);
+                       item0, slot0);
     const int cap = w.NB > items ? w.NB : items;
-    hipLaunchKernelGGL(varlen_fill_kernel, dim3((cap + 255) / 256), dim3(256), 0, stream, blk0, item0, d.Bt, blk_seq,
-                       item_seq);
-    vp = VarPlan{tok0, len, blk0, item0, blk_seq, item_seq, d.Bt, w.NB, w.S_max};
+    hipLaunchKernelGGL(varlen_fill_kernel, dim3((cap + 255) / 256), dim3(256), 0, stream, blk0, item0, d.Bt, seg_blocks,
+                       blk_seq, item_seq);
+    vp = VarPlan{tok0, len, blk0, item0, slot0, blk_seq, item_seq, d.Bt, w.NB, w.S_max};
     trace_mark(trace, stream, "varlen_tables");
   }
 
@@ -1147,6 +1236,8 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
   p.Btr = reinterpret_cast<const uint8_t *>(Btr);
   p.prep = prep;
   p.y = static_cast<uint8_t *>(y);
+  p.h0 = h0;
+  p.Hin = seg_state;
   p.final_state = final_state;
   p.seg_state = seg_state;
   p.seg_decay = seg_decay;
@@ -1161,25 +1252,24 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
   if (varlen || S > 1) {
     // (a packed batch always takes this route: whether any sequence has more than one segment is
     // known on the device only; workgroups of last segments leave the states-only pass at once)
-    p.Hin = nullptr;
     constexpr int kStatesHeads = 4;  // heads per workgroup of the states-only kernel (2 was measured: slower)
     p.cols = d.H / kStatesHeads;
     p.segs = S - 1;
-    p.total = varlen ? p.cols * items : p.cols * p.segs * d.Bt;
+    p.total = p.cols * p.segs * d.Bt;
+    if (varlen) p.total = p.cols * items;
     p.per_xcd = (p.total + kXcds - 1) / kXcds;
     hipLaunchKernelGGL((chunk_scan_kernel<true, kStatesHeads>), dim3(kXcds * p.per_xcd), dim3(128 * kStatesHeads), 0,
                        stream, p);
     trace_mark(trace, stream, "segment_states");
-    hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), d.Bt * d.H), dim3(kThreads), 0, stream,
-                       seg_state, seg_decay, h0, S, d.H, vp);
+    const int rows_bh = d.Bt * d.H;  // a packed batch may have many one-segment sequences: rows are looped over
+    hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), varlen && rows_bh > 2048 ? 2048 : rows_bh),
+                       dim3(kThreads), 0, stream, seg_state, seg_decay, h0, S, d.H, rows_bh, vp);
     trace_mark(trace, stream, "segment_pass");
-    p.Hin = seg_state;
-  } else {
-    p.Hin = h0;
   }
   p.cols = d.H / kHeadsPerWg;
   p.segs = S;
-  p.total = varlen ? p.cols * items : p.cols * p.segs * d.Bt;
+  p.total = p.cols * p.segs * d.Bt;
+  if (varlen) p.total = p.cols * items;
   p.per_xcd = (p.total + kXcds - 1) / kXcds;
   hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0, stream, p);
   trace_mark(trace, stream, "chunk_scan");

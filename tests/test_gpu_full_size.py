@@ -131,3 +131,36 @@ def test_full_size_multi_step_decode_equals_single_steps(ssd):
     assert torch.isfinite(y.float()).all()
     assert_close(y, to_np64(y1), 2e-2, "multi-step y vs single steps")
     assert torch.equal(state, s1)  # the state update involves no sum: identical bits
+
+
+def test_full_size_ragged_batch_sampled_sequences(ssd):
+    """Config 3's token count and heads as a packed batch of 16 ragged sequences (lengths
+    log-uniform over a 64x range), library-chosen segments: sampled (sequence, head) pairs
+    against the oracle, every token of them."""
+    cfg = inputs.CONFIGS["c3_2p7b_long"]
+    T, H = cfg.seqlen, cfg.nheads
+    r = np.random.default_rng(7)
+    w = np.exp(r.uniform(0.0, np.log(64.0), 16))
+    lens = np.maximum(1, np.floor(w / w.sum() * T).astype(np.int64))
+    lens[np.argmax(lens)] += T - lens.sum()
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    print("full-size ragged batch", lens.tolist(), flush=True)
+    inp = inputs.make_prefill_inputs(cfg, seed=0)
+    pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
+    dev = {k: v.cuda() for k, v in pk.items()}
+    h0 = 0.5 * torch.randn((16, H, cfg.headdim, cfg.dstate), generator=torch.Generator().manual_seed(3))
+    y, st = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
+                                   torch.from_numpy(cu).cuda(), cfg.chunk, h0=h0.cuda())
+    y2, st2 = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
+                                     torch.from_numpy(cu).cuda(), cfg.chunk, h0=h0.cuda())
+    torch.cuda.synchronize()
+    assert torch.isfinite(y.float()).all() and torch.isfinite(st).all()
+    assert torch.equal(y, y2) and torch.equal(st, st2)
+    picks = sorted({(0, 0), (15, H - 1), (int(np.argmax(lens)), 17), (int(np.argmin(lens)), 40)} |
+                   {(int(r.integers(16)), int(r.integers(H))) for _ in range(6)})
+    for q, h in picks:
+        a, b = int(cu[q]), int(cu[q + 1])
+        y_ref, st_ref = ssd_oracle.prefill(pk["x"][None, a:b], pk["dt"][None, a:b], pk["A"], pk["B"][None, a:b],
+                                           pk["C"][None, a:b], pk["D"], h0=h0[q:q + 1], pairs=[(0, h)])
+        assert_close(y[a:b, h], y_ref[0], 2e-2, "ragged y seq %d head %d" % (q, h))
+        assert_close(st[q, h], st_ref[0], 2e-2, "ragged state seq %d head %d" % (q, h))
