@@ -222,6 +222,20 @@ def main():
             log("[bench] %s: %.4f ms, %.1f TFLOP/s causal" % (name, ms, extra[name]["tflops_causal"]))
             torch.cuda.empty_cache()
 
+    # ---- chunk-length and group-count sweeps at the headline shape (not measured by the paper) -----
+    sweeps = {}
+    if not args.no_extra_configs and cfg.headdim == 64 and cfg.dstate == 128:
+        for label, c in [("chunk_%d" % L, cfg.with_(chunk=L)) for L in (64, 128, 256, 512, 1024)] + \
+                        [("ngroups_%d" % G, cfg.with_(ngroups=G)) for G in (4, 20) if cfg.nheads % (4 * G) == 0] + \
+                        [("headdim_128", cfg.with_(headdim=128, nheads=cfg.nheads // 2)),
+                         ("dstate_64", cfg.with_(dstate=64)), ("dstate_256", cfg.with_(dstate=256))]:
+            ms, k, _ = time_prefill(c, max(5, args.steps // 4), 2, with_decode=False)
+            rep = prefill_report(c, ms, k)
+            sweeps[label] = dict(path=rep["path"], ms=round(ms, 5), tflops_causal=round(rep["tflops_causal"], 1),
+                                 tflops_dense=round(rep["tflops_dense"], 1))
+            log("[bench] sweep %s (%s): %.4f ms, %.1f TFLOP/s causal" % (label, rep["path"], ms, rep["tflops_causal"]))
+            torch.cuda.empty_cache()
+
     # ---- ragged batches and piecewise prompts (same token count and head shape as the headline) -----
     varlen = {}
     if not args.no_varlen and head["path"] == "mfma_bf16" and cfg.batch == 1:
@@ -461,7 +475,7 @@ def main():
                    "headdim": cfg.headdim, "dstate": cfg.dstate, "ngroups": cfg.ngroups, "chunk": cfg.chunk,
                    "step": "ssd_prefill + one ssd_decode_step", "flop_count": "algorithmic, causal-only"},
         "prefill": head, "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "other_configs": extra,
-        "varlen": varlen,
+        "varlen": varlen, "sweeps": sweeps,
     }
     print(json.dumps(out))
 

@@ -1,5 +1,8 @@
-// MFMA prefill for the Mamba-2 head shape (headdim 64, dstate 128, bf16 io, chunk % 64 == 0,
-// heads per group a multiple of 4).
+// MFMA prefill for the Mamba-2 head shape (headdim 64 or a multiple of it, dstate 128, bf16 io,
+// chunk % 64 == 0, heads per group x (headdim / 64) a multiple of 4).  A head with headdim 64 k is
+// processed as k independent heads of 64 columns ("head" below means such a 64-column slice): its
+// columns never interact, x, y and the state are laid out exactly as those of k narrower heads, and
+// the slices share the head's decay records, A and D.
 //
 // The chunked algorithm (Alg. 1; Eq. 3) is evaluated on 64-token blocks.  Below the diagonal
 // blocks the decay mask of Eq. 3 has rank one per block pair, so the off-diagonal part of the
@@ -404,7 +407,8 @@ struct ScanParams {
   float *final_state;      // (sequences, H, P, N): written by the last segment of each sequence
   float *seg_state;        // states-only: local end state of a segment -> the slot of the NEXT segment
   float *seg_decay;        // states-only: log2 of the segment's total decay, one per slot
-  int T, H, G, hpg, NB, seg_blocks, S;
+  int T, H, G, hpg, NB, seg_blocks, S;  // H, hpg count 64-column slices
+  int pdiv, Hrec;          // slices per head (headdim / 64); heads (owners of decay records, A, D)
   int cols, segs, total, per_xcd;  // workgroup mapping, see wg_coords
   VarPlan vp;              // tok0 == nullptr: plain batch
 };
@@ -558,7 +562,8 @@ void chunk_scan_kernel(const ScanParams p) {
   // plain batch; (g, block), (h, block), (h, segment) with batch-wide block / segment numbers otherwise
   const bool plain = p.vp.tok0 == nullptr;
   const size_t tile0 = plain ? (sv.blk0 * p.G + static_cast<size_t>(g) * sv.blk_stride) : (g * sv.blk_stride + sv.blk0);
-  const size_t rec0 = plain ? (sv.blk0 * p.H + static_cast<size_t>(h) * sv.blk_stride) : (h * sv.blk_stride + sv.blk0);
+  const int hrec = h / p.pdiv;  // the head this slice belongs to
+  const size_t rec0 = plain ? (sv.blk0 * p.Hrec + static_cast<size_t>(hrec) * sv.blk_stride) : (hrec * sv.blk_stride + sv.blk0);
   const size_t slot0 = plain ? (sv.slot0 * p.H + static_cast<size_t>(h) * sv.slot_stride) : (h * sv.slot_stride + sv.slot0);
   const size_t bh = static_cast<size_t>(sv.b) * p.H + h;  // row of final_state
   const int r = lane & 31, kg = lane >> 5;
@@ -702,7 +707,7 @@ void chunk_scan_kernel(const ScanParams p) {
   // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][column of lane r] ----
   const int pcol = 32 * ph + pi_of_row(r);  // headdim column of this lane's state column
   f32x16 Hacc[4];
-  float Dh = kStatesOnly ? 0.f : p.D[h];
+  float Dh = kStatesOnly ? 0.f : p.D[hrec];
   // Pin the value as "arrived" before the loop: otherwise the wait for it is placed at its first use
   // inside the loop, where it also waits for every younger load of every iteration.
   asm volatile("" : "+v"(Dh));
@@ -1115,8 +1120,9 @@ int choose_seg_blocks(const Dims &d) {
     const int k = std::atoi(e);
     if (k >= chunk_blocks) return k;
   }
-  const long groups = static_cast<long>(d.Bt) * (d.H / kHeadsPerWg);
-  const double seqs = static_cast<double>(d.Bt) * d.H;
+  const int slices = d.H * (d.P / kP);
+  const long groups = static_cast<long>(d.Bt) * (slices / kHeadsPerWg);
+  const double seqs = static_cast<double>(d.Bt) * slices;
   const int hi = nblocks > chunk_blocks ? nblocks : chunk_blocks;
   int best_blocks = hi;
   double best = 0.0;
@@ -1159,6 +1165,7 @@ Layout make_layout(const Dims &d, bool varlen) {
     if (tight < w.S_max) w.S_max = static_cast<int>(tight);
   }
   const size_t BG = static_cast<size_t>(rows) * d.G, BH = static_cast<size_t>(rows) * d.H;
+  const size_t BHs = BH * (d.P / kP);  // 64-column slices
   size_t off = 0;
   w.off_G = off;
   off += round_up(BG * w.NB * kBlk * kBlk * sizeof(uint16_t), 256);
@@ -1167,9 +1174,9 @@ Layout make_layout(const Dims &d, bool varlen) {
   w.off_prep = off;
   off += round_up(BH * w.NB * kRec * sizeof(float), 256);
   w.off_state = off;
-  off += round_up(BH * w.S_max * kP * kN * sizeof(float), 256);
+  off += round_up(BHs * w.S_max * kP * kN * sizeof(float), 256);
   w.off_decay = off;
-  off += round_up(BH * w.S_max * sizeof(float), 256);
+  off += round_up(BHs * w.S_max * sizeof(float), 256);
   w.off_tables = off;
   if (varlen) off += round_up((5 * (static_cast<size_t>(nseq) + 1) + w.NB + w.items_max) * sizeof(int32_t), 256);
   w.total = off;
@@ -1179,8 +1186,9 @@ Layout make_layout(const Dims &d, bool varlen) {
 bool shape_ok(const Dims &d, unsigned long long tokens, unsigned long long nb) {
   // one sequence of x, C and the per-head block records must be addressable with 32-bit byte offsets
   const unsigned long long lim = 0xFFFF0000ull;
-  return d.bf16 && d.P == kP && d.N == kN && d.L % kBlk == 0 && d.hpg % kHeadsPerWg == 0 && d.Bt <= 65535 &&
-         d.H <= 65535 && tokens * d.H * (kP * 2) <= lim && tokens * d.G * (kN * 2) <= lim &&
+  return d.bf16 && d.P % kP == 0 && d.P <= 16 * kP && d.N == kN && d.L % kBlk == 0 &&
+         (d.hpg * (d.P / kP)) % kHeadsPerWg == 0 && d.Bt <= 65535 && d.H <= 65535 &&
+         tokens * d.H * (static_cast<unsigned long long>(d.P) * 2) <= lim && tokens * d.G * (kN * 2) <= lim &&
          nb * (kN * kBlk * 2) <= lim;
 }
 
@@ -1242,9 +1250,12 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
   p.seg_state = seg_state;
   p.seg_decay = seg_decay;
   p.T = d.T;
-  p.H = d.H;
+  const int pdiv = d.P / kP, Hs = d.H * pdiv;
+  p.H = Hs;
+  p.pdiv = pdiv;
+  p.Hrec = d.H;
   p.G = d.G;
-  p.hpg = d.hpg;
+  p.hpg = d.hpg * pdiv;
   p.NB = w.NB;
   p.seg_blocks = seg_blocks;
   p.S = S;
@@ -1253,7 +1264,7 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
     // (a packed batch always takes this route: whether any sequence has more than one segment is
     // known on the device only; workgroups of last segments leave the states-only pass at once)
     constexpr int kStatesHeads = 4;  // heads per workgroup of the states-only kernel (2 was measured: slower)
-    p.cols = d.H / kStatesHeads;
+    p.cols = Hs / kStatesHeads;
     p.segs = S - 1;
     p.total = p.cols * p.segs * d.Bt;
     if (varlen) p.total = p.cols * items;
@@ -1261,12 +1272,12 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
     hipLaunchKernelGGL((chunk_scan_kernel<true, kStatesHeads>), dim3(kXcds * p.per_xcd), dim3(128 * kStatesHeads), 0,
                        stream, p);
     trace_mark(trace, stream, "segment_states");
-    const int rows_bh = d.Bt * d.H;  // a packed batch may have many one-segment sequences: rows are looped over
-    hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), varlen && rows_bh > 2048 ? 2048 : rows_bh),
-                       dim3(kThreads), 0, stream, seg_state, seg_decay, h0, S, d.H, rows_bh, vp);
+    const int rows_bh = d.Bt * Hs;  // a packed batch may have many one-segment sequences: rows are looped over
+    hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), rows_bh > (varlen ? 2048 : 65535) ? (varlen ? 2048 : 65535) : rows_bh),
+                       dim3(kThreads), 0, stream, seg_state, seg_decay, h0, S, Hs, rows_bh, vp);
     trace_mark(trace, stream, "segment_pass");
   }
-  p.cols = d.H / kHeadsPerWg;
+  p.cols = Hs / kHeadsPerWg;
   p.segs = S;
   p.total = p.cols * p.segs * d.Bt;
   if (varlen) p.total = p.cols * items;
