@@ -192,6 +192,44 @@ SSD_API ssd_status ssd_decode_steps_layers(int32_t nsteps, int32_t nlayers, cons
                                    const float *D, void *y, void *hip_stream);
 
 /*
+ * The step in front of the SSD core: the depthwise causal convolution of a
+ * Mamba-2 block with its rolling cache (Alg. 2, "Update conv state" and
+ * "DepthwiseConv"; section "The O(1) state cache": the cache holds the k-1
+ * inputs before the current token, shape (batch, channels, k-1)).  Per channel c
+ *     window_t = [ the k-1 inputs before token t, u_t ]
+ *     z[t][c]  = act( bias[c] + sum_{j<k} weight[c][j] * window_t[j] )
+ * so weight[c][k-1] multiplies the current input.  ssd_conv1d_prefill filters a
+ * whole prompt (inputs before it come from conv_state_in, or are zero when it
+ * is NULL) and stores the last k-1 inputs to conv_state_out (nullable);
+ * ssd_conv1d_step is the one-token case and updates conv_state in place.
+ *   u                 (batch, seqlen, channels) / (batch, channels), io dtype, channels-last
+ *   weight            (channels, ksize) fp32;  bias (channels) fp32 or NULL;  2 <= ksize <= 8
+ *   conv_state*       (batch, channels, ksize-1), io dtype; conv_state_in must
+ *                     not be conv_state_out
+ *   split[3], z0..z2  the output is scattered by channel range into up to three
+ *                     dense tensors (batch, seqlen, split[i]) -- a Mamba-2 block
+ *                     feeds the ranges x | B | C to the SSD core as separate
+ *                     tensors; channels = split[0] + split[1] + split[2];
+ *                     split[1], split[2] may be 0 (then z1, z2 are ignored).
+ *                     split is a HOST array.
+ *   activation        0 = none, 1 = SiLU (the paper does not name one; Mamba-2
+ *                     applies SiLU here)
+ * Arithmetic is fp32; z is rounded to the io dtype (RNE).  All pointers except
+ * split are device pointers, 16-byte aligned.
+ * Errors: SSD_ERR_NULL, _SHAPE, _DTYPE, _ALIGN, _HIP.
+ */
+SSD_API ssd_status ssd_conv1d_prefill(int32_t batch, int32_t seqlen, int32_t ksize, int32_t io_dtype,
+                              const int32_t *split, const void *u, const float *weight,
+                              const float *bias, const void *conv_state_in,
+                              void *z0, void *z1, void *z2, void *conv_state_out,
+                              int32_t activation, void *hip_stream);
+SSD_API ssd_status ssd_conv1d_step(int32_t batch, int32_t ksize, int32_t io_dtype,
+                           const int32_t *split, void *conv_state, const void *u,
+                           const float *weight, const float *bias,
+                           void *z0, void *z1, void *z2, int32_t activation,
+                           void *hip_stream);
+
+/*
  * Measurement aid: ssd_prefill with a HIP event recorded on `hip_stream` after
  * every kernel of the call (the prefill of Alg. 1 is several kernels).  Unlike
  * every other entry point it creates and destroys HIP events and WAITS for the

@@ -238,3 +238,34 @@ def prefill_varlen(x, dt, A, B, C, D, cu_seqlens, h0=None, nthreads: int = 0):
         y[a:b] = yq[0]
         state[q] = sq[0]
     return y, state
+
+
+def conv1d_prefill(u, weight, bias=None, conv_state=None, activation="silu"):
+    """Depthwise causal convolution with a rolling cache (Alg. 2, "Update conv state" and
+    "DepthwiseConv"): ``u (Bt,T,C)``, ``weight (C,k)``, ``bias (C)``, ``conv_state (Bt,C,k-1)`` = the
+    k-1 inputs before the prompt (zeros if None).  ``z[t,c] = act(bias[c] + sum_j weight[c,j] *
+    window_t[j,c])`` with ``window_t`` the k inputs ending at token t.  Returns ``(z, new cache)``,
+    float64.  Plain loops over tokens and taps."""
+    u, weight = _f64(u), _f64(weight)
+    Bt, T, C = u.shape
+    k = weight.shape[1]
+    prev = np.zeros((Bt, C, k - 1)) if conv_state is None else _f64(conv_state)
+    ext = np.concatenate([prev.transpose(0, 2, 1), u], axis=1)      # (Bt, k-1+T, C)
+    z = np.zeros((Bt, T, C))
+    for t in range(T):
+        for j in range(k):
+            z[:, t, :] += weight[None, :, j] * ext[:, t + j, :]
+    if bias is not None:
+        z += _f64(bias)[None, None, :]
+    if activation == "silu":
+        z = z / (1.0 + np.exp(-z))
+    elif activation != "none":
+        raise ValueError("activation must be 'none' or 'silu'")
+    new_state = np.ascontiguousarray(ext[:, T:, :].transpose(0, 2, 1))  # the last k-1 inputs
+    return z, new_state
+
+
+def conv1d_step(conv_state, u, weight, bias=None, activation="silu"):
+    """One token of :func:`conv1d_prefill`: ``u (Bt,C)``.  Returns ``(z (Bt,C), new cache)``."""
+    z, st = conv1d_prefill(_f64(u)[:, None, :], weight, bias, conv_state, activation)
+    return z[:, 0, :], st

@@ -197,6 +197,61 @@ ssd_status ssd_decode_step(const ssd_shape *shape, float *state, const void *x, 
   return ssd_decode_step_layers(1, shape, state, x, dt, A, B, C, D, y, hip_stream);
 }
 
+namespace {
+// Shared checks of the two convolution entry points.  Returns SSD_OK and fills z / width.
+ssd_status conv_args(int32_t batch, int32_t ksize, int32_t io_dtype, const int32_t *split, const void *u,
+                     const float *weight, void *z0, void *z1, void *z2, int32_t activation, void *z[3], int width[3]) {
+  if (io_dtype != SSD_F32 && io_dtype != SSD_BF16) return SSD_ERR_DTYPE;
+  if (!split) return SSD_ERR_NULL;
+  if (batch < 1 || ksize < 2 || ksize > 8 || split[0] < 1 || split[1] < 0 || split[2] < 0) return SSD_ERR_SHAPE;
+  if (activation != 0 && activation != 1) return SSD_ERR_SHAPE;
+  const long double chans = static_cast<long double>(split[0]) + split[1] + split[2];
+  if (chans > 1.0e9L || chans * batch > 2.0e11L) return SSD_ERR_SHAPE;
+  z[0] = z0;
+  z[1] = z1;
+  z[2] = z2;
+  for (int i = 0; i < 3; ++i) {
+    width[i] = split[i];
+    if (width[i] > 0 && !z[i]) return SSD_ERR_NULL;
+    if (width[i] > 0 && !aligned16(z[i])) return SSD_ERR_ALIGN;
+  }
+  if (!u || !weight) return SSD_ERR_NULL;
+  if (!aligned16(u)) return SSD_ERR_ALIGN;
+  return SSD_OK;
+}
+}  // namespace
+
+ssd_status ssd_conv1d_prefill(int32_t batch, int32_t seqlen, int32_t ksize, int32_t io_dtype, const int32_t *split,
+                              const void *u, const float *weight, const float *bias, const void *conv_state_in,
+                              void *z0, void *z1, void *z2, void *conv_state_out, int32_t activation,
+                              void *hip_stream) {
+  void *z[3];
+  int width[3];
+  const ssd_status st = conv_args(batch, ksize, io_dtype, split, u, weight, z0, z1, z2, activation, z, width);
+  if (st != SSD_OK) return st;
+  if (seqlen < 1 || batch > 65535 || (seqlen + 31) / 32 > 65535) return SSD_ERR_SHAPE;
+  if (static_cast<long double>(seqlen) * batch * (static_cast<long double>(split[0]) + split[1] + split[2]) > 1.0e15L)
+    return SSD_ERR_SHAPE;
+  if (conv_state_in && conv_state_in == conv_state_out) return SSD_ERR_SHAPE;  // read and written by different threads
+  const hipError_t e = ssd::launch_conv_prefill(batch, seqlen, ksize, io_dtype == SSD_BF16, u, weight, bias,
+                                                conv_state_in, z, width, conv_state_out, activation,
+                                                static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
+}
+
+ssd_status ssd_conv1d_step(int32_t batch, int32_t ksize, int32_t io_dtype, const int32_t *split, void *conv_state,
+                           const void *u, const float *weight, const float *bias, void *z0, void *z1, void *z2,
+                           int32_t activation, void *hip_stream) {
+  void *z[3];
+  int width[3];
+  const ssd_status st = conv_args(batch, ksize, io_dtype, split, u, weight, z0, z1, z2, activation, z, width);
+  if (st != SSD_OK) return st;
+  if (!conv_state) return SSD_ERR_NULL;
+  const hipError_t e = ssd::launch_conv_step(batch, ksize, io_dtype == SSD_BF16, conv_state, u, weight, bias, z, width,
+                                             activation, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
+}
+
 const char *ssd_status_string(ssd_status status) {
   switch (status) {
     case SSD_OK: return "ok";

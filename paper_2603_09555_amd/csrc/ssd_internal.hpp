@@ -94,6 +94,13 @@ hipError_t launch_prefill_mfma_varlen(const Dims &d, const int32_t *cu_seqlens, 
                                       void *y, float *final_state, void *workspace, hipStream_t stream,
                                       KernelTrace *trace = nullptr);
 
+// Depthwise causal convolution (channels-last); z / width: up to three dense outputs by channel range.
+hipError_t launch_conv_prefill(int Bt, int T, int ksize, bool bf16, const void *u, const float *w, const float *bias,
+                               const void *state_in, void *const z[3], const int width[3], void *state_out, int act,
+                               hipStream_t stream);
+hipError_t launch_conv_step(int Bt, int ksize, bool bf16, void *state, const void *u, const float *w, const float *bias,
+                            void *const z[3], const int width[3], int act, hipStream_t stream);
+
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace ssd

@@ -20,6 +20,7 @@ SSD_OK = 0
 
 EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
            "ssd_decode_steps_layers", "ssd_prefill_varlen_workspace_bytes", "ssd_prefill_varlen",
+           "ssd_conv1d_prefill", "ssd_conv1d_step",
            "ssd_prefill_path", "ssd_status_string", "ssd_version"]
 
 
@@ -56,6 +57,11 @@ _lib.ssd_prefill_varlen_workspace_bytes.restype = _sz
 _lib.ssd_prefill_varlen_workspace_bytes.argtypes = [_sp]
 _lib.ssd_prefill_varlen.restype = ctypes.c_int
 _lib.ssd_prefill_varlen.argtypes = [_sp] + [_vp] * 11 + [_sz, _vp]
+_i32 = ctypes.c_int32
+_lib.ssd_conv1d_prefill.restype = ctypes.c_int
+_lib.ssd_conv1d_prefill.argtypes = [_i32, _i32, _i32, _i32, ctypes.POINTER(_i32)] + [_vp] * 8 + [_i32, _vp]
+_lib.ssd_conv1d_step.restype = ctypes.c_int
+_lib.ssd_conv1d_step.argtypes = [_i32, _i32, _i32, ctypes.POINTER(_i32)] + [_vp] * 7 + [_i32, _vp]
 _lib.ssd_decode_steps_layers.restype = ctypes.c_int
 _lib.ssd_decode_steps_layers.argtypes = [ctypes.c_int32, ctypes.c_int32, _sp] + [_vp] * 9
 _lib.ssd_prefill_path.restype = ctypes.c_char_p
@@ -236,3 +242,54 @@ def ssd_prefill_varlen(x, dt, A, B, C, D, cu_seqlens, chunk, h0=None, y=None, fi
     if st != SSD_OK:
         raise SSDError(st, "ssd_prefill_varlen")
     return y, final_state
+
+
+def _conv_split(channels, split):
+    split = list(split) if split is not None else [channels]
+    split += [0] * (3 - len(split))
+    if len(split) != 3 or sum(split) != channels or split[0] < 1 or min(split) < 0:
+        raise ValueError("split must be up to three non-negative widths summing to the channel count")
+    return split
+
+
+def ssd_conv1d_prefill(u, weight, bias=None, conv_state=None, split=None, activation="silu"):
+    """``ssd_conv1d_prefill``: ``u (Bt,T,C)`` channels-last, ``weight (C,k)`` fp32, ``bias (C)`` fp32 or None,
+    ``conv_state (Bt,C,k-1)`` or None.  Returns ``(outputs, new_conv_state)`` where outputs is a list of
+    dense tensors ``(Bt,T,split[i])`` (one tensor ``(Bt,T,C)`` without ``split``)."""
+    Bt, T, C = u.shape
+    k = weight.shape[1]
+    split = _conv_split(C, split)
+    io = {torch.float32: SSD_F32, torch.bfloat16: SSD_BF16}.get(u.dtype, -1)
+    if weight.dtype != torch.float32 or tuple(weight.shape) != (C, k) or (bias is not None and (
+            bias.dtype != torch.float32 or tuple(bias.shape) != (C,))) or (conv_state is not None and (
+            conv_state.dtype != u.dtype or tuple(conv_state.shape) != (Bt, C, k - 1))):
+        raise ValueError("inconsistent tensor shapes or dtypes")
+    outs = [torch.empty((Bt, T, w), dtype=u.dtype, device=u.device) if w > 0 else None for w in split]
+    new_state = torch.empty((Bt, C, k - 1), dtype=u.dtype, device=u.device)
+    _check_dev(u, weight, bias, conv_state, new_state, *outs)
+    st = _lib.ssd_conv1d_prefill(Bt, T, k, io, (_i32 * 3)(*split), _ptr(u), _ptr(weight), _ptr(bias), _ptr(conv_state),
+                                 _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]), _ptr(new_state),
+                                 {"none": 0, "silu": 1}[activation], _stream_ptr())
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_conv1d_prefill")
+    return [o for o in outs if o is not None], new_state
+
+
+def ssd_conv1d_step(conv_state, u, weight, bias=None, split=None, activation="silu"):
+    """``ssd_conv1d_step``: ``u (Bt,C)``, ``conv_state (Bt,C,k-1)`` updated in place.  Returns the list of
+    outputs ``(Bt,split[i])``."""
+    Bt, C = u.shape
+    k = weight.shape[1]
+    split = _conv_split(C, split)
+    io = {torch.float32: SSD_F32, torch.bfloat16: SSD_BF16}.get(u.dtype, -1)
+    if weight.dtype != torch.float32 or tuple(weight.shape) != (C, k) or conv_state.dtype != u.dtype \
+            or tuple(conv_state.shape) != (Bt, C, k - 1) or (bias is not None and tuple(bias.shape) != (C,)):
+        raise ValueError("inconsistent tensor shapes or dtypes")
+    outs = [torch.empty((Bt, w), dtype=u.dtype, device=u.device) if w > 0 else None for w in split]
+    _check_dev(u, weight, bias, conv_state, *outs)
+    st = _lib.ssd_conv1d_step(Bt, k, io, (_i32 * 3)(*split), _ptr(conv_state), _ptr(u), _ptr(weight), _ptr(bias),
+                              _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]), {"none": 0, "silu": 1}[activation],
+                              _stream_ptr())
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_conv1d_step")
+    return [o for o in outs if o is not None]

@@ -127,6 +127,30 @@ def test_varlen_rejects_before_any_hip_call(ssd):
         assert lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(shape(ssd, **dict(ok, **bad)))) == 0
 
 
+def test_conv_rejects_before_any_hip_call(ssd):
+    lib = ssd.raw()
+    fake = ctypes.c_void_p(4096)
+    i3 = ctypes.c_int32 * 3
+
+    def pre(batch=2, T=100, k=4, io=1, split=(64, 16, 16), u=fake, w=fake, z=(fake, fake, fake), sin=None, sout=fake,
+            act=1):
+        return lib.ssd_conv1d_prefill(batch, T, k, io, i3(*split) if split else None, u, w, None, sin, z[0], z[1], z[2],
+                                      sout, act, None)
+
+    assert pre(split=None) == -1
+    assert pre(u=None) == -1 and pre(w=None) == -1
+    assert pre(z=(fake, None, fake)) == -1
+    assert pre(k=1) == -2 and pre(k=9) == -2 and pre(T=0) == -2 and pre(batch=0) == -2 and pre(act=2) == -2
+    assert pre(split=(0, 8, 8)) == -2 and pre(split=(8, -1, 8)) == -2
+    assert pre(io=5) == -3
+    assert pre(u=ctypes.c_void_p(4100)) == -7 and pre(z=(fake, ctypes.c_void_p(4100), fake)) == -7
+    assert pre(sin=fake, sout=fake) == -2   # the cache may not be updated in place by the prompt kernel
+    st = lib.ssd_conv1d_step(2, 4, 1, i3(64, 16, 16), None, fake, fake, None, fake, fake, fake, 1, None)
+    assert st == -1
+    assert lib.ssd_conv1d_step(2, 4, 1, i3(64, 16, 16), fake, fake, fake, None, fake, None, fake, 1, None) == -1
+    assert lib.ssd_conv1d_step(2, 4, 7, i3(64, 16, 16), fake, fake, fake, None, fake, fake, fake, 1, None) == -3
+
+
 def test_decode_steps_rejects_before_any_hip_call(ssd):
     lib = ssd.raw()
     fake = ctypes.c_void_p(4096)

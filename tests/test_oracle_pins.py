@@ -255,6 +255,61 @@ def test_varlen_oracle_equal_lengths_is_the_batched_prefill():
     np.testing.assert_array_equal(stv, st)
 
 
+# ---- the depthwise convolution in front of the core -------------------------------------------
+def test_conv_hand_example_one_step():
+    """k = 4, one channel: cache (oldest first) [1, 2, 3], input 4, weights [0.5, -1, 2, 0.25],
+    bias 0.125: z = 0.5*1 - 1*2 + 2*3 + 0.25*4 + 0.125 = 5.625; the cache becomes [2, 3, 4]."""
+    st = np.array([[[1.0, 2.0, 3.0]]])
+    z, st2 = ssd_oracle.conv1d_step(st, np.array([[4.0]]), np.array([[0.5, -1.0, 2.0, 0.25]]), np.array([0.125]),
+                                    activation="none")
+    assert z.shape == (1, 1) and z[0, 0] == 5.625
+    np.testing.assert_array_equal(st2, [[[2.0, 3.0, 4.0]]])
+    zs, _ = ssd_oracle.conv1d_step(st, np.array([[4.0]]), np.array([[0.5, -1.0, 2.0, 0.25]]), np.array([0.125]))
+    np.testing.assert_allclose(zs[0, 0], 5.625 / (1.0 + np.exp(-5.625)), rtol=1e-15)
+
+
+def test_conv_prefill_is_an_fir_filter():
+    """Zero cache, no activation: per channel the prompt is filtered by the FIR filter whose taps are
+    the weights reversed (scipy.signal.lfilter), and equals the head of numpy's full convolution."""
+    from scipy.signal import lfilter
+    r = np.random.default_rng(21)
+    Bt, T, C, k = 2, 19, 5, 4
+    u = r.standard_normal((Bt, T, C))
+    w = r.standard_normal((C, k))
+    b = r.standard_normal(C)
+    z, st = ssd_oracle.conv1d_prefill(u, w, b, None, activation="none")
+    for bi in range(Bt):
+        for c in range(C):
+            np.testing.assert_allclose(z[bi, :, c], lfilter(w[c, ::-1], [1.0], u[bi, :, c]) + b[c], rtol=1e-12,
+                                       atol=1e-12)
+            np.testing.assert_allclose(z[bi, :, c], np.convolve(u[bi, :, c], w[c, ::-1])[:T] + b[c], rtol=1e-12,
+                                       atol=1e-12)
+    np.testing.assert_array_equal(st, u[:, T - (k - 1):, :].transpose(0, 2, 1))
+
+
+def test_conv_split_prompt_and_steps_agree_with_one_prefill():
+    r = np.random.default_rng(22)
+    Bt, T, C, k = 2, 11, 3, 4
+    u = r.standard_normal((Bt, T, C))
+    w = r.standard_normal((C, k))
+    b = r.standard_normal(C)
+    st0 = r.standard_normal((Bt, C, k - 1))
+    z, st = ssd_oracle.conv1d_prefill(u, w, b, st0)
+    for cut in (1, 2, 5, 10):   # including pieces shorter than the cache
+        z1, s1 = ssd_oracle.conv1d_prefill(u[:, :cut], w, b, st0)
+        z2, s2 = ssd_oracle.conv1d_prefill(u[:, cut:], w, b, s1)
+        np.testing.assert_allclose(np.concatenate([z1, z2], axis=1), z, rtol=1e-13, atol=1e-13)
+        np.testing.assert_array_equal(s2, st)
+    s = st0
+    for t in range(T):
+        zt, s = ssd_oracle.conv1d_step(s, u[:, t], w, b)
+        np.testing.assert_allclose(zt, z[:, t], rtol=1e-13, atol=1e-13)
+    np.testing.assert_array_equal(s, st)
+    # the cache is the k-1 inputs before the prompt: a prompt preceded by them, from a zero cache
+    zz, _ = ssd_oracle.conv1d_prefill(np.concatenate([st0.transpose(0, 2, 1), u], axis=1), w, b, None)
+    np.testing.assert_allclose(zz[:, k - 1:], z, rtol=1e-13, atol=1e-13)
+
+
 def test_bf16_decay_would_be_visible():
     """The paper's decay-precision ablation: rounding exp(dt*A) to bf16 shows up far above the
     fp32 tolerance (1e-4), so a parity test at that tolerance can tell the two apart."""
