@@ -109,6 +109,7 @@ def main():
                     help="steps per HIP graph and per multi-step launch in the decode comparison")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-varlen", action="store_true")
+    ap.add_argument("--no-conv", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-configs", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -303,6 +304,57 @@ def main():
         del inp, pk, y, sl, yp, ws, st
         torch.cuda.empty_cache()
 
+    # ---- the depthwise convolution in front of the core, at the headline shape ---------------------
+    conv = {}
+    if not args.no_conv:
+        k = 4
+        split = (cfg.nheads * cfg.headdim, cfg.ngroups * cfg.dstate, cfg.ngroups * cfg.dstate)
+        C = sum(split)
+        io = cfg.torch_io_dtype
+        g = torch.Generator(device=dev)
+        g.manual_seed(4321)
+        u = torch.randn((cfg.batch, cfg.seqlen, C), generator=g, device=dev).to(io)
+        wgt = torch.randn((C, k), generator=g, device=dev) / k
+        bia = 0.1 * torch.randn((C,), generator=g, device=dev)
+        for _ in range(3):
+            ssd.ssd_conv1d_prefill(u, wgt, bia, None, split=split)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        # outputs are allocated by the binding; allocate once outside the timed region instead
+        outs = [torch.empty((cfg.batch, cfg.seqlen, w_), dtype=io, device=dev) for w_ in split]
+        cache = torch.empty((cfg.batch, C, k - 1), dtype=io, device=dev)
+        import ctypes as _ct
+        i3 = (_ct.c_int32 * 3)(*split)
+        vp = lambda t: _ct.c_void_p(t.data_ptr())
+        call = lambda: ssd.raw().ssd_conv1d_prefill(cfg.batch, cfg.seqlen, k, 1 if io == torch.bfloat16 else 0, i3, vp(u),
+                                                    vp(wgt), vp(bia), None, vp(outs[0]), vp(outs[1]), vp(outs[2]),
+                                                    vp(cache), 1, _ct.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert call() == 0
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / args.steps
+        nbytes = 2 * u.numel() * u.element_size()
+        zc = torch.empty_like(u)  # a plain device copy of the same tensor, for scale
+        zc.copy_(u)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            zc.copy_(u)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_us = e0.elapsed_time(e1) * 1e3 / args.steps
+        del zc
+        conv["prefill"] = dict(copy_same_size_us=round(copy_us, 2), batch=cfg.batch, seqlen=cfg.seqlen, channels=C, ksize=k, us=round(us, 2),
+                               bytes=nbytes, hbm_gbs=round(nbytes / us / 1e3, 1),
+                               frac_of_hbm_peak=round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4))
+        log("[bench] conv1d prefill (%d x %d channels): %.1f us, %.0f GB/s" % (cfg.seqlen, C, us, nbytes / us / 1e3))
+        del u, outs, cache
+        torch.cuda.empty_cache()
+
     # ---- decode: 64 stacked layers, states seeded by a 2048-token prefill, 1024 steps ---------
     decode = {}
     if not args.no_decode:
@@ -475,7 +527,7 @@ def main():
                    "headdim": cfg.headdim, "dstate": cfg.dstate, "ngroups": cfg.ngroups, "chunk": cfg.chunk,
                    "step": "ssd_prefill + one ssd_decode_step", "flop_count": "algorithmic, causal-only"},
         "prefill": head, "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "other_configs": extra,
-        "varlen": varlen, "sweeps": sweeps,
+        "varlen": varlen, "sweeps": sweeps, "conv": conv,
     }
     print(json.dumps(out))
 

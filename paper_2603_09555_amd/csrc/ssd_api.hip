@@ -229,8 +229,9 @@ ssd_status ssd_conv1d_prefill(int32_t batch, int32_t seqlen, int32_t ksize, int3
   int width[3];
   const ssd_status st = conv_args(batch, ksize, io_dtype, split, u, weight, z0, z1, z2, activation, z, width);
   if (st != SSD_OK) return st;
-  if (seqlen < 1 || batch > 65535 || (seqlen + 31) / 32 > 65535) return SSD_ERR_SHAPE;
-  if (static_cast<long double>(seqlen) * batch * (static_cast<long double>(split[0]) + split[1] + split[2]) > 1.0e15L)
+  if (seqlen < 1 || batch > 65535) return SSD_ERR_SHAPE;
+  // one thread per (run of tokens, channel): the thread count of a batch row must fit 32 bits
+  if (static_cast<long double>(seqlen) * (static_cast<long double>(split[0]) + split[1] + split[2]) > 3.0e10L)
     return SSD_ERR_SHAPE;
   if (conv_state_in && conv_state_in == conv_state_out) return SSD_ERR_SHAPE;  // read and written by different threads
   const hipError_t e = ssd::launch_conv_prefill(batch, seqlen, ksize, io_dtype == SSD_BF16, u, weight, bias,

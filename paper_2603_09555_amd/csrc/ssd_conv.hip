@@ -20,8 +20,18 @@ namespace {
 constexpr int kConvThreads = 256;
 constexpr int kRun = 32;  // tokens per thread in the prefill kernel
 
+// SiLU v / (1 + exp(-v)) with the hardware exp2 and reciprocal (each within 1 ulp): the kernels are
+// streams, and an IEEE division per element would make them ALU bound.
 __device__ __forceinline__ float act_apply(float v, int act) {
-  return act == 1 ? v / (1.f + __expf(-v)) : v;  // 1: SiLU
+  if (act != 1) return v;
+  const float e = __builtin_amdgcn_exp2f(v * -1.4426950408889634f);
+  return v * __builtin_amdgcn_rcpf(1.f + e);
+}
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {  // two fp32 -> packed bf16, RNE
+  f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 struct ConvOut {
@@ -37,16 +47,20 @@ __device__ __forceinline__ typename Io::type *out_ptr(const ConvOut &o, size_t r
   return static_cast<typename Io::type *>(o.ptr[part]) + row * width + (c - o.begin[part]);
 }
 
-// One thread: VEC consecutive channels, kRun consecutive tokens.  grid (ceil(C / (VEC*256)), ceil(T / kRun), Bt).
+// One thread: VEC consecutive channels, kRun consecutive tokens.  Threads are numbered over (run of
+// tokens, channel group) without padding, channel group fastest: grid (ceil(runs * C / VEC / 256), 1, Bt).
 template <typename Io, int VEC, int K>
 __global__ __launch_bounds__(kConvThreads) void conv_prefill_kernel(
     const void *__restrict__ u, const float *__restrict__ w, const float *__restrict__ bias,
     const void *__restrict__ state_in, ConvOut out, void *__restrict__ state_out, int T, int C, int act) {
   using E = typename Io::type;
-  const int c0 = (blockIdx.x * kConvThreads + threadIdx.x) * VEC;
-  if (c0 >= C) return;
+  const int groups = C / VEC;
+  const unsigned gid = blockIdx.x * kConvThreads + threadIdx.x;
+  const int run = static_cast<int>(gid / groups);
+  const int t0 = run * kRun;
+  if (t0 >= T) return;
+  const int c0 = static_cast<int>(gid % groups) * VEC;
   const int b = blockIdx.z;
-  const int t0 = blockIdx.y * kRun;
   const int t1 = min(T, t0 + kRun);
   float wt[VEC][K], bs[VEC];
 #pragma unroll
@@ -63,46 +77,101 @@ __global__ __launch_bounds__(kConvThreads) void conv_prefill_kernel(
     if (t >= 0) return Io::load(ub, static_cast<size_t>(t) * C + v);
     return sb ? Io::load(sb, static_cast<size_t>(v) * (K - 1) + (K - 1 + t)) : 0.f;
   };
+  constexpr bool kVec = VEC > 1 && sizeof(E) == 2;
+  static_assert(VEC == 1 || (kVec && (VEC == 4 || VEC == 8)), "one channel per thread, or 4 / 8 bf16 channels");
+  struct Raw {
+    uint32_t w[VEC > 1 ? VEC / 2 : 1];  // VEC bf16 values
+  };
+  auto load_raw = [&](const E *ptr) {
+    Raw r;
+    if constexpr (VEC == 8) {
+      const uint4 q = *reinterpret_cast<const uint4 *>(ptr);
+      r.w[0] = q.x, r.w[1] = q.y, r.w[2] = q.z, r.w[3] = q.w;
+    } else if constexpr (VEC == 4) {
+      const uint2 q = *reinterpret_cast<const uint2 *>(ptr);
+      r.w[0] = q.x, r.w[1] = q.y;
+    }
+    return r;
+  };
+  auto unpack_row = [&](const Raw &q, float *dst) {  // bf16 -> fp32
 #pragma unroll
-  for (int j = 1; j < K; ++j)
+    for (int k = 0; k < VEC / 2; ++k) {
+      dst[2 * k] = __uint_as_float(q.w[k] << 16);
+      dst[2 * k + 1] = __uint_as_float(q.w[k] & 0xffff0000u);
+    }
+  };
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) win[j][v] = input_at(t0 - K + j, v);
-  for (int t = t0; t < t1; ++t) {
+  for (int j = 1; j < K; ++j) {
+    const int t = t0 - K + j;
+    if (kVec && t >= 0) {
+      unpack_row(load_raw(ub + static_cast<size_t>(t) * C), win[j]);
+    } else {
 #pragma unroll
-    for (int j = 0; j + 1 < K; ++j)
+      for (int v = 0; v < VEC; ++v) win[j][v] = input_at(t, v);
+    }
+  }
+  // Tokens are taken kBatch at a time, and the rows of the next batch are requested before the
+  // current one is computed, so a thread has kBatch to 2 kBatch 16-byte requests in flight all the
+  // time.  Rows stay raw until they enter the window: registers decide how many waves a SIMD can
+  // hold.  Two batches per loop trip, so that the buffer index is a compile-time constant.
+  constexpr int kBatch = 4;
+  struct Rows {
+    Raw q[kBatch];
+    float s[kBatch];
+  } buf[2];
+  auto request = [&](Rows &r, int tb) __attribute__((always_inline)) {
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) win[j][v] = win[j + 1][v];
-    if constexpr (VEC == 8 && sizeof(E) == 2) {
-      const uint4 q = *reinterpret_cast<const uint4 *>(ub + static_cast<size_t>(t) * C);
-      const uint32_t qq[4] = {q.x, q.y, q.z, q.w};
+    for (int i = 0; i < kBatch; ++i) {
+      const int t = min(tb + i, t1 - 1);  // surplus requests beyond the run repeat its last row
+      if constexpr (kVec)
+        r.q[i] = load_raw(ub + static_cast<size_t>(t) * C);
+      else
+        r.s[i] = Io::load(ub, static_cast<size_t>(t) * C);
+    }
+  };
+  auto process = [&](const Rows &r, int tb) __attribute__((always_inline)) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        win[K - 1][2 * k] = __uint_as_float(qq[k] << 16);
-        win[K - 1][2 * k + 1] = __uint_as_float(qq[k] & 0xffff0000u);
+    for (int i = 0; i < kBatch; ++i) {
+      const int t = tb + i;
+      if (t < t1) {
+#pragma unroll
+        for (int j = 0; j + 1 < K; ++j)
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) win[j][v] = win[j + 1][v];
+        if constexpr (kVec)
+          unpack_row(r.q[i], win[K - 1]);
+        else
+          win[K - 1][0] = r.s[i];
+        float z[VEC];
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) {
+          float a = bs[v];
+#pragma unroll
+          for (int j = 0; j < K; ++j) a = fmaf(wt[v][j], win[j][v], a);
+          z[v] = act_apply(a, act);
+        }
+        E *zp = out_ptr<Io>(out, static_cast<size_t>(b) * T + t, c0);
+        if constexpr (kVec) {
+          uint32_t pk[VEC / 2];
+#pragma unroll
+          for (int k = 0; k < VEC / 2; ++k) pk[k] = pack_bf16x2(z[2 * k], z[2 * k + 1]);
+          if constexpr (VEC == 8)
+            *reinterpret_cast<uint4 *>(zp) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+          else
+            *reinterpret_cast<uint2 *>(zp) = make_uint2(pk[0], pk[1]);
+        } else {
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) Io::store(zp, v, z[v]);
+        }
       }
-    } else {
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) win[K - 1][v] = Io::load(ub, static_cast<size_t>(t) * C + v);
     }
-    float z[VEC];
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-      float a = bs[v];
-#pragma unroll
-      for (int j = 0; j < K; ++j) a = fmaf(wt[v][j], win[j][v], a);
-      z[v] = act_apply(a, act);
-    }
-    E *zp = out_ptr<Io>(out, static_cast<size_t>(b) * T + t, c0);
-    if constexpr (VEC == 8 && sizeof(E) == 2) {
-      uint32_t pk[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k)
-        pk[k] = static_cast<uint32_t>(f32_to_bf16_bits(z[2 * k])) | (static_cast<uint32_t>(f32_to_bf16_bits(z[2 * k + 1])) << 16);
-      *reinterpret_cast<uint4 *>(zp) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-    } else {
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) Io::store(zp, v, z[v]);
-    }
+  };
+  request(buf[0], t0);
+  for (int tb = t0; tb < t1; tb += 2 * kBatch) {
+    request(buf[1], tb + kBatch);
+    process(buf[0], tb);
+    request(buf[0], tb + 2 * kBatch);
+    process(buf[1], tb + kBatch);
   }
   // the thread that owns the last tokens leaves the cache: inputs T-(K-1) .. T-1
   if (t1 == T && state_out) {
@@ -144,12 +213,17 @@ template <typename Io, int K>
 hipError_t prefill_typed(int Bt, int T, int C, bool vec8, const void *u, const float *w, const float *bias,
                          const void *state_in, const ConvOut &out, void *state_out, int act, hipStream_t stream) {
   const int runs = (T + kRun - 1) / kRun;
-  if (vec8) {
-    const dim3 grid((C / 8 + kConvThreads - 1) / kConvThreads, runs, Bt);
-    hipLaunchKernelGGL((conv_prefill_kernel<Io, 8, K>), grid, dim3(kConvThreads), 0, stream, u, w, bias, state_in, out,
-                       state_out, T, C, act);
-  } else {
-    const dim3 grid((C + kConvThreads - 1) / kConvThreads, runs, Bt);
+  if constexpr (sizeof(typename Io::type) == 2) {
+    if (vec8) {
+      constexpr int kV = 4;
+      const dim3 grid(static_cast<unsigned>((static_cast<size_t>(runs) * (C / kV) + kConvThreads - 1) / kConvThreads), 1, Bt);
+      hipLaunchKernelGGL((conv_prefill_kernel<Io, kV, K>), grid, dim3(kConvThreads), 0, stream, u, w, bias, state_in,
+                         out, state_out, T, C, act);
+      return hipGetLastError();
+    }
+  }
+  {
+    const dim3 grid(static_cast<unsigned>((static_cast<size_t>(runs) * C + kConvThreads - 1) / kConvThreads), 1, Bt);
     hipLaunchKernelGGL((conv_prefill_kernel<Io, 1, K>), grid, dim3(kConvThreads), 0, stream, u, w, bias, state_in, out,
                        state_out, T, C, act);
   }
