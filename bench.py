@@ -108,6 +108,7 @@ def main():
     ap.add_argument("--decode-block", type=int, default=64,
                     help="steps per HIP graph and per multi-step launch in the decode comparison")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the decode step")
     ap.add_argument("--no-varlen", action="store_true")
     ap.add_argument("--no-conv", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -426,24 +427,26 @@ def main():
             # the same stacked launches replayed from a HIP graph (the launch work done once), and all
             # steps of a block in ONE launch with the state kept on chip between the steps
             nb = min(nsteps, args.decode_block)
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.stream(side):
-                with torch.cuda.graph(graph, stream=side):
-                    for i in range(nb):
-                        ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=yd)
-            torch.cuda.current_stream().wait_stream(side)
-            graph.replay()
-            torch.cuda.synchronize()
-            nrep = max(1, nsteps // nb)
-            e0.record()
-            for _ in range(nrep):
+            us_graph = None
+            if not args.no_graph:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.stream(side):
+                    with torch.cuda.graph(graph, stream=side):
+                        for i in range(nb):
+                            ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=yd)
+                torch.cuda.current_stream().wait_stream(side)
                 graph.replay()
-            e1.record()
-            torch.cuda.synchronize()
-            us_graph = e0.elapsed_time(e1) * 1e3 / (nrep * nb)
-            del graph
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(max(1, nsteps // nb)):
+                    graph.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                us_graph = e0.elapsed_time(e1) * 1e3 / (max(1, nsteps // nb) * nb)
+                del graph
+            nrep = max(1, nsteps // nb)
             ys_blk = torch.empty((nb, Ly, c.batch, c.nheads, c.headdim), dtype=io, device=dev)
             ssd.ssd_decode_steps_layers(state, xs[:nb], dts[:nb], A, Bs[:nb], Cs[:nb], D, y=ys_blk)
             torch.cuda.synchronize()
@@ -459,15 +462,15 @@ def main():
             fused_bytes = (2 * 4 * state.numel() / nb + Ly * c.batch * (2 * c.nheads * c.headdim * io_b +
                                                                        4 * c.nheads + 2 * c.ngroups * c.dstate * io_b))
             decode[name].update(
-                graph_us_per_step=round(us_graph, 3), graph_hbm_gbs=round(bytes_step / us_graph / 1e3, 1),
-                steps_per_graph=nb,
+                graph_us_per_step=None if us_graph is None else round(us_graph, 3),
+                graph_hbm_gbs=None if us_graph is None else round(bytes_step / us_graph / 1e3, 1), steps_per_graph=nb,
                 multi_step=dict(steps_per_launch=nb, us_per_step=round(us_fused, 3),
                                 speedup_vs_stacked=round(us / us_fused, 2),
                                 bytes_per_step=int(fused_bytes), hbm_gbs=round(fused_bytes / us_fused / 1e3, 1),
                                 gflops=round(decode_flops(c, Ly) / us_fused / 1e3, 1),
                                 frac_of_fp32_valu_peak=round(decode_flops(c, Ly) / us_fused / 1e6 / PEAK_VALU_F32_TFLOPS, 4)))
-            log("[bench] decode %s: graph replay %.2f us/step; %d steps per launch %.2f us/step (%.1fx)" %
-                (name, us_graph, nb, us_fused, us / us_fused))
+            log("[bench] decode %s: graph replay %s us/step; %d steps per launch %.2f us/step (%.1fx)" %
+                (name, "-" if us_graph is None else "%.2f" % us_graph, nb, us_fused, us / us_fused))
             del ys_blk
             if c.batch == 1:
                 # per-layer launches (64 per step), the host-driven analogue
