@@ -43,6 +43,10 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_vec_kernel(
   constexpr int N = LPR * 4;
   constexpr int RPP = kDecodeThreads / LPR;  // rows per pass
   const size_t pair = blockIdx.x;            // (layer*Bt + b)*H + h
+  // blockIdx.y: with few (layer, row, head) units the rows of a state are shared out over gridDim.y
+  // workgroups (contiguous ranges of whole passes), so that a small launch still fills the chip
+  const int rows_per_wg = (P + gridDim.y - 1) / gridDim.y;
+  const int p_begin = blockIdx.y * rows_per_wg, p_end = min(P, p_begin + rows_per_wg);
   const int h = static_cast<int>(pair % H);
   const size_t lb = pair / H;                // layer*Bt + b
   const int layer = static_cast<int>(pair / BtH);
@@ -58,13 +62,13 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_vec_kernel(
   const float4 Cv = load4<Io>(C, bc);
 
   float *hbase = state + pair * static_cast<size_t>(P) * N + lane_n * 4;
-  for (int p0 = row0; p0 < P; p0 += RPP * kDecodeUnroll) {
+  for (int p0 = p_begin + row0; p0 < p_end; p0 += RPP * kDecodeUnroll) {
     float4 hv[kDecodeUnroll];
     float xv[kDecodeUnroll];
 #pragma unroll
     for (int u = 0; u < kDecodeUnroll; ++u) {
       const int p = p0 + u * RPP;
-      if (p < P) {
+      if (p < p_end) {
         hv[u] = *reinterpret_cast<const float4 *>(hbase + static_cast<size_t>(p) * N);
         xv[u] = Io::load(x, pair * P + p);
       }
@@ -72,7 +76,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_vec_kernel(
 #pragma unroll
     for (int u = 0; u < kDecodeUnroll; ++u) {
       const int p = p0 + u * RPP;
-      if (p < P) {
+      if (p < p_end) {
         const float ux = dtv * xv[u];
         float4 v = hv[u];
         v.x = fmaf(dA, v.x, ux * Bv.x);
@@ -241,10 +245,18 @@ hipError_t launch_typed(int nlayers, const Dims &d, float *state, const void *x,
   const size_t npairs = static_cast<size_t>(nlayers) * d.Bt * d.H;
   const dim3 grid(static_cast<unsigned>(npairs)), block(kDecodeThreads);
   const int BtH = d.Bt * d.H;
-#define SSD_DECODE_CASE(LPR_)                                                                       \
-  case LPR_:                                                                                        \
-    hipLaunchKernelGGL((decode_vec_kernel<Io, LPR_>), grid, block, 0, stream, state, x, dt, A, B, C, \
-                       D, y, BtH, d.H, d.P, d.G, d.hpg);                                            \
+  // Small launches (a single layer at a small batch) split each state over several workgroups: the
+  // step is latency bound there, and 80 workgroups leave most of the 256 CUs idle.
+  auto split_for = [&](int rows_per_pass) {
+    int split = 1;
+    while (npairs * split < 1024 && d.P / (2 * split) >= rows_per_pass && split < 8) split *= 2;
+    return split;
+  };
+#define SSD_DECODE_CASE(LPR_)                                                                            \
+  case LPR_:                                                                                             \
+    hipLaunchKernelGGL((decode_vec_kernel<Io, LPR_>),                                                    \
+                       dim3(static_cast<unsigned>(npairs), split_for(kDecodeThreads / LPR_)), block, 0,  \
+                       stream, state, x, dt, A, B, C, D, y, BtH, d.H, d.P, d.G, d.hpg);                  \
     break;
   if (d.N % 4 == 0) {
     switch (d.N / 4) {
