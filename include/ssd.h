@@ -128,8 +128,8 @@ SSD_API ssd_status ssd_prefill(const ssd_shape *shape, const void *x, const floa
  *   workspace         at least ssd_prefill_varlen_workspace_bytes() bytes, 256-byte aligned
  * Tokens outside every sequence are left untouched in y.
  * Implemented for the MFMA kernel family (bf16 io, headdim a multiple of 64,
- * dstate 128, chunk a multiple of 64, heads per group x headdim / 64 a
- * multiple of 4); any other shape
+ * dstate a multiple of 8 up to 128, chunk a multiple of 64, heads per group x
+ * headdim / 64 a multiple of 4); any other shape
  * returns SSD_ERR_UNSUPPORTED and ssd_prefill_varlen_workspace_bytes returns 0.
  * Errors: SSD_ERR_NULL, _SHAPE, _DTYPE, _ALIGN, _UNSUPPORTED, _WORKSPACE, _HIP.
  */

@@ -1,5 +1,6 @@
-// MFMA prefill for the Mamba-2 head shape (headdim 64 or a multiple of it, dstate 128, bf16 io,
-// chunk % 64 == 0, heads per group x (headdim / 64) a multiple of 4).  A head with headdim 64 k is
+// MFMA prefill for the Mamba-2 head shape (headdim 64 or a multiple of it, dstate 128 -- other state
+// sizes are mapped onto it, see "state slices" at the launcher -- bf16 io, chunk % 64 == 0, heads per
+// group x (headdim / 64) a multiple of 4).  A head with headdim 64 k is
 // processed as k independent heads of 64 columns ("head" below means such a 64-column slice): its
 // columns never interact, x, y and the state are laid out exactly as those of k narrower heads, and
 // the slices share the head's decay records, A and D.
@@ -92,6 +93,15 @@ __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_ex
 __device__ __forceinline__ f32x16 mfma(const Operand &a, const Operand &b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, c, 0, 0, 0);
 }
+
+// ---- state slices ----------------------------------------------------------------------------------
+// The kernels are written for 128 state columns.  A launch works on columns [off, off + valid) of a
+// dstate axis of `width` columns (valid <= 128; columns beyond `valid` are zero padding): dstate 64 is
+// one padded slice, dstate 256 is two slices, each an SSD of its own with the same x and dt, whose
+// outputs add up (everything is linear in the triple B, C, state).
+struct NSlice {
+  int width, off, valid;
+};
 
 // ---- tables of a variable-length call -----------------------------------------------------------
 // A packed batch (sequences back to back along the token axis, boundaries in a device array of
@@ -229,26 +239,30 @@ __global__ __launch_bounds__(256) void varlen_fill_kernel(const int32_t *__restr
 // One workgroup per (block, group).  The block covers rows [row0, row0 + 64) of the (tokens, G, N)
 // arrays B and C, of which only rows below row_end belong to its sequence; its results go to tile
 // number `tile` of Gd (64 l x 64 s, bf16) and of Btr (128 n x 64 s, bf16).  sB: kBlk * (kN + 2)
-// elements of LDS.
+// elements of LDS.  ns: which columns of the dstate axis this launch works on (see NSlice); with a
+// slice that is not the whole axis, the slice of C is also copied, zero padded to 128 columns, to
+// Cpad (tokens, G, 128), from which the scan then reads it.
 __device__ __forceinline__ void scores_bt_block(uint16_t *sB, size_t row0, size_t row_end, size_t tile, int g,
                                                 const uint16_t *__restrict__ B, const uint16_t *__restrict__ C,
-                                                uint16_t *__restrict__ Gd, uint16_t *__restrict__ Btr, int G) {
+                                                uint16_t *__restrict__ Gd, uint16_t *__restrict__ Btr, int G,
+                                                const NSlice ns, uint16_t *__restrict__ Cpad) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ws = wave >> 1, wl = wave & 1;
   const int r = lane & 31, kg = lane >> 5;
 
   // G^T tile (rows s, columns l): lane ends up with four consecutive s for its l.
   const size_t srow = row0 + 32 * ws + r, lrow = row0 + 32 * wl + r;
-  const uint16_t *Bp = B + (srow * G + g) * kN + 8 * kg;
-  const uint16_t *Cp = C + (lrow * G + g) * kN + 8 * kg;
+  const uint16_t *Bp = B + (srow * G + g) * ns.width + ns.off + 8 * kg;
+  const uint16_t *Cp = C + (lrow * G + g) * ns.width + ns.off + 8 * kg;
   f32x16 acc = {};
 #pragma unroll
   for (int q = 0; q < kN / 16; ++q) {
     Operand a, c;
     a.q = mk4(0, 0, 0, 0);
     c.q = mk4(0, 0, 0, 0);
-    if (srow < row_end) a.q = *reinterpret_cast<const u32x4 *>(Bp + 16 * q);
-    if (lrow < row_end) c.q = *reinterpret_cast<const u32x4 *>(Cp + 16 * q);
+    const bool in_slice = 8 * kg + 16 * q < ns.valid;  // columns beyond the slice count as zero
+    if (srow < row_end && in_slice) a.q = *reinterpret_cast<const u32x4 *>(Bp + 16 * q);
+    if (lrow < row_end && in_slice) c.q = *reinterpret_cast<const u32x4 *>(Cp + 16 * q);
     acc = mfma(a, c, acc);
   }
   uint16_t *Gout = Gd + tile * kBlk * kBlk;
@@ -266,7 +280,13 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, size_t row0, size_
   for (int c = threadIdx.x; c < kBlk * (kN / 8); c += kThreads) {
     const int row = c / (kN / 8), ch = c % (kN / 8);
     u32x4 v = mk4(0, 0, 0, 0);
-    if (row0 + row < row_end) v = *reinterpret_cast<const u32x4 *>(B + ((row0 + row) * G + g) * kN + 8 * ch);
+    const bool have = row0 + row < row_end && 8 * ch < ns.valid;
+    if (have) v = *reinterpret_cast<const u32x4 *>(B + ((row0 + row) * G + g) * ns.width + ns.off + 8 * ch);
+    if (Cpad != nullptr && row0 + row < row_end) {  // the slice of C, zero padded to 128 columns
+      u32x4 cv = mk4(0, 0, 0, 0);
+      if (have) cv = *reinterpret_cast<const u32x4 *>(C + ((row0 + row) * G + g) * ns.width + ns.off + 8 * ch);
+      *reinterpret_cast<u32x4 *>(Cpad + ((row0 + row) * G + g) * kN + 8 * ch) = cv;
+    }
     uint32_t *dst = reinterpret_cast<uint32_t *>(sB + row * (kN + 2) + 8 * ch);
     dst[0] = v.x;
     dst[1] = v.y;
@@ -360,7 +380,8 @@ __global__ __launch_bounds__(kThreads) void block_prep_kernel(const uint16_t *__
                                                               const float *__restrict__ dt,
                                                               const float *__restrict__ A,
                                                               float *__restrict__ prep, int T, int H, int G,
-                                                              int NB, int n_scores, const VarPlan vp) {
+                                                              int NB, int n_scores, const VarPlan vp,
+                                                              const NSlice ns, uint16_t *__restrict__ Cpad) {
   __shared__ __align__(16) uint16_t sB[kBlk * (kN + 2)];
   __shared__ float tile[kBlk + kBlk / 2][kCumHeads + 1];
   const int wg = blockIdx.x;
@@ -380,7 +401,7 @@ __global__ __launch_bounds__(kThreads) void block_prep_kernel(const uint16_t *__
       row0 = static_cast<size_t>(bg / G) * T + static_cast<size_t>(jb) * kBlk;
       row_end = static_cast<size_t>(bg / G) * T + T;
     }
-    scores_bt_block(sB, row0, row_end, static_cast<size_t>(bg) * NB + jb, bg % G, B, C, Gd, Btr, G);
+    scores_bt_block(sB, row0, row_end, static_cast<size_t>(bg) * NB + jb, bg % G, B, C, Gd, Btr, G, ns, Cpad);
   } else {
     const int hgroups = (H + kCumHeads - 1) / kCumHeads;
     const int b = i / (NB * hgroups);
@@ -409,6 +430,7 @@ struct ScanParams {
   float *seg_decay;        // states-only: log2 of the segment's total decay, one per slot
   int T, H, G, hpg, NB, seg_blocks, S;  // H, hpg count 64-column slices
   int pdiv, Hrec;          // slices per head (headdim / 64); heads (owners of decay records, A, D)
+  NSlice ns;               // columns of h0 / final_state (rows of ns.width floats) this launch works on
   int cols, segs, total, per_xcd;  // workgroup mapping, see wg_coords
   VarPlan vp;              // tok0 == nullptr: plain batch
 };
@@ -707,26 +729,31 @@ void chunk_scan_kernel(const ScanParams p) {
   // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][column of lane r] ----
   const int pcol = 32 * ph + pi_of_row(r);  // headdim column of this lane's state column
   f32x16 Hacc[4];
-  float Dh = kStatesOnly ? 0.f : p.D[hrec];
+  float Dh = kStatesOnly || p.D == nullptr ? 0.f : p.D[hrec];
   // Pin the value as "arrived" before the loop: otherwise the wait for it is placed at its first use
   // inside the loop, where it also waits for every younger load of every iteration.
   asm volatile("" : "+v"(Dh));
   const float *hp = nullptr;
+  int hp_valid = kN;  // state columns present at hp
   if (!kStatesOnly) {
     // A sequence of one segment starts from h0 itself (this workgroup reads it here and is the only
     // one to write final_state, so the two may share memory); with several segments every segment,
     // the first included, starts from the slot that the pass over segment states has filled.
-    if (sv.S > 1)
+    if (sv.S > 1) {
       hp = p.Hin + (slot0 + sg) * (kP * kN) + static_cast<size_t>(pcol) * kN;
-    else if (p.h0 != nullptr)
-      hp = p.h0 + bh * (kP * kN) + static_cast<size_t>(pcol) * kN;
+    } else if (p.h0 != nullptr) {
+      hp = p.h0 + (bh * kP + pcol) * p.ns.width + p.ns.off;
+      hp_valid = p.ns.valid;
+    }
   }
   if (hp != nullptr) {
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const f32x4 v = *reinterpret_cast<const f32x4 *>(hp + 32 * nt + 8 * i4 + 4 * kg);
+        const int n0 = 32 * nt + 8 * i4 + 4 * kg;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (n0 < hp_valid) v = *reinterpret_cast<const f32x4 *>(hp + n0);
         Hacc[nt][4 * i4 + 0] = v.x;
         Hacc[nt][4 * i4 + 1] = v.y;
         Hacc[nt][4 * i4 + 2] = v.z;
@@ -1026,19 +1053,24 @@ void chunk_scan_kernel(const ScanParams p) {
 
   // ---- write the state out (canonical (p, n) layout, four consecutive n per 16-byte store) ----
   float *out = nullptr;
+  int out_valid = kN;
   if (kStatesOnly) {
-    out = p.seg_state + (slot0 + sg + 1) * (kP * kN);
+    out = p.seg_state + (slot0 + sg + 1) * (kP * kN) + static_cast<size_t>(pcol) * kN;
     if (lane == 0 && ph == 0) p.seg_decay[slot0 + sg] = seg_total;
   } else if (sg == sv.S - 1) {
-    out = p.final_state + bh * kP * kN;
+    out = p.final_state + (bh * kP + pcol) * p.ns.width + p.ns.off;
+    out_valid = p.ns.valid;
   }
   if (out != nullptr) {
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4)
-        *reinterpret_cast<f32x4 *>(out + static_cast<size_t>(pcol) * kN + 32 * nt + 8 * i4 + 4 * kg) =
-            f32x4{Hacc[nt][4 * i4 + 0], Hacc[nt][4 * i4 + 1], Hacc[nt][4 * i4 + 2], Hacc[nt][4 * i4 + 3]};
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int n0 = 32 * nt + 8 * i4 + 4 * kg;
+        if (n0 < out_valid)
+          *reinterpret_cast<f32x4 *>(out + n0) =
+              f32x4{Hacc[nt][4 * i4 + 0], Hacc[nt][4 * i4 + 1], Hacc[nt][4 * i4 + 2], Hacc[nt][4 * i4 + 3]};
+      }
   }
 }
 
@@ -1051,7 +1083,7 @@ void chunk_scan_kernel(const ScanParams p) {
 __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restrict__ seg_state,
                                                                 const float *__restrict__ seg_decay,
                                                                 const float *__restrict__ h0, int S_plain, int H,
-                                                                int rows, const VarPlan vp) {
+                                                                int rows, const VarPlan vp, const NSlice ns) {
   constexpr int kAhead = 16;
   const int e = (blockIdx.x * kThreads + threadIdx.x) * 4;
   if (vp.tok0 != nullptr && vp.slot0[vp.nseq] == 0) return;  // no sequence has more than one segment
@@ -1066,7 +1098,8 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
   }
   if (S < 2) continue;  // a single segment starts from h0 itself
   f32x4 run = {0.f, 0.f, 0.f, 0.f};
-  if (h0) run = *reinterpret_cast<const f32x4 *>(h0 + bh * kP * kN + e);
+  if (h0 && e % kN < ns.valid)  // h0 rows hold ns.width columns, of which this launch owns a slice
+    run = *reinterpret_cast<const f32x4 *>(h0 + (bh * kP + e / kN) * ns.width + ns.off + e % kN);
   float *sp = seg_state + slot0 * (kP * kN) + e;
   const float *dp = seg_decay + slot0;
   *reinterpret_cast<f32x4 *>(sp) = run;
@@ -1141,6 +1174,19 @@ int choose_seg_blocks(const Dims &d) {
   return best_blocks;
 }
 
+// y += t over n 16-byte pieces of bf16 (sum in fp32, rounded once): adds the output of a later state
+// slice to the output so far.
+__global__ __launch_bounds__(kThreads) void add_outputs_kernel(uint16_t *__restrict__ y, const uint16_t *__restrict__ t,
+                                                               size_t n) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (i >= n) return;
+  const u32x4 a = reinterpret_cast<const u32x4 *>(y)[i], b = reinterpret_cast<const u32x4 *>(t)[i];
+  u32x4 r;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) r[k] = pack2(bf_lo(a[k]) + bf_lo(b[k]), bf_hi(a[k]) + bf_hi(b[k]));
+  reinterpret_cast<u32x4 *>(y)[i] = r;
+}
+
 // Workspace.  Plain batch: rows = Bt sequences of NB blocks each.  Variable-length batch: one "row" whose
 // NB is the block capacity ceil(total / 64) + nseq (every sequence may end in a partial block), whose
 // segment list holds at most NB / (blocks per chunk) + nseq + 1 entries (a segment is at least a
@@ -1149,7 +1195,7 @@ int choose_seg_blocks(const Dims &d) {
 // most min(that, 4 ceil(total / 64) / (blocks per chunk) + 4); then the int32 tables of VarPlan.
 struct Layout {
   int NB, S_max, items_max;
-  size_t off_G, off_Bt, off_prep, off_state, off_decay, off_tables, total;
+  size_t off_G, off_Bt, off_prep, off_state, off_decay, off_tables, off_Cpad, off_ytmp, total;
 };
 
 Layout make_layout(const Dims &d, bool varlen) {
@@ -1179,6 +1225,13 @@ Layout make_layout(const Dims &d, bool varlen) {
   off += round_up(BHs * w.S_max * sizeof(float), 256);
   w.off_tables = off;
   if (varlen) off += round_up((5 * (static_cast<size_t>(nseq) + 1) + w.NB + w.items_max) * sizeof(int32_t), 256);
+  // dstate other than 128: a 128-column copy of the slice of C in work; more than one slice: the
+  // output of the later slices before it is added to y
+  const size_t tokens = static_cast<size_t>(rows) * d.T;
+  w.off_Cpad = off;
+  if (d.N != kN) off += round_up(tokens * d.G * kN * sizeof(uint16_t), 256);
+  w.off_ytmp = off;
+  if (d.N > kN) off += round_up(tokens * d.H * d.P * sizeof(uint16_t), 256);
   w.total = off;
   return w;
 }
@@ -1186,16 +1239,18 @@ Layout make_layout(const Dims &d, bool varlen) {
 bool shape_ok(const Dims &d, unsigned long long tokens, unsigned long long nb) {
   // one sequence of x, C and the per-head block records must be addressable with 32-bit byte offsets
   const unsigned long long lim = 0xFFFF0000ull;
-  return d.bf16 && d.P % kP == 0 && d.P <= 16 * kP && d.N == kN && d.L % kBlk == 0 &&
+  return d.bf16 && d.P % kP == 0 && d.P <= 16 * kP && d.N % 8 == 0 && d.N <= 4 * kN && d.L % kBlk == 0 &&
          (d.hpg * (d.P / kP)) % kHeadsPerWg == 0 && d.Bt <= 65535 && d.H <= 65535 &&
-         tokens * d.H * (static_cast<unsigned long long>(d.P) * 2) <= lim && tokens * d.G * (kN * 2) <= lim &&
+         tokens * d.H * (static_cast<unsigned long long>(d.P) * 2) <= lim &&
+         tokens * d.G * (static_cast<unsigned long long>(d.N > kN ? d.N : kN) * 2) <= lim &&
          nb * (kN * kBlk * 2) <= lim;
 }
 
 // d: plain batch (cu == nullptr), or Bt = number of sequences and T = total tokens of a packed batch.
-hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *dt, const float *A, const void *B,
-                  const void *C, const float *D, const float *h0, void *y, float *final_state, void *workspace,
-                  hipStream_t stream, KernelTrace *trace) {
+// One state slice ns (see NSlice): y and final_state columns of that slice are written.
+hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const void *x, const float *dt,
+                        const float *A, const void *B, const void *C, const float *D, const float *h0, void *y,
+                        float *final_state, void *workspace, hipStream_t stream, KernelTrace *trace) {
   const bool varlen = cu != nullptr;
   const Layout w = make_layout(d, varlen);
   char *ws = static_cast<char *>(workspace);
@@ -1204,6 +1259,7 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
   float *prep = reinterpret_cast<float *>(ws + w.off_prep);
   float *seg_state = reinterpret_cast<float *>(ws + w.off_state);
   float *seg_decay = reinterpret_cast<float *>(ws + w.off_decay);
+  uint16_t *Cpad = d.N != kN ? reinterpret_cast<uint16_t *>(ws + w.off_Cpad) : nullptr;
   const int rows = varlen ? 1 : d.Bt;
   Dims one = d;  // the segment length of a packed batch is chosen as for one sequence of all its tokens
   if (varlen) one.Bt = 1;
@@ -1233,13 +1289,14 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
   const int n_cumsum = w.NB * ((d.H + kCumHeads - 1) / kCumHeads) * rows;
   hipLaunchKernelGGL(block_prep_kernel, dim3(n_scores + n_cumsum), dim3(kThreads), 0, stream,
                      static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(C), Gd, Btr, dt, A, prep,
-                     d.T, d.H, d.G, w.NB, n_scores, vp);
+                     d.T, d.H, d.G, w.NB, n_scores, vp, ns, Cpad);
   trace_mark(trace, stream, "block_prep");
 
   ScanParams p;
   p.x = static_cast<const uint8_t *>(x);
-  p.C = static_cast<const uint8_t *>(C);
+  p.C = Cpad != nullptr ? reinterpret_cast<const uint8_t *>(Cpad) : static_cast<const uint8_t *>(C);
   p.D = D;
+  p.ns = ns;
   p.Gd = reinterpret_cast<const uint8_t *>(Gd);
   p.Btr = reinterpret_cast<const uint8_t *>(Btr);
   p.prep = prep;
@@ -1274,7 +1331,7 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
     trace_mark(trace, stream, "segment_states");
     const int rows_bh = d.Bt * Hs;  // a packed batch may have many one-segment sequences: rows are looped over
     hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), rows_bh > (varlen ? 2048 : 65535) ? (varlen ? 2048 : 65535) : rows_bh),
-                       dim3(kThreads), 0, stream, seg_state, seg_decay, h0, S, Hs, rows_bh, vp);
+                       dim3(kThreads), 0, stream, seg_state, seg_decay, h0, S, Hs, rows_bh, vp, ns);
     trace_mark(trace, stream, "segment_pass");
   }
   p.cols = Hs / kHeadsPerWg;
@@ -1284,6 +1341,28 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
   p.per_xcd = (p.total + kXcds - 1) / kXcds;
   hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0, stream, p);
   trace_mark(trace, stream, "chunk_scan");
+  return hipGetLastError();
+}
+
+// All state slices: the first writes y (with the skip term D x), every later one goes to a scratch
+// output without the skip term and is added.
+hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *dt, const float *A, const void *B,
+                  const void *C, const float *D, const float *h0, void *y, float *final_state, void *workspace,
+                  hipStream_t stream, KernelTrace *trace) {
+  const Layout w = make_layout(d, cu != nullptr);
+  for (int off = 0; off < d.N; off += kN) {
+    const NSlice ns = {d.N, off, d.N - off < kN ? d.N - off : kN};
+    void *out = off == 0 ? y : static_cast<char *>(workspace) + w.off_ytmp;
+    const hipError_t e = launch_slice(d, ns, cu, x, dt, A, B, C, off == 0 ? D : nullptr, h0, out, final_state,
+                                      workspace, stream, off == 0 ? trace : nullptr);
+    if (e != hipSuccess) return e;
+    if (off > 0) {
+      const size_t pieces = static_cast<size_t>(cu != nullptr ? 1 : d.Bt) * d.T * d.H * d.P / 8;
+      hipLaunchKernelGGL(add_outputs_kernel, dim3(static_cast<unsigned>((pieces + kThreads - 1) / kThreads)),
+                         dim3(kThreads), 0, stream, static_cast<uint16_t *>(y),
+                         reinterpret_cast<const uint16_t *>(out), pieces);
+    }
+  }
   return hipGetLastError();
 }
 
@@ -1304,7 +1383,8 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
 // Packed variable-length batch: d.Bt sequences, d.T tokens in total, boundaries in the device array cu.
 bool mfma_varlen_supported(const Dims &d) {
   const unsigned long long nb = (static_cast<unsigned long long>(d.T) + kBlk - 1) / kBlk + d.Bt;
-  return shape_ok(d, static_cast<unsigned long long>(d.T), nb) && nb <= 0x7fffffffull / 64;
+  // (one state slice only: the sum over slices would also touch tokens that belong to no sequence)
+  return shape_ok(d, static_cast<unsigned long long>(d.T), nb) && nb <= 0x7fffffffull / 64 && d.N <= kN;
 }
 
 size_t mfma_varlen_workspace_bytes(const Dims &d) { return make_layout(d, true).total; }

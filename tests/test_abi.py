@@ -122,7 +122,7 @@ def test_varlen_rejects_before_any_hip_call(ssd):
     assert call(shape(ssd, **ok), w=None) == -5
     assert call(shape(ssd, **dict(ok, seqlen=0))) == -2
     # outside the MFMA kernel family: fp32 io, other head shapes, chunk not a multiple of 64
-    for bad in (dict(io_dtype=0), dict(headdim=32), dict(dstate=64), dict(chunk=100), dict(ngroups=4)):
+    for bad in (dict(io_dtype=0), dict(headdim=32), dict(dstate=256), dict(dstate=100), dict(chunk=100), dict(ngroups=4)):
         assert call(shape(ssd, **dict(ok, **bad))) == -4
         assert lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(shape(ssd, **dict(ok, **bad)))) == 0
 

@@ -302,6 +302,10 @@ MFMA_CASES = [
     (2, 300, 4, 128, 128, 2, 64, 1),     # headdim 128: two 64-column slices per head, two heads per group
     (1, 500, 4, 192, 128, 1, 128, 2),    # headdim 192
     (1, 700, 2, 256, 128, 2, 64, 0),     # headdim 256, one head per group
+    (2, 300, 4, 64, 64, 1, 64, 1),       # dstate 64: one zero-padded state slice
+    (1, 1000, 8, 64, 256, 2, 128, 2),    # dstate 256: two state slices, outputs added
+    (1, 500, 4, 64, 32, 1, 256, 0),      # dstate 32
+    (2, 300, 4, 128, 192, 1, 64, 1),     # dstate 192 (one and a half slices), headdim 128
 ]
 
 
@@ -372,22 +376,23 @@ VARLEN_CASES = [
     ([1000, 1048], 12, 1, 256, 2, False),
     ([17] * 40, 4, 1, 64, 0, True),                              # many short sequences
     ([130, 0, 700, 64], (2, 128), 1, 64, 2, True),               # headdim 128 (H given as (heads, headdim))
+    ([130, 0, 700, 64], (4, 64, 64), 1, 64, 2, True),            # dstate 64 (heads, headdim, dstate)
 ]
 
 
 @pytest.mark.parametrize("case", VARLEN_CASES, ids=lambda c: "-".join(str(v) for v in c[1:]) + "-n%d" % len(c[0]))
 def test_varlen_prefill_matches_oracle(ssd, case, monkeypatch):
     lengths, H, G, L, seg_chunks, with_h0 = case
-    H, P = H if isinstance(H, tuple) else (H, 64)
+    H, P, N = (tuple(H) + (128,))[:3] if isinstance(H, tuple) else (H, 64, 128)
     lens = [v[0] if isinstance(v, tuple) else v for v in lengths]   # gaps are simply more sequences
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     T, nseq = int(cu[-1]), len(lens)
     if seg_chunks:
         monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg_chunks))
-    cfg = cfg_of(1, T, H, P, 128, G, L, "bf16")
+    cfg = cfg_of(1, T, H, P, N, G, L, "bf16")
     inp = inputs.make_prefill_inputs(cfg, seed=31)
     pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
-    h0 = inputs.make_state(cfg_of(nseq, 1, H, P, 128, G, L, "bf16"), seed=31) if with_h0 else None
+    h0 = inputs.make_state(cfg_of(nseq, 1, H, P, N, G, L, "bf16"), seed=31) if with_h0 else None
     print("varlen case", lens, "H", H, "G", G, "L", L, "seg_chunks", seg_chunks, "h0", with_h0, flush=True)
     dev = {k: v.cuda() for k, v in pk.items()}
     y = torch.full_like(dev["x"], 7.0)
