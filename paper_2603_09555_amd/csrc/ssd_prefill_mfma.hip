@@ -42,8 +42,8 @@
 //                  zero start (only the chunk-state accumulation), so that segments can run in parallel.
 //   segment_pass   sequential pass over segment end states -> state entering each segment.
 //   chunk_scan<false> per (batch, 4 heads, segment): everything above, from the entering state.
-// A segment is a whole number of 64-token blocks, at least one chunk; with one segment only the first
-// and the last kernel run.
+// A segment is a whole number of 64-token blocks; with one segment only the first and the last kernel
+// run.
 #include <cstdlib>
 
 #include "ssd_internal.hpp"
@@ -1124,8 +1124,9 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
   }
 }
 
-// Blocks per segment.  A segment is any whole number of 64-token blocks but at least one chunk long
-// (which bounds the number of segments, and with it the workspace, by the number of chunks).  The
+// Blocks per segment.  A segment is any whole number of 64-token blocks; the number of segments, and
+// with it the workspace, is bounded by max_segments (plain batch) or by one segment per chunk (packed
+// batch).  The
 // choice minimises a small cost model fitted to measurements on MI355X (microseconds): one workgroup
 // per CU is resident, workgroups run in rounds of 256, a workgroup walks its blocks (plus a prologue
 // worth about two) at a per-block time that grows with the number of workgroups competing for
@@ -1142,7 +1143,19 @@ double rounds_time(long wgs, int blocks, double t_idle, double t_busy) {
   }
   return t;
 }
-int choose_seg_blocks(const Dims &d) {
+// Most segments a plain batch may be cut into (the workspace holds one state slot per segment and
+// head): one per chunk, or -- short prompts, few heads -- one per block as long as that does not
+// exceed what fills the chip several times over.
+int max_segments(const Dims &d) {
+  const int nblocks = (d.T + kBlk - 1) / kBlk;
+  const long groups = static_cast<long>(d.Bt) * (d.H * (d.P / kP) / kHeadsPerWg);
+  long by_fill = (8L * kNumCUs + groups - 1) / groups;
+  if (by_fill > 64) by_fill = 64;
+  if (by_fill > nblocks) by_fill = nblocks;
+  return d.Nc > by_fill ? d.Nc : static_cast<int>(by_fill);
+}
+// min_blocks: the shortest segment allowed (packed batches size their tables for whole chunks).
+int choose_seg_blocks(const Dims &d, int min_blocks) {
   const int chunk_blocks = d.L / kBlk;
   const int nblocks = (d.T + kBlk - 1) / kBlk;
   if (const char *e = std::getenv("SSD_SEG_CHUNKS")) {
@@ -1151,18 +1164,18 @@ int choose_seg_blocks(const Dims &d) {
   }
   if (const char *e = std::getenv("SSD_SEG_BLOCKS")) {
     const int k = std::atoi(e);
-    if (k >= chunk_blocks) return k;
+    if (k >= min_blocks) return k;
   }
   const int slices = d.H * (d.P / kP);
   const long groups = static_cast<long>(d.Bt) * (slices / kHeadsPerWg);
   const double seqs = static_cast<double>(d.Bt) * slices;
-  const int hi = nblocks > chunk_blocks ? nblocks : chunk_blocks;
+  const int hi = nblocks > min_blocks ? nblocks : min_blocks;
   int best_blocks = hi;
   double best = 0.0;
   bool have = false;
-  for (int cand = chunk_blocks; cand <= hi; ++cand) {
+  for (int cand = min_blocks; cand <= hi; ++cand) {
     const long segs = (nblocks + cand - 1) / cand;
-    if (cand > chunk_blocks && (nblocks + cand - 2) / (cand - 1) == segs) continue;  // same count, longer segments
+    if (cand > min_blocks && (nblocks + cand - 2) / (cand - 1) == segs) continue;  // same count, longer segments
     double cost = rounds_time(groups * segs, cand, 3.2, 4.0);
     if (segs > 1) cost += rounds_time(groups * (segs - 1), cand, 1.6, 2.2) + 3.5 + 0.0089 * segs * seqs + 8.0;
     if (!have || cost < best) {
@@ -1204,7 +1217,7 @@ Layout make_layout(const Dims &d, bool varlen) {
   const int nseq = varlen ? d.Bt : 0;
   w.NB = (d.T + kBlk - 1) / kBlk + nseq;
   const int cb = d.L / kBlk;  // a segment is at least one chunk
-  w.items_max = varlen ? w.NB / cb + nseq + 1 : d.Nc;
+  w.items_max = varlen ? w.NB / cb + nseq + 1 : max_segments(d);
   w.S_max = w.items_max;      // state slots per head
   if (varlen) {
     const long tight = 4L * ((d.T + kBlk - 1) / kBlk) / cb + 4;
@@ -1263,7 +1276,8 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   const int rows = varlen ? 1 : d.Bt;
   Dims one = d;  // the segment length of a packed batch is chosen as for one sequence of all its tokens
   if (varlen) one.Bt = 1;
-  const int seg_blocks = choose_seg_blocks(one);
+  // shortest segment: a chunk for a packed batch; what the state slots allow for a plain one
+  const int seg_blocks = choose_seg_blocks(one, varlen ? d.L / kBlk : (w.NB + w.S_max - 1) / w.S_max);
 
   VarPlan vp = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
   int S = (w.NB + seg_blocks - 1) / seg_blocks;  // plain batch: segments per sequence
