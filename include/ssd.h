@@ -110,6 +110,29 @@ SSD_API ssd_status ssd_prefill(const ssd_shape *shape, const void *x, const floa
                        size_t workspace_bytes, void *hip_stream);
 
 /*
+ * ssd_prefill with the step-size activation fused in (section "Mapping SSD
+ * onto JAX primitives" names softplus and clip among the elementwise
+ * neighbours of the decay computation; Alg. 1, "Discretise"): the kernels read
+ * the raw projection output and use
+ *     dt = clamp( softplus(dt_raw + dt_bias[h]), dt_min, dt_max )
+ * wherever ssd_prefill uses dt.  Each part is optional: dt_bias NULL = no bias,
+ * dt_softplus 0 = no softplus, dt_max <= 0 = no clamp.  Same workspace size,
+ * results, errors and aliasing rules as ssd_prefill; SSD_ERR_NULL if
+ * dt_transform is NULL, SSD_ERR_SHAPE if dt_max > 0 and dt_min > dt_max.
+ * The struct is read during the call only; dt_bias is a DEVICE array (nheads).
+ */
+typedef struct {
+  const float *dt_bias;
+  int32_t dt_softplus;
+  float dt_min, dt_max;
+} ssd_dt_transform;
+SSD_API ssd_status ssd_prefill_dt(const ssd_shape *shape, const ssd_dt_transform *dt_transform,
+                          const void *x, const float *dt_raw, const float *A,
+                          const void *B, const void *C, const float *D,
+                          const float *h0, void *y, float *final_state,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Prefill of a packed, variable-length batch: `batch` independent sequences
  * laid back to back along the token axis (ragged prompt batches, prompts fed in
  * pieces with their cached state as h0 -- section "The O(1) state cache":

@@ -269,3 +269,17 @@ def conv1d_step(conv_state, u, weight, bias=None, activation="silu"):
     """One token of :func:`conv1d_prefill`: ``u (Bt,C)``.  Returns ``(z (Bt,C), new cache)``."""
     z, st = conv1d_prefill(_f64(u)[:, None, :], weight, bias, conv_state, activation)
     return z[:, 0, :], st
+
+
+def dt_transform(raw, bias=None, softplus=False, limit=None):
+    """Step size from the raw projection output (Alg. 1, "Discretise"; softplus and clip are the
+    elementwise neighbours named in section "Mapping SSD onto JAX primitives"):
+    ``clamp(softplus(raw + bias[h]), lo, hi)``, each part optional.  ``raw (..., H)``, float64 out."""
+    v = _f64(raw).copy()
+    if bias is not None:
+        v = v + _f64(bias)
+    if softplus:
+        v = np.logaddexp(0.0, v)          # log(1 + exp(v)) without overflow
+    if limit is not None:
+        v = np.clip(v, limit[0], limit[1])
+    return v

@@ -56,10 +56,17 @@ size_t workspace_bytes(const Dims &d) {
 ssd_status prefill_impl(const ssd_shape *shape, const void *x, const float *dt, const float *A,
                         const void *B, const void *C, const float *D, const float *h0, void *y,
                         float *final_state, void *workspace, size_t workspace_bytes_given,
-                        void *hip_stream, ssd::KernelTrace *trace) {
+                        void *hip_stream, ssd::KernelTrace *trace, const ssd_dt_transform *dtx = nullptr) {
   Dims d;
   const ssd_status st = make_dims(shape, false, &d);
   if (st != SSD_OK) return st;
+  if (dtx != nullptr) {
+    if (dtx->dt_max > 0.f && !(dtx->dt_min <= dtx->dt_max)) return SSD_ERR_SHAPE;
+    d.dtx.bias = dtx->dt_bias;
+    d.dtx.softplus = dtx->dt_softplus != 0;
+    d.dtx.lo = dtx->dt_min;
+    d.dtx.hi = dtx->dt_max;
+  }
   if (!x || !dt || !A || !B || !C || !D || !y || !final_state) return SSD_ERR_NULL;
   if (!aligned16(x) || !aligned16(dt) || !aligned16(B) || !aligned16(C) || !aligned16(y) ||
       !aligned16(final_state) || (h0 && !aligned16(h0)))
@@ -99,6 +106,15 @@ ssd_status ssd_prefill(const ssd_shape *shape, const void *x, const float *dt, c
                        void *hip_stream) {
   return prefill_impl(shape, x, dt, A, B, C, D, h0, y, final_state, workspace, workspace_bytes_given,
                       hip_stream, nullptr);
+}
+
+ssd_status ssd_prefill_dt(const ssd_shape *shape, const ssd_dt_transform *dt_transform, const void *x,
+                          const float *dt_raw, const float *A, const void *B, const void *C, const float *D,
+                          const float *h0, void *y, float *final_state, void *workspace,
+                          size_t workspace_bytes_given, void *hip_stream) {
+  if (!dt_transform) return SSD_ERR_NULL;
+  return prefill_impl(shape, x, dt_raw, A, B, C, D, h0, y, final_state, workspace, workspace_bytes_given, hip_stream,
+                      nullptr, dt_transform);
 }
 
 ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, const float *dt, const float *A,

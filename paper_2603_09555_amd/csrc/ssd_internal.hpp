@@ -10,12 +10,29 @@
 
 namespace ssd {
 
+// Optional map from the caller's dt values to the step size (section "Mapping SSD onto JAX
+// primitives" lists softplus and clip among the elementwise neighbours that must fuse with the
+// decay computation): dt = clamp(softplus(raw + bias[h]), lo, hi).  Default: dt is used as given.
+struct DtXform {
+  const float *bias = nullptr;  // (nheads), device; nullptr = none
+  int softplus = 0;
+  float lo = 0.f, hi = 0.f;     // clamp to [lo, hi] if hi > 0
+  bool identity() const { return bias == nullptr && softplus == 0 && !(hi > 0.f); }
+};
+__device__ __forceinline__ float dt_apply(float v, int h, const DtXform &t) {
+  if (t.bias != nullptr) v += t.bias[h];
+  if (t.softplus) v = v > 20.f ? v : log1pf(expf(v));
+  if (t.hi > 0.f) v = fminf(fmaxf(v, t.lo), t.hi);
+  return v;
+}
+
 // Validated problem dimensions (host side).
 struct Dims {
   int Bt, T, H, P, N, G, L;
   int Nc;     // number of chunks, ceil(T / L)
   int hpg;    // heads per B/C group
   bool bf16;  // io dtype of x, B, C, y
+  DtXform dtx;  // prefill only
 };
 
 // ---- bf16 <-> fp32 (bf16 = upper half of the fp32 pattern, round-to-nearest-even) ----

@@ -270,6 +270,13 @@ __global__ __launch_bounds__(kThreads) void chunk_output_kernel(
   }
 }
 
+// dt = clamp(softplus(raw + bias), lo, hi), written out once (the generic kernels read dt in three places).
+__global__ __launch_bounds__(kThreads) void dt_transform_kernel(const float *__restrict__ raw, float *__restrict__ out,
+                                                                size_t n, int H, const DtXform dtx) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
+  if (i < n) out[i] = dt_apply(raw[i], static_cast<int>(i % H), dtx);
+}
+
 // A chunk longer than the sequence is one short chunk.
 Dims clamp_chunk(Dims d) {
   if (d.L > d.T) d.L = d.T;
@@ -310,7 +317,8 @@ size_t generic_workspace_bytes(const Dims &d_in) {
   const size_t BH = static_cast<size_t>(d.Bt) * d.H;
   const size_t cs = round_up(BH * d.Nc * d.L, 64);
   const size_t st = BH * d.Nc * d.P * d.N;
-  return round_up((cs + st) * sizeof(float), 256);
+  const size_t dtc = round_up(BH * d.T, 64);  // transformed copy of dt, used only with a DtXform
+  return round_up((cs + st + dtc) * sizeof(float), 256);
 }
 
 hipError_t launch_prefill_generic(const Dims &d_in, const void *x, const float *dt, const float *A,
@@ -318,6 +326,14 @@ hipError_t launch_prefill_generic(const Dims &d_in, const void *x, const float *
                                   float *final_state, void *workspace, hipStream_t stream,
                                   KernelTrace *trace) {
   const Dims d = clamp_chunk(d_in);
+  if (!d.dtx.identity()) {
+    const size_t BH = static_cast<size_t>(d.Bt) * d.H;
+    const size_t n = BH * d.T;
+    float *copy = static_cast<float *>(workspace) + round_up(BH * d.Nc * d.L, 64) + BH * d.Nc * d.P * d.N;
+    hipLaunchKernelGGL(dt_transform_kernel, dim3(static_cast<unsigned>((n + kThreads - 1) / kThreads)), dim3(kThreads),
+                       0, stream, dt, copy, n, d.H, d.dtx);
+    dt = copy;
+  }
   return d.bf16
              ? launch_typed<IoBf16>(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace)
              : launch_typed<IoF32>(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);

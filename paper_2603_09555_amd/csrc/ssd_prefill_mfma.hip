@@ -318,7 +318,8 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, size_t row0, size_
 //   [130]      exp2(c31)           state: start of the block -> middle of the block
 //   [131]      [128] * [130] of the next block: middle of the block -> middle of the next block
 // The block covers rows [row0, row0 + 64) of dt (tokens, H); rows from row_end on are not part of
-// the sequence and count as dt = 0 (state-neutral padding).  dt is transposed through LDS, 64 tokens
+// the sequence and count as dt = 0 (state-neutral padding).  The caller's dt values pass through
+// dt_apply (optional bias, softplus, clamp) as they are read.  dt is transposed through LDS, 64 tokens
 // of the block plus the first 32 of the next one (for [131]).  Head h's record goes to record number
 // h * rec_stride + rec_off.
 constexpr int kRec = 2 * kBlk + 4;
@@ -326,18 +327,19 @@ constexpr int kCumHeads = 16;
 constexpr float kMaxExp = 100.f;
 __device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1], size_t row0, size_t row_end, int h0,
                                                    size_t rec_stride, size_t rec_off, const float *__restrict__ dt,
-                                                   const float *__restrict__ A, float *__restrict__ prep, int H) {
+                                                   const float *__restrict__ A, float *__restrict__ prep, int H,
+                                                   const DtXform dtx) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int i = threadIdx.x; i < kBlk * kCumHeads; i += kThreads) {
     const int tok = i / kCumHeads, hh = i % kCumHeads;
     float v = 0.f;
-    if (row0 + tok < row_end && h0 + hh < H) v = dt[(row0 + tok) * H + h0 + hh];
+    if (row0 + tok < row_end && h0 + hh < H) v = dt_apply(dt[(row0 + tok) * H + h0 + hh], h0 + hh, dtx);
     tile[tok][hh] = v;
   }
   for (int i = threadIdx.x; i < (kBlk / 2) * kCumHeads; i += kThreads) {
     const int tok = kBlk + i / kCumHeads, hh = i % kCumHeads;
     float v = 0.f;
-    if (row0 + tok < row_end && h0 + hh < H) v = dt[(row0 + tok) * H + h0 + hh];
+    if (row0 + tok < row_end && h0 + hh < H) v = dt_apply(dt[(row0 + tok) * H + h0 + hh], h0 + hh, dtx);
     tile[tok][hh] = v;
   }
   __syncthreads();
@@ -381,7 +383,8 @@ __global__ __launch_bounds__(kThreads) void block_prep_kernel(const uint16_t *__
                                                               const float *__restrict__ A,
                                                               float *__restrict__ prep, int T, int H, int G,
                                                               int NB, int n_scores, const VarPlan vp,
-                                                              const NSlice ns, uint16_t *__restrict__ Cpad) {
+                                                              const NSlice ns, uint16_t *__restrict__ Cpad,
+                                                              const DtXform dtx) {
   __shared__ __align__(16) uint16_t sB[kBlk * (kN + 2)];
   __shared__ float tile[kBlk + kBlk / 2][kCumHeads + 1];
   const int wg = blockIdx.x;
@@ -410,7 +413,7 @@ __global__ __launch_bounds__(kThreads) void block_prep_kernel(const uint16_t *__
       row_end = static_cast<size_t>(b) * T + T;
     }
     block_cumsum_block(tile, row0, row_end, ((i / NB) % hgroups) * kCumHeads, NB,
-                       static_cast<size_t>(b) * H * NB + jb, dt, A, prep, H);
+                       static_cast<size_t>(b) * H * NB + jb, dt, A, prep, H, dtx);
   }
 }
 
@@ -1303,7 +1306,7 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   const int n_cumsum = w.NB * ((d.H + kCumHeads - 1) / kCumHeads) * rows;
   hipLaunchKernelGGL(block_prep_kernel, dim3(n_scores + n_cumsum), dim3(kThreads), 0, stream,
                      static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(C), Gd, Btr, dt, A, prep,
-                     d.T, d.H, d.G, w.NB, n_scores, vp, ns, Cpad);
+                     d.T, d.H, d.G, w.NB, n_scores, vp, ns, Cpad, d.dtx);
   trace_mark(trace, stream, "block_prep");
 
   ScanParams p;

@@ -20,7 +20,7 @@ SSD_OK = 0
 
 EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
            "ssd_decode_steps_layers", "ssd_prefill_varlen_workspace_bytes", "ssd_prefill_varlen",
-           "ssd_conv1d_prefill", "ssd_conv1d_step",
+           "ssd_conv1d_prefill", "ssd_conv1d_step", "ssd_prefill_dt",
            "ssd_prefill_path", "ssd_status_string", "ssd_version"]
 
 
@@ -46,6 +46,13 @@ _lib.ssd_prefill_workspace_bytes.restype = _sz
 _lib.ssd_prefill_workspace_bytes.argtypes = [_sp]
 _lib.ssd_prefill.restype = ctypes.c_int
 _lib.ssd_prefill.argtypes = [_sp] + [_vp] * 10 + [_sz, _vp]
+class ssd_dt_transform(ctypes.Structure):
+    _fields_ = [("dt_bias", ctypes.c_void_p), ("dt_softplus", ctypes.c_int32), ("dt_min", ctypes.c_float),
+                ("dt_max", ctypes.c_float)]
+
+
+_lib.ssd_prefill_dt.restype = ctypes.c_int
+_lib.ssd_prefill_dt.argtypes = [_sp, ctypes.POINTER(ssd_dt_transform)] + [_vp] * 10 + [_sz, _vp]
 _lib.ssd_prefill_profile.restype = ctypes.c_int
 _lib.ssd_prefill_profile.argtypes = [_sp] + [_vp] * 10 + [_sz, _vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_float),
                                      ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_int32)]
@@ -112,13 +119,17 @@ def _stream_ptr():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, workspace=None, profile=None):
+def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, workspace=None, profile=None,
+                dt_bias=None, dt_softplus=False, dt_limit=None):
     """``ssd_prefill`` of the C ABI on torch device tensors.  Returns ``(y, final_state)``.
 
     ``x (Bt,T,H,P)``, ``B, C (Bt,T,G,N)`` in fp32 or bf16; ``dt (Bt,T,H)``, ``A, D (H)``,
     ``h0 (Bt,H,P,N)`` fp32.  Output and workspace tensors are allocated with torch unless given.
     With ``profile`` a list, the call goes through ``ssd_prefill_profile`` (it waits for the
     device) and ``(kernel name, milliseconds)`` pairs are appended to the list.
+    With ``dt_bias (H)``, ``dt_softplus`` or ``dt_limit=(lo, hi)`` the call goes through
+    ``ssd_prefill_dt``: ``dt`` is then the raw value and the kernels apply
+    ``clamp(softplus(dt + dt_bias), lo, hi)`` as they read it.
     """
     Bt, T, H, P = x.shape
     G, N = B.shape[2], B.shape[3]
@@ -142,7 +153,16 @@ def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, wor
     _check_dev(x, dt, A, B, C, D, h0, y, final_state, workspace)
     args = (ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(h0), _ptr(y),
             _ptr(final_state), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_ptr())
-    if profile is None:
+    if dt_bias is not None or dt_softplus or dt_limit is not None:
+        if profile is not None:
+            raise ValueError("profile and a dt transform cannot be combined")
+        if dt_bias is not None and (dt_bias.dtype != torch.float32 or tuple(dt_bias.shape) != (H,)):
+            raise ValueError("dt_bias must be fp32 of shape (H,)")
+        _check_dev(dt_bias)
+        lo, hi = dt_limit if dt_limit is not None else (0.0, 0.0)
+        xf = ssd_dt_transform(None if dt_bias is None else dt_bias.data_ptr(), int(bool(dt_softplus)), lo, hi)
+        st = _lib.ssd_prefill_dt(args[0], ctypes.byref(xf), *args[1:])
+    elif profile is None:
         st = _lib.ssd_prefill(*args)
     else:
         ms = (ctypes.c_float * 8)()

@@ -127,6 +127,21 @@ def test_varlen_rejects_before_any_hip_call(ssd):
         assert lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(shape(ssd, **dict(ok, **bad)))) == 0
 
 
+def test_prefill_dt_rejects_before_any_hip_call(ssd):
+    lib = ssd.raw()
+    fake = ctypes.c_void_p(4096)
+    s = shape(ssd)
+    need = lib.ssd_prefill_workspace_bytes(ctypes.byref(s))
+
+    def call(xf, x=fake):
+        return lib.ssd_prefill_dt(ctypes.byref(s), ctypes.byref(xf) if xf is not None else None, x, fake, fake, fake,
+                                  fake, fake, None, fake, fake, fake, ctypes.c_size_t(need), None)
+
+    assert call(None) == -1
+    assert call(ssd.ssd_dt_transform(None, 1, 0.1, 0.01)) == -2     # dt_min > dt_max
+    assert call(ssd.ssd_dt_transform(None, 1, 0.0, 0.0), x=None) == -1
+
+
 def test_conv_rejects_before_any_hip_call(ssd):
     lib = ssd.raw()
     fake = ctypes.c_void_p(4096)

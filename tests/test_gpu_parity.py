@@ -440,3 +440,35 @@ def test_varlen_leaves_unowned_tokens_alone_and_rejects_bad_boundaries(ssd):
                                torch.tensor(bad, dtype=torch.int32).cuda(), L, y=y2, final_state=st2)
         torch.cuda.synchronize()
         assert (y2 == 7.0).all() and (st2 == 5.0).all(), bad
+
+
+# ---- step-size activation fused into the prefill ---------------------------------------------
+@pytest.mark.parametrize("case", [
+    # Bt, T, H, P, N, G, L, io, bias, softplus, limit
+    (2, 300, 8, 64, 128, 1, 128, "bf16", True, True, (1e-3, 1e-1)),     # MFMA family: fused in the block preparation
+    (1, 1000, 4, 64, 128, 1, 256, "bf16", True, True, None),
+    (1, 200, 4, 64, 128, 1, 64, "bf16", False, False, (2e-3, 5e-2)),    # clamp only
+    (2, 100, 4, 32, 16, 2, 32, "f32", True, True, (1e-3, 1e-1)),        # generic family
+    (1, 65, 2, 16, 8, 1, 64, "bf16", True, False, None),                # bias only
+], ids=lambda c: "x".join(str(v) for v in c))
+def test_prefill_with_fused_dt_transform(ssd, case, monkeypatch):
+    Bt, T, H, P, N, G, L, io, with_bias, softplus, limit = case
+    cfg = cfg_of(Bt, T, H, P, N, G, L, io)
+    inp = inputs.make_prefill_inputs(cfg, seed=71)
+    g = torch.Generator().manual_seed(72)
+    # raw values: what a projection would emit before the activation
+    raw = 0.5 * torch.randn((Bt, T, H), generator=g) + (inputs.DT_BIAS if softplus else 0.02)
+    bias = 0.3 * torch.randn((H,), generator=g) if with_bias else None
+    if not softplus and limit is None:
+        raw = raw.abs() * 0.05 + 0.02     # stay positive without an activation
+        bias = bias.abs() * 0.01 if bias is not None else None
+    print("dt transform case", case, flush=True)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    y, st = ssd.ssd_prefill(dev["x"], raw.cuda(), dev["A"], dev["B"], dev["C"], dev["D"], L,
+                            dt_bias=None if bias is None else bias.cuda(), dt_softplus=softplus, dt_limit=limit)
+    torch.cuda.synchronize()
+    dt_ref = ssd_oracle.dt_transform(raw, bias, softplus, limit)
+    assert dt_ref.min() > 0
+    y_ref, st_ref = ssd_oracle.prefill(inp["x"], dt_ref, inp["A"], inp["B"], inp["C"], inp["D"])
+    assert_close(y, y_ref, TOL[io], "fused dt: y")
+    assert_close(st, st_ref, TOL[io], "fused dt: state")

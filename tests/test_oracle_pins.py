@@ -310,6 +310,20 @@ def test_conv_split_prompt_and_steps_agree_with_one_prefill():
     np.testing.assert_allclose(zz[:, k - 1:], z, rtol=1e-13, atol=1e-13)
 
 
+def test_dt_transform_values():
+    import torch
+    z = np.array([[-30.0, -1.0, 0.0, 1.0, 30.0, 800.0]])
+    out = ssd_oracle.dt_transform(z, softplus=True)
+    assert out[0, 2] == np.log(2.0) and out[0, 5] == 800.0
+    np.testing.assert_allclose(out[0, 0], np.exp(-30.0), rtol=1e-12)       # log1p(e^v) ~ e^v far below zero
+    np.testing.assert_allclose(out, torch.nn.functional.softplus(torch.from_numpy(z)).numpy(), rtol=1e-12)
+    b = np.array([0.5, -0.5, 0.0, 1.0, 2.0, 3.0])
+    np.testing.assert_array_equal(ssd_oracle.dt_transform(z, bias=b), z + b)
+    np.testing.assert_array_equal(ssd_oracle.dt_transform(z, limit=(-1.0, 2.0)), np.clip(z, -1.0, 2.0))
+    full = ssd_oracle.dt_transform(z, bias=b, softplus=True, limit=(1e-3, 1e-1))
+    assert full.min() >= 1e-3 and full.max() <= 1e-1
+
+
 def test_bf16_decay_would_be_visible():
     """The paper's decay-precision ablation: rounding exp(dt*A) to bf16 shows up far above the
     fp32 tolerance (1e-4), so a parity test at that tolerance can tell the two apart."""
