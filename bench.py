@@ -109,6 +109,7 @@ def main():
                     help="steps per HIP graph and per multi-step launch in the decode comparison")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the decode step")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the MFMA / streaming peak probes")
     ap.add_argument("--no-varlen", action="store_true")
     ap.add_argument("--no-conv", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -191,6 +192,22 @@ def main():
         del src, dst
         torch.cuda.empty_cache()
 
+    # ---- measured machine peaks (the library's own probe kernels), for scale -------------------
+    peaks = {}
+    if not args.no_peaks:
+        pa = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
+        pb = torch.empty_like(pa)
+        for kind in ("copy", "read", "write"):
+            rate, ms = ssd.peak_probe(kind, pa, pb, reps=10)
+            peaks["stream_%s_gbs" % kind] = round(rate / 1e9, 1)
+        for label, iters in (("short", 300), ("long", 4000)):
+            rate, ms = ssd.peak_probe("mfma", pa, None, iters=iters, reps=3)
+            peaks["mfma_bf16_tflops_%s" % label] = round(rate / 1e12, 1)
+            peaks["mfma_%s_ms" % label] = round(ms, 3)
+        log("[bench] measured peaks: %s" % peaks)
+        del pa, pb
+        torch.cuda.empty_cache()
+
     # ---- headline: the timed step --------------------------------------------------------
     cfg = inputs.CONFIGS[args.workload]
     log("[bench] workload %s, path %s" % (cfg.name, ssd.prefill_path(shape_of(cfg))))
@@ -211,6 +228,9 @@ def main():
     roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 3), peak=peak, unit="TFLOP/s",
                     frac=round(achieved / peak, 5), traffic=HBM_TRAFFIC_BYTES.get((cfg.name, dom)),
                     kernel_ms=round(kern[dom], 5), flops_per_launch=dom_flops)
+    if peaks.get("mfma_bf16_tflops_long") and bound == "mfma":
+        roofline["peak_measured"] = peaks["mfma_bf16_tflops_long"]
+        roofline["frac_of_measured"] = round(achieved / peaks["mfma_bf16_tflops_long"], 5)
 
     # ---- the other prefill configurations (reported, not the headline) -------------------------
     extra = {}
@@ -530,7 +550,7 @@ def main():
                    "headdim": cfg.headdim, "dstate": cfg.dstate, "ngroups": cfg.ngroups, "chunk": cfg.chunk,
                    "step": "ssd_prefill + one ssd_decode_step", "flop_count": "algorithmic, causal-only"},
         "prefill": head, "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "other_configs": extra,
-        "varlen": varlen, "sweeps": sweeps, "conv": conv,
+        "varlen": varlen, "sweeps": sweeps, "conv": conv, "measured_peaks": peaks,
     }
     print(json.dumps(out))
 

@@ -270,6 +270,24 @@ SSD_API ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, co
                                const char **kernel_names, int32_t *num_kernels);
 
 /*
+ * Measurement aid: machine peaks as this library's own kernels reach them, to
+ * set the figures of the SSD kernels against.  Like ssd_prefill_profile it
+ * creates HIP events and WAITS.
+ *   kind 0   MFMA issue loop: 2048 workgroups of 4 waves, each wave `iters`
+ *            times eight v_mfma_f32_32x32x16_bf16; `a` = device scratch of at
+ *            least 2048*256 floats (`bytes` its size), `b` unused
+ *   kind 1   streaming copy of `bytes` bytes from `a` to `b` (16 bytes per lane)
+ *   kind 2   streaming read of `a` (b: 16 bytes of scratch)
+ *   kind 3   streaming write of `b` (a: any valid device pointer)
+ * One warm-up launch, then `reps` launches back to back; *ms (HOST) = their
+ * total time in milliseconds, *work (HOST) = flops (kind 0) or bytes moved
+ * (read + written) of ONE launch.
+ * Errors: SSD_ERR_NULL, _SHAPE, _ALIGN, _HIP.
+ */
+SSD_API ssd_status ssd_peak_probe(int32_t kind, int32_t iters, int32_t reps, void *a, void *b,
+                          size_t bytes, float *ms, double *work, void *hip_stream);
+
+/*
  * Name of the kernel family ssd_prefill would use for this shape:
  * "mfma_bf16" (MFMA contractions over LDS-staged tiles), "generic_f32"
  * (plain fp32 kernels, any shape), or "invalid".  Host-only.  The environment

@@ -269,6 +269,17 @@ ssd_status ssd_conv1d_step(int32_t batch, int32_t ksize, int32_t io_dtype, const
   return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
 }
 
+ssd_status ssd_peak_probe(int32_t kind, int32_t iters, int32_t reps, void *a, void *b, size_t bytes, float *ms,
+                          double *work, void *hip_stream) {
+  if (!ms || !work || !a) return SSD_ERR_NULL;
+  if (kind < 0 || kind > 3 || reps < 1 || reps > 100000) return SSD_ERR_SHAPE;
+  if (kind == 0 && (iters < 1 || bytes < static_cast<size_t>(2048) * 256 * sizeof(float))) return SSD_ERR_SHAPE;
+  if (kind != 0 && (!b || bytes < 16)) return kind != 0 && !b ? SSD_ERR_NULL : SSD_ERR_SHAPE;
+  if (!aligned16(a) || (b && !aligned16(b))) return SSD_ERR_ALIGN;
+  const hipError_t e = ssd::run_peak_probe(kind, iters, reps, a, b, bytes, ms, work, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
+}
+
 const char *ssd_status_string(ssd_status status) {
   switch (status) {
     case SSD_OK: return "ok";

@@ -118,6 +118,9 @@ hipError_t launch_conv_prefill(int Bt, int T, int ksize, bool bf16, const void *
 hipError_t launch_conv_step(int Bt, int ksize, bool bf16, void *state, const void *u, const float *w, const float *bias,
                             void *const z[3], const int width[3], int act, hipStream_t stream);
 
+hipError_t run_peak_probe(int kind, int iters, int reps, void *a, void *b, size_t bytes, float *ms, double *work,
+                          hipStream_t stream);
+
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace ssd

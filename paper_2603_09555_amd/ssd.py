@@ -20,7 +20,7 @@ SSD_OK = 0
 
 EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
            "ssd_decode_steps_layers", "ssd_prefill_varlen_workspace_bytes", "ssd_prefill_varlen",
-           "ssd_conv1d_prefill", "ssd_conv1d_step", "ssd_prefill_dt",
+           "ssd_conv1d_prefill", "ssd_conv1d_step", "ssd_prefill_dt", "ssd_peak_probe",
            "ssd_prefill_path", "ssd_status_string", "ssd_version"]
 
 
@@ -53,6 +53,9 @@ class ssd_dt_transform(ctypes.Structure):
 
 _lib.ssd_prefill_dt.restype = ctypes.c_int
 _lib.ssd_prefill_dt.argtypes = [_sp, ctypes.POINTER(ssd_dt_transform)] + [_vp] * 10 + [_sz, _vp]
+_lib.ssd_peak_probe.restype = ctypes.c_int
+_lib.ssd_peak_probe.argtypes = [ctypes.c_int32] * 3 + [_vp, _vp, _sz, ctypes.POINTER(ctypes.c_float),
+                                ctypes.POINTER(ctypes.c_double), _vp]
 _lib.ssd_prefill_profile.restype = ctypes.c_int
 _lib.ssd_prefill_profile.argtypes = [_sp] + [_vp] * 10 + [_sz, _vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_float),
                                      ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_int32)]
@@ -313,3 +316,18 @@ def ssd_conv1d_step(conv_state, u, weight, bias=None, split=None, activation="si
     if st != SSD_OK:
         raise SSDError(st, "ssd_conv1d_step")
     return [o for o in outs if o is not None]
+
+
+def peak_probe(kind, a, b=None, iters=0, reps=1):
+    """``ssd_peak_probe``: returns ``(work per second, milliseconds per launch)`` -- flop/s for
+    ``kind="mfma"``, bytes/s for ``"copy"``, ``"read"``, ``"write"``.  ``a``, ``b``: device tensors."""
+    k = {"mfma": 0, "copy": 1, "read": 2, "write": 3}[kind]
+    ms, work = ctypes.c_float(0), ctypes.c_double(0)
+    nbytes = a.numel() * a.element_size() if k in (0, 1, 2) else b.numel() * b.element_size()
+    _check_dev(a, b)
+    st = _lib.ssd_peak_probe(k, iters, reps, _ptr(a), _ptr(b), nbytes, ctypes.byref(ms), ctypes.byref(work),
+                             _stream_ptr())
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_peak_probe")
+    per = ms.value / reps
+    return work.value / (per * 1e-3), per
