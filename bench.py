@@ -228,6 +228,13 @@ def main():
     roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 3), peak=peak, unit="TFLOP/s",
                     frac=round(achieved / peak, 5), traffic=HBM_TRAFFIC_BYTES.get((cfg.name, dom)),
                     kernel_ms=round(kern[dom], 5), flops_per_launch=dom_flops)
+    if bound == "mfma" and dom == "chunk_scan":
+        # what the kernel actually issues: 38 v_mfma_f32_32x32x16_bf16 per wave and 64-token block, two waves
+        # per 64-column head slice (confirmed by SQ_INSTS_MFMA, profiles/prefill_c3_sq_counters.txt)
+        nblk = (cfg.seqlen + 63) // 64
+        waves = cfg.batch * cfg.nheads * (cfg.headdim // 64) * 2 * ((cfg.dstate + 127) // 128)
+        roofline["executed_mfma_flops_per_launch"] = 38 * 32768 * nblk * waves
+        roofline["executed_tflops"] = round(38 * 32768 * nblk * waves / kern[dom] / 1e9, 1)
     if peaks.get("mfma_bf16_tflops_long") and bound == "mfma":
         roofline["peak_measured"] = peaks["mfma_bf16_tflops_long"]
         roofline["frac_of_measured"] = round(achieved / peaks["mfma_bf16_tflops_long"], 5)
