@@ -150,10 +150,12 @@ SSD_API ssd_status ssd_prefill_dt(const ssd_shape *shape, const ssd_dt_transform
  *   h0 (nullable), final_state   (nseq, nheads, headdim, dstate) fp32
  *   workspace         at least ssd_prefill_varlen_workspace_bytes() bytes, 256-byte aligned
  * Tokens outside every sequence are left untouched in y.
- * Implemented for the MFMA kernel family (bf16 io, headdim a multiple of 64,
- * dstate a multiple of 8 up to 128, chunk a multiple of 64, heads per group x
- * headdim / 64 a multiple of 4); any other shape
- * returns SSD_ERR_UNSUPPORTED and ssd_prefill_varlen_workspace_bytes returns 0.
+ * Shapes of the MFMA kernel family (bf16 io, headdim a multiple of 64, dstate a
+ * multiple of 8 up to 128, chunk a multiple of 64, heads per group x headdim /
+ * 64 a multiple of 4) run on it; every other shape and fp32 io run on the
+ * generic fp32 kernels, which need batch x nheads <= 65535 and
+ * ceil(seqlen / chunk) + batch <= 65535 (else SSD_ERR_UNSUPPORTED, and
+ * ssd_prefill_varlen_workspace_bytes returns 0).
  * Errors: SSD_ERR_NULL, _SHAPE, _DTYPE, _ALIGN, _UNSUPPORTED, _WORKSPACE, _HIP.
  */
 SSD_API size_t ssd_prefill_varlen_workspace_bytes(const ssd_shape *shape);

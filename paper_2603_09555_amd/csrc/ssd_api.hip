@@ -147,10 +147,21 @@ ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, const floa
   return st;
 }
 
+namespace {
+// The generic kernels take a packed batch while (sequences x heads) and the chunk capacity fit a grid axis.
+bool generic_varlen_ok(const Dims &d) {
+  const long long cap = (static_cast<long long>(d.T) + d.L - 1) / d.L + d.Bt;
+  return static_cast<long long>(d.Bt) * d.H <= 65535 && cap <= 65535;
+}
+bool use_mfma_varlen(const Dims &d) { return !force_generic() && ssd::mfma_varlen_supported(d); }
+}  // namespace
+
 size_t ssd_prefill_varlen_workspace_bytes(const ssd_shape *shape) {
   Dims d;
-  if (make_dims(shape, false, &d, true) != SSD_OK || force_generic() || !ssd::mfma_varlen_supported(d)) return 0;
-  return ssd::mfma_varlen_workspace_bytes(d);
+  if (make_dims(shape, false, &d, true) != SSD_OK) return 0;
+  const size_t m = ssd::mfma_varlen_supported(d) ? ssd::mfma_varlen_workspace_bytes(d) : 0;
+  const size_t g = generic_varlen_ok(d) ? ssd::generic_varlen_workspace_bytes(d) : 0;
+  return g > m ? g : m;  // large enough for either family (0: neither takes this shape)
 }
 
 ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_seqlens, const void *x, const float *dt,
@@ -164,12 +175,16 @@ ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_seqlens,
   if (!aligned16(x) || !aligned16(dt) || !aligned16(B) || !aligned16(C) || !aligned16(y) ||
       !aligned16(final_state) || (h0 && !aligned16(h0)) || (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u))
     return SSD_ERR_ALIGN;
-  if (force_generic() || !ssd::mfma_varlen_supported(d)) return SSD_ERR_UNSUPPORTED;
-  const size_t need = ssd::mfma_varlen_workspace_bytes(d);
+  const bool mfma = use_mfma_varlen(d);
+  if (!mfma && !generic_varlen_ok(d)) return SSD_ERR_UNSUPPORTED;
+  const size_t need = ssd_prefill_varlen_workspace_bytes(shape);
   if (!workspace || workspace_bytes_given < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
     return SSD_ERR_WORKSPACE;
-  const hipError_t e = ssd::launch_prefill_mfma_varlen(d, cu_seqlens, x, dt, A, B, C, D, h0, y, final_state,
-                                                       workspace, static_cast<hipStream_t>(hip_stream));
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e =
+      mfma ? ssd::launch_prefill_mfma_varlen(d, cu_seqlens, x, dt, A, B, C, D, h0, y, final_state, workspace, stream)
+           : ssd::launch_prefill_generic_varlen(d, cu_seqlens, x, dt, A, B, C, D, h0, y, final_state, workspace,
+                                                stream);
   return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
 }
 

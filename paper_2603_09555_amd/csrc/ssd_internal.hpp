@@ -103,6 +103,20 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
                                void *y, float *final_state, void *workspace, hipStream_t stream,
                                KernelTrace *trace = nullptr);
 
+// Device-side tables of a packed variable-length batch (all int32; see ssd_prefill_mfma.hip, "tables of a
+// variable-length call").  tok0 == nullptr: plain batch.
+struct VarPlan {
+  const int32_t *tok0, *len, *blk0, *item0, *slot0, *blk_seq, *item_seq;
+  int nseq, nb_cap, slot_cap;
+};
+void launch_varlen_tables(const int32_t *cu, int total, int blk_len, int seg_blocks, int item_cap, const VarPlan &vp,
+                          hipStream_t stream);
+size_t generic_varlen_workspace_bytes(const Dims &d);
+hipError_t launch_prefill_generic_varlen(const Dims &d, const int32_t *cu_seqlens, const void *x, const float *dt,
+                                         const float *A, const void *B, const void *C, const float *D,
+                                         const float *h0, void *y, float *final_state, void *workspace,
+                                         hipStream_t stream);
+
 // Packed variable-length batch (d.Bt sequences, d.T tokens in total, cu_seqlens on the device).
 bool mfma_varlen_supported(const Dims &d);
 size_t mfma_varlen_workspace_bytes(const Dims &d);

@@ -16,24 +16,60 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// Where a chunk lives.  Plain batch: grid coordinates (chunk c of Nc, bh = b * H + h).  Packed
+// variable-length batch (vp.tok0 != nullptr): the first coordinate counts chunks over the whole batch
+// (every sequence has whole chunks of its own, the last one short), the second is the head; workspace
+// arrays are then indexed (h, batch-wide chunk number) with vp.nb_cap chunks per head.
+struct ChunkView {
+  bool ok;        // false: the grid position is beyond the last chunk
+  int h, len;     // head; tokens in the chunk
+  size_t tok;     // first token (row of the (tokens, ...) arrays)
+  size_t idx;     // index of the chunk in cs / states
+};
+__device__ __forceinline__ ChunkView chunk_view(int c, int bh, int T, int H, int L, int Nc, const VarPlan &vp) {
+  ChunkView v;
+  if (vp.tok0 == nullptr) {
+    const int b = bh / H;
+    v.ok = true;
+    v.h = bh % H;
+    v.len = min(L, T - c * L);
+    v.tok = static_cast<size_t>(b) * T + static_cast<size_t>(c) * L;
+    v.idx = static_cast<size_t>(bh) * Nc + c;
+    return v;
+  }
+  v.ok = c < vp.blk0[vp.nseq];
+  v.h = bh;
+  v.len = 0;
+  v.tok = 0;
+  v.idx = 0;
+  if (v.ok) {
+    const int q = vp.blk_seq[c];
+    const int cq = c - vp.blk0[q];
+    v.len = min(L, vp.len[q] - cq * L);
+    v.tok = static_cast<size_t>(vp.tok0[q]) + static_cast<size_t>(cq) * L;
+    v.idx = static_cast<size_t>(bh) * vp.nb_cap + c;
+  }
+  return v;
+}
+
 // ---- 1. per-chunk inclusive prefix sum of dt*A ------------------------------------------------
 // grid (Nc, Bt*H), one wave per chunk.  cs layout: (Bt, H, Nc, L).
 __global__ __launch_bounds__(64) void chunk_cumsum_kernel(const float *__restrict__ dt,
                                                           const float *__restrict__ A,
                                                           float *__restrict__ cs, int T, int H, int L,
-                                                          int Nc) {
-  const int c = blockIdx.x;
-  const int bh = blockIdx.y;
-  const int b = bh / H, h = bh % H;
+                                                          int Nc, const VarPlan vp) {
+  const ChunkView cv = chunk_view(blockIdx.x, blockIdx.y, T, H, L, Nc, vp);
+  if (!cv.ok) return;
+  const int h = cv.h;
   const int lane = threadIdx.x;
   const float Ah = A[h];
-  const int len = min(L, T - c * L);
+  const int len = cv.len;
   float carry = 0.f;
-  float *out = cs + (static_cast<size_t>(bh) * Nc + c) * L;
+  float *out = cs + cv.idx * L;
   for (int base = 0; base < len; base += 64) {
     const int l = base + lane;
     float v = 0.f;
-    if (l < len) v = dt[(static_cast<size_t>(b) * T + c * L + l) * H + h] * Ah;
+    if (l < len) v = dt[(cv.tok + l) * H + h] * Ah;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
       const float up = __shfl_up(v, off, 64);
@@ -52,17 +88,17 @@ template <typename Io>
 __global__ __launch_bounds__(kThreads) void chunk_states_kernel(
     const void *__restrict__ x, const float *__restrict__ dt, const void *__restrict__ B,
     const float *__restrict__ cs, float *__restrict__ states, int T, int H, int P, int N, int G,
-    int hpg, int L, int Nc) {
+    int hpg, int L, int Nc, const VarPlan vp) {
   __shared__ float Xs[32][64 + 1];
   __shared__ float Bs[32][64 + 1];
   const int ntn = (N + 63) / 64;
   const int p_base = (blockIdx.x / ntn) * 64;
   const int n_base = (blockIdx.x % ntn) * 64;
-  const int c = blockIdx.y;
-  const int bh = blockIdx.z;
-  const int b = bh / H, h = bh % H, g = h / hpg;
-  const int len = min(L, T - c * L);
-  const float *csc = cs + (static_cast<size_t>(bh) * Nc + c) * L;
+  const ChunkView cv = chunk_view(blockIdx.y, blockIdx.z, T, H, L, Nc, vp);
+  if (!cv.ok) return;  // uniform over the workgroup
+  const int h = cv.h, g = h / hpg;
+  const int len = cv.len;
+  const float *csc = cs + cv.idx * L;
   const float cs_end = csc[len - 1];
   const int tp = threadIdx.x / 16, tn = threadIdx.x % 16;
   float acc[4][4] = {};
@@ -71,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void chunk_states_kernel(
       const int s = s0 + i / 64, col = i % 64;
       float xv = 0.f, bv = 0.f;
       if (s < len) {
-        const size_t t = static_cast<size_t>(b) * T + c * L + s;
+        const size_t t = cv.tok + s;
         if (p_base + col < P) {
           const float w = expf(cs_end - csc[s]) * dt[t * H + h];
           xv = w * Io::load(x, (t * H + h) * P + p_base + col);
@@ -97,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void chunk_states_kernel(
     }
     __syncthreads();
   }
-  float *out = states + (static_cast<size_t>(bh) * Nc + c) * P * N;
+  float *out = states + cv.idx * P * N;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -113,16 +149,26 @@ __global__ __launch_bounds__(kThreads) void chunk_states_kernel(
 __global__ __launch_bounds__(kThreads) void state_pass_kernel(float *__restrict__ states,
                                                               const float *__restrict__ cs,
                                                               const float *__restrict__ h0,
-                                                              float *__restrict__ final_state, int T,
-                                                              int PN, int L, int Nc) {
+                                                              float *__restrict__ final_state, int T, int H,
+                                                              int PN, int L, int Nc, const VarPlan vp) {
   const int e = blockIdx.x * kThreads + threadIdx.x;
-  const int bh = blockIdx.y;
+  const int bh = blockIdx.y;  // (sequence, head)
   if (e >= PN) return;
+  // chunks of this sequence: count, length of the sequence, index of its first chunk in cs / states
+  int nc = Nc, seq_len = T;
+  size_t first = static_cast<size_t>(bh) * Nc;
+  if (vp.tok0 != nullptr) {
+    const int q = bh / H, h = bh % H;
+    nc = vp.blk0[q + 1] - vp.blk0[q];
+    seq_len = vp.len[q];
+    first = static_cast<size_t>(h) * vp.nb_cap + vp.blk0[q];
+    if (vp.item0[vp.nseq] == 0) return;  // rejected boundaries: empty tables, nothing is written
+  }
   float run = h0 ? h0[static_cast<size_t>(bh) * PN + e] : 0.f;
-  for (int c = 0; c < Nc; ++c) {
-    const int len = min(L, T - c * L);
-    const float decay = expf(cs[(static_cast<size_t>(bh) * Nc + c) * L + len - 1]);
-    float *sp = states + (static_cast<size_t>(bh) * Nc + c) * PN + e;
+  for (int c = 0; c < nc; ++c) {
+    const int len = min(L, seq_len - c * L);
+    const float decay = expf(cs[(first + c) * L + len - 1]);
+    float *sp = states + (first + c) * PN + e;
     const float s = *sp;
     *sp = run;
     run = decay * run + s;
@@ -138,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void chunk_output_kernel(
     const void *__restrict__ x, const float *__restrict__ dt, const void *__restrict__ B,
     const void *__restrict__ C, const float *__restrict__ D, const float *__restrict__ cs,
     const float *__restrict__ states, void *__restrict__ y, int T, int H, int P, int N, int G, int hpg,
-    int L, int Nc) {
+    int L, int Nc, const VarPlan vp) {
   __shared__ float Cs[32][32 + 1];   // C[l][n] tile
   __shared__ float Ts[64][32 + 1];   // H_c[p][n] tile, or B[s][n] tile (first 32 rows)
   __shared__ float Ms[32][32 + 1];   // masked, decayed scores M[l][s]
@@ -148,20 +194,20 @@ __global__ __launch_bounds__(kThreads) void chunk_output_kernel(
   const int ntp = (P + 63) / 64;
   const int l_base = (blockIdx.x / ntp) * 32;
   const int p_base = (blockIdx.x % ntp) * 64;
-  const int c = blockIdx.y;
-  const int bh = blockIdx.z;
-  const int b = bh / H, h = bh % H, g = h / hpg;
-  const int len = min(L, T - c * L);
+  const ChunkView cv = chunk_view(blockIdx.y, blockIdx.z, T, H, L, Nc, vp);
+  if (!cv.ok) return;  // uniform over the workgroup
+  const int h = cv.h, g = h / hpg;
+  const int len = cv.len;
   if (l_base >= len) return;
-  const float *csc = cs + (static_cast<size_t>(bh) * Nc + c) * L;
-  const size_t t0 = static_cast<size_t>(b) * T + static_cast<size_t>(c) * L;
+  const float *csc = cs + cv.idx * L;
+  const size_t t0 = cv.tok;
   const int tl = threadIdx.x / 16, tp = threadIdx.x % 16;  // rows tl, tl+16; cols tp+16j
 
   if (threadIdx.x < 32) cs_l[threadIdx.x] = (l_base + threadIdx.x < len) ? csc[l_base + threadIdx.x] : 0.f;
 
   // ---- state -> output: acc = C[l,:] . H_c[p,:], then scaled by exp(cs_l) ----
   float acc[2][4] = {};
-  const float *Hc = states + (static_cast<size_t>(bh) * Nc + c) * P * N;
+  const float *Hc = states + cv.idx * P * N;
   for (int n0 = 0; n0 < N; n0 += 32) {
     for (int i = threadIdx.x; i < 32 * 32; i += kThreads) {
       const int r = i / 32, n = n0 + i % 32;
@@ -284,59 +330,100 @@ Dims clamp_chunk(Dims d) {
   return d;
 }
 
+// rows: independent (sequence, head) pairs of the state pass; chunks: first grid coordinate of the
+// per-chunk kernels (chunks per batch row, or the chunk capacity of a packed batch); heads_dim: their
+// second coordinate (Bt * H, or H for a packed batch).
 template <typename Io>
-hipError_t launch_typed(const Dims &d, const void *x, const float *dt, const float *A, const void *B,
+hipError_t launch_typed(const Dims &d, const VarPlan &vp, const void *x, const float *dt, const float *A, const void *B,
                         const void *C, const float *D, const float *h0, void *y, float *final_state,
-                        void *workspace, hipStream_t stream, KernelTrace *trace) {
-  const size_t BH = static_cast<size_t>(d.Bt) * d.H;
-  float *cs = static_cast<float *>(workspace);
-  float *states = cs + round_up(BH * d.Nc * d.L, 64);
+                        float *cs, float *states, hipStream_t stream, KernelTrace *trace) {
+  const bool varlen = vp.tok0 != nullptr;
+  const unsigned rows = static_cast<unsigned>(d.Bt) * d.H;
+  const unsigned chunks = varlen ? vp.nb_cap : d.Nc;
+  const unsigned heads_dim = varlen ? d.H : rows;
   const int PN = d.P * d.N;
 
-  hipLaunchKernelGGL(chunk_cumsum_kernel, dim3(d.Nc, BH), dim3(64), 0, stream, dt, A, cs, d.T, d.H, d.L,
-                     d.Nc);
+  hipLaunchKernelGGL(chunk_cumsum_kernel, dim3(chunks, heads_dim), dim3(64), 0, stream, dt, A, cs, d.T, d.H, d.L,
+                     d.Nc, vp);
   trace_mark(trace, stream, "chunk_cumsum");
   const unsigned tiles_pn = ((d.P + 63) / 64) * ((d.N + 63) / 64);
-  hipLaunchKernelGGL((chunk_states_kernel<Io>), dim3(tiles_pn, d.Nc, BH), dim3(kThreads), 0, stream, x, dt,
-                     B, cs, states, d.T, d.H, d.P, d.N, d.G, d.hpg, d.L, d.Nc);
+  hipLaunchKernelGGL((chunk_states_kernel<Io>), dim3(tiles_pn, chunks, heads_dim), dim3(kThreads), 0, stream, x, dt,
+                     B, cs, states, d.T, d.H, d.P, d.N, d.G, d.hpg, d.L, d.Nc, vp);
   trace_mark(trace, stream, "chunk_states");
-  hipLaunchKernelGGL(state_pass_kernel, dim3((PN + kThreads - 1) / kThreads, BH), dim3(kThreads), 0, stream,
-                     states, cs, h0, final_state, d.T, PN, d.L, d.Nc);
+  hipLaunchKernelGGL(state_pass_kernel, dim3((PN + kThreads - 1) / kThreads, rows), dim3(kThreads), 0, stream,
+                     states, cs, h0, final_state, d.T, d.H, PN, d.L, d.Nc, vp);
   trace_mark(trace, stream, "state_pass");
   const unsigned tiles_lp = ((d.L + 31) / 32) * ((d.P + 63) / 64);
-  hipLaunchKernelGGL((chunk_output_kernel<Io>), dim3(tiles_lp, d.Nc, BH), dim3(kThreads), 0, stream, x, dt,
-                     B, C, D, cs, states, y, d.T, d.H, d.P, d.N, d.G, d.hpg, d.L, d.Nc);
+  hipLaunchKernelGGL((chunk_output_kernel<Io>), dim3(tiles_lp, chunks, heads_dim), dim3(kThreads), 0, stream, x, dt,
+                     B, C, D, cs, states, y, d.T, d.H, d.P, d.N, d.G, d.hpg, d.L, d.Nc, vp);
   trace_mark(trace, stream, "chunk_output");
   return hipGetLastError();
 }
 
+// Workspace: cs (heads x chunks x L), chunk states (heads x chunks x P x N), a transformed copy of dt,
+// and for a packed batch its int32 tables.  chunks = Nc per batch row, or ceil(T / L) + nseq.
+struct GenLayout {
+  size_t chunks, off_states, off_dt, off_tables, total;  // offsets in floats, total in bytes
+};
+GenLayout gen_layout(const Dims &d, bool varlen) {
+  GenLayout w;
+  const size_t heads = varlen ? d.H : static_cast<size_t>(d.Bt) * d.H;
+  w.chunks = varlen ? static_cast<size_t>(d.Nc) + d.Bt : d.Nc;
+  w.off_states = round_up(heads * w.chunks * d.L, 64);
+  w.off_dt = w.off_states + heads * w.chunks * d.P * d.N;
+  w.off_tables = w.off_dt + round_up((varlen ? 1 : static_cast<size_t>(d.Bt)) * d.T * d.H, 64);
+  size_t fl = w.off_tables;
+  if (varlen) fl += round_up(5 * (static_cast<size_t>(d.Bt) + 1) + 2 * w.chunks + d.Bt + 1, 64);
+  w.total = round_up(fl * sizeof(float), 256);
+  return w;
+}
+
+// dt through the optional transform, into the workspace copy.
+const float *prepared_dt(const Dims &d, const GenLayout &w, size_t n, const float *dt, void *workspace,
+                         hipStream_t stream) {
+  if (d.dtx.identity()) return dt;
+  float *copy = static_cast<float *>(workspace) + w.off_dt;
+  hipLaunchKernelGGL(dt_transform_kernel, dim3(static_cast<unsigned>((n + kThreads - 1) / kThreads)), dim3(kThreads),
+                     0, stream, dt, copy, n, d.H, d.dtx);
+  return copy;
+}
+
 }  // namespace
 
-size_t generic_workspace_bytes(const Dims &d_in) {
-  const Dims d = clamp_chunk(d_in);
-  const size_t BH = static_cast<size_t>(d.Bt) * d.H;
-  const size_t cs = round_up(BH * d.Nc * d.L, 64);
-  const size_t st = BH * d.Nc * d.P * d.N;
-  const size_t dtc = round_up(BH * d.T, 64);  // transformed copy of dt, used only with a DtXform
-  return round_up((cs + st + dtc) * sizeof(float), 256);
-}
+size_t generic_workspace_bytes(const Dims &d_in) { return gen_layout(clamp_chunk(d_in), false).total; }
 
 hipError_t launch_prefill_generic(const Dims &d_in, const void *x, const float *dt, const float *A,
                                   const void *B, const void *C, const float *D, const float *h0, void *y,
                                   float *final_state, void *workspace, hipStream_t stream,
                                   KernelTrace *trace) {
   const Dims d = clamp_chunk(d_in);
-  if (!d.dtx.identity()) {
-    const size_t BH = static_cast<size_t>(d.Bt) * d.H;
-    const size_t n = BH * d.T;
-    float *copy = static_cast<float *>(workspace) + round_up(BH * d.Nc * d.L, 64) + BH * d.Nc * d.P * d.N;
-    hipLaunchKernelGGL(dt_transform_kernel, dim3(static_cast<unsigned>((n + kThreads - 1) / kThreads)), dim3(kThreads),
-                       0, stream, dt, copy, n, d.H, d.dtx);
-    dt = copy;
-  }
-  return d.bf16
-             ? launch_typed<IoBf16>(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace)
-             : launch_typed<IoF32>(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);
+  const GenLayout w = gen_layout(d, false);
+  dt = prepared_dt(d, w, static_cast<size_t>(d.Bt) * d.T * d.H, dt, workspace, stream);
+  float *cs = static_cast<float *>(workspace), *states = cs + w.off_states;
+  const VarPlan none = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
+  return d.bf16 ? launch_typed<IoBf16>(d, none, x, dt, A, B, C, D, h0, y, final_state, cs, states, stream, trace)
+                : launch_typed<IoF32>(d, none, x, dt, A, B, C, D, h0, y, final_state, cs, states, stream, trace);
+}
+
+// Packed variable-length batch: d.Bt sequences, d.T tokens in total.
+size_t generic_varlen_workspace_bytes(const Dims &d_in) { return gen_layout(clamp_chunk(d_in), true).total; }
+
+hipError_t launch_prefill_generic_varlen(const Dims &d_in, const int32_t *cu, const void *x, const float *dt,
+                                         const float *A, const void *B, const void *C, const float *D,
+                                         const float *h0, void *y, float *final_state, void *workspace,
+                                         hipStream_t stream) {
+  const Dims d = clamp_chunk(d_in);
+  const GenLayout w = gen_layout(d, true);
+  dt = prepared_dt(d, w, static_cast<size_t>(d.T) * d.H, dt, workspace, stream);
+  float *cs = static_cast<float *>(workspace), *states = cs + w.off_states;
+  int32_t *t = reinterpret_cast<int32_t *>(cs + w.off_tables);
+  const int n1 = d.Bt + 1, cap = static_cast<int>(w.chunks);
+  // blocks of the tables = chunks; "segments" of one chunk each (only their total is used: zero
+  // marks rejected boundaries)
+  const VarPlan vp = {t, t + n1, t + 2 * n1, t + 3 * n1, t + 4 * n1, t + 5 * n1, t + 5 * n1 + cap, d.Bt, cap, 0};
+  launch_varlen_tables(cu, d.T, d.L, 1, cap + d.Bt + 1, vp, stream);
+  return d.bf16 ? launch_typed<IoBf16>(d, vp, x, dt, A, B, C, D, h0, y, final_state, cs, states, stream, nullptr)
+                : launch_typed<IoF32>(d, vp, x, dt, A, B, C, D, h0, y, final_state, cs, states, stream, nullptr);
 }
 
 }  // namespace ssd

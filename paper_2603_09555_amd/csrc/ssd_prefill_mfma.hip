@@ -117,13 +117,9 @@ struct NSlice {
 // numbers (capacities nb_cap, slot_cap are upper bounds that the host can compute from the token
 // count and the number of sequences alone).  Boundaries that are not non-decreasing within
 // [0, total] give empty tables: every later kernel then finds nothing to do.
-struct VarPlan {
-  const int32_t *tok0, *len, *blk0, *item0, *slot0, *blk_seq, *item_seq;
-  int nseq, nb_cap, slot_cap;
-};
 
 __global__ __launch_bounds__(256) void varlen_scan_kernel(const int32_t *__restrict__ cu, int nseq, int total,
-                                                          int seg_blocks, int32_t *__restrict__ tok0,
+                                                          int blk_len, int seg_blocks, int32_t *__restrict__ tok0,
                                                           int32_t *__restrict__ len, int32_t *__restrict__ blk0,
                                                           int32_t *__restrict__ item0, int32_t *__restrict__ slot0) {
   __shared__ int sblk[256], sitem[256], sslot[256];
@@ -138,7 +134,7 @@ __global__ __launch_bounds__(256) void varlen_scan_kernel(const int32_t *__restr
   for (int q = q0; q < q1; ++q) {
     const int a = cu[q], b = cu[q + 1];
     if (a < 0 || b < a || b > total) mine_bad = true;
-    const int n = (b - a + 63) / 64;
+    const int n = (b - a + blk_len - 1) / blk_len;
     const int segs = max(1, (n + seg_blocks - 1) / seg_blocks);
     nb += n;
     ni += segs;
@@ -168,7 +164,7 @@ __global__ __launch_bounds__(256) void varlen_scan_kernel(const int32_t *__restr
   int rb = sblk[tid], ri = sitem[tid], rs = sslot[tid];
   for (int q = q0; q < q1; ++q) {
     const int a = cu[q], l = cu[q + 1] - a;
-    const int n = (l + 63) / 64;
+    const int n = (l + blk_len - 1) / blk_len;
     const int segs = max(1, (n + seg_blocks - 1) / seg_blocks);
     tok0[q] = bad ? 0 : a;
     len[q] = bad ? 0 : l;
@@ -1293,12 +1289,8 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
     items = w.NB / seg_blocks + d.Bt + 1;
     if (items > w.items_max) items = w.items_max;
     S = 0;  // per sequence, from the tables
-    hipLaunchKernelGGL(varlen_scan_kernel, dim3(1), dim3(256), 0, stream, cu, d.Bt, d.T, seg_blocks, tok0, len, blk0,
-                       item0, slot0);
-    const int cap = w.NB > items ? w.NB : items;
-    hipLaunchKernelGGL(varlen_fill_kernel, dim3((cap + 255) / 256), dim3(256), 0, stream, blk0, item0, d.Bt, seg_blocks,
-                       blk_seq, item_seq);
     vp = VarPlan{tok0, len, blk0, item0, slot0, blk_seq, item_seq, d.Bt, w.NB, w.S_max};
+    launch_varlen_tables(cu, d.T, kBlk, seg_blocks, items, vp, stream);
     trace_mark(trace, stream, "varlen_tables");
   }
 
@@ -1384,6 +1376,19 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
 }
 
 }  // namespace
+
+// Tables of a packed batch for blocks of blk_len tokens (the MFMA kernels: 64; the generic kernels:
+// one chunk) and segments of seg_blocks blocks.  vp names the table arrays (device, int32: tok0, len,
+// blk0, item0, slot0 of nseq + 1 entries each, blk_seq of nb_cap, item_seq of item_cap entries).
+void launch_varlen_tables(const int32_t *cu, int total, int blk_len, int seg_blocks, int item_cap, const VarPlan &vp,
+                          hipStream_t stream) {
+  hipLaunchKernelGGL(varlen_scan_kernel, dim3(1), dim3(256), 0, stream, cu, vp.nseq, total, blk_len, seg_blocks,
+                     const_cast<int32_t *>(vp.tok0), const_cast<int32_t *>(vp.len), const_cast<int32_t *>(vp.blk0),
+                     const_cast<int32_t *>(vp.item0), const_cast<int32_t *>(vp.slot0));
+  const int cap = vp.nb_cap > item_cap ? vp.nb_cap : item_cap;
+  hipLaunchKernelGGL(varlen_fill_kernel, dim3((cap + 255) / 256), dim3(256), 0, stream, vp.blk0, vp.item0, vp.nseq,
+                     seg_blocks, const_cast<int32_t *>(vp.blk_seq), const_cast<int32_t *>(vp.item_seq));
+}
 
 bool mfma_supported(const Dims &d) {
   return shape_ok(d, static_cast<unsigned long long>(d.T), (static_cast<unsigned long long>(d.T) + kBlk - 1) / kBlk);

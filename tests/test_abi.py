@@ -121,10 +121,15 @@ def test_varlen_rejects_before_any_hip_call(ssd):
     assert call(shape(ssd, **ok), wb=need - 1) == -5
     assert call(shape(ssd, **ok), w=None) == -5
     assert call(shape(ssd, **dict(ok, seqlen=0))) == -2
-    # outside the MFMA kernel family: fp32 io, other head shapes, chunk not a multiple of 64
-    for bad in (dict(io_dtype=0), dict(headdim=32), dict(dstate=256), dict(dstate=100), dict(chunk=100), dict(ngroups=4)):
-        assert call(shape(ssd, **dict(ok, **bad))) == -4
-        assert lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(shape(ssd, **dict(ok, **bad)))) == 0
+    # outside the MFMA kernel family (fp32 io, other head shapes, chunk not a multiple of 64): the generic
+    # kernels take the batch, so there is a workspace size for it
+    for other in (dict(io_dtype=0), dict(headdim=32), dict(dstate=256), dict(dstate=100), dict(chunk=100),
+                  dict(ngroups=4)):
+        assert lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(shape(ssd, **dict(ok, **other)))) > 0
+    # beyond what either family takes: sequences x heads over a grid axis, with fp32 io
+    big = dict(ok, io_dtype=0, batch=9000, seqlen=20000)
+    assert call(shape(ssd, **big)) == -4
+    assert lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(shape(ssd, **big))) == 0
 
 
 def test_prefill_dt_rejects_before_any_hip_call(ssd):

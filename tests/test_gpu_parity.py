@@ -472,3 +472,53 @@ def test_prefill_with_fused_dt_transform(ssd, case, monkeypatch):
     y_ref, st_ref = ssd_oracle.prefill(inp["x"], dt_ref, inp["A"], inp["B"], inp["C"], inp["D"])
     assert_close(y, y_ref, TOL[io], "fused dt: y")
     assert_close(st, st_ref, TOL[io], "fused dt: state")
+
+
+GENERIC_VARLEN_CASES = [
+    # lengths, H, P, N, G, L, io, with h0
+    ([5, 0, 33, 64, 1, 100], 4, 32, 16, 2, 32, "f32", True),      # fp32 io: the 1e-4 tolerance family
+    ([70, 7], 3, 24, 20, 3, 7, "f32", False),                      # nothing is a multiple of any tile
+    ([130, 0, 300], 2, 72, 40, 1, 128, "bf16", True),              # bf16, head shape outside the MFMA family
+    ([200, 57, 64], 4, 64, 256, 1, 64, "bf16", True),              # dstate 256 packed: generic kernels
+    ([1000], 2, 16, 8, 1, 2048, "f32", False),                     # chunk longer than everything
+]
+
+
+@pytest.mark.parametrize("case", GENERIC_VARLEN_CASES, ids=lambda c: "x".join(str(v) for v in c[1:]) + "-n%d" % len(c[0]))
+def test_varlen_prefill_generic_family_matches_oracle(ssd, case):
+    lens, H, P, N, G, L, io, with_h0 = case
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T, nseq = int(cu[-1]), len(lens)
+    cfg = cfg_of(1, T, H, P, N, G, L, io)
+    inp = inputs.make_prefill_inputs(cfg, seed=83)
+    pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
+    h0 = inputs.make_state(cfg_of(nseq, 1, H, P, N, G, L, io), seed=83) if with_h0 else None
+    print("generic varlen case", case, flush=True)
+    dev = {k: v.cuda() for k, v in pk.items()}
+    y, st = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
+                                   torch.from_numpy(cu).cuda(), L, h0=None if h0 is None else h0.cuda())
+    torch.cuda.synchronize()
+    y_ref, st_ref = ssd_oracle.prefill_varlen(pk["x"], pk["dt"], pk["A"], pk["B"], pk["C"], pk["D"], cu, h0=h0)
+    assert_close(y, y_ref, TOL[io], "generic varlen y")
+    assert_close(st, st_ref, TOL[io], "generic varlen final states")
+
+
+def test_varlen_families_agree_and_bad_boundaries_are_a_no_op_on_both(ssd, monkeypatch):
+    lens = [100, 0, 300, 65]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cfg = cfg_of(1, int(cu[-1]), 4, 64, 128, 1, 64, "bf16")
+    inp = inputs.make_prefill_inputs(cfg, seed=89)
+    dev = {k: (v[0] if k in ("x", "dt", "B", "C") else v).cuda() for k, v in inp.items()}
+    cud = torch.from_numpy(cu).cuda()
+    y1, s1 = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cud, 64)
+    monkeypatch.setenv("SSD_FORCE_GENERIC", "1")
+    y2, s2 = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cud, 64)
+    torch.cuda.synchronize()
+    assert_close(y1, to_np64(y2), 2e-2, "varlen: MFMA vs generic y")
+    assert_close(s1, to_np64(s2), 2e-2, "varlen: MFMA vs generic state")
+    y3 = torch.full_like(dev["x"], 7.0)
+    s3 = torch.full((4, 4, 64, 128), 5.0, device="cuda")
+    ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
+                           torch.tensor([0, 200, 100, 300, 465], dtype=torch.int32).cuda(), 64, y=y3, final_state=s3)
+    torch.cuda.synchronize()
+    assert (y3 == 7.0).all() and (s3 == 5.0).all()
