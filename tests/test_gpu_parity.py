@@ -522,3 +522,46 @@ def test_varlen_families_agree_and_bad_boundaries_are_a_no_op_on_both(ssd, monke
                            torch.tensor([0, 200, 100, 300, 465], dtype=torch.int32).cuda(), 64, y=y3, final_state=s3)
     torch.cuda.synchronize()
     assert (y3 == 7.0).all() and (s3 == 5.0).all()
+
+
+def test_prefill_replayed_from_a_hip_graph(ssd):
+    """The library allocates nothing and never synchronises, so a prefill (plain and packed) can be
+    captured into a HIP graph; every replay, with eager work and synchronisations in between and the
+    inputs changed in place, equals the eager call on the same inputs."""
+    cfg = cfg_of(2, 1000, 8, 64, 128, 1, 256, "bf16")
+    sh = ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk,
+                        torch.bfloat16)
+    dev = {k: v.cuda() for k, v in inputs.make_prefill_inputs(cfg, seed=91).items()}
+    pk = {k: (v.reshape((-1,) + tuple(v.shape[2:])) if k in ("x", "dt", "B", "C") else v) for k, v in dev.items()}
+    cu = torch.tensor([0, 700, 700, 1300, 2000], dtype=torch.int32).cuda()
+    y, st = torch.empty_like(dev["x"]), torch.empty((2, 8, 64, 128), device="cuda")
+    yv, stv = torch.empty_like(pk["x"]), torch.empty((4, 8, 64, 128), device="cuda")
+    ws = torch.empty((ssd.prefill_workspace_bytes(sh),), dtype=torch.uint8, device="cuda")
+    shv = ssd.make_shape(4, 2000, 8, 64, 128, 1, 256, torch.bfloat16)
+    wsv = torch.empty((ssd.raw().ssd_prefill_varlen_workspace_bytes(shv),), dtype=torch.uint8, device="cuda")
+
+    def both(y, st, yv, stv):
+        ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk, y=y, final_state=st,
+                        workspace=ws)
+        ssd.ssd_prefill_varlen(pk["x"], pk["dt"], pk["A"], pk["B"], pk["C"], pk["D"], cu, cfg.chunk, y=yv,
+                               final_state=stv, workspace=wsv)
+
+    both(y, st, yv, stv)  # warm-up outside the capture
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            both(y, st, yv, stv)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        dev["x"].mul_(-0.5 if rep else 1.0)          # new inputs in the same buffers (pk views them)
+        dev["dt"].mul_(1.1).clamp_(1e-3, 1e-1)
+        y.zero_(), st.zero_(), yv.zero_(), stv.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        ye, se, yve, sve = torch.empty_like(y), torch.empty_like(st), torch.empty_like(yv), torch.empty_like(stv)
+        both(ye, se, yve, sve)
+        torch.cuda.synchronize()
+        assert torch.equal(y, ye) and torch.equal(st, se), "plain prefill, replay %d" % rep
+        assert torch.equal(yv, yve) and torch.equal(stv, sve), "packed prefill, replay %d" % rep
