@@ -339,29 +339,50 @@ __device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1],
     tile[tok][hh] = v;
   }
   __syncthreads();
-  for (int hh = wave; hh < kCumHeads && h0 + hh < H; hh += kThreads / 64) {
-    const int h = h0 + hh;
-    const float dtv = tile[lane][hh];
-    float v = dtv * (A[h] * kLog2e);
+  // A wave takes the heads wave, wave + 4, wave + 8, wave + 12 of the group of 16.  Their prefix sums
+  // are four independent chains of cross-lane steps, written side by side so that the latency of one
+  // chain's step is covered by the steps of the others.
+  constexpr int kPer = kCumHeads / (kThreads / 64);
+  float dtv[kPer], v[kPer], nx[kPer], ah[kPer];
+  bool live[kPer];
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const float up = __shfl_up(v, off, 64);
-      if (lane >= off) v += up;
-    }
-    const float c31 = __shfl(v, 31, 64);
-    const float c63 = __shfl(v, 63, 64);
+  for (int k = 0; k < kPer; ++k) {
+    const int hh = wave + k * (kThreads / 64);
+    live[k] = h0 + hh < H;
+    ah[k] = live[k] ? A[h0 + hh] * kLog2e : 0.f;
+    dtv[k] = tile[lane][hh];
+    v[k] = dtv[k] * ah[k];
     // prefix sum at token 31 of the next block: the sum of its first 32 terms
-    float nx = lane < kBlk / 2 ? tile[kBlk + lane][hh] * (A[h] * kLog2e) : 0.f;
+    nx[k] = lane < kBlk / 2 ? tile[kBlk + lane][hh] * ah[k] : 0.f;
+  }
 #pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) nx += __shfl_xor(nx, m, 64);
-    float *rec = prep + (static_cast<size_t>(h) * rec_stride + rec_off) * kRec;
-    rec[lane] = fast_exp2(fminf(fmaxf(v - c31, -kMaxExp), kMaxExp));
-    rec[kBlk + lane] = dtv * fast_exp2(fminf(fmaxf(c31 - v, -kMaxExp), kMaxExp));
-    if (lane < 4)
-      rec[2 * kBlk + lane] = lane == 0   ? fast_exp2(c63 - c31)
-                             : lane == 1 ? c63
-                             : lane == 2 ? fast_exp2(c31)
-                                         : fast_exp2(c63 - c31) * fast_exp2(nx);
+  for (int off = 1; off < 64; off <<= 1) {
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) {
+      const float up = __shfl_up(v[k], off, 64);
+      if (lane >= off) v[k] += up;
+    }
+  }
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+#pragma unroll
+    for (int k = 0; k < kPer; ++k) nx[k] += __shfl_xor(nx[k], m, 64);
+  }
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) {
+    const float c31 = __shfl(v[k], 31, 64);
+    const float c63 = __shfl(v[k], 63, 64);
+    if (live[k]) {
+      const int h = h0 + wave + k * (kThreads / 64);
+      float *rec = prep + (static_cast<size_t>(h) * rec_stride + rec_off) * kRec;
+      rec[lane] = fast_exp2(fminf(fmaxf(v[k] - c31, -kMaxExp), kMaxExp));
+      rec[kBlk + lane] = dtv[k] * fast_exp2(fminf(fmaxf(c31 - v[k], -kMaxExp), kMaxExp));
+      if (lane < 4)
+        rec[2 * kBlk + lane] = lane == 0   ? fast_exp2(c63 - c31)
+                               : lane == 1 ? c63
+                               : lane == 2 ? fast_exp2(c31)
+                                           : fast_exp2(c63 - c31) * fast_exp2(nx[k]);
+    }
   }
 }
 
