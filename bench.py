@@ -9,7 +9,11 @@ throughput in TFLOP/s by the *algorithmic, causal-only* FLOP count at the config
 length (work the method must do: no per-head recomputation of C.B^T, no padding, no masked
 upper triangle); the dense-convention figure is printed beside it.  The decode workload
 (64 stacked layers, 1024 back-to-back steps, batch 16 and batch 1) is timed in a second
-region and reported as HBM GB/s under ``decode``.  One JSON line is printed last.
+region and reported as HBM GB/s under ``decode`` (with the HIP-graph replay and the many-steps-per-
+launch variant beside it).  Further objects of the same line, none of them part of the timed step:
+``other_configs`` (configs 0-2), ``sweeps`` (chunk length, groups, head shapes), ``varlen`` (packed
+ragged batches, piecewise prompts), ``conv`` (the depthwise convolution), ``measured_peaks`` (the
+library's MFMA and streaming probes).  One JSON line is printed last.
 """
 from __future__ import annotations
 

@@ -1097,14 +1097,14 @@ void chunk_scan_kernel(const ScanParams p) {
 // ---- segment_pass: slot[0] = h0; slot[sg] = exp2(decay[sg-1]) * slot[sg-1] + local[sg-1] --------
 // grid (P*N/1024, rows <= sequences*H), four consecutive state elements per thread.  seg_state slot sg (sg >= 1)
 // holds the local end state of segment sg-1 on entry and the state entering segment sg on exit.
-// The chain over segments is serial, but the loads do not depend on it: they are issued sixteen
-// segments at a time before the chain consumes them, so the kernel pays a few memory round trips
+// The chain over segments is serial, but the loads do not depend on it: they are issued eight
+// segments at a time (sixteen measured slower) before the chain consumes them, so the kernel pays a few memory round trips
 // instead of one per segment.
 __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restrict__ seg_state,
                                                                 const float *__restrict__ seg_decay,
                                                                 const float *__restrict__ h0, int S_plain, int H,
                                                                 int rows, const VarPlan vp, const NSlice ns) {
-  constexpr int kAhead = 16;
+  constexpr int kAhead = 8;
   const int e = (blockIdx.x * kThreads + threadIdx.x) * 4;
   if (vp.tok0 != nullptr && vp.slot0[vp.nseq] == 0) return;  // no sequence has more than one segment
   for (size_t bh = blockIdx.y; bh < static_cast<size_t>(rows); bh += gridDim.y) {  // (sequence, head)
