@@ -164,3 +164,46 @@ def test_full_size_ragged_batch_sampled_sequences(ssd):
                                            pk["C"][None, a:b], pk["D"], h0=h0[q:q + 1], pairs=[(0, h)])
         assert_close(y[a:b, h], y_ref[0], 2e-2, "ragged y seq %d head %d" % (q, h))
         assert_close(st[q, h], st_ref[0], 2e-2, "ragged state seq %d head %d" % (q, h))
+
+
+def test_longest_addressable_sequence(ssd):
+    """One sequence close to the largest the MFMA kernels address with 32-bit byte offsets (x of one
+    batch row just under 4 GiB): 4,000,000 tokens x 8 heads.  With A = -16 and dt >= 0.05 the state
+    forgets within a few hundred tokens (decay <= e^-0.8 per token), so the oracle can check windows
+    anywhere in the sequence from a zero state after a 512-token run-in: the first tokens, the
+    tokens around the 2 GiB and 3 GiB byte offsets of x, and the ragged end with the final state."""
+    T, H, P, N, L = 4_000_000, 8, 64, 128, 256
+    sh = ssd.make_shape(1, T, H, P, N, 1, L, torch.bfloat16)
+    assert ssd.prefill_path(sh) == "mfma_bf16"
+    print("longest sequence", T, "tokens;", T * H * P * 2 / 2 ** 30, "GiB of x", flush=True)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(97)
+    x = torch.empty((1, T, H, P), dtype=torch.bfloat16, device="cuda")
+    B = torch.empty((1, T, 1, N), dtype=torch.bfloat16, device="cuda")
+    C = torch.empty_like(B)
+    step = 1 << 18
+    for t0 in range(0, T, step):   # drawn in pieces to bound the fp32 temporaries
+        n = min(step, T - t0)
+        x[0, t0:t0 + n] = torch.randn((n, H, P), generator=g, device="cuda").bfloat16()
+        B[0, t0:t0 + n] = (0.25 * torch.randn((n, 1, N), generator=g, device="cuda")).bfloat16()
+        C[0, t0:t0 + n] = (0.25 * torch.randn((n, 1, N), generator=g, device="cuda")).bfloat16()
+    dt = torch.rand((1, T, H), generator=g, device="cuda") * 0.05 + 0.05
+    A = torch.full((H,), -16.0, device="cuda")
+    D = torch.randn((H,), generator=g, device="cuda")
+    y, st = ssd.ssd_prefill(x, dt, A, B, C, D, L)
+    torch.cuda.synchronize()
+    assert torch.isfinite(st).all()
+    run_in, width = 512, 1024
+    row_bytes = H * P * 2
+    starts = [0, (2 << 30) // row_bytes - width // 2, (3 << 30) // row_bytes - width // 2, T - width]
+    for s0 in starts:
+        a = max(0, s0 - run_in)
+        b = min(T, s0 + width)
+        sl = slice(a, b)
+        y_ref, st_ref = ssd_oracle.prefill(x[:, sl].cpu(), dt[:, sl].cpu(), A.cpu(), B[:, sl].cpu(), C[:, sl].cpu(),
+                                           D.cpu(), pairs=[(0, 0), (0, 3), (0, H - 1)])
+        got = y[0, s0:b][:, [0, 3, H - 1]].transpose(0, 1)        # (3, width, P)
+        assert torch.isfinite(got.float()).all()
+        assert_close(got, y_ref[:, s0 - a:], 2e-2, "y in the window at token %d" % s0)
+        if b == T:
+            assert_close(st[0, [0, 3, H - 1]], st_ref, 2e-2, "final state")
