@@ -289,7 +289,8 @@ ssd_status ssd_peak_probe(int32_t kind, int32_t iters, int32_t reps, void *a, vo
   if (!ms || !work || !a) return SSD_ERR_NULL;
   if (kind < 0 || kind > 3 || reps < 1 || reps > 100000) return SSD_ERR_SHAPE;
   if (kind == 0 && (iters < 1 || bytes < static_cast<size_t>(2048) * 256 * sizeof(float))) return SSD_ERR_SHAPE;
-  if (kind != 0 && (!b || bytes < 16)) return kind != 0 && !b ? SSD_ERR_NULL : SSD_ERR_SHAPE;
+  if (kind != 0 && !b) return SSD_ERR_NULL;
+  if (kind != 0 && bytes < 16) return SSD_ERR_SHAPE;
   if (!aligned16(a) || (b && !aligned16(b))) return SSD_ERR_ALIGN;
   const hipError_t e = ssd::run_peak_probe(kind, iters, reps, a, b, bytes, ms, work, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;

@@ -565,3 +565,21 @@ def test_prefill_replayed_from_a_hip_graph(ssd):
         torch.cuda.synchronize()
         assert torch.equal(y, ye) and torch.equal(st, se), "plain prefill, replay %d" % rep
         assert torch.equal(yv, yve) and torch.equal(stv, sve), "packed prefill, replay %d" % rep
+
+
+def test_peak_probes_run_and_the_copy_probe_copies(ssd):
+    a = torch.arange(1 << 22, dtype=torch.int32, device="cuda")          # 16 MiB
+    b = torch.zeros_like(a)
+    rate, ms = ssd.peak_probe("copy", a, b, reps=2)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and rate > 1e11 and ms > 0
+    odd = torch.arange(1000 * 4 + 4, dtype=torch.int32, device="cuda")    # not a multiple of the 32 KB slabs
+    out = torch.zeros_like(odd)
+    ssd.peak_probe("copy", odd, out)
+    torch.cuda.synchronize()
+    assert torch.equal(odd, out)
+    for kind in ("read", "write"):
+        rate, _ = ssd.peak_probe(kind, a, b, reps=2)
+        assert rate > 1e11
+    rate, _ = ssd.peak_probe("mfma", a, None, iters=50, reps=2)
+    assert rate > 1e13
