@@ -31,7 +31,8 @@
 // slice of the state and never exchanges data with another wave.  The C, B^T and G tiles are
 // staged once per workgroup in double-buffered LDS and shared by the four heads; each wave
 // stages its own slice of the scaled input.  Global loads for block j+2 are issued while block
-// j+1 is being computed, with one barrier per block.
+// j+1 is being computed; two barriers per block (tiles of the next block visible; both halves of the
+// output rows in LDS).
 //
 // Kernels (launch order):
 //   block_prep     one launch for both preparation steps: per (batch, group, block) G = tril(C B^T)
@@ -573,6 +574,12 @@ __device__ __forceinline__ int pi_of_row(int m) { return 16 * ((m >> 2) & 1) + 4
 // copy that the staging step leaves in LDS instead of loading it again, the loads of the block after
 // next are issued in the middle of an iteration, as soon as their registers are free, and the stores
 // of y are spread over the second half.
+#ifndef SSD_ROW_STORES
+#define SSD_ROW_STORES 1
+#endif
+// y leaves as whole 128-byte rows (the two waves of a head exchange their halves through LDS, one more
+// barrier per block) instead of 64-byte half rows per wave.
+constexpr bool kRowStores = SSD_ROW_STORES != 0;
 constexpr int kRawStride = 40;                       // raw x rows: 32 columns + 16 bytes, in bf16 elements
 constexpr int kGLowStride = 32 + 8;                  // G rows 0..31 keep only columns 0..31 (the rest is masked)
 constexpr int kGTile = 32 * kGLowStride + 32 * kGStride;  // elements of a compacted G tile
@@ -799,8 +806,17 @@ void chunk_scan_kernel(const ScanParams p) {
   const uint32_t a_bt = r * kBtStride + 8 * kg;  // + 32 nt rows, + 16 q
   const uint16_t *const raw_src = myRaw + r * kRawStride + 16 * kg;   // + 32 rows for the second half, + 8 c
   uint16_t *const raw_rw = myRaw + r * kRawStride + 16 * kg;
-  const uint16_t *const raw_dst_row = myRaw + (lane >> 2) * kRawStride + 8 * (lane & 3);  // row layout: token lane/4 (+16k)
-  const uint32_t vy = static_cast<uint32_t>(lane >> 2) * xrow + xcol + 16 * (lane & 3);
+  // output rows.  Half rows: lane i handles 16 bytes of token i/4 (+16k) of the wave's own half.  Whole
+  // rows: the wave handles tokens 32ph + i/8 (+8k), lane i the 16-byte piece i%8 of the 128-byte row --
+  // pieces 0..3 come from the tile of the head's first wave, 4..7 from that of its second wave.
+  const uint16_t *const raw_dst_row =
+      kRowStores && !kStatesOnly
+          ? sRaw[kStatesOnly ? 0 : 2 * hw + ((lane & 7) >> 2)] + (32 * ph + (lane >> 3)) * kRawStride + 8 * (lane & 3)
+          : myRaw + (lane >> 2) * kRawStride + 8 * (lane & 3);
+  const uint32_t vy = kRowStores ? static_cast<uint32_t>(32 * ph + (lane >> 3)) * xrow +
+                                       static_cast<uint32_t>(h) * (kP * 2) + 16 * (lane & 7)
+                                 : static_cast<uint32_t>(lane >> 2) * xrow + xcol + 16 * (lane & 3);
+  constexpr int kRowStep = kRowStores ? 8 : 16;  // tokens between a lane's four pieces
   auto lds16 = [](const uint16_t *ptr) {
     Operand o;
     o.q = *reinterpret_cast<const u32x4 *>(ptr);
@@ -919,14 +935,14 @@ void chunk_scan_kernel(const ScanParams p) {
       for (int c = 0; c < 8; ++c) stage_column(c, 0);
 #pragma unroll
       for (int piece = 0; piece < 5; ++piece) stage_tile(piece, 0);
-      stage_raw(0);
+      if constexpr (!kRowStores) stage_raw(0);
       // the following blocks are requested in the order the loop requests blocks (shared tiles, own
       // slices, row factors): the compiler derives its waits from the order of outstanding loads,
       // and they stay exact only if the path into the loop and the path around it agree on it
       load_part(1, at(jb0 + 1));
       load_part(2, at(jb0 + 1));
       load_part(0, at(jb0 + 1), 1);
-      load_part(0, at(jb0 + 2), 0);
+      if constexpr (!kRowStores) load_part(0, at(jb0 + 2), 0);
       load_rowf(jb0);
     }
     wait_all_loads();
@@ -944,6 +960,13 @@ void chunk_scan_kernel(const ScanParams p) {
       float pend_next = 0.f;
       const uint16_t *const tC = sC[buf], *const tG = sG[buf], *const tBt = sBt[buf];
 
+      if constexpr (kRowStores) {
+        // the raw rows of this block go to LDS only now: until the barrier that ended the previous
+        // iteration the other wave of the head was still reading the previous block's y from this
+        // tile.  Then the register set is refilled with the block after next.
+        stage_raw(par);
+        load_part(0, at(jb + 2), par);
+      }
       Operand xo[4];  // Xm^T[row r][s = 16q + 8kg ..]
 #pragma unroll
       for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
@@ -1034,21 +1057,25 @@ void chunk_scan_kernel(const ScanParams p) {
         __builtin_amdgcn_sched_barrier(0);
       }
 
-      // ---- y goes out in row layout: lane i stores 16 bytes of token i/4 + 16k, four lanes cover the
-      //      wave's 64 bytes of a token, so every request is a whole 64-byte piece of a row (the
-      //      output layout of the MFMA would give 32-byte pieces, which the memory system handles much
-      //      worse next to the concurrent reads of x).  Tokens beyond the sequence are beyond the
-      //      descriptor and are dropped.  Then the raw rows of the next block replace this block's (LDS
-      //      operations of a wave execute in order), and its register set is refilled. ----
+      // ---- y goes out in row layout, read back from LDS: the output layout of the MFMA would give
+      //      32-byte pieces, which the memory system handles much worse next to the concurrent reads of
+      //      x than 64-byte half rows, and those worse than whole 128-byte rows.  For whole rows the
+      //      two waves of a head wait for each other's halves (the barrier below) and each stores the
+      //      rows of 32 tokens; the raw rows of the next block then go to LDS at the top of the next
+      //      iteration instead of here.  Tokens beyond the sequence are beyond the descriptor and are
+      //      dropped. ----
+      if constexpr (kRowStores) __syncthreads();  // both halves of every row of y are in LDS
       {
         u32x4 yo[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) yo[k] = *reinterpret_cast<const u32x4 *>(raw_dst_row + 16 * k * kRawStride);
+        for (int k = 0; k < 4; ++k) yo[k] = *reinterpret_cast<const u32x4 *>(raw_dst_row + kRowStep * k * kRawStride);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) buf_store16(ry, vy + static_cast<uint32_t>(16 * k) * xrow, yo[k]);
+        for (int k = 0; k < 4; ++k) buf_store16(ry, vy + static_cast<uint32_t>(kRowStep * k) * xrow, yo[k]);
       }
-      stage_raw(setA);
-      load_part(0, at(jb + 3), setA);
+      if constexpr (!kRowStores) {
+        stage_raw(setA);
+        load_part(0, at(jb + 3), setA);
+      }
       pending = pend_next;
       rowf0 = rowf0n;
       rowf1 = rowf1n;
