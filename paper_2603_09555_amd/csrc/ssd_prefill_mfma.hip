@@ -1179,14 +1179,16 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
 // worth about two) at a per-block time that grows with the number of workgroups competing for
 // memory, and more than one segment costs the states pass (same structure, cheaper blocks), the
 // serial pass over segment states (traffic proportional to segments x sequences) and two launches.
+// The constants are a least-squares fit to 31 timed (shape, segment length) points of the three
+// bf16 benchmark shapes (residual 5 us rms).
 // SSD_SEG_CHUNKS=k forces k chunks per segment (tests), SSD_SEG_BLOCKS=k forces k blocks (tuning).
 constexpr int kNumCUs = 256;
 double rounds_time(long wgs, int blocks, double t_idle, double t_busy) {
   double t = 0.0;
   for (long left = wgs; left > 0; left -= kNumCUs) {
     const double n = static_cast<double>(left < kNumCUs ? left : kNumCUs);
-    const double load = n < 192.0 ? n / 192.0 : 1.0;
-    t += (blocks + 2) * (t_idle + (t_busy - t_idle) * load);
+    const double load = n / kNumCUs;
+    t += (blocks + 1.9) * (t_idle + (t_busy - t_idle) * load);
   }
   return t;
 }
@@ -1223,8 +1225,8 @@ int choose_seg_blocks(const Dims &d, int min_blocks) {
   for (int cand = min_blocks; cand <= hi; ++cand) {
     const long segs = (nblocks + cand - 1) / cand;
     if (cand > min_blocks && (nblocks + cand - 2) / (cand - 1) == segs) continue;  // same count, longer segments
-    double cost = rounds_time(groups * segs, cand, 3.2, 4.0);
-    if (segs > 1) cost += rounds_time(groups * (segs - 1), cand, 1.6, 2.2) + 3.5 + 0.0089 * segs * seqs + 8.0;
+    double cost = rounds_time(groups * segs, cand, 2.57, 3.35);
+    if (segs > 1) cost += rounds_time(groups * (segs - 1), cand, 1.16, 1.16) + 3.1 + 0.0261 * segs * seqs + 7.0;
     if (!have || cost < best) {
       have = true;
       best = cost;
