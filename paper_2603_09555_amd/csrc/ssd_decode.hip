@@ -34,6 +34,33 @@ __device__ __forceinline__ float4 load4<IoBf16>(const void *base, size_t i) {
   return r;
 }
 
+// Four consecutive io values as loaded (kept packed while they wait in registers), and their conversion.
+template <typename Io>
+struct Raw4;
+template <>
+struct Raw4<IoF32> {
+  float4 v;
+  __device__ __forceinline__ void load(const void *base, size_t i) {
+    v = *reinterpret_cast<const float4 *>(static_cast<const float *>(base) + i);
+  }
+  __device__ __forceinline__ float4 get() const { return v; }
+};
+template <>
+struct Raw4<IoBf16> {
+  uint2 v;
+  __device__ __forceinline__ void load(const void *base, size_t i) {
+    v = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(base) + i);
+  }
+  __device__ __forceinline__ float4 get() const {
+    float4 r;
+    r.x = __uint_as_float(v.x << 16);
+    r.y = __uint_as_float(v.x & 0xffff0000u);
+    r.z = __uint_as_float(v.y << 16);
+    r.w = __uint_as_float(v.y & 0xffff0000u);
+    return r;
+  }
+};
+
 // LPR = lanes per state row = N / 4 (a power of two, <= 64).
 template <typename Io, int LPR>
 __global__ __launch_bounds__(kDecodeThreads) void decode_vec_kernel(
@@ -178,44 +205,37 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_steps_kernel(
     for (int v = 0; v < NV; ++v)
       hv[u][v] = *reinterpret_cast<const float4 *>(hbase + static_cast<size_t>(row0 + u * RPP) * N + v * (4 * LPR));
 
-  float dt_n = dt[pair];
-  float4 B_n[NV], C_n[NV];
+  // Inputs of a step: two sets, one consumed while the other is in flight; B and C stay packed in
+  // the io dtype until they are used (registers decide how many waves a SIMD holds).  Two steps per
+  // loop trip, so that the set index is a compile-time constant and no set is ever copied.  (Three
+  // sets, two steps ahead, took 168 registers and measured 10 % slower.)
+  struct StepIn {
+    float dt;
+    Raw4<Io> B[NV], C[NV];
+    float x[ROWS];
+  } in[2];
+  auto request = [&](StepIn &d, int s) __attribute__((always_inline)) {
+    d.dt = dt[s * npairs + pair];
 #pragma unroll
-  for (int v = 0; v < NV; ++v) {
-    B_n[v] = load4<Io>(B, bc + v * (4 * LPR));
-    C_n[v] = load4<Io>(C, bc + v * (4 * LPR));
-  }
-  float x_n[ROWS];
+    for (int v = 0; v < NV; ++v) {
+      d.B[v].load(B, s * bc_step + bc + v * (4 * LPR));
+      d.C[v].load(C, s * bc_step + bc + v * (4 * LPR));
+    }
 #pragma unroll
-  for (int u = 0; u < ROWS; ++u) x_n[u] = Io::load(x, pair * P + row0 + u * RPP);
-
-  // (Writing two steps per loop trip with alternating input sets saves the register copies below but
-  // costs registers, hence resident waves; it measured 10 % slower.)
-  for (int s = 0; s < nsteps; ++s) {
-    const float dtv = dt_n;
+    for (int u = 0; u < ROWS; ++u) d.x[u] = Io::load(x, (s * npairs + pair) * P + row0 + u * RPP);
+  };
+  auto step = [&](int s, const StepIn &c, StepIn &n) __attribute__((always_inline)) {
+    request(n, s + 1 < nsteps ? s + 1 : s);  // the surplus loads of the last step are not used
+    const float dA = expf(c.dt * Ah);
     float4 Bv[NV], Cv[NV];
-    float xv[ROWS];
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      Bv[v] = B_n[v];
-      Cv[v] = C_n[v];
+      Bv[v] = c.B[v].get();
+      Cv[v] = c.C[v].get();
     }
-#pragma unroll
-    for (int u = 0; u < ROWS; ++u) xv[u] = x_n[u];
-    const int sn = s + 1 < nsteps ? s + 1 : s;  // the surplus loads of the last step are not used
-    dt_n = dt[sn * npairs + pair];
-#pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      B_n[v] = load4<Io>(B, sn * bc_step + bc + v * (4 * LPR));
-      C_n[v] = load4<Io>(C, sn * bc_step + bc + v * (4 * LPR));
-    }
-#pragma unroll
-    for (int u = 0; u < ROWS; ++u) x_n[u] = Io::load(x, (sn * npairs + pair) * P + row0 + u * RPP);
-
-    const float dA = expf(dtv * Ah);
 #pragma unroll
     for (int u = 0; u < ROWS; ++u) {
-      const float ux = dtv * xv[u];
+      const float ux = c.dt * c.x[u];
       float part = 0.f;
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
@@ -228,9 +248,16 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_steps_kernel(
         part = fmaf(Cv[v].w, w.w, fmaf(Cv[v].z, w.z, fmaf(Cv[v].y, w.y, fmaf(Cv[v].x, w.x, part))));
       }
       part = row_sum<LPR>(part);
-      if (lane_n == 0) Io::store(y, (s * npairs + pair) * P + row0 + u * RPP, fmaf(Dh, xv[u], part));
+      if (lane_n == 0) Io::store(y, (s * npairs + pair) * P + row0 + u * RPP, fmaf(Dh, c.x[u], part));
     }
+  };
+  request(in[0], 0);
+  int s = 0;
+  for (; s + 1 < nsteps; s += 2) {
+    step(s, in[0], in[1]);
+    step(s + 1, in[1], in[0]);
   }
+  if (s < nsteps) step(s, in[0], in[1]);
 #pragma unroll
   for (int u = 0; u < ROWS; ++u)
 #pragma unroll
