@@ -81,8 +81,8 @@ def decode_flops(cfg, nlayers):
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a copy of known size gives on this chip; see
 # profiles/hbm_traffic_fetch_write_size.txt).  Measured values, not computed here: null for others.
 HBM_TRAFFIC_BYTES = {
-    ("c3_2p7b_long", "chunk_scan"): int((2 * 110741.3 + 166642.6) * 1024),
-    ("c3_2p7b_long", "segment_states"): int((2 * 85107.4 + 28188.3) * 1024),
+    ("c3_2p7b_long", "chunk_scan"): int((2 * 110494.4 + 166413.4) * 1024),
+    ("c3_2p7b_long", "segment_states"): int((2 * 85116.5 + 28187.9) * 1024),
 }
 
 # Which algorithmic FLOPs each kernel of a prefill call is responsible for.
