@@ -551,6 +551,30 @@ def main():
                           "recurrence; same algorithmic FLOP count as the GPU figure" % (len(sample), len(all_pairs),
                                                                                        cfg.name, cfg.seqlen, reps))
         log("[bench] cpu oracle: %.4f TFLOP/s on %d threads (%.1f s)" % (cpu["value"], cores, t_cpu))
+        # the oracle's decode step on the batch-1 decode workload (64 layers, state streamed from DRAM in
+        # fp64), a few steps: the like-for-like CPU figure for the decode GB/s
+        import numpy as np
+        c4 = inputs.CONFIGS["c4_decode_b1"]
+        Ly = min(args.decode_layers, 64)
+        r = np.random.default_rng(5)
+        st = r.standard_normal((Ly, c4.batch, c4.nheads, c4.headdim, c4.dstate))
+        xs = r.standard_normal((Ly, c4.batch, c4.nheads, c4.headdim))
+        dts = r.uniform(1e-3, 1e-1, (Ly, c4.batch, c4.nheads))
+        Al = -r.uniform(1, 16, (Ly, c4.nheads))
+        Dl = r.standard_normal((Ly, c4.nheads))
+        Bl = 0.25 * r.standard_normal((Ly, c4.batch, c4.ngroups, c4.dstate))
+        Cl = 0.25 * r.standard_normal((Ly, c4.batch, c4.ngroups, c4.dstate))
+        ssd_oracle.decode_step_layers(st, xs, dts, Al, Bl, Cl, Dl)
+        t0 = time.perf_counter()
+        nst = 3
+        for _ in range(nst):
+            _, st = ssd_oracle.decode_step_layers(st, xs, dts, Al, Bl, Cl, Dl)
+        t_dec = (time.perf_counter() - t0) / nst
+        cpu["decode"] = dict(layers=Ly, batch=c4.batch, steps=nst, us_per_step=round(t_dec * 1e6, 1),
+                             state_gbs_fp64=round(2 * 8 * st.size / t_dec / 1e9, 2),
+                             note="fp64 state read and written once per step, as the oracle stands (it also "
+                                  "copies the state once per layer and step)")
+        log("[bench] cpu oracle decode: %.0f us/step, %.1f GB/s of fp64 state" % (t_dec * 1e6, 2 * 8 * st.size / t_dec / 1e9))
 
     out = {
         "metric": "ssd_prefill_tflops", "value": round(head["tflops_causal"], 3), "unit": "TFLOP/s",
