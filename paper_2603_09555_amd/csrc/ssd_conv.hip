@@ -18,7 +18,7 @@ namespace ssd {
 namespace {
 
 constexpr int kConvThreads = 256;
-constexpr int kRun = 32;  // tokens per thread in the prefill kernel
+constexpr int kRunMin = 16, kRunMax = 64;  // tokens per thread in the prefill kernel: chosen per launch
 
 // SiLU v / (1 + exp(-v)) with the hardware exp2 and reciprocal (each within 1 ulp): the kernels are
 // streams, and an IEEE division per element would make them ALU bound.
@@ -47,21 +47,22 @@ __device__ __forceinline__ typename Io::type *out_ptr(const ConvOut &o, size_t r
   return static_cast<typename Io::type *>(o.ptr[part]) + row * width + (c - o.begin[part]);
 }
 
-// One thread: VEC consecutive channels, kRun consecutive tokens.  Threads are numbered over (run of
+// One thread: VEC consecutive channels, `run` consecutive tokens.  Threads are numbered over (run of
 // tokens, channel group) without padding, channel group fastest: grid (ceil(runs * C / VEC / 256), 1, Bt).
 template <typename Io, int VEC, int K>
 __global__ __launch_bounds__(kConvThreads) void conv_prefill_kernel(
     const void *__restrict__ u, const float *__restrict__ w, const float *__restrict__ bias,
-    const void *__restrict__ state_in, ConvOut out, void *__restrict__ state_out, int T, int C, int act) {
+    const void *__restrict__ state_in, ConvOut out, void *__restrict__ state_out, int T, int C, int act,
+    int run_len) {
   using E = typename Io::type;
   const int groups = C / VEC;
   const unsigned gid = blockIdx.x * kConvThreads + threadIdx.x;
   const int run = static_cast<int>(gid / groups);
-  const int t0 = run * kRun;
+  const int t0 = run * run_len;
   if (t0 >= T) return;
   const int c0 = static_cast<int>(gid % groups) * VEC;
   const int b = blockIdx.z;
-  const int t1 = min(T, t0 + kRun);
+  const int t1 = min(T, t0 + run_len);
   float wt[VEC][K], bs[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) {
@@ -209,23 +210,45 @@ __global__ __launch_bounds__(kConvThreads) void conv_step_kernel(void *__restric
   Io::store(out.ptr[part], b * width + (c - out.begin[part]), act_apply(a, act));
 }
 
+// Tokens per thread: long runs amortise the k-1 rows a thread reads in front of its own and the
+// weights it loads, but the threads should also fill the chip a whole number of times (the kernel holds
+// five waves per SIMD): the length in [16, 64] with the least (rounds of waves) x (rows read per run).
+int choose_run(int T, size_t groups_total, int ksize) {
+  const double slots = 256.0 * 4 * 5 * 64;  // threads resident at once
+  int best = kRunMin;
+  double best_cost = 0.0;
+  for (int len = kRunMin; len <= kRunMax; ++len) {
+    const double runs = (T + len - 1) / len;
+    const double rounds = static_cast<double>(static_cast<long long>((runs * groups_total + slots - 1) / slots));
+    const double cost = rounds * (len + ksize - 1 + 4);  // + about four rows' worth of start-up per thread
+    if (len == kRunMin || cost < best_cost) {
+      best = len;
+      best_cost = cost;
+    }
+  }
+  return best;
+}
+
 template <typename Io, int K>
 hipError_t prefill_typed(int Bt, int T, int C, bool vec8, const void *u, const float *w, const float *bias,
                          const void *state_in, const ConvOut &out, void *state_out, int act, hipStream_t stream) {
-  const int runs = (T + kRun - 1) / kRun;
   if constexpr (sizeof(typename Io::type) == 2) {
     if (vec8) {
       constexpr int kV = 4;
+      const int run_len = choose_run(T, static_cast<size_t>(Bt) * (C / kV), K);
+      const int runs = (T + run_len - 1) / run_len;
       const dim3 grid(static_cast<unsigned>((static_cast<size_t>(runs) * (C / kV) + kConvThreads - 1) / kConvThreads), 1, Bt);
       hipLaunchKernelGGL((conv_prefill_kernel<Io, kV, K>), grid, dim3(kConvThreads), 0, stream, u, w, bias, state_in,
-                         out, state_out, T, C, act);
+                         out, state_out, T, C, act, run_len);
       return hipGetLastError();
     }
   }
   {
+    const int run_len = choose_run(T, static_cast<size_t>(Bt) * C, K);
+    const int runs = (T + run_len - 1) / run_len;
     const dim3 grid(static_cast<unsigned>((static_cast<size_t>(runs) * C + kConvThreads - 1) / kConvThreads), 1, Bt);
     hipLaunchKernelGGL((conv_prefill_kernel<Io, 1, K>), grid, dim3(kConvThreads), 0, stream, u, w, bias, state_in, out,
-                       state_out, T, C, act);
+                       state_out, T, C, act, run_len);
   }
   return hipGetLastError();
 }
