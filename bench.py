@@ -32,7 +32,7 @@ PEAK_VALU_F32_TFLOPS = 157.3     # fp32 vector
 PEAK_HBM_GBS = 8000.0
 
 
-# ---- algorithmic work (stated in the design doc) ---------------------------------------------------
+# ---- algorithmic work: what the method must compute, independent of how a kernel does it -------
 def chunk_lengths(T, L):
     L = min(L, T)
     full, tail = divmod(T, L)
