@@ -293,7 +293,9 @@ SSD_API ssd_status ssd_peak_probe(int32_t kind, int32_t iters, int32_t reps, voi
  * Name of the kernel family ssd_prefill would use for this shape:
  * "mfma_bf16" (MFMA contractions over LDS-staged tiles), "generic_f32"
  * (plain fp32 kernels, any shape), or "invalid".  Host-only.  The environment
- * variable SSD_FORCE_GENERIC=1 forces "generic_f32" (debugging aid).
+ * variable SSD_FORCE_GENERIC=1 forces "generic_f32" (debugging aid; it also
+ * changes the workspace sizes, so it must not change between a workspace
+ * query and the call it is for).
  */
 SSD_API const char *ssd_prefill_path(const ssd_shape *shape);
 

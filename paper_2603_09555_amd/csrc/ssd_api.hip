@@ -47,10 +47,9 @@ bool force_generic() {
 
 bool use_mfma(const Dims &d) { return !force_generic() && ssd::mfma_supported(d); }
 
+// The family that will run decides (SSD_FORCE_GENERIC must not change between the query and the call).
 size_t workspace_bytes(const Dims &d) {
-  const size_t g = ssd::generic_workspace_bytes(d);
-  const size_t m = ssd::mfma_supported(d) ? ssd::mfma_workspace_bytes(d) : 0;
-  return g > m ? g : m;  // large enough for either family, so forcing the generic one stays valid
+  return use_mfma(d) ? ssd::mfma_workspace_bytes(d) : ssd::generic_workspace_bytes(d);
 }
 
 ssd_status prefill_impl(const ssd_shape *shape, const void *x, const float *dt, const float *A,
@@ -159,9 +158,8 @@ bool use_mfma_varlen(const Dims &d) { return !force_generic() && ssd::mfma_varle
 size_t ssd_prefill_varlen_workspace_bytes(const ssd_shape *shape) {
   Dims d;
   if (make_dims(shape, false, &d, true) != SSD_OK) return 0;
-  const size_t m = ssd::mfma_varlen_supported(d) ? ssd::mfma_varlen_workspace_bytes(d) : 0;
-  const size_t g = generic_varlen_ok(d) ? ssd::generic_varlen_workspace_bytes(d) : 0;
-  return g > m ? g : m;  // large enough for either family (0: neither takes this shape)
+  if (use_mfma_varlen(d)) return ssd::mfma_varlen_workspace_bytes(d);
+  return generic_varlen_ok(d) ? ssd::generic_varlen_workspace_bytes(d) : 0;  // 0: neither family takes this shape
 }
 
 ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_seqlens, const void *x, const float *dt,

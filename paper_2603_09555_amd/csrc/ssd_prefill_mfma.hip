@@ -1194,14 +1194,20 @@ double rounds_time(long wgs, int blocks, double t_idle, double t_busy) {
 }
 // Most segments a plain batch may be cut into (the workspace holds one state slot per segment and
 // head): one per chunk, or -- short prompts, few heads -- one per block as long as that does not
-// exceed what fills the chip several times over.
+// exceed what fills the chip several times over; and never more than fill the chip four times over
+// (at least 64), which keeps the workspace of a very long prompt small: the choice below would not
+// take more anyway.
 int max_segments(const Dims &d) {
   const int nblocks = (d.T + kBlk - 1) / kBlk;
   const long groups = static_cast<long>(d.Bt) * (d.H * (d.P / kP) / kHeadsPerWg);
   long by_fill = (8L * kNumCUs + groups - 1) / groups;
   if (by_fill > 64) by_fill = 64;
   if (by_fill > nblocks) by_fill = nblocks;
-  return d.Nc > by_fill ? d.Nc : static_cast<int>(by_fill);
+  long most = (4L * kNumCUs + groups - 1) / groups;
+  if (most < 64) most = 64;
+  long s = d.Nc > by_fill ? d.Nc : by_fill;
+  if (s > most) s = most;
+  return static_cast<int>(s);
 }
 // min_blocks: the shortest segment allowed (packed batches size their tables for whole chunks).
 int choose_seg_blocks(const Dims &d, int min_blocks) {
@@ -1326,7 +1332,8 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   Dims one = d;  // the segment length of a packed batch is chosen as for one sequence of all its tokens
   if (varlen) one.Bt = 1;
   // shortest segment: a chunk for a packed batch; what the state slots allow for a plain one
-  const int seg_blocks = choose_seg_blocks(one, varlen ? d.L / kBlk : (w.NB + w.S_max - 1) / w.S_max);
+  int seg_blocks = choose_seg_blocks(one, varlen ? d.L / kBlk : (w.NB + w.S_max - 1) / w.S_max);
+  if (!varlen && (w.NB + seg_blocks - 1) / seg_blocks > w.S_max) seg_blocks = (w.NB + w.S_max - 1) / w.S_max;
 
   VarPlan vp = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
   int S = (w.NB + seg_blocks - 1) / seg_blocks;  // plain batch: segments per sequence
