@@ -450,6 +450,11 @@ struct ScanParams {
   float *seg_state;        // states-only: local end state of a segment -> the slot of the NEXT segment
   float *seg_decay;        // states-only: log2 of the segment's total decay, one per slot
   int T, H, G, hpg, NB, seg_blocks, S;  // H, hpg count 64-column slices
+  // The states-only pass may cut every segment into `parts` pieces of `part_blocks` blocks (more,
+  // shorter workgroups when the segments alone would leave most of the chip idle); the pass over
+  // segment states then chains the pieces, and a sequence has `slots` state slots, of which segment
+  // sg of the full scan starts from slot sg * parts.  Plain batches only; parts = 1 otherwise.
+  int parts, part_blocks, slots;
   int pdiv, Hrec;          // slices per head (headdim / 64); heads (owners of decay records, A, D)
   NSlice ns;               // columns of h0 / final_state (rows of ns.width floats) this launch works on
   int cols, segs, total, per_xcd;  // workgroup mapping, see wg_coords
@@ -489,8 +494,8 @@ __device__ __forceinline__ bool wg_coords(const ScanParams &p, bool last_too, Se
   v.len = static_cast<uint32_t>(p.T);
   v.blk0 = static_cast<size_t>(v.b) * p.NB;   // times G (tiles) or H (records) in the caller's stride
   v.blk_stride = p.NB;
-  v.slot0 = static_cast<size_t>(v.b) * p.S;
-  v.slot_stride = p.S;
+  v.slot0 = static_cast<size_t>(v.b) * p.slots;
+  v.slot_stride = p.slots;
   return true;
 }
 // Variable-length batch: the list (see varlen_fill_kernel) and with it the split over the XCDs come
@@ -616,8 +621,10 @@ void chunk_scan_kernel(const ScanParams p) {
   const size_t slot0 = plain ? (sv.slot0 * p.H + static_cast<size_t>(h) * sv.slot_stride) : (h * sv.slot_stride + sv.slot0);
   const size_t bh = static_cast<size_t>(sv.b) * p.H + h;  // row of final_state
   const int r = lane & 31, kg = lane >> 5;
-  const int jb0 = min(sv.nb, sg * p.seg_blocks);
-  const int jb1 = min(sv.nb, jb0 + p.seg_blocks);
+  // (the states-only pass walks a piece of a segment, the full scan a whole segment)
+  const int walk = kStatesOnly ? p.part_blocks : p.seg_blocks;
+  const int jb0 = min(sv.nb, sg * walk);
+  const int jb1 = min(sv.nb, jb0 + walk);
   const int cg = lane & 3, tg = lane >> 2;  // x staging: columns 8cg..8cg+7 of the half, tokens 4tg..4tg+3
   uint16_t *const myX = sXm[hw] + 32 * ph * kXStride;  // this wave's 32 rows of Xm^T
   uint16_t *const myRaw = sRaw[kStatesOnly ? 0 : wave];
@@ -767,7 +774,7 @@ void chunk_scan_kernel(const ScanParams p) {
     // one to write final_state, so the two may share memory); with several segments every segment,
     // the first included, starts from the slot that the pass over segment states has filled.
     if (sv.S > 1) {
-      hp = p.Hin + (slot0 + sg) * (kP * kN) + static_cast<size_t>(pcol) * kN;
+      hp = p.Hin + (slot0 + static_cast<size_t>(sg) * p.parts) * (kP * kN) + static_cast<size_t>(pcol) * kN;
     } else if (p.h0 != nullptr) {
       hp = p.h0 + (bh * kP + pcol) * p.ns.width + p.ns.off;
       hp_valid = p.ns.valid;
@@ -1209,8 +1216,25 @@ int max_segments(const Dims &d) {
   if (s > most) s = most;
   return static_cast<int>(s);
 }
+// Modelled time of the states-only pass plus the chain over state slots when each of the S - 1
+// segments it covers is cut into k pieces (see ScanParams::parts); the best k among the divisors of
+// the segment length, at most max_slots slots.  max_parts = 1: segments are not cut.
+double states_cost(long groups, double seqs, int S, int seg_blocks, int max_slots, int max_parts, int *parts) {
+  double best = 0.0;
+  *parts = 1;
+  for (int k = 1; k <= max_parts && k <= seg_blocks; ++k) {
+    if (seg_blocks % k != 0 || (k > 1 && (S - 1) * k + 1 > max_slots)) continue;
+    const double cost = rounds_time(groups * (S - 1) * k, seg_blocks / k, 1.16, 1.16) + 0.0261 * ((S - 1) * k + 1) * seqs;
+    if (k == 1 || cost < best) {
+      best = cost;
+      *parts = k;
+    }
+  }
+  return best;
+}
+
 // min_blocks: the shortest segment allowed (packed batches size their tables for whole chunks).
-int choose_seg_blocks(const Dims &d, int min_blocks) {
+int choose_seg_blocks(const Dims &d, int min_blocks, int max_slots, int max_parts) {
   const int chunk_blocks = d.L / kBlk;
   const int nblocks = (d.T + kBlk - 1) / kBlk;
   if (const char *e = std::getenv("SSD_SEG_CHUNKS")) {
@@ -1232,7 +1256,8 @@ int choose_seg_blocks(const Dims &d, int min_blocks) {
     const long segs = (nblocks + cand - 1) / cand;
     if (cand > min_blocks && (nblocks + cand - 2) / (cand - 1) == segs) continue;  // same count, longer segments
     double cost = rounds_time(groups * segs, cand, 2.57, 3.35);
-    if (segs > 1) cost += rounds_time(groups * (segs - 1), cand, 1.16, 1.16) + 3.1 + 0.0261 * segs * seqs + 7.0;
+    int parts;
+    if (segs > 1) cost += states_cost(groups, seqs, static_cast<int>(segs), cand, max_slots, max_parts, &parts) + 3.1 + 7.0;
     if (!have || cost < best) {
       have = true;
       best = cost;
@@ -1332,7 +1357,7 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   Dims one = d;  // the segment length of a packed batch is chosen as for one sequence of all its tokens
   if (varlen) one.Bt = 1;
   // shortest segment: a chunk for a packed batch; what the state slots allow for a plain one
-  int seg_blocks = choose_seg_blocks(one, varlen ? d.L / kBlk : (w.NB + w.S_max - 1) / w.S_max);
+  int seg_blocks = choose_seg_blocks(one, varlen ? d.L / kBlk : (w.NB + w.S_max - 1) / w.S_max, w.S_max, varlen ? 1 : 8);
   if (!varlen && (w.NB + seg_blocks - 1) / seg_blocks > w.S_max) seg_blocks = (w.NB + w.S_max - 1) / w.S_max;
 
   VarPlan vp = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
@@ -1382,13 +1407,24 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   p.NB = w.NB;
   p.seg_blocks = seg_blocks;
   p.S = S;
+  // pieces per segment for the states-only pass (see ScanParams): the split with the least modelled
+  // time of that pass plus the longer chain over state slots, among the divisors of the segment length
+  int parts = 1;
+  if (!varlen && S > 1) {
+    const long groups = static_cast<long>(d.Bt) * (d.H * (d.P / kP) / kHeadsPerWg);
+    const double seqs = static_cast<double>(d.Bt) * d.H * (d.P / kP);
+    (void)states_cost(groups, seqs, S, seg_blocks, w.S_max, 8, &parts);
+  }
+  p.parts = parts;
+  p.part_blocks = seg_blocks / parts;
+  p.slots = (S - 1) * parts + 1;
   p.vp = vp;
   if (varlen || S > 1) {
     // (a packed batch always takes this route: whether any sequence has more than one segment is
     // known on the device only; workgroups of last segments leave the states-only pass at once)
     constexpr int kStatesHeads = 4;  // heads per workgroup of the states-only kernel (2 was measured: slower)
     p.cols = Hs / kStatesHeads;
-    p.segs = S - 1;
+    p.segs = (S - 1) * parts;
     p.total = p.cols * p.segs * d.Bt;
     if (varlen) p.total = p.cols * items;
     p.per_xcd = (p.total + kXcds - 1) / kXcds;
@@ -1397,7 +1433,7 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
     trace_mark(trace, stream, "segment_states");
     const int rows_bh = d.Bt * Hs;  // a packed batch may have many one-segment sequences: rows are looped over
     hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), rows_bh > (varlen ? 2048 : 65535) ? (varlen ? 2048 : 65535) : rows_bh),
-                       dim3(kThreads), 0, stream, seg_state, seg_decay, h0, S, Hs, rows_bh, vp, ns);
+                       dim3(kThreads), 0, stream, seg_state, seg_decay, h0, p.slots, Hs, rows_bh, vp, ns);
     trace_mark(trace, stream, "segment_pass");
   }
   p.cols = Hs / kHeadsPerWg;
