@@ -1188,7 +1188,8 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
 // serial pass over segment states (traffic proportional to segments x sequences) and two launches.
 // The constants are a least-squares fit to 31 timed (shape, segment length) points of the three
 // bf16 benchmark shapes (residual 5 us rms).
-// SSD_SEG_CHUNKS=k forces k chunks per segment (tests), SSD_SEG_BLOCKS=k forces k blocks (tuning).
+// SSD_SEG_CHUNKS=k forces k chunks per segment (tests), SSD_SEG_BLOCKS=k forces k blocks and
+// SSD_SEG_PARTS=k forces k pieces per segment in the states-only pass (tuning).
 constexpr int kNumCUs = 256;
 double rounds_time(long wgs, int blocks, double t_idle, double t_busy) {
   double t = 0.0;
@@ -1414,6 +1415,10 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
     const long groups = static_cast<long>(d.Bt) * (d.H * (d.P / kP) / kHeadsPerWg);
     const double seqs = static_cast<double>(d.Bt) * d.H * (d.P / kP);
     (void)states_cost(groups, seqs, S, seg_blocks, w.S_max, 8, &parts);
+    if (const char *e = std::getenv("SSD_SEG_PARTS")) {  // tuning aid, like SSD_SEG_BLOCKS
+      const int k = std::atoi(e);
+      if (k >= 1 && seg_blocks % k == 0 && (S - 1) * k + 1 <= w.S_max) parts = k;
+    }
   }
   p.parts = parts;
   p.part_blocks = seg_blocks / parts;
