@@ -583,3 +583,65 @@ def test_peak_probes_run_and_the_copy_probe_copies(ssd):
         assert rate > 1e11
     rate, _ = ssd.peak_probe("mfma", a, None, iters=50, reps=2)
     assert rate > 1e13
+
+
+def _random_cases(seed, n):
+    """Seeded random shapes: MFMA-family and generic-family, plain and packed, with and without h0."""
+    r = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        mfma = bool(i % 2)
+        if mfma:
+            P = int(r.choice([64, 128]))
+            N = int(r.choice([32, 64, 128, 192, 256]))
+            G = int(r.choice([1, 2]))
+            H = G * int(r.choice([4, 8])) if P == 64 else G * int(r.choice([2, 4]))
+            L = int(r.choice([64, 128, 256]))
+            io = "bf16"
+        else:
+            P = int(r.integers(1, 80))
+            N = int(r.integers(1, 70))
+            G = int(r.choice([1, 2, 3]))
+            H = G * int(r.integers(1, 4))
+            L = int(r.integers(1, 200))
+            io = str(r.choice(["f32", "bf16"]))
+        nseq = int(r.integers(1, 5))
+        lens = [int(v) for v in r.integers(0, 400 if mfma else 150, nseq)]
+        if sum(lens) == 0:
+            lens[0] = 1 + int(r.integers(0, 100))
+        out.append((lens, H, P, N, G, L, io, bool(r.integers(0, 2)), int(r.integers(0, 3))))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_cases(2024, 24), ids=lambda c: "%s-%dx%dx%dx%dx%d-%s-h0%d-seg%d" % (
+    "+".join(map(str, c[0])), c[1], c[2], c[3], c[4], c[5], c[6], c[7], c[8]))
+def test_random_shapes_plain_and_packed(ssd, case, monkeypatch):
+    """Each random case runs packed (all sequences in one call) and plain (the longest sequence alone,
+    batch 1): both against the oracle."""
+    lens, H, P, N, G, L, io, with_h0, seg = case
+    if seg:
+        monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+    tol = TOL[io]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T, nseq = int(cu[-1]), len(lens)
+    cfg = cfg_of(1, T, H, P, N, G, L, io)
+    inp = inputs.make_prefill_inputs(cfg, seed=sum(lens) + H)
+    pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
+    h0 = inputs.make_state(cfg_of(nseq, 1, H, P, N, G, L, io), seed=3, scale=0.5) if with_h0 else None
+    print("random case", case, flush=True)
+    dev = {k: v.cuda() for k, v in pk.items()}
+    y, st = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
+                                   torch.from_numpy(cu).cuda(), L, h0=None if h0 is None else h0.cuda())
+    torch.cuda.synchronize()
+    y_ref, st_ref = ssd_oracle.prefill_varlen(pk["x"], pk["dt"], pk["A"], pk["B"], pk["C"], pk["D"], cu, h0=h0)
+    assert_close(y, y_ref, tol, "packed y")
+    assert_close(st, st_ref, tol, "packed states")
+    q = int(np.argmax(lens))
+    a, b = int(cu[q]), int(cu[q + 1])
+    # (clones: a slice of a contiguous tensor is a view at an offset that need not be 16-byte aligned)
+    yq, sq = ssd.ssd_prefill(dev["x"][None, a:b].clone(), dev["dt"][None, a:b].clone(), dev["A"],
+                             dev["B"][None, a:b].clone(), dev["C"][None, a:b].clone(), dev["D"], L,
+                             h0=None if h0 is None else h0[q:q + 1].cuda())
+    torch.cuda.synchronize()
+    assert_close(yq[0], y_ref[a:b], tol, "plain y")
+    assert_close(sq[0], st_ref[q], tol, "plain state")
