@@ -553,8 +553,12 @@ __device__ __forceinline__ Rsrc make_rsrc(const void *base, uint32_t bytes) {
 __device__ __forceinline__ u32x4 buf_load16(Rsrc r, uint32_t voff, uint32_t soff) {
   return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
 }
+// kPolicy is the instruction's cache-policy field: 0 = default (write-back through L2 and the memory-side
+// cache), kStreamStore = sc0 | nt, a non-temporal store that does not displace what those caches hold.
+constexpr int kStreamStore = 3;
+template <int kPolicy = 0>
 __device__ __forceinline__ void buf_store16(Rsrc r, uint32_t voff, u32x4 v) {
-  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, 0);
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, kPolicy);
 }
 
 // Waits until no vector memory operation of the wave is outstanding.  Used once, at the end of a
@@ -591,9 +595,13 @@ constexpr int kGTile = 32 * kGLowStride + 32 * kGStride;  // elements of a compa
 // HPW = heads per workgroup (two waves each).  Both kernels take four heads: the full kernel's LDS tiles
 // fill the CU; the states-only kernel could run two smaller workgroups per CU, but its grid then no
 // longer divides evenly over the CUs and the measured time was worse.
-template <bool kStatesOnly, int HPW>
+// kStreamY: y leaves with non-temporal stores, so that writing it does not evict x, which the states-only
+// pass has just pulled into the memory-side cache, before this kernel reads it again (chosen per launch,
+// see stream_y()).
+template <bool kStatesOnly, int HPW, bool kStreamY = false>
 __global__ __launch_bounds__(128 * HPW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void chunk_scan_kernel(const ScanParams p) {
+  static_assert(!(kStatesOnly && kStreamY), "the states-only pass writes no y");
   static_assert(kStatesOnly || HPW == kHeadsPerWg, "the full kernel is written for four heads per workgroup");
   constexpr int kThr = 128 * HPW;
   constexpr int kBtPieces = kN * kBlk * 2 / 16 / kThr;  // 16-byte pieces of the B^T tile per thread
@@ -1077,7 +1085,8 @@ void chunk_scan_kernel(const ScanParams p) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) yo[k] = *reinterpret_cast<const u32x4 *>(raw_dst_row + kRowStep * k * kRawStride);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) buf_store16(ry, vy + static_cast<uint32_t>(kRowStep * k) * xrow, yo[k]);
+        for (int k = 0; k < 4; ++k)
+          buf_store16<kStreamY ? kStreamStore : 0>(ry, vy + static_cast<uint32_t>(kRowStep * k) * xrow, yo[k]);
       }
       if constexpr (!kRowStores) {
         stage_raw(setA);
@@ -1340,6 +1349,21 @@ bool shape_ok(const Dims &d, unsigned long long tokens, unsigned long long nb) {
          nb * (kN * kBlk * 2) <= lim;
 }
 
+// Whether the full kernel writes y with non-temporal stores.  x is read twice, by the states-only pass and
+// again by the full kernel; the 256 MiB memory-side cache (Infinity Cache) keeps it in between unless the
+// y written meanwhile pushes it out.  Measured on the convolution -> prefill pipeline at 80 heads of 64
+// columns: x of 160 MiB, 7-14 % less time for the full kernel, 4-7 % for the pipeline; x of 180 MiB or
+// more, where x with the other operands no longer fits, 1-2 % slower; x below a quarter of the cache,
+// where x and y both fit, no difference, and the consumer of y is better off finding it cached.
+// SSD_Y_STREAM=0/1 overrides (tuning aid).
+constexpr unsigned long long kMemCacheBytes = 256ull << 20;
+bool stream_y(const Dims &d, const NSlice &ns, bool two_passes, int rows) {
+  if (const char *e = std::getenv("SSD_Y_STREAM")) return std::atoi(e) != 0;
+  if (!two_passes || ns.width > kN) return false;  // no second read of x; later state slices re-read y to add to it
+  const unsigned long long x_bytes = 2ull * rows * d.T * d.H * d.P;
+  return 4 * x_bytes > kMemCacheBytes && 3 * x_bytes <= 2 * kMemCacheBytes;
+}
+
 // d: plain batch (cu == nullptr), or Bt = number of sequences and T = total tokens of a packed batch.
 // One state slice ns (see NSlice): y and final_state columns of that slice are written.
 hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const void *x, const float *dt,
@@ -1446,7 +1470,12 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   p.total = p.cols * p.segs * d.Bt;
   if (varlen) p.total = p.cols * items;
   p.per_xcd = (p.total + kXcds - 1) / kXcds;
-  hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0, stream, p);
+  if (stream_y(d, ns, varlen || S > 1, rows))
+    hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg, true>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0,
+                       stream, p);
+  else
+    hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0, stream,
+                       p);
   trace_mark(trace, stream, "chunk_scan");
   return hipGetLastError();
 }

@@ -350,6 +350,65 @@ def test_mfma_and_generic_paths_agree(ssd, monkeypatch):
     assert_close(st, to_np64(stg), 2e-2, "mfma vs generic state")
 
 
+@pytest.mark.parametrize("case", [(2, 1000, 8, 64, 128, 2, 128, 2), (1, 700, 4, 128, 128, 1, 64, 1)],
+                         ids=lambda c: "x".join(map(str, c)))
+def test_cache_policy_of_the_y_stores_changes_no_bit(ssd, case, monkeypatch):
+    """The full kernel writes y with ordinary or with non-temporal stores, chosen from the size of x;
+    either way the result matches the oracle and the two agree bit for bit (plain and packed batches)."""
+    *dims, seg = case
+    cfg = cfg_of(*dims, "bf16")
+    monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+    outs = {}
+    for pol in ("0", "1"):
+        monkeypatch.setenv("SSD_Y_STREAM", pol)
+        print("y store policy", pol, case, flush=True)
+        inp, y, st = run_prefill(ssd, cfg, seed=31)
+        dev = {k: v.cuda() for k, v in inp.items()}
+        Bt, T = cfg.batch, cfg.seqlen
+        cu = torch.arange(0, Bt * T + 1, T, dtype=torch.int32, device="cuda")
+        flat = lambda t: t.reshape(Bt * T, *t.shape[2:]).contiguous()
+        yp, stp = ssd.ssd_prefill_varlen(flat(dev["x"]), flat(dev["dt"]), dev["A"], flat(dev["B"]), flat(dev["C"]),
+                                         dev["D"], cu, cfg.chunk)
+        torch.cuda.synchronize()
+        outs[pol] = (y.clone(), st.clone(), yp.clone(), stp.clone())
+    monkeypatch.delenv("SSD_Y_STREAM")
+    y_ref, st_ref = oracle_prefill(inp)
+    assert_close(outs["1"][0], y_ref, 2e-2, "streamed y")
+    assert_close(outs["1"][1], st_ref, 2e-2, "final state beside streamed y")
+    for a, b in zip(outs["0"], outs["1"]):
+        assert torch.equal(a, b)
+    assert_close(outs["1"][2].reshape(outs["1"][0].shape), y_ref, 2e-2, "streamed y, packed batch")
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+def test_cache_policy_of_the_decode_state_changes_no_bit(ssd, io, monkeypatch):
+    """The decode step streams the state past the caches when the states of the call exceed the memory-side
+    cache; forced on and off on a small call, both match the oracle and agree bit for bit."""
+    Ly, Bt, H, P, N, G = 3, 2, 8, 64, 128, 2
+    iod = torch.float32 if io == "f32" else torch.bfloat16
+    g = torch.Generator().manual_seed(19)
+    state = torch.randn((Ly, Bt, H, P, N), generator=g)
+    x = torch.randn((Ly, Bt, H, P), generator=g).to(iod)
+    dt = torch.rand((Ly, Bt, H), generator=g) * 0.1 + 1e-3
+    A = -(torch.rand((Ly, H), generator=g) * 15 + 1)
+    D = torch.randn((Ly, H), generator=g)
+    B = (0.25 * torch.randn((Ly, Bt, G, N), generator=g)).to(iod)
+    C = (0.25 * torch.randn((Ly, Bt, G, N), generator=g)).to(iod)
+    outs = {}
+    for pol in ("0", "1"):
+        monkeypatch.setenv("SSD_DECODE_STREAM", pol)
+        print("decode state policy", pol, io, flush=True)
+        sd = state.cuda().clone()
+        y = ssd.ssd_decode_step_layers(sd, x.cuda(), dt.cuda(), A.cuda(), B.cuda(), C.cuda(), D.cuda())
+        torch.cuda.synchronize()
+        outs[pol] = (y, sd)
+    monkeypatch.delenv("SSD_DECODE_STREAM")
+    y_ref, st_ref = ssd_oracle.decode_step_layers(state, x, dt, A, B, C, D)
+    assert_close(outs["1"][0], y_ref, TOL[io], "decode y, streamed state")
+    assert_close(outs["1"][1], st_ref, 1e-5, "decode state, streamed")
+    assert torch.equal(outs["0"][0], outs["1"][0]) and torch.equal(outs["0"][1], outs["1"][1])
+
+
 def test_mfma_extreme_decay_and_determinism(ssd):
     cfg = cfg_of(1, 640, 4, 64, 128, 1, 256, "bf16")
     inp = inputs.make_prefill_inputs(cfg, seed=31)
