@@ -384,7 +384,30 @@ def main():
                                bytes=nbytes, hbm_gbs=round(nbytes / us / 1e3, 1),
                                frac_of_hbm_peak=round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4))
         log("[bench] conv1d prefill (%d x %d channels): %.1f us, %.0f GB/s" % (cfg.seqlen, C, us, nbytes / us / 1e3))
-        del u, outs, cache
+        # the pair as a layer runs it: the convolution's outputs are the core's x, B and C
+        pin = inputs.make_prefill_inputs(cfg, seed=0, device=dev)
+        xv = outs[0].view(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim)
+        Bv = outs[1].view(cfg.batch, cfg.seqlen, cfg.ngroups, cfg.dstate)
+        Cv = outs[2].view(cfg.batch, cfg.seqlen, cfg.ngroups, cfg.dstate)
+        yp = torch.empty_like(xv)
+        stp = torch.empty((cfg.batch, cfg.nheads, cfg.headdim, cfg.dstate), dtype=torch.float32, device=dev)
+        wsp = torch.empty((max(ssd.prefill_workspace_bytes(shape_of(cfg)), 256),), dtype=torch.uint8, device=dev)
+
+        def pair():
+            call()
+            ssd.ssd_prefill(xv, pin["dt"], pin["A"], Bv, Cv, pin["D"], cfg.chunk, y=yp, final_state=stp, workspace=wsp)
+        for _ in range(3):
+            pair()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            pair()
+        e1.record()
+        torch.cuda.synchronize()
+        pair_us = e0.elapsed_time(e1) * 1e3 / args.steps
+        conv["prefill"]["conv_then_ssd_prefill_us"] = round(pair_us, 2)
+        log("[bench] conv1d prefill followed by ssd_prefill on its outputs: %.1f us" % pair_us)
+        del u, outs, cache, pin, xv, Bv, Cv, yp, stp, wsp
         torch.cuda.empty_cache()
 
     # ---- decode: 64 stacked layers, states seeded by a 2048-token prefill, 1024 steps ---------

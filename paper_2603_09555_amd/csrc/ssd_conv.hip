@@ -83,13 +83,18 @@ __global__ __launch_bounds__(kConvThreads) void conv_prefill_kernel(
   struct Raw {
     uint32_t w[VEC > 1 ? VEC / 2 : 1];  // VEC bf16 values
   };
+  // The input is read with non-temporal loads: it is used once, and what the memory-side cache holds
+  // after the kernel should be the outputs, which the SSD core reads next (measured on convolution ->
+  // prefill at 16384 tokens x 5376 channels: 6-8 % less for the pair, 16 % when the cache starts dirty).
+  typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+  typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
   auto load_raw = [&](const E *ptr) {
     Raw r;
     if constexpr (VEC == 8) {
-      const uint4 q = *reinterpret_cast<const uint4 *>(ptr);
+      const u32x4_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(ptr));
       r.w[0] = q.x, r.w[1] = q.y, r.w[2] = q.z, r.w[3] = q.w;
     } else if constexpr (VEC == 4) {
-      const uint2 q = *reinterpret_cast<const uint2 *>(ptr);
+      const u32x2_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t *>(ptr));
       r.w[0] = q.x, r.w[1] = q.y;
     }
     return r;
