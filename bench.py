@@ -81,8 +81,8 @@ def decode_flops(cfg, nlayers):
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a copy of known size gives on this chip; see
 # profiles/hbm_traffic_fetch_write_size.txt).  Measured values, not computed here: null for others.
 HBM_TRAFFIC_BYTES = {
-    ("c3_2p7b_long", "chunk_scan"): int((2 * 110494.4 + 166413.4) * 1024),
-    ("c3_2p7b_long", "segment_states"): int((2 * 85116.5 + 28187.9) * 1024),
+    ("c3_2p7b_long", "chunk_scan"): int((2 * 109647.3 + 166425.2) * 1024),
+    ("c3_2p7b_long", "segment_states"): int((2 * 85108.1 + 28185.8) * 1024),
 }
 
 # Which algorithmic FLOPs each kernel of a prefill call is responsible for.
@@ -201,7 +201,7 @@ def main():
     if not args.no_peaks:
         pa = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
         pb = torch.empty_like(pa)
-        for kind in ("copy", "read", "write"):
+        for kind in ("copy", "read", "write", "copy_nt", "read_nt", "write_nt"):
             rate, ms = ssd.peak_probe(kind, pa, pb, reps=10)
             peaks["stream_%s_gbs" % kind] = round(rate / 1e9, 1)
         for label, iters in (("short", 300), ("long", 4000)):

@@ -281,6 +281,8 @@ SSD_API ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, co
  *   kind 1   streaming copy of `bytes` bytes from `a` to `b` (16 bytes per lane)
  *   kind 2   streaming read of `a` (b: 16 bytes of scratch)
  *   kind 3   streaming write of `b` (a: any valid device pointer)
+ *   kind 4..6  as 1..3 with non-temporal loads and stores (what the decode step
+ *            uses for a state larger than the memory-side cache)
  * One warm-up launch, then `reps` launches back to back; *ms (HOST) = their
  * total time in milliseconds, *work (HOST) = flops (kind 0) or bytes moved
  * (read + written) of ONE launch.

@@ -285,7 +285,7 @@ ssd_status ssd_conv1d_step(int32_t batch, int32_t ksize, int32_t io_dtype, const
 ssd_status ssd_peak_probe(int32_t kind, int32_t iters, int32_t reps, void *a, void *b, size_t bytes, float *ms,
                           double *work, void *hip_stream) {
   if (!ms || !work || !a) return SSD_ERR_NULL;
-  if (kind < 0 || kind > 3 || reps < 1 || reps > 100000) return SSD_ERR_SHAPE;
+  if (kind < 0 || kind > 6 || reps < 1 || reps > 100000) return SSD_ERR_SHAPE;
   if (kind == 0 && (iters < 1 || bytes < static_cast<size_t>(2048) * 256 * sizeof(float))) return SSD_ERR_SHAPE;
   if (kind != 0 && !b) return SSD_ERR_NULL;
   if (kind != 0 && bytes < 16) return SSD_ERR_SHAPE;

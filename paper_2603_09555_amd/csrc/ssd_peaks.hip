@@ -35,9 +35,31 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(float *__restrict__ sink
   sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = s;
 }
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <bool kNt>
+__device__ __forceinline__ uint4 ld16(const uint4 *p) {
+  if constexpr (kNt) {
+    const u32x4_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(q.x, q.y, q.z, q.w);
+  } else {
+    return *p;
+  }
+}
+template <bool kNt>
+__device__ __forceinline__ void st16(uint4 *p, const uint4 v) {
+  if constexpr (kNt) {
+    const u32x4_t q = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(q, reinterpret_cast<u32x4_t *>(p));
+  } else {
+    *p = v;
+  }
+}
+
 // 16 bytes per lane per step, consecutive lanes on consecutive addresses; eight steps are requested
 // before the first is used.  mode 0: copy (read src, write dst); 1: read only (a sum is
-// written once per thread); 2: write only.
+// written once per thread); 2: write only.  kNt: non-temporal loads and stores, the accesses the
+// decode step uses for a state that no cache can hold.
+template <bool kNt>
 __global__ __launch_bounds__(256) void stream_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n,
                                                      int mode) {
   // a workgroup takes 32 KB slabs (eight consecutive 4 KB rows of 256 lanes x 16 bytes), grid-stride
@@ -49,14 +71,14 @@ __global__ __launch_bounds__(256) void stream_kernel(const uint4 *__restrict__ s
     uint4 v[8];
     if (mode != 2) {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] = src[i + k * 256];
+      for (int k = 0; k < 8; ++k) v[k] = ld16<kNt>(src + i + k * 256);
     } else {
 #pragma unroll
       for (int k = 0; k < 8; ++k) v[k] = make_uint4(static_cast<uint32_t>(i), k, 2, 3);
     }
     if (mode != 1) {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) dst[i + k * 256] = v[k];
+      for (int k = 0; k < 8; ++k) st16<kNt>(dst + i + k * 256, v[k]);
     } else {
 #pragma unroll
       for (int k = 0; k < 8; ++k) keep += v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
@@ -64,8 +86,8 @@ __global__ __launch_bounds__(256) void stream_kernel(const uint4 *__restrict__ s
   }
   for (size_t i = slabs * slab + static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
        i += static_cast<size_t>(gridDim.x) * 256) {
-    uint4 v = mode != 2 ? src[i] : make_uint4(static_cast<uint32_t>(i), 1, 2, 3);
-    if (mode != 1) dst[i] = v; else keep += v.x ^ v.y ^ v.z ^ v.w;
+    uint4 v = mode != 2 ? ld16<kNt>(src + i) : make_uint4(static_cast<uint32_t>(i), 1, 2, 3);
+    if (mode != 1) st16<kNt>(dst + i, v); else keep += v.x ^ v.y ^ v.z ^ v.w;
   }
   if (mode == 1 && keep == 0x12345678u) dst[0] = make_uint4(keep, 0, 0, 0);  // (practically never) keeps the loads alive
 }
@@ -73,7 +95,7 @@ __global__ __launch_bounds__(256) void stream_kernel(const uint4 *__restrict__ s
 }  // namespace
 
 // kind 0: MFMA loop (work = iters; buffer a: at least 2048 * 256 floats).  kinds 1..3: copy / read /
-// write of `bytes` bytes (a = source, b = destination).  Returns the elapsed milliseconds of `reps`
+// write of `bytes` bytes (a = source, b = destination); kinds 4..6: the same, non-temporal.  Returns the elapsed milliseconds of `reps`
 // back-to-back launches in *ms and the work of ONE launch (flops or bytes moved) in *work.
 hipError_t run_peak_probe(int kind, int iters, int reps, void *a, void *b, size_t bytes, float *ms, double *work,
                           hipStream_t stream) {
@@ -89,9 +111,12 @@ hipError_t run_peak_probe(int kind, int iters, int reps, void *a, void *b, size_
   auto once = [&]() {
     if (kind == 0)
       hipLaunchKernelGGL(mfma_loop_kernel, dim3(wgs), dim3(256), 0, stream, static_cast<float *>(a), iters);
-    else
-      hipLaunchKernelGGL(stream_kernel, dim3(wgs * 2), dim3(256), 0, stream, static_cast<const uint4 *>(a),
+    else if (kind <= 3)
+      hipLaunchKernelGGL(stream_kernel<false>, dim3(wgs * 2), dim3(256), 0, stream, static_cast<const uint4 *>(a),
                          static_cast<uint4 *>(b), bytes / 16, kind - 1);
+    else
+      hipLaunchKernelGGL(stream_kernel<true>, dim3(wgs * 2), dim3(256), 0, stream, static_cast<const uint4 *>(a),
+                         static_cast<uint4 *>(b), bytes / 16, kind - 4);
   };
   once();  // warm-up
   (void)hipEventRecord(e0, stream);
@@ -105,7 +130,7 @@ hipError_t run_peak_probe(int kind, int iters, int reps, void *a, void *b, size_
   if (kind == 0)
     *work = static_cast<double>(wgs) * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
   else
-    *work = static_cast<double>(bytes / 16 * 16) * (kind == 1 ? 2.0 : 1.0);
+    *work = static_cast<double>(bytes / 16 * 16) * (kind == 1 || kind == 4 ? 2.0 : 1.0);
   return e;
 }
 

@@ -320,10 +320,11 @@ def ssd_conv1d_step(conv_state, u, weight, bias=None, split=None, activation="si
 
 def peak_probe(kind, a, b=None, iters=0, reps=1):
     """``ssd_peak_probe``: returns ``(work per second, milliseconds per launch)`` -- flop/s for
-    ``kind="mfma"``, bytes/s for ``"copy"``, ``"read"``, ``"write"``.  ``a``, ``b``: device tensors."""
-    k = {"mfma": 0, "copy": 1, "read": 2, "write": 3}[kind]
+    ``kind="mfma"``, bytes/s for ``"copy"``, ``"read"``, ``"write"`` and their non-temporal forms
+    ``"copy_nt"``, ``"read_nt"``, ``"write_nt"``.  ``a``, ``b``: device tensors."""
+    k = {"mfma": 0, "copy": 1, "read": 2, "write": 3, "copy_nt": 4, "read_nt": 5, "write_nt": 6}[kind]
     ms, work = ctypes.c_float(0), ctypes.c_double(0)
-    nbytes = a.numel() * a.element_size() if k in (0, 1, 2) else b.numel() * b.element_size()
+    nbytes = a.numel() * a.element_size() if k in (0, 1, 2, 4, 5) else b.numel() * b.element_size()
     _check_dev(a, b)
     st = _lib.ssd_peak_probe(k, iters, reps, _ptr(a), _ptr(b), nbytes, ctypes.byref(ms), ctypes.byref(work),
                              _stream_ptr())

@@ -156,7 +156,7 @@ def test_peak_probe_rejects_before_any_hip_call(ssd):
         return lib.ssd_peak_probe(kind, iters, reps, a, b, ctypes.c_size_t(nbytes), ms_, ctypes.byref(work), None)
 
     assert call(ms_=None) == -1 and call(a=None) == -1 and call(b=None) == -1
-    assert call(kind=4) == -2 and call(kind=-1) == -2 and call(reps=0) == -2 and call(nbytes=8) == -2
+    assert call(kind=7) == -2 and call(kind=-1) == -2 and call(reps=0) == -2 and call(nbytes=8) == -2
     assert call(kind=0, iters=0) == -2 and call(kind=0, nbytes=1024) == -2      # scratch too small for the MFMA loop
     assert call(a=ctypes.c_void_p(4100)) == -7
 

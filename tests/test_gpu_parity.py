@@ -637,9 +637,14 @@ def test_peak_probes_run_and_the_copy_probe_copies(ssd):
     ssd.peak_probe("copy", odd, out)
     torch.cuda.synchronize()
     assert torch.equal(odd, out)
-    for kind in ("read", "write"):
+    for kind in ("read", "write", "read_nt", "write_nt"):
         rate, _ = ssd.peak_probe(kind, a, b, reps=2)
         assert rate > 1e11
+    b.zero_()
+    ssd.peak_probe("copy_nt", a, b)
+    ssd.peak_probe("copy_nt", odd, out.zero_())
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(odd, out)
     rate, _ = ssd.peak_probe("mfma", a, None, iters=50, reps=2)
     assert rate > 1e13
 
