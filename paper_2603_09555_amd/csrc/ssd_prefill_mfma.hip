@@ -615,6 +615,10 @@ void chunk_scan_kernel(const ScanParams p) {
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: addresses derived from it stay scalar
   const int hw = wave >> 1, ph = wave & 1;  // head inside the workgroup, half of headdim
+  // Waves w and w + 4 of the workgroup share a SIMD.  Giving one of the two the higher issue priority
+  // for the whole kernel lets it run ahead between barriers instead of both contending for the same
+  // pipe in the same phase (measured: 3 % on 8 x 4096 tokens x 48 heads, nothing lost elsewhere).
+  if (wave >= 4) __builtin_amdgcn_s_setprio(1);
   SeqView sv;
   if (!wg_coords(p, !kStatesOnly, sv)) return;  // uniform over the workgroup
   const int col = sv.col, sg = sv.sg;
