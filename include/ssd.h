@@ -167,6 +167,20 @@ SSD_API ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_
                               void *hip_stream);
 
 /*
+ * ssd_prefill_varlen with the step-size activation of ssd_prefill_dt fused in
+ * (Alg. 1, "Discretise"): dt = clamp(softplus(dt_raw + dt_bias[h]), dt_min,
+ * dt_max) wherever ssd_prefill_varlen uses dt.  Same workspace size, results
+ * and errors as ssd_prefill_varlen; SSD_ERR_NULL if dt_transform is NULL,
+ * SSD_ERR_SHAPE if dt_max > 0 and dt_min > dt_max.
+ */
+SSD_API ssd_status ssd_prefill_varlen_dt(const ssd_shape *shape, const ssd_dt_transform *dt_transform,
+                                 const int32_t *cu_seqlens, const void *x,
+                                 const float *dt_raw, const float *A, const void *B,
+                                 const void *C, const float *D, const float *h0,
+                                 void *y, float *final_state, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream);
+
+/*
  * One cached decode step (Alg. 2, "Discretise" + "SSM step"; output per Eq. 2),
  * for every (batch row, head):
  *     dA      = exp(dt * A_h)
@@ -215,6 +229,26 @@ SSD_API ssd_status ssd_decode_steps_layers(int32_t nsteps, int32_t nlayers, cons
                                    float *state, const void *x, const float *dt,
                                    const float *A, const void *B, const void *C,
                                    const float *D, void *y, void *hip_stream);
+
+/*
+ * The two decode entry points above with the step-size activation fused in
+ * (Alg. 2, "Discretise": the step applies softplus to the projected dt plus its
+ * bias before it forms exp(dt * A)): the kernels read the raw projection output
+ * and use dt = clamp(softplus(dt_raw + dt_bias[layer][h]), dt_min, dt_max).
+ * dt_transform as for ssd_prefill_dt, except that dt_bias is a DEVICE array
+ * (nlayers, nheads).  Errors as the plain entry points, plus SSD_ERR_NULL if
+ * dt_transform is NULL and SSD_ERR_SHAPE if dt_max > 0 and dt_min > dt_max.
+ */
+SSD_API ssd_status ssd_decode_step_layers_dt(int32_t nlayers, const ssd_shape *shape,
+                                     const ssd_dt_transform *dt_transform, float *state,
+                                     const void *x, const float *dt_raw, const float *A,
+                                     const void *B, const void *C, const float *D,
+                                     void *y, void *hip_stream);
+SSD_API ssd_status ssd_decode_steps_layers_dt(int32_t nsteps, int32_t nlayers, const ssd_shape *shape,
+                                      const ssd_dt_transform *dt_transform, float *state,
+                                      const void *x, const float *dt_raw, const float *A,
+                                      const void *B, const void *C, const float *D,
+                                      void *y, void *hip_stream);
 
 /*
  * The step in front of the SSD core: the depthwise causal convolution of a

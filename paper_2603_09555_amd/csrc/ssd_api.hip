@@ -52,6 +52,17 @@ size_t workspace_bytes(const Dims &d) {
   return use_mfma(d) ? ssd::mfma_workspace_bytes(d) : ssd::generic_workspace_bytes(d);
 }
 
+// Copies the caller's step-size map into the validated dimensions (nullptr: dt is used as given).
+ssd_status set_dt_transform(Dims *d, const ssd_dt_transform *dtx) {
+  if (dtx == nullptr) return SSD_OK;
+  if (dtx->dt_max > 0.f && !(dtx->dt_min <= dtx->dt_max)) return SSD_ERR_SHAPE;
+  d->dtx.bias = dtx->dt_bias;
+  d->dtx.softplus = dtx->dt_softplus != 0;
+  d->dtx.lo = dtx->dt_min;
+  d->dtx.hi = dtx->dt_max;
+  return SSD_OK;
+}
+
 ssd_status prefill_impl(const ssd_shape *shape, const void *x, const float *dt, const float *A,
                         const void *B, const void *C, const float *D, const float *h0, void *y,
                         float *final_state, void *workspace, size_t workspace_bytes_given,
@@ -59,13 +70,8 @@ ssd_status prefill_impl(const ssd_shape *shape, const void *x, const float *dt, 
   Dims d;
   const ssd_status st = make_dims(shape, false, &d);
   if (st != SSD_OK) return st;
-  if (dtx != nullptr) {
-    if (dtx->dt_max > 0.f && !(dtx->dt_min <= dtx->dt_max)) return SSD_ERR_SHAPE;
-    d.dtx.bias = dtx->dt_bias;
-    d.dtx.softplus = dtx->dt_softplus != 0;
-    d.dtx.lo = dtx->dt_min;
-    d.dtx.hi = dtx->dt_max;
-  }
+  const ssd_status sx = set_dt_transform(&d, dtx);
+  if (sx != SSD_OK) return sx;
   if (!x || !dt || !A || !B || !C || !D || !y || !final_state) return SSD_ERR_NULL;
   if (!aligned16(x) || !aligned16(dt) || !aligned16(B) || !aligned16(C) || !aligned16(y) ||
       !aligned16(final_state) || (h0 && !aligned16(h0)))
@@ -162,13 +168,15 @@ size_t ssd_prefill_varlen_workspace_bytes(const ssd_shape *shape) {
   return generic_varlen_ok(d) ? ssd::generic_varlen_workspace_bytes(d) : 0;  // 0: neither family takes this shape
 }
 
-ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_seqlens, const void *x, const float *dt,
-                              const float *A, const void *B, const void *C, const float *D, const float *h0,
-                              void *y, float *final_state, void *workspace, size_t workspace_bytes_given,
-                              void *hip_stream) {
+namespace {
+ssd_status varlen_impl(const ssd_shape *shape, const ssd_dt_transform *dtx, const int32_t *cu_seqlens, const void *x,
+                       const float *dt, const float *A, const void *B, const void *C, const float *D, const float *h0,
+                       void *y, float *final_state, void *workspace, size_t workspace_bytes_given, void *hip_stream) {
   Dims d;  // batch = number of sequences, seqlen = total tokens
   const ssd_status st = make_dims(shape, false, &d, true);
   if (st != SSD_OK) return st;
+  const ssd_status sx = set_dt_transform(&d, dtx);
+  if (sx != SSD_OK) return sx;
   if (!cu_seqlens || !x || !dt || !A || !B || !C || !D || !y || !final_state) return SSD_ERR_NULL;
   if (!aligned16(x) || !aligned16(dt) || !aligned16(B) || !aligned16(C) || !aligned16(y) ||
       !aligned16(final_state) || (h0 && !aligned16(h0)) || (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u))
@@ -185,40 +193,80 @@ ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_seqlens,
                                                 stream);
   return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
 }
+}  // namespace
+
+ssd_status ssd_prefill_varlen(const ssd_shape *shape, const int32_t *cu_seqlens, const void *x, const float *dt,
+                              const float *A, const void *B, const void *C, const float *D, const float *h0,
+                              void *y, float *final_state, void *workspace, size_t workspace_bytes_given,
+                              void *hip_stream) {
+  return varlen_impl(shape, nullptr, cu_seqlens, x, dt, A, B, C, D, h0, y, final_state, workspace,
+                     workspace_bytes_given, hip_stream);
+}
+
+ssd_status ssd_prefill_varlen_dt(const ssd_shape *shape, const ssd_dt_transform *dt_transform,
+                                 const int32_t *cu_seqlens, const void *x, const float *dt_raw, const float *A,
+                                 const void *B, const void *C, const float *D, const float *h0, void *y,
+                                 float *final_state, void *workspace, size_t workspace_bytes_given,
+                                 void *hip_stream) {
+  if (!dt_transform) return SSD_ERR_NULL;
+  return varlen_impl(shape, dt_transform, cu_seqlens, x, dt_raw, A, B, C, D, h0, y, final_state, workspace,
+                     workspace_bytes_given, hip_stream);
+}
+
+namespace {
+ssd_status decode_impl(int32_t nsteps, int32_t nlayers, const ssd_shape *shape, const ssd_dt_transform *dtx,
+                       float *state, const void *x, const float *dt, const float *A, const void *B, const void *C,
+                       const float *D, void *y, void *hip_stream, bool multi);
+}  // namespace
 
 ssd_status ssd_decode_step_layers(int32_t nlayers, const ssd_shape *shape, float *state, const void *x,
                                   const float *dt, const float *A, const void *B, const void *C,
                                   const float *D, void *y, void *hip_stream) {
-  Dims d;
-  const ssd_status st = make_dims(shape, true, &d);
-  if (st != SSD_OK) return st;
-  if (nlayers < 1) return SSD_ERR_SHAPE;
-  const long double pairs = static_cast<long double>(nlayers) * d.Bt * d.H;
-  if (pairs > 2.0e9L) return SSD_ERR_SHAPE;  // one workgroup per (layer, batch row, head)
-  if (!state || !x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
-  if (!aligned16(state) || !aligned16(x) || !aligned16(B) || !aligned16(C) || !aligned16(y))
-    return SSD_ERR_ALIGN;
-  const hipError_t e = ssd::launch_decode(nlayers, d, state, x, dt, A, B, C, D, y,
-                                          static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
+  return decode_impl(1, nlayers, shape, nullptr, state, x, dt, A, B, C, D, y, hip_stream, false);
+}
+
+ssd_status ssd_decode_step_layers_dt(int32_t nlayers, const ssd_shape *shape, const ssd_dt_transform *dt_transform,
+                                     float *state, const void *x, const float *dt_raw, const float *A,
+                                     const void *B, const void *C, const float *D, void *y, void *hip_stream) {
+  if (!dt_transform) return SSD_ERR_NULL;
+  return decode_impl(1, nlayers, shape, dt_transform, state, x, dt_raw, A, B, C, D, y, hip_stream, false);
 }
 
 ssd_status ssd_decode_steps_layers(int32_t nsteps, int32_t nlayers, const ssd_shape *shape, float *state,
                                    const void *x, const float *dt, const float *A, const void *B, const void *C,
                                    const float *D, void *y, void *hip_stream) {
+  return decode_impl(nsteps, nlayers, shape, nullptr, state, x, dt, A, B, C, D, y, hip_stream, true);
+}
+
+ssd_status ssd_decode_steps_layers_dt(int32_t nsteps, int32_t nlayers, const ssd_shape *shape,
+                                      const ssd_dt_transform *dt_transform, float *state, const void *x,
+                                      const float *dt_raw, const float *A, const void *B, const void *C,
+                                      const float *D, void *y, void *hip_stream) {
+  if (!dt_transform) return SSD_ERR_NULL;
+  return decode_impl(nsteps, nlayers, shape, dt_transform, state, x, dt_raw, A, B, C, D, y, hip_stream, true);
+}
+
+namespace {
+ssd_status decode_impl(int32_t nsteps, int32_t nlayers, const ssd_shape *shape, const ssd_dt_transform *dtx,
+                       float *state, const void *x, const float *dt, const float *A, const void *B, const void *C,
+                       const float *D, void *y, void *hip_stream, bool multi) {
   Dims d;
   const ssd_status st = make_dims(shape, true, &d);
   if (st != SSD_OK) return st;
+  const ssd_status sx = set_dt_transform(&d, dtx);
+  if (sx != SSD_OK) return sx;
   if (nlayers < 1 || nsteps < 1) return SSD_ERR_SHAPE;
   const long double pairs = static_cast<long double>(nlayers) * d.Bt * d.H;
-  if (pairs > 2.0e9L || pairs * d.P * nsteps > 1.0e15L) return SSD_ERR_SHAPE;
+  if (pairs > 2.0e9L || pairs * d.P * nsteps > 1.0e15L) return SSD_ERR_SHAPE;  // one workgroup per (layer, batch row, head)
   if (!state || !x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
   if (!aligned16(state) || !aligned16(x) || !aligned16(B) || !aligned16(C) || !aligned16(y))
     return SSD_ERR_ALIGN;
-  const hipError_t e = ssd::launch_decode_steps(nsteps, nlayers, d, state, x, dt, A, B, C, D, y,
-                                                static_cast<hipStream_t>(hip_stream));
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const hipError_t e = multi ? ssd::launch_decode_steps(nsteps, nlayers, d, state, x, dt, A, B, C, D, y, stream)
+                             : ssd::launch_decode(nlayers, d, state, x, dt, A, B, C, D, y, stream);
   return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
 }
+}  // namespace
 
 ssd_status ssd_decode_step(const ssd_shape *shape, float *state, const void *x, const float *dt,
                            const float *A, const void *B, const void *C, const float *D, void *y,

@@ -91,7 +91,8 @@ template <typename Io, int LPR, bool kStream>
 __global__ __launch_bounds__(kDecodeThreads) void decode_vec_kernel(
     float *__restrict__ state, const void *__restrict__ x, const float *__restrict__ dt,
     const float *__restrict__ A, const void *__restrict__ B, const void *__restrict__ C,
-    const float *__restrict__ D, void *__restrict__ y, int BtH, int H, int P, int G, int hpg) {
+    const float *__restrict__ D, void *__restrict__ y, int BtH, int H, int P, int G, int hpg,
+    const DtXform dtx) {
   constexpr int N = LPR * 4;
   constexpr int RPP = kDecodeThreads / LPR;  // rows per pass
   const size_t pair = blockIdx.x;            // (layer*Bt + b)*H + h
@@ -105,7 +106,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_vec_kernel(
   const int lane_n = threadIdx.x % LPR;
   const int row0 = threadIdx.x / LPR;
 
-  const float dtv = dt[pair];
+  const float dtv = dt_apply(dt[pair], layer * H + h, dtx);
   const float Ah = A[static_cast<size_t>(layer) * H + h];
   const float Dh = D[static_cast<size_t>(layer) * H + h];
   const float dA = expf(dtv * Ah);
@@ -150,14 +151,15 @@ template <typename Io>
 __global__ __launch_bounds__(kDecodeThreads) void decode_any_kernel(
     float *__restrict__ state, const void *__restrict__ x, const float *__restrict__ dt,
     const float *__restrict__ A, const void *__restrict__ B, const void *__restrict__ C,
-    const float *__restrict__ D, void *__restrict__ y, int BtH, int H, int P, int N, int G, int hpg) {
+    const float *__restrict__ D, void *__restrict__ y, int BtH, int H, int P, int N, int G, int hpg,
+    const DtXform dtx) {
   const size_t pair = blockIdx.x;
   const int h = static_cast<int>(pair % H);
   const size_t lb = pair / H;
   const int layer = static_cast<int>(pair / BtH);
   const int lane = threadIdx.x % 64;
   const int wave = threadIdx.x / 64;
-  const float dtv = dt[pair];
+  const float dtv = dt_apply(dt[pair], layer * H + h, dtx);
   const float dA = expf(dtv * A[static_cast<size_t>(layer) * H + h]);
   const float Dh = D[static_cast<size_t>(layer) * H + h];
   const size_t bc = (lb * G + h / hpg) * static_cast<size_t>(N);
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_steps_kernel(
     float *__restrict__ state, const void *__restrict__ x, const float *__restrict__ dt,
     const float *__restrict__ A, const void *__restrict__ B, const void *__restrict__ C,
     const float *__restrict__ D, void *__restrict__ y, int nsteps, size_t npairs, size_t nbc, int BtH,
-    int H, int G, int hpg) {
+    int H, int G, int hpg, const DtXform dtx) {
   constexpr int N = LPR * 4 * NV;
   constexpr int RPP = kDecodeThreads / LPR;
   constexpr int P = ROWS * RPP;
@@ -219,6 +221,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_steps_kernel(
   const int row0 = threadIdx.x / LPR;
   const float Ah = A[static_cast<size_t>(layer) * H + h];
   const float Dh = D[static_cast<size_t>(layer) * H + h];
+  const float dt_bias = dtx.bias != nullptr ? dtx.bias[static_cast<size_t>(layer) * H + h] : 0.f;
   const size_t bc = (lb * G + h / hpg) * N + lane_n * 4;
   const size_t bc_step = nbc * N;  // elements of B (or C) per step
 
@@ -251,7 +254,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_steps_kernel(
   };
   auto step = [&](int s, const StepIn &c, StepIn &n) __attribute__((always_inline)) {
     request(n, s + 1 < nsteps ? s + 1 : s);  // the surplus loads of the last step are not used
-    const float dA = expf(c.dt * Ah);
+    const float dtv = dt_apply_biased(c.dt, dt_bias, dtx);
+    const float dA = expf(dtv * Ah);
     float4 Bv[NV], Cv[NV];
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
@@ -260,7 +264,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_steps_kernel(
     }
 #pragma unroll
     for (int u = 0; u < ROWS; ++u) {
-      const float ux = c.dt * c.x[u];
+      const float ux = dtv * c.x[u];
       float part = 0.f;
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
@@ -312,11 +316,11 @@ hipError_t launch_typed(int nlayers, const Dims &d, float *state, const void *x,
     if (stream_state)                                                                                    \
       hipLaunchKernelGGL((decode_vec_kernel<Io, LPR_, true>),                                            \
                          dim3(static_cast<unsigned>(npairs), split_for(kDecodeThreads / LPR_)), block, 0, \
-                         stream, state, x, dt, A, B, C, D, y, BtH, d.H, d.P, d.G, d.hpg);                \
+                         stream, state, x, dt, A, B, C, D, y, BtH, d.H, d.P, d.G, d.hpg, d.dtx);         \
     else                                                                                                 \
       hipLaunchKernelGGL((decode_vec_kernel<Io, LPR_, false>),                                           \
                          dim3(static_cast<unsigned>(npairs), split_for(kDecodeThreads / LPR_)), block, 0, \
-                         stream, state, x, dt, A, B, C, D, y, BtH, d.H, d.P, d.G, d.hpg);                \
+                         stream, state, x, dt, A, B, C, D, y, BtH, d.H, d.P, d.G, d.hpg, d.dtx);         \
     break;
   if (d.N % 4 == 0) {
     switch (d.N / 4) {
@@ -329,11 +333,11 @@ hipError_t launch_typed(int nlayers, const Dims &d, float *state, const void *x,
       SSD_DECODE_CASE(64)
       default:
         hipLaunchKernelGGL((decode_any_kernel<Io>), grid, block, 0, stream, state, x, dt, A, B, C, D, y,
-                           BtH, d.H, d.P, d.N, d.G, d.hpg);
+                           BtH, d.H, d.P, d.N, d.G, d.hpg, d.dtx);
     }
   } else {
     hipLaunchKernelGGL((decode_any_kernel<Io>), grid, block, 0, stream, state, x, dt, A, B, C, D, y, BtH,
-                       d.H, d.P, d.N, d.G, d.hpg);
+                       d.H, d.P, d.N, d.G, d.hpg, d.dtx);
   }
 #undef SSD_DECODE_CASE
   return hipGetLastError();
@@ -351,7 +355,7 @@ bool launch_steps_resident(int nsteps, int nlayers, const Dims &d, float *state,
 #define SSD_STEPS_CASE(LPR_, NV_, ROWS_)                                                                      \
   if (d.N == 4 * LPR_ * NV_ && d.P == ROWS_ * (kDecodeThreads / LPR_)) {                                      \
     hipLaunchKernelGGL((decode_steps_kernel<Io, LPR_, NV_, ROWS_>), grid, block, 0, stream, state, x, dt, A, B, \
-                       C, D, y, nsteps, npairs, nbc, BtH, d.H, d.G, d.hpg);                                    \
+                       C, D, y, nsteps, npairs, nbc, BtH, d.H, d.G, d.hpg, d.dtx);                             \
     return true;                                                                                              \
   }
   SSD_STEPS_CASE(16, 2, 4)  // P 64,  N 128

@@ -14,16 +14,20 @@ namespace ssd {
 // primitives" lists softplus and clip among the elementwise neighbours that must fuse with the
 // decay computation): dt = clamp(softplus(raw + bias[h]), lo, hi).  Default: dt is used as given.
 struct DtXform {
-  const float *bias = nullptr;  // (nheads), device; nullptr = none
+  const float *bias = nullptr;  // (nheads) -- decode: (nlayers, nheads) --, device; nullptr = none
   int softplus = 0;
   float lo = 0.f, hi = 0.f;     // clamp to [lo, hi] if hi > 0
   bool identity() const { return bias == nullptr && softplus == 0 && !(hi > 0.f); }
 };
-__device__ __forceinline__ float dt_apply(float v, int h, const DtXform &t) {
-  if (t.bias != nullptr) v += t.bias[h];
+// (bias already fetched: kernels that apply the map step after step read it once)
+__device__ __forceinline__ float dt_apply_biased(float v, float bias, const DtXform &t) {
+  v += bias;
   if (t.softplus) v = v > 20.f ? v : log1pf(expf(v));
   if (t.hi > 0.f) v = fminf(fmaxf(v, t.lo), t.hi);
   return v;
+}
+__device__ __forceinline__ float dt_apply(float v, int h, const DtXform &t) {
+  return dt_apply_biased(v, t.bias != nullptr ? t.bias[h] : 0.f, t);
 }
 
 // Validated problem dimensions (host side).
@@ -32,7 +36,7 @@ struct Dims {
   int Nc;     // number of chunks, ceil(T / L)
   int hpg;    // heads per B/C group
   bool bf16;  // io dtype of x, B, C, y
-  DtXform dtx;  // prefill only
+  DtXform dtx;  // step-size map of the *_dt entry points (identity otherwise)
 };
 
 // ---- bf16 <-> fp32 (bf16 = upper half of the fp32 pattern, round-to-nearest-even) ----

@@ -20,7 +20,8 @@ SSD_OK = 0
 
 EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
            "ssd_decode_steps_layers", "ssd_prefill_varlen_workspace_bytes", "ssd_prefill_varlen",
-           "ssd_conv1d_prefill", "ssd_conv1d_step", "ssd_prefill_dt", "ssd_peak_probe",
+           "ssd_conv1d_prefill", "ssd_conv1d_step", "ssd_prefill_dt", "ssd_prefill_varlen_dt",
+           "ssd_decode_step_layers_dt", "ssd_decode_steps_layers_dt", "ssd_peak_probe",
            "ssd_prefill_path", "ssd_status_string", "ssd_version"]
 
 
@@ -74,6 +75,12 @@ _lib.ssd_conv1d_step.restype = ctypes.c_int
 _lib.ssd_conv1d_step.argtypes = [_i32, _i32, _i32, ctypes.POINTER(_i32)] + [_vp] * 7 + [_i32, _vp]
 _lib.ssd_decode_steps_layers.restype = ctypes.c_int
 _lib.ssd_decode_steps_layers.argtypes = [ctypes.c_int32, ctypes.c_int32, _sp] + [_vp] * 9
+_lib.ssd_prefill_varlen_dt.restype = ctypes.c_int
+_lib.ssd_prefill_varlen_dt.argtypes = [_sp, ctypes.POINTER(ssd_dt_transform)] + [_vp] * 11 + [_sz, _vp]
+_lib.ssd_decode_step_layers_dt.restype = ctypes.c_int
+_lib.ssd_decode_step_layers_dt.argtypes = [ctypes.c_int32, _sp, ctypes.POINTER(ssd_dt_transform)] + [_vp] * 9
+_lib.ssd_decode_steps_layers_dt.restype = ctypes.c_int
+_lib.ssd_decode_steps_layers_dt.argtypes = [ctypes.c_int32, ctypes.c_int32, _sp, ctypes.POINTER(ssd_dt_transform)] + [_vp] * 9
 _lib.ssd_prefill_path.restype = ctypes.c_char_p
 _lib.ssd_prefill_path.argtypes = [_sp]
 _lib.ssd_status_string.restype = ctypes.c_char_p
@@ -122,6 +129,17 @@ def _stream_ptr():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+def _dt_transform(dt_bias, dt_softplus, dt_limit, bias_shape):
+    """The ``ssd_dt_transform`` of a call, or None when dt is to be used as given."""
+    if dt_bias is None and not dt_softplus and dt_limit is None:
+        return None
+    if dt_bias is not None and (dt_bias.dtype != torch.float32 or tuple(dt_bias.shape) != tuple(bias_shape)):
+        raise ValueError("dt_bias must be fp32 of shape %s" % (tuple(bias_shape),))
+    _check_dev(dt_bias)
+    lo, hi = dt_limit if dt_limit is not None else (0.0, 0.0)
+    return ssd_dt_transform(None if dt_bias is None else dt_bias.data_ptr(), int(bool(dt_softplus)), lo, hi)
+
+
 def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, workspace=None, profile=None,
                 dt_bias=None, dt_softplus=False, dt_limit=None):
     """``ssd_prefill`` of the C ABI on torch device tensors.  Returns ``(y, final_state)``.
@@ -156,14 +174,10 @@ def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, wor
     _check_dev(x, dt, A, B, C, D, h0, y, final_state, workspace)
     args = (ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(h0), _ptr(y),
             _ptr(final_state), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_ptr())
-    if dt_bias is not None or dt_softplus or dt_limit is not None:
+    xf = _dt_transform(dt_bias, dt_softplus, dt_limit, (H,))
+    if xf is not None:
         if profile is not None:
             raise ValueError("profile and a dt transform cannot be combined")
-        if dt_bias is not None and (dt_bias.dtype != torch.float32 or tuple(dt_bias.shape) != (H,)):
-            raise ValueError("dt_bias must be fp32 of shape (H,)")
-        _check_dev(dt_bias)
-        lo, hi = dt_limit if dt_limit is not None else (0.0, 0.0)
-        xf = ssd_dt_transform(None if dt_bias is None else dt_bias.data_ptr(), int(bool(dt_softplus)), lo, hi)
         st = _lib.ssd_prefill_dt(args[0], ctypes.byref(xf), *args[1:])
     elif profile is None:
         st = _lib.ssd_prefill(*args)
@@ -196,8 +210,10 @@ def ssd_decode_step(state, x, dt, A, B, C, D, y=None):
     return y
 
 
-def ssd_decode_step_layers(state, x, dt, A, B, C, D, y=None):
-    """``ssd_decode_step_layers``: every tensor has a leading layer axis; one launch."""
+def ssd_decode_step_layers(state, x, dt, A, B, C, D, y=None, dt_bias=None, dt_softplus=False, dt_limit=None):
+    """``ssd_decode_step_layers``: every tensor has a leading layer axis; one launch.  With ``dt_bias
+    (Ly,H)``, ``dt_softplus`` or ``dt_limit=(lo, hi)`` the call goes through ``ssd_decode_step_layers_dt``
+    and ``dt`` is the raw value."""
     Ly, Bt, H, P, N = state.shape
     G = B.shape[2]
     shape = make_shape(Bt, 1, H, P, N, G, 1, x.dtype)
@@ -208,17 +224,22 @@ def ssd_decode_step_layers(state, x, dt, A, B, C, D, y=None):
             or tuple(B.shape) != (Ly, Bt, G, N) or tuple(C.shape) != (Ly, Bt, G, N):
         raise ValueError("inconsistent tensor shapes")
     _check_dev(state, x, dt, A, B, C, D, y)
-    st = _lib.ssd_decode_step_layers(Ly, ctypes.byref(shape), _ptr(state), _ptr(x), _ptr(dt), _ptr(A),
-                                     _ptr(B), _ptr(C), _ptr(D), _ptr(y), _stream_ptr())
+    xf = _dt_transform(dt_bias, dt_softplus, dt_limit, (Ly, H))
+    tail = (_ptr(state), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(y), _stream_ptr())
+    if xf is not None:
+        st = _lib.ssd_decode_step_layers_dt(Ly, ctypes.byref(shape), ctypes.byref(xf), *tail)
+    else:
+        st = _lib.ssd_decode_step_layers(Ly, ctypes.byref(shape), *tail)
     if st != SSD_OK:
         raise SSDError(st, "ssd_decode_step_layers")
     return y
 
 
-def ssd_decode_steps_layers(state, x, dt, A, B, C, D, y=None):
+def ssd_decode_steps_layers(state, x, dt, A, B, C, D, y=None, dt_bias=None, dt_softplus=False, dt_limit=None):
     """``ssd_decode_steps_layers``: ``x (steps,Ly,Bt,H,P)``, ``dt (steps,Ly,Bt,H)``,
     ``B, C (steps,Ly,Bt,G,N)``, ``A, D (Ly,H)``; ``state (Ly,Bt,H,P,N)`` updated in place to the
-    state after the last step.  Returns ``y (steps,Ly,Bt,H,P)``.  One launch."""
+    state after the last step.  Returns ``y (steps,Ly,Bt,H,P)``.  One launch.  ``dt_bias (Ly,H)``,
+    ``dt_softplus``, ``dt_limit``: as for ``ssd_decode_step_layers`` (``ssd_decode_steps_layers_dt``)."""
     Ly, Bt, H, P, N = state.shape
     S, G = x.shape[0], B.shape[3]
     shape = make_shape(Bt, 1, H, P, N, G, 1, x.dtype)
@@ -229,17 +250,23 @@ def ssd_decode_steps_layers(state, x, dt, A, B, C, D, y=None):
             or tuple(B.shape) != (S, Ly, Bt, G, N) or tuple(C.shape) != (S, Ly, Bt, G, N):
         raise ValueError("inconsistent tensor shapes")
     _check_dev(state, x, dt, A, B, C, D, y)
-    st = _lib.ssd_decode_steps_layers(S, Ly, ctypes.byref(shape), _ptr(state), _ptr(x), _ptr(dt), _ptr(A),
-                                      _ptr(B), _ptr(C), _ptr(D), _ptr(y), _stream_ptr())
+    xf = _dt_transform(dt_bias, dt_softplus, dt_limit, (Ly, H))
+    tail = (_ptr(state), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(y), _stream_ptr())
+    if xf is not None:
+        st = _lib.ssd_decode_steps_layers_dt(S, Ly, ctypes.byref(shape), ctypes.byref(xf), *tail)
+    else:
+        st = _lib.ssd_decode_steps_layers(S, Ly, ctypes.byref(shape), *tail)
     if st != SSD_OK:
         raise SSDError(st, "ssd_decode_steps_layers")
     return y
 
 
-def ssd_prefill_varlen(x, dt, A, B, C, D, cu_seqlens, chunk, h0=None, y=None, final_state=None, workspace=None):
+def ssd_prefill_varlen(x, dt, A, B, C, D, cu_seqlens, chunk, h0=None, y=None, final_state=None, workspace=None,
+                       dt_bias=None, dt_softplus=False, dt_limit=None):
     """``ssd_prefill_varlen``: packed batch ``x (tokens,H,P)``, ``dt (tokens,H)``, ``B, C (tokens,G,N)``,
     ``cu_seqlens (nseq+1)`` int32 on the device, ``h0 (nseq,H,P,N)`` optional.
-    Returns ``(y (tokens,H,P), final_state (nseq,H,P,N))``."""
+    Returns ``(y (tokens,H,P), final_state (nseq,H,P,N))``.  ``dt_bias (H)``, ``dt_softplus``, ``dt_limit``: as
+    for ``ssd_prefill`` (``ssd_prefill_varlen_dt``)."""
     T, H, P = x.shape
     G, N = B.shape[1], B.shape[2]
     nseq = cu_seqlens.numel() - 1
@@ -259,9 +286,13 @@ def ssd_prefill_varlen(x, dt, A, B, C, D, cu_seqlens, chunk, h0=None, y=None, fi
     if workspace is None:
         workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
     _check_dev(x, dt, A, B, C, D, h0, y, final_state, workspace, cu_seqlens)
-    st = _lib.ssd_prefill_varlen(ctypes.byref(shape), _ptr(cu_seqlens), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C),
-                                 _ptr(D), _ptr(h0), _ptr(y), _ptr(final_state), _ptr(workspace),
-                                 workspace.numel() * workspace.element_size(), _stream_ptr())
+    xf = _dt_transform(dt_bias, dt_softplus, dt_limit, (H,))
+    tail = (_ptr(cu_seqlens), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(h0), _ptr(y),
+            _ptr(final_state), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_ptr())
+    if xf is not None:
+        st = _lib.ssd_prefill_varlen_dt(ctypes.byref(shape), ctypes.byref(xf), *tail)
+    else:
+        st = _lib.ssd_prefill_varlen(ctypes.byref(shape), *tail)
     if st != SSD_OK:
         raise SSDError(st, "ssd_prefill_varlen")
     return y, final_state

@@ -147,6 +147,32 @@ def test_prefill_dt_rejects_before_any_hip_call(ssd):
     assert call(ssd.ssd_dt_transform(None, 1, 0.0, 0.0), x=None) == -1
 
 
+def test_varlen_and_decode_dt_variants_reject_before_any_hip_call(ssd):
+    lib = ssd.raw()
+    fake = ctypes.c_void_p(4096)
+    s = shape(ssd)
+    need = lib.ssd_prefill_varlen_workspace_bytes(ctypes.byref(s))
+    ok_xf = ssd.ssd_dt_transform(None, 1, 0.0, 0.0)
+    bad_xf = ssd.ssd_dt_transform(None, 1, 0.1, 0.01)     # dt_min > dt_max
+
+    def var(xf, x=fake):
+        return lib.ssd_prefill_varlen_dt(ctypes.byref(s), ctypes.byref(xf) if xf is not None else None, fake, x, fake,
+                                         fake, fake, fake, fake, None, fake, fake, fake, ctypes.c_size_t(need), None)
+
+    def dec(xf, x=fake, nlayers=2):
+        return lib.ssd_decode_step_layers_dt(nlayers, ctypes.byref(s), ctypes.byref(xf) if xf is not None else None,
+                                             fake, x, fake, fake, fake, fake, fake, fake, None)
+
+    def decs(xf, x=fake, nsteps=3):
+        return lib.ssd_decode_steps_layers_dt(nsteps, 2, ctypes.byref(s), ctypes.byref(xf) if xf is not None else None,
+                                              fake, x, fake, fake, fake, fake, fake, fake, None)
+
+    for f in (var, dec, decs):
+        assert f(None) == -1 and f(bad_xf) == -2 and f(ok_xf, x=None) == -1
+        assert f(ok_xf, x=ctypes.c_void_p(4100)) == -7
+    assert dec(ok_xf, nlayers=0) == -2 and decs(ok_xf, nsteps=0) == -2
+
+
 def test_peak_probe_rejects_before_any_hip_call(ssd):
     lib = ssd.raw()
     fake = ctypes.c_void_p(4096)

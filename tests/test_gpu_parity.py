@@ -533,6 +533,73 @@ def test_prefill_with_fused_dt_transform(ssd, case, monkeypatch):
     assert_close(st, st_ref, TOL[io], "fused dt: state")
 
 
+@pytest.mark.parametrize("case", [
+    # lengths, H, P, N, G, L, io
+    ([300, 64, 1, 500], 4, 64, 128, 1, 128, "bf16"),      # MFMA family
+    ([70, 7, 100], 3, 24, 20, 3, 16, "f32"),              # generic family
+], ids=lambda c: "x".join(str(v) for v in c[1:]) + "-n%d" % len(c[0]))
+def test_varlen_prefill_with_fused_dt_transform(ssd, case):
+    lens, H, P, N, G, L, io = case
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    T = int(cu[-1])
+    cfg = cfg_of(1, T, H, P, N, G, L, io)
+    inp = inputs.make_prefill_inputs(cfg, seed=73)
+    pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
+    g = torch.Generator().manual_seed(74)
+    raw = 0.5 * torch.randn((T, H), generator=g) + inputs.DT_BIAS
+    bias = 0.3 * torch.randn((H,), generator=g)
+    limit = (1e-3, 1e-1)
+    print("varlen dt transform case", case, flush=True)
+    dev = {k: v.cuda() for k, v in pk.items()}
+    y, st = ssd.ssd_prefill_varlen(dev["x"], raw.cuda(), dev["A"], dev["B"], dev["C"], dev["D"],
+                                   torch.from_numpy(cu).cuda(), L, dt_bias=bias.cuda(), dt_softplus=True, dt_limit=limit)
+    torch.cuda.synchronize()
+    dt_ref = ssd_oracle.dt_transform(raw, bias, True, limit)
+    y_ref, st_ref = ssd_oracle.prefill_varlen(pk["x"], dt_ref, pk["A"], pk["B"], pk["C"], pk["D"], cu)
+    assert_close(y, y_ref, TOL[io], "varlen fused dt: y")
+    assert_close(st, st_ref, TOL[io], "varlen fused dt: states")
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [
+    # Ly, Bt, H, P, N, G, steps, bias, softplus, limit
+    (3, 2, 8, 64, 128, 2, 6, True, True, (1e-3, 1e-1)),     # vector kernel / register-resident multi-step kernel
+    (2, 1, 5, 7, 6, 5, 3, True, True, None),                # any-shape kernel, per-step launches
+    (1, 2, 4, 64, 64, 1, 5, False, False, (2e-3, 5e-2)),    # clamp only
+], ids=lambda c: "x".join(str(v) for v in c))
+def test_decode_with_fused_dt_transform(ssd, case, io):
+    """Alg. 2, "Discretise": the decode entry points apply the step-size activation themselves."""
+    Ly, Bt, H, P, N, G, S, with_bias, softplus, limit = case
+    iod = torch.float32 if io == "f32" else torch.bfloat16
+    g = torch.Generator().manual_seed(75)
+    state = torch.randn((Ly, Bt, H, P, N), generator=g)
+    x = torch.randn((S, Ly, Bt, H, P), generator=g).to(iod)
+    raw = 0.5 * torch.randn((S, Ly, Bt, H), generator=g) + (inputs.DT_BIAS if softplus else 0.02)
+    bias = 0.3 * torch.randn((Ly, H), generator=g) if with_bias else None
+    A = -(torch.rand((Ly, H), generator=g) * 15 + 1)
+    D = torch.randn((Ly, H), generator=g)
+    B = (0.25 * torch.randn((S, Ly, Bt, G, N), generator=g)).to(iod)
+    C = (0.25 * torch.randn((S, Ly, Bt, G, N), generator=g)).to(iod)
+    # bias has a layer axis: broadcast (Ly, 1, H) against raw (S, Ly, Bt, H)
+    dt_ref = ssd_oracle.dt_transform(raw, None if bias is None else bias[:, None, :], softplus, limit)
+    y_ref, st_ref = ssd_oracle.decode_steps_layers(state, x, dt_ref, A, B, C, D)
+    kw = dict(dt_bias=None if bias is None else bias.cuda(), dt_softplus=softplus, dt_limit=limit)
+    print("decode dt transform case", case, io, flush=True)
+    dev = [t.cuda() for t in (x, raw, A, B, C, D)]
+    sd = state.cuda().clone()
+    y = ssd.ssd_decode_steps_layers(sd, *dev, **kw)
+    torch.cuda.synchronize()
+    assert_close(y, y_ref, TOL[io], "multi-step decode, fused dt: y")
+    assert_close(sd, st_ref, 1e-4, "multi-step decode, fused dt: state")
+    s1 = state.cuda().clone()
+    for s in range(S):
+        ys = ssd.ssd_decode_step_layers(s1, dev[0][s].clone(), dev[1][s].clone(), dev[2], dev[3][s].clone(),
+                                        dev[4][s].clone(), dev[5], **kw)
+        torch.cuda.synchronize()
+        assert_close(ys, y_ref[s], TOL[io], "single decode step %d, fused dt: y" % s)
+    assert_close(s1, st_ref, 1e-4, "single decode steps, fused dt: state")
+
+
 GENERIC_VARLEN_CASES = [
     # lengths, H, P, N, G, L, io, with h0
     ([5, 0, 33, 64, 1, 100], 4, 32, 16, 2, 32, "f32", True),      # fp32 io: the 1e-4 tolerance family
