@@ -1282,11 +1282,20 @@ int choose_seg_blocks(const Dims &d, int min_blocks, int max_slots, int max_part
 }
 
 // y += t over n 16-byte pieces of bf16 (sum in fp32, rounded once): adds the output of a later state
-// slice to the output so far.
+// slice to the output so far.  For a packed batch only the tokens that belong to a sequence are touched:
+// the sequences lie back to back, so those are [tok0[0], tok0[nseq-1] + len[nseq-1]) of the tables
+// (empty when the boundaries were rejected); per_token = 16-byte pieces per token.
 __global__ __launch_bounds__(kThreads) void add_outputs_kernel(uint16_t *__restrict__ y, const uint16_t *__restrict__ t,
-                                                               size_t n) {
+                                                               size_t n, const int32_t *__restrict__ tok0,
+                                                               const int32_t *__restrict__ len, int nseq,
+                                                               size_t per_token) {
   const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
   if (i >= n) return;
+  if (tok0 != nullptr) {
+    const size_t begin = static_cast<size_t>(tok0[0]) * per_token;
+    const size_t end = (static_cast<size_t>(tok0[nseq - 1]) + len[nseq - 1]) * per_token;
+    if (i < begin || i >= end) return;
+  }
   const u32x4 a = reinterpret_cast<const u32x4 *>(y)[i], b = reinterpret_cast<const u32x4 *>(t)[i];
   u32x4 r;
 #pragma unroll
@@ -1497,10 +1506,15 @@ hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *
                                       workspace, stream, off == 0 ? trace : nullptr);
     if (e != hipSuccess) return e;
     if (off > 0) {
-      const size_t pieces = static_cast<size_t>(cu != nullptr ? 1 : d.Bt) * d.T * d.H * d.P / 8;
+      const size_t per_token = static_cast<size_t>(d.H) * d.P / 8;
+      const size_t pieces = static_cast<size_t>(cu != nullptr ? 1 : d.Bt) * d.T * per_token;
+      // (the tables of a packed batch: as laid out by launch_slice, which has just rebuilt them)
+      const int32_t *tok0 = cu != nullptr ? reinterpret_cast<const int32_t *>(static_cast<char *>(workspace) + w.off_tables)
+                                          : nullptr;
       hipLaunchKernelGGL(add_outputs_kernel, dim3(static_cast<unsigned>((pieces + kThreads - 1) / kThreads)),
                          dim3(kThreads), 0, stream, static_cast<uint16_t *>(y),
-                         reinterpret_cast<const uint16_t *>(out), pieces);
+                         reinterpret_cast<const uint16_t *>(out), pieces, tok0,
+                         tok0 != nullptr ? tok0 + (d.Bt + 1) : nullptr, d.Bt, per_token);
     }
   }
   return hipGetLastError();
@@ -1536,8 +1550,7 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
 // Packed variable-length batch: d.Bt sequences, d.T tokens in total, boundaries in the device array cu.
 bool mfma_varlen_supported(const Dims &d) {
   const unsigned long long nb = (static_cast<unsigned long long>(d.T) + kBlk - 1) / kBlk + d.Bt;
-  // (one state slice only: the sum over slices would also touch tokens that belong to no sequence)
-  return shape_ok(d, static_cast<unsigned long long>(d.T), nb) && nb <= 0x7fffffffull / 64 && d.N <= kN;
+  return shape_ok(d, static_cast<unsigned long long>(d.T), nb) && nb <= 0x7fffffffull / 64;
 }
 
 size_t mfma_varlen_workspace_bytes(const Dims &d) { return make_layout(d, true).total; }

@@ -436,6 +436,8 @@ VARLEN_CASES = [
     ([17] * 40, 4, 1, 64, 0, True),                              # many short sequences
     ([130, 0, 700, 64], (2, 128), 1, 64, 2, True),               # headdim 128 (H given as (heads, headdim))
     ([130, 0, 700, 64], (4, 64, 64), 1, 64, 2, True),            # dstate 64 (heads, headdim, dstate)
+    ([130, 0, 700, 64], (4, 64, 256), 1, 64, 2, False),          # dstate 256: two state slices, outputs added
+    ([300, 5, 200], (4, 128, 192), 2, 128, 1, True),             # dstate 192, headdim 128, two groups
 ]
 
 
@@ -474,10 +476,12 @@ def test_varlen_prefill_matches_oracle(ssd, case, monkeypatch):
         assert_close(st[q], to_np64(sq[0]), 2e-2, "varlen state vs single sequence %d" % q)
 
 
-def test_varlen_leaves_unowned_tokens_alone_and_rejects_bad_boundaries(ssd):
+@pytest.mark.parametrize("N", [128, 256])   # 256: two state slices, whose sum must skip unowned tokens too
+def test_varlen_leaves_unowned_tokens_alone_and_rejects_bad_boundaries(ssd, N):
     H, L = 4, 64
     T = 400
-    cfg = cfg_of(1, T, H, 64, 128, 1, L, "bf16")
+    cfg = cfg_of(1, T, H, 64, N, 1, L, "bf16")
+    assert ssd.prefill_path(ssd.make_shape(2, T, H, 64, N, 1, L, torch.bfloat16)) == "mfma_bf16"
     inp = inputs.make_prefill_inputs(cfg, seed=37)
     dev = {k: (v[0] if k in ("x", "dt", "B", "C") else v).cuda() for k, v in inp.items()}
     # tokens [0, 10) and [300, 400) belong to no sequence
@@ -494,7 +498,7 @@ def test_varlen_leaves_unowned_tokens_alone_and_rejects_bad_boundaries(ssd):
     # boundaries that decrease, or run past the token count: the call is a no-op
     for bad in ([0, 200, 100], [0, 100, 401], [-1, 100, 300]):
         y2 = torch.full_like(dev["x"], 7.0)
-        st2 = torch.full((2, H, 64, 128), 5.0, device="cuda")
+        st2 = torch.full((2, H, 64, N), 5.0, device="cuda")
         ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
                                torch.tensor(bad, dtype=torch.int32).cuda(), L, y=y2, final_state=st2)
         torch.cuda.synchronize()
@@ -605,7 +609,7 @@ GENERIC_VARLEN_CASES = [
     ([5, 0, 33, 64, 1, 100], 4, 32, 16, 2, 32, "f32", True),      # fp32 io: the 1e-4 tolerance family
     ([70, 7], 3, 24, 20, 3, 7, "f32", False),                      # nothing is a multiple of any tile
     ([130, 0, 300], 2, 72, 40, 1, 128, "bf16", True),              # bf16, head shape outside the MFMA family
-    ([200, 57, 64], 4, 64, 256, 1, 64, "bf16", True),              # dstate 256 packed: generic kernels
+    ([200, 57, 64], 4, 64, 100, 1, 64, "bf16", True),              # dstate not a multiple of 8: generic kernels
     ([1000], 2, 16, 8, 1, 2048, "f32", False),                     # chunk longer than everything
 ]
 
