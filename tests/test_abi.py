@@ -32,6 +32,38 @@ def test_header_symbols_are_exported(ssd):
         assert hasattr(lib, n), "libssd_hip.so does not export %s" % n
 
 
+def test_header_is_plain_c_and_a_c_program_links(ssd, tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 with no C++ or HIP in sight, and a C program
+    linked against the library can call the entry points that need no GPU (host-side validation)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib = os.path.join(root, "paper_2603_09555_amd", "libssd_hip.so")
+    src = tmp_path / "use_ssd.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include "ssd.h"
+int main(void) {
+  ssd_shape s = {1, 2048, 24, 64, 128, 1, 256, SSD_BF16};
+  size_t ws = ssd_prefill_workspace_bytes(&s);
+  ssd_status st = ssd_prefill(&s, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL, 0, NULL);
+  s.nheads = 0;
+  printf("%d %zu %d %zu %s|%s\n", ssd_version(), ws, (int)st, ssd_prefill_workspace_bytes(&s),
+         ssd_prefill_path(&s), ssd_status_string(SSD_ERR_NULL));
+  return 0;
+}
+""")
+    exe = tmp_path / "use_ssd"
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(root, "include"), str(src), lib,
+                    "-Wl,-rpath," + os.path.dirname(lib), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == ssd.version() and int(out[1]) > 0 and int(out[2]) == -1 and int(out[3]) == 0
+    assert out[4].startswith("invalid|")
+
+
 def test_version_and_status_strings(ssd):
     assert ssd.version() >= 100
     assert ssd.status_string(0) == "ok"
