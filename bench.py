@@ -174,6 +174,32 @@ def main():
         kern = {k: sum(v) / len(v) for k, v in kern.items()}
         return ms, kern, inp
 
+    def time_step_cold(cfg, reps=9):
+        """The same step with the caches overwritten before every call (512 MiB of unrelated dirty data:
+        twice the memory-side cache), timed per call with events; the median.  The back-to-back loop above
+        finds part of x cached from the step before, as a layer finds the x its convolution just wrote;
+        this is the other end of the range."""
+        inp = inputs.make_prefill_inputs(cfg, seed=0, device=dev)
+        nxt = {k: v[0].contiguous() for k, v in inputs.make_decode_inputs(cfg, 1, seed=0, device=dev).items()}
+        y = torch.empty_like(inp["x"])
+        st = torch.empty((cfg.batch, cfg.nheads, cfg.headdim, cfg.dstate), dtype=torch.float32, device=dev)
+        yd = torch.empty_like(nxt["x"])
+        ws = torch.empty((max(ssd.prefill_workspace_bytes(shape_of(cfg)), 256),), dtype=torch.uint8, device=dev)
+        junk = torch.empty((512 << 20,), dtype=torch.uint8, device=dev)
+        evs = []
+        for i in range(reps + 2):
+            junk.fill_(i & 1)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ssd.ssd_prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], cfg.chunk, y=y,
+                            final_state=st, workspace=ws)
+            ssd.ssd_decode_step(st, nxt["x"], nxt["dt"], inp["A"], nxt["B"], nxt["C"], inp["D"], y=yd)
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in evs[2:])
+        return ts[len(ts) // 2]
+
     def prefill_report(cfg, ms, kern):
         fl_c, fl_d = prefill_flops(cfg, True), prefill_flops(cfg, False)
         tot_c, tot_d = sum(fl_c.values()), sum(fl_d.values())
@@ -219,6 +245,10 @@ def main():
     head = prefill_report(cfg, ms_step, kern)
     log("[bench] %s: %.3f ms/step, %.1f TFLOP/s (causal count), kernels %s" %
         (cfg.name, ms_step, head["tflops_causal"], head["kernels_ms"]))
+    head["cold_cache_ms"] = round(time_step_cold(cfg), 5)
+    head["cold_cache_tflops_causal"] = round(sum(prefill_flops(cfg, True).values()) / head["cold_cache_ms"] / 1e9, 1)
+    log("[bench] %s with the caches overwritten before every step: %.3f ms/step, %.1f TFLOP/s" %
+        (cfg.name, head["cold_cache_ms"], head["cold_cache_tflops_causal"]))
 
     # roofline of the dominant kernel of the step
     dom = max(kern, key=kern.get)
