@@ -437,6 +437,24 @@ def main():
         pair_us = e0.elapsed_time(e1) * 1e3 / args.steps
         conv["prefill"]["conv_then_ssd_prefill_us"] = round(pair_us, 2)
         log("[bench] conv1d prefill followed by ssd_prefill on its outputs: %.1f us" % pair_us)
+        # the same pair with the other cache policy for y (the library chooses from the size of x; the
+        # environment variable overrides the choice per call)
+        other = {}
+        for pol in ("0", "1", "0", "1"):   # twice each, the better one kept: clocks drift over the legs of a run
+            os.environ["SSD_Y_STREAM"] = pol
+            for _ in range(3):
+                pair()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(args.steps):
+                pair()
+            e1.record()
+            torch.cuda.synchronize()
+            other[pol] = min(other.get(pol, 1e30), round(e0.elapsed_time(e1) * 1e3 / args.steps, 2))
+        del os.environ["SSD_Y_STREAM"]
+        conv["prefill"]["pair_us_y_stores_cached"] = other["0"]
+        conv["prefill"]["pair_us_y_stores_non_temporal"] = other["1"]
+        log("[bench] the pair with y stored through the caches %.1f us, non-temporally %.1f us" % (other["0"], other["1"]))
         del u, outs, cache, pin, xv, Bv, Cv, yp, stp, wsp
         torch.cuda.empty_cache()
 
@@ -508,6 +526,23 @@ def main():
                                 "state streams from HBM")
             log("[bench] decode %s: %.2f us/step, %.0f GB/s (%.1f%% of HBM peak)" %
                 (name, us, gbs, 100 * gbs / PEAK_HBM_GBS))
+            # the other cache policy for the state (the library streams it past the caches when the states
+            # of a call exceed the memory-side cache; the environment variable overrides that per call)
+            for pol, key in (("0", "us_per_step_state_cached"), ("1", "us_per_step_state_non_temporal")):
+                os.environ["SSD_DECODE_STREAM"] = pol
+                nshort = min(nsteps, 64)
+                for i in range(3):
+                    ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=yd)
+                torch.cuda.synchronize()
+                e0.record()
+                for i in range(nshort):
+                    ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=yd)
+                e1.record()
+                torch.cuda.synchronize()
+                decode[name][key] = round(e0.elapsed_time(e1) * 1e3 / nshort, 3)
+            del os.environ["SSD_DECODE_STREAM"]
+            log("[bench] decode %s: state through the caches %.2f us/step, non-temporal %.2f us/step" %
+                (name, decode[name]["us_per_step_state_cached"], decode[name]["us_per_step_state_non_temporal"]))
             # the same stacked launches replayed from a HIP graph (the launch work done once), and all
             # steps of a block in ONE launch with the state kept on chip between the steps
             nb = min(nsteps, args.decode_block)
