@@ -1,15 +1,17 @@
 """Error metrics shared by the GPU parity tests.
 
 Tolerance: max relative error 1e-4 for fp32 inputs, 2e-2 for bf16 inputs with fp32
-accumulation.  "Relative" is made precise in two ways, and both are gated:
+accumulation.  "Relative" is made precise in two ways, and both are gated for every tensor:
   (i)  scale-normalised: max|g - o| / max|o| <= tol
   (ii) element-wise, allclose-style (the form of the paper's own parity table):
        |g - o| <= tol*|o| + tol*rms(o) for every element.
 Where the output is ill-conditioned with respect to rms(o) -- a large random initial state makes
-y a sum of big terms that cancel -- (ii) is replaced by the componentwise bound of rounding-error
+y a sum of big terms that cancel -- a third gate is ADDED: the componentwise bound of rounding-error
 analysis, |g - o| <= tol * mag, with mag = the same recurrence evaluated by the oracle on the
 absolute values of x, B, C, D and h0 (every decay factor is positive, so mag is exactly the sum
-of the absolute values of the terms that make up each output).
+of the absolute values of the terms that make up each output).  ``allclose_tol`` sets the limit of
+gate (ii) apart from ``tol``; the only callers that pass it take the figure from the CPU model of
+the documented bf16 operand roundings (``blocked_model.py``), never from a GPU run.
 """
 import numpy as np
 import torch
@@ -38,14 +40,14 @@ def errors(got, ref):
     return dict(norm=norm, worst_allclose=worst, max_ref=mx)
 
 
-def assert_close(got, ref, tol, what="", mag=None):
+def assert_close(got, ref, tol, what="", mag=None, allclose_tol=None):
     e = errors(got, ref)
     assert e["norm"] <= tol, "%s: normalised max err %.3e, tol %.1e" % (what, e["norm"], tol)
-    if mag is None:
-        assert e["worst_allclose"] <= tol, \
-            "%s: worst allclose ratio %.3e (normalised max err %.3e), tol %.1e" % (what, e["worst_allclose"],
-                                                                                  e["norm"], tol)
-    else:
+    lim = tol if allclose_tol is None else allclose_tol
+    assert e["worst_allclose"] <= lim, \
+        "%s: worst allclose ratio %.3e (normalised max err %.3e), limit %.3e" % (what, e["worst_allclose"],
+                                                                                e["norm"], lim)
+    if mag is not None:
         g, o, m = to_np64(got), to_np64(ref), to_np64(mag)
         worst = float((np.abs(g - o) / np.where(m > 0, m, 1.0)).max())
         e["worst_componentwise"] = worst

@@ -1,10 +1,13 @@
 """GPU parity at the full benchmark sizes, in the launch configuration ``bench.py`` times.
 
-The oracle cannot evaluate every (batch row, head) sequence of these shapes in seconds, but
-sequences are independent (one scalar A and one state per head), so it evaluates a seeded
-sample of them completely -- every token, every channel, the final state -- and those are
-compared element by element.  Properties that hold at any size cover the rest: every output
-is finite, and a second run is bitwise identical.
+Sequences are independent (one scalar A and one state per head) and the oracle scans a whole
+benchmark configuration in seconds on the host cores, so the prefill configurations are compared
+with it completely: every (batch row, head) sequence, every token, every channel, the final
+state, under both gates of ``parity.assert_close``.  The decode configuration runs as the
+benchmark words it -- a 2048-token prefill per layer, then 1024 single-token steps of all 64
+layers -- and every step's output and the final state are compared: all layers at batch 1, and at
+batch 16 all rows and heads of four layers (the oracle's cost for all 64 would be minutes).
+A second run must be bitwise identical.
 """
 import numpy as np
 import pytest
@@ -23,18 +26,8 @@ def ssd():
     return binding
 
 
-def sample_pairs(cfg, n, seed):
-    """n distinct (b, h) pairs: the first and the last sequence plus seeded random ones."""
-    rng = np.random.default_rng(seed)
-    total = cfg.batch * cfg.nheads
-    picks = {0, total - 1}
-    while len(picks) < min(n, total):
-        picks.add(int(rng.integers(total)))
-    return [(i // cfg.nheads, i % cfg.nheads) for i in sorted(picks)]
-
-
-@pytest.mark.parametrize("name,npairs", [("c1_130m", 24), ("c2_780m_b8", 8), ("c3_2p7b_long", 6)])
-def test_full_size_prefill_sampled_sequences(ssd, name, npairs):
+@pytest.mark.parametrize("name", ["c1_130m", "c2_780m_b8", "c3_2p7b_long"])
+def test_full_size_prefill_every_sequence(ssd, name):
     cfg = inputs.CONFIGS[name]
     print("full-size prefill", cfg, flush=True)
     inp = inputs.make_prefill_inputs(cfg, seed=0)
@@ -47,31 +40,39 @@ def test_full_size_prefill_sampled_sequences(ssd, name, npairs):
     torch.cuda.synchronize()
     assert torch.isfinite(y.float()).all() and torch.isfinite(st).all()
     assert torch.equal(y, y2) and torch.equal(st, st2)
-    pairs = sample_pairs(cfg, npairs, seed=41)
-    y_ref, st_ref = ssd_oracle.prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], pairs=pairs)
-    bs = torch.tensor([b for b, _ in pairs], device="cuda")
-    hs = torch.tensor([h for _, h in pairs], device="cuda")
-    y_got = y[bs, :, hs, :]      # (n, T, P)
-    st_got = st[bs, hs]          # (n, P, N)
-    e = assert_close(y_got, y_ref, 2e-2, "%s y on sampled sequences" % name)
-    assert_close(st_got, st_ref, 2e-2, "%s final state on sampled sequences" % name)
-    print("errors", e, flush=True)
+    y_ref, st_ref = ssd_oracle.prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"])
+    print("oracle done", y_ref.shape, flush=True)
+    e = assert_close(y, y_ref, 2e-2, "%s y, all %d sequences" % (name, cfg.batch * cfg.nheads))
+    assert_close(st, st_ref, 2e-2, "%s final state, all sequences" % name)
+    # per sequence as well: a sequence whose outputs are small must not hide behind the tensor-wide scale
+    yg = to_np64(y)
+    err = np.abs(yg - y_ref).max(axis=(1, 3))                       # (Bt, H)
+    scale = np.abs(y_ref).max(axis=(1, 3))
+    worst = float((err / scale).max())
+    print("errors", e, "worst per-sequence normalised error %.3e" % worst, flush=True)
+    assert worst <= 2e-2, "worst per-sequence normalised error %.3e" % worst
 
 
-@pytest.mark.parametrize("name", ["c4_decode_b1", "c4_decode_b16"])
-def test_full_size_stacked_decode_sampled_sequences(ssd, name):
-    """All 64 layers in one launch per step, states seeded by a 2048-token prefill per layer; the
-    oracle runs the token recurrence over prompt + generated steps for sampled (layer, row, head)."""
+STEP_BLOCK = 128   # decode steps whose inputs are resident at a time
+
+
+@pytest.mark.parametrize("name,nchecked", [("c4_decode_b1", 64), ("c4_decode_b16", 4)])
+def test_full_size_decode_1024_steps(ssd, name, nchecked):
+    """Config 4 as stated: states seeded by a 2048-token prefill per layer, then 1024 single-token steps,
+    all 64 layers in one launch per step.  The oracle runs the token recurrence over prompt + generated
+    steps for every (row, head) of the checked layers; y of every step and the final state are compared."""
     cfg = inputs.CONFIGS[name]
-    Ly, nsteps = cfg.nlayers, 24
+    Ly, nsteps = cfg.nlayers, cfg.decode_steps
+    assert nsteps == 1024 and nsteps % STEP_BLOCK == 0
     print("full-size decode", cfg, "steps", nsteps, flush=True)
     dev = "cuda"
     rng = np.random.default_rng(43)
-    layers = sorted({0, Ly - 1, int(rng.integers(Ly))})
+    layers = list(range(Ly)) if nchecked >= Ly else sorted(
+        {0, Ly - 1} | {int(v) for v in rng.choice(np.arange(1, Ly - 1), nchecked - 2, replace=False)})
     state = torch.empty((Ly, cfg.batch, cfg.nheads, cfg.headdim, cfg.dstate), dtype=torch.float32, device=dev)
     A = torch.empty((Ly, cfg.nheads), dtype=torch.float32, device=dev)
     D = torch.empty_like(A)
-    kept = {}
+    prompt = {}
     ytmp = None
     for l in range(Ly):
         inp = inputs.make_prefill_inputs(cfg, seed=0, layer=l, device=dev)
@@ -81,32 +82,45 @@ def test_full_size_stacked_decode_sampled_sequences(ssd, name):
                         final_state=state[l])
         A[l], D[l] = inp["A"], inp["D"]
         if l in layers:
-            kept[l] = {k: v.cpu() for k, v in inp.items()}
+            prompt[l] = {k: v.cpu() for k, v in inp.items()}
     del ytmp, inp
-    steps = [inputs.make_decode_inputs(cfg, nsteps, seed=0, layer=l, device=dev) for l in range(Ly)]
-    xs = torch.stack([s["x"] for s in steps], dim=1)      # (steps, Ly, Bt, H, P)
-    dts = torch.stack([s["dt"] for s in steps], dim=1)
-    Bs = torch.stack([s["B"] for s in steps], dim=1)
-    Cs = torch.stack([s["C"] for s in steps], dim=1)
-    del steps
-    ys = torch.empty((nsteps, Ly, cfg.batch, cfg.nheads, cfg.headdim), dtype=xs.dtype, device=dev)
-    for i in range(nsteps):
-        ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=ys[i])
     torch.cuda.synchronize()
-    assert torch.isfinite(ys.float()).all() and torch.isfinite(state).all()
+    print("prefilled", Ly, "layers", flush=True)
+    # the steps, in blocks of STEP_BLOCK (the inputs of all 1024 steps of 64 layers at batch 16 are 22 GB)
+    gen = {l: {k: [] for k in ("x", "dt", "B", "C")} for l in layers}    # CPU copies for the oracle
+    got = {l: [] for l in layers}                                          # GPU outputs of the checked layers
+    for blk in range(nsteps // STEP_BLOCK):
+        per = [inputs.make_decode_inputs(cfg, STEP_BLOCK, seed=100 + blk, layer=l, device=dev) for l in range(Ly)]
+        xs = torch.stack([s["x"] for s in per], dim=1)      # (steps, Ly, Bt, H, P)
+        dts = torch.stack([s["dt"] for s in per], dim=1)
+        Bs = torch.stack([s["B"] for s in per], dim=1)
+        Cs = torch.stack([s["C"] for s in per], dim=1)
+        del per
+        ys = torch.empty_like(xs)
+        for i in range(STEP_BLOCK):
+            ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=ys[i])
+        torch.cuda.synchronize()
+        assert torch.isfinite(ys.float()).all()
+        for l in layers:
+            for k, t in (("x", xs), ("dt", dts), ("B", Bs), ("C", Cs)):
+                gen[l][k].append(t[:, l].transpose(0, 1).cpu())            # (Bt, steps, ...)
+            got[l].append(ys[:, l].transpose(0, 1).cpu())
+        del xs, dts, Bs, Cs, ys
+        print("steps", (blk + 1) * STEP_BLOCK, flush=True)
+    assert torch.isfinite(state).all()
+    worst = 0.0
     for l in layers:
-        pairs = sample_pairs(cfg, 4, seed=47 + l)
-        p = kept[l]
-        full = {"x": torch.cat([p["x"], xs[:, l].transpose(0, 1).cpu()], dim=1),
-                "dt": torch.cat([p["dt"], dts[:, l].transpose(0, 1).cpu()], dim=1),
-                "B": torch.cat([p["B"], Bs[:, l].transpose(0, 1).cpu()], dim=1),
-                "C": torch.cat([p["C"], Cs[:, l].transpose(0, 1).cpu()], dim=1)}
-        y_ref, st_ref = ssd_oracle.prefill(full["x"], full["dt"], p["A"], full["B"], full["C"], p["D"], pairs=pairs)
-        bs = torch.tensor([b for b, _ in pairs], device=dev)
-        hs = torch.tensor([h for _, h in pairs], device=dev)
-        y_got = ys[:, l][:, bs, hs, :].transpose(0, 1)    # (n, steps, P)
-        assert_close(y_got, y_ref[:, cfg.seqlen:], 2e-2, "%s layer %d decode y" % (name, l))
-        assert_close(state[l][bs, hs], st_ref, 2e-2, "%s layer %d state after %d steps" % (name, l, nsteps))
+        p = prompt[l]
+        full = {k: torch.cat([p[k]] + gen[l][k], dim=1) for k in ("x", "dt", "B", "C")}
+        y_ref, st_ref = ssd_oracle.prefill(full["x"], full["dt"], p["A"], full["B"], full["C"], p["D"])
+        y_got = torch.cat(got[l], dim=1)                                   # (Bt, 1024, H, P)
+        e = assert_close(y_got, y_ref[:, cfg.seqlen:], 2e-2, "%s layer %d decode y, 1024 steps" % (name, l))
+        assert_close(state[l], st_ref, 2e-2, "%s layer %d state after 1024 steps" % (name, l))
+        worst = max(worst, e["worst_allclose"])
+        gen[l] = got[l] = prompt[l] = None
+        if l % 8 == 0 or nchecked < Ly:
+            print("layer", l, "ok", e, flush=True)
+    print("checked layers", layers, "worst allclose ratio %.3e" % worst, flush=True)
 
 
 def test_full_size_multi_step_decode_equals_single_steps(ssd):
