@@ -46,6 +46,7 @@
 // A segment is a whole number of 64-token blocks; with one segment only the first and the last kernel
 // run.
 #include <cstdlib>
+#include <type_traits>
 
 #include "ssd_internal.hpp"
 
@@ -308,12 +309,22 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, size_t row0, size_
 // One workgroup per (block, 16 heads starting at h0).  With cs_s the block-relative inclusive prefix
 // sum of dt*A*log2(e) (the "segsum" input) and c31, c63 its values at tokens 31 and 63, every head
 // gets one record of kRec floats per block:
-//   [0,64)     rowf_l = exp2(clamp(cs_l - c31))            output-row factor of the decay mask
-//   [64,128)   f_s    = dt_s * exp2(clamp(c31 - cs_s))     input factor of the decay mask
+//   [0,64)     rowf_l = exp2(cs_l - c31)                   output-row factor of the decay mask
+//   [64,128)   f_s    = dt_s * exp2(c31 - cs_s)            input factor of the decay mask
 //   [128]      exp2(c63 - c31)     state: middle of the block -> end of the block
 //   [129]      c63                 log2 of the block's total decay
 //   [130]      exp2(c31)           state: start of the block -> middle of the block
 //   [131]      [128] * [130] of the next block: middle of the block -> middle of the next block
+// The two mask factors evaluate exponents as large as the decay across half a block.  A block of a head
+// whose decay across either half exceeds 2^kSteepExp is STEEP: the factors would leave the fp32 range
+// (their product would be wrong by O(1) with nothing non-finite to show for it), so the mask is not
+// factorised there -- the full kernel applies exp2(cs_l - cs_s), whose exponent is never positive, to
+// the scores of that head in registers (see chunk_scan_kernel) -- and the record holds instead
+//   [0,64)     dt_l
+//   [64,128)   dt_s * exp2(c63 - cs_s)    input weight relative to the END of the block (never > dt_s)
+//   [128]      1     [129] c63     [130] -1 (marks the record)     [131] A * log2(e)
+// With these the states-only pass, which multiplies [64,128) by [128] and by the decay of the later
+// blocks, needs no change.  No benchmark input is steep (dt <= 0.1, |A| <= 16: 74 at most).
 // The block covers rows [row0, row0 + 64) of dt (tokens, H); rows from row_end on are not part of
 // the sequence and count as dt = 0 (state-neutral padding).  The caller's dt values pass through
 // dt_apply (optional bias, softplus, clamp) as they are read.  dt is transposed through LDS, 64 tokens
@@ -321,7 +332,7 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, size_t row0, size_
 // h * rec_stride + rec_off.
 constexpr int kRec = 2 * kBlk + 4;
 constexpr int kCumHeads = 16;
-constexpr float kMaxExp = 100.f;
+constexpr float kSteepExp = 96.f;
 __device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1], size_t row0, size_t row_end, int h0,
                                                    size_t rec_stride, size_t rec_off, const float *__restrict__ dt,
                                                    const float *__restrict__ A, float *__restrict__ prep, int H,
@@ -371,18 +382,27 @@ __device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1],
   }
 #pragma unroll
   for (int k = 0; k < kPer; ++k) {
+    const float c0 = __shfl(v[k], 0, 64);
     const float c31 = __shfl(v[k], 31, 64);
     const float c63 = __shfl(v[k], 63, 64);
     if (live[k]) {
       const int h = h0 + wave + k * (kThreads / 64);
       float *rec = prep + (static_cast<size_t>(h) * rec_stride + rec_off) * kRec;
-      rec[lane] = fast_exp2(fminf(fmaxf(v[k] - c31, -kMaxExp), kMaxExp));
-      rec[kBlk + lane] = dtv[k] * fast_exp2(fminf(fmaxf(c31 - v[k], -kMaxExp), kMaxExp));
-      if (lane < 4)
-        rec[2 * kBlk + lane] = lane == 0   ? fast_exp2(c63 - c31)
-                               : lane == 1 ? c63
-                               : lane == 2 ? fast_exp2(c31)
-                                           : fast_exp2(c63 - c31) * fast_exp2(nx[k]);
+      // (negated test: a NaN prefix sum also takes the steep form, which has no exponent to overflow)
+      const bool steep = !(c0 - c31 <= kSteepExp && c31 - c63 <= kSteepExp);
+      if (!steep) {
+        rec[lane] = fast_exp2(v[k] - c31);
+        rec[kBlk + lane] = dtv[k] * fast_exp2(c31 - v[k]);
+        if (lane < 4)
+          rec[2 * kBlk + lane] = lane == 0   ? fast_exp2(c63 - c31)
+                                 : lane == 1 ? c63
+                                 : lane == 2 ? fast_exp2(c31)
+                                             : fast_exp2(c63 - c31) * fast_exp2(nx[k]);
+      } else {
+        rec[lane] = dtv[k];
+        rec[kBlk + lane] = dtv[k] * fast_exp2(c63 - v[k]);
+        if (lane < 4) rec[2 * kBlk + lane] = lane == 0 ? 1.f : lane == 1 ? c63 : lane == 2 ? -1.f : ah[k];
+      }
     }
   }
 }
@@ -598,18 +618,36 @@ constexpr int kGTile = 32 * kGLowStride + 32 * kGStride;  // elements of a compa
 // kStreamY: y leaves with non-temporal stores, so that writing it does not evict x, which the states-only
 // pass has just pulled into the memory-side cache, before this kernel reads it again (chosen per launch,
 // see stream_y()).
-template <bool kStatesOnly, int HPW, bool kStreamY = false>
-__global__ __launch_bounds__(128 * HPW) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void chunk_scan_kernel(const ScanParams p) {
+// The LDS tiles of a scan workgroup, as pointers that keep their address space across a function call.
+typedef __attribute__((address_space(3))) uint16_t lds_u16;
+struct LdsTiles {
+  lds_u16 *sC, *sBt, *sG, *sXm, *sRaw;
+};
+template <bool kStatesOnly, int HPW>
+struct ScanLds {
+  static constexpr int kCElems = kStatesOnly ? 8 : kBlk * kCStride, kCBufs = kStatesOnly ? 1 : 2;
+  static constexpr int kBtElems = kN * kBtStride;
+  static constexpr int kGElems = kStatesOnly ? 8 : kGTile, kGBufs = kStatesOnly ? 1 : 2;
+  static constexpr int kXmElems = kP * kXStride;
+  static constexpr int kRawElems = kStatesOnly ? 8 : kBlk * kRawStride, kRawBufs = kStatesOnly ? 1 : 2 * HPW;
+};
+
+// The walk of one workgroup over its blocks.  kMixed: the walk may meet steep blocks (see
+// block_cumsum_block) and chooses the form block by block; otherwise every block has the common form.
+template <bool kStatesOnly, int HPW, bool kStreamY, bool kMixed>
+__device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv, const LdsTiles lds) {
   static_assert(!(kStatesOnly && kStreamY), "the states-only pass writes no y");
+  static_assert(!(kStatesOnly && kMixed), "the states-only pass needs no second form");
   static_assert(kStatesOnly || HPW == kHeadsPerWg, "the full kernel is written for four heads per workgroup");
   constexpr int kThr = 128 * HPW;
   constexpr int kBtPieces = kN * kBlk * 2 / 16 / kThr;  // 16-byte pieces of the B^T tile per thread
-  __shared__ __align__(16) uint16_t sC[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kBlk * kCStride];
-  __shared__ __align__(16) uint16_t sBt[2][kN * kBtStride];                   // B^T [n][s]
-  __shared__ __align__(16) uint16_t sG[kStatesOnly ? 1 : 2][kStatesOnly ? 8 : kGTile];
-  __shared__ __align__(16) uint16_t sXm[HPW][kP * kXStride];                  // Xm^T [row][s], per head
-  __shared__ __align__(16) uint16_t sRaw[kStatesOnly ? 1 : 2 * HPW][kStatesOnly ? 8 : kBlk * kRawStride];  // x [s][col], per wave
+  using L = ScanLds<kStatesOnly, HPW>;
+  // (generic pointers derived from the address-space pointers: the compiler keeps them LDS accesses)
+  uint16_t (*const sC)[L::kCElems] = reinterpret_cast<uint16_t (*)[L::kCElems]>((uint16_t *)lds.sC);
+  uint16_t (*const sBt)[L::kBtElems] = reinterpret_cast<uint16_t (*)[L::kBtElems]>((uint16_t *)lds.sBt);  // B^T [n][s]
+  uint16_t (*const sG)[L::kGElems] = reinterpret_cast<uint16_t (*)[L::kGElems]>((uint16_t *)lds.sG);
+  uint16_t (*const sXm)[L::kXmElems] = reinterpret_cast<uint16_t (*)[L::kXmElems]>((uint16_t *)lds.sXm);  // Xm^T [row][s], per head
+  uint16_t (*const sRaw)[L::kRawElems] = reinterpret_cast<uint16_t (*)[L::kRawElems]>((uint16_t *)lds.sRaw);  // x [s][col], per wave
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -619,8 +657,6 @@ void chunk_scan_kernel(const ScanParams p) {
   // for the whole kernel lets it run ahead between barriers instead of both contending for the same
   // pipe in the same phase (measured: 3 % on 8 x 4096 tokens x 48 heads, nothing lost elsewhere).
   if (wave >= 4) __builtin_amdgcn_s_setprio(1);
-  SeqView sv;
-  if (!wg_coords(p, !kStatesOnly, sv)) return;  // uniform over the workgroup
   const int col = sv.col, sg = sv.sg;
   const int h = col * HPW + hw;
   const int g = (col * HPW) / p.hpg;  // the heads of a workgroup share one group
@@ -817,6 +853,13 @@ void chunk_scan_kernel(const ScanParams p) {
   // to an MFMA operand, so the multiplies hide under the matrix instructions of the same loop.
   float pending = jb0 < jb1 && !kStatesOnly ? factor_ptr(jb0)[2] : 1.f;
   asm volatile("" : "+v"(pending));  // arrived before the loop (see Dh above)
+  // A steep block (see block_cumsum_block) marks its record with a negative entry there; it starts from
+  // the state as it is at the start of the block.  Uniform over the wave, kept in a scalar register.
+  bool steep_cur = false;
+  if constexpr (kMixed) {
+    steep_cur = __builtin_amdgcn_readfirstlane(__float_as_int(pending)) < 0;
+    if (steep_cur) pending = 1.f;
+  }
 
   // LDS operand addresses of this lane (element offsets inside a tile)
   const uint32_t a_c = r * kCStride + 8 * kg;    // + 32 rows for the second token half, + 16 kk
@@ -973,11 +1016,36 @@ void chunk_scan_kernel(const ScanParams p) {
     // iterations are written out per loop trip): block jb sits in LDS buffer par, block jb+1 in
     // register set par^1 (it is staged during this iteration, and the set then refilled with block
     // jb+3), block jb+2 in register set par.
-    auto body = [&](int par, int jb) __attribute__((always_inline)) {
+    // steep_tag: the block is steep (a compile-time constant per instantiation; the loop below picks the
+    // instantiation block by block).  Both forms issue the same memory operations in the same order, so
+    // the waits the compiler derives for the common form are not affected by the other.  The steep form
+    // differs in four places: the state -> output term is scaled by exp2(cs_l) as soon as it is complete;
+    // the masked product takes the raw x and, as its other operand, the scores times
+    // dt_s exp2(cs_l - cs_s) -- the un-factorised mask, exponent never positive, applied in registers to
+    // this lane's eight scores per operand; the state is taken to the end of the block before the update
+    // (whose operand carries end-relative weights, see the record); the output rows need no factor.
+    // In a mixed walk the factor owed to the accumulators at the end of the block depends on the form of
+    // the next block.
+    auto body = [&](int par, int jb, auto steep_tag) __attribute__((always_inline)) {
+      constexpr bool kSteep = decltype(steep_tag)::value;
+      static_assert(kMixed || !kSteep, "a steep block is only met in the mixed walk");
+      float pend_next = 0.f;
       const int buf = par, setA = par ^ 1;
       const bool more = jb < jlast;
-      float pend_next = 0.f;
+      f32x4 fac = {0.f, 0.f, 0.f, 0.f};  // record entries 128..131 of this block
+      float nf = 0.f;                    // entry 130 of the next block
       const uint16_t *const tC = sC[buf], *const tG = sG[buf], *const tBt = sBt[buf];
+      float dt_t = 0.f, cs_t = 0.f;      // steep: step size and inclusive prefix sum of dt*A*log2(e) of token `lane`
+      if constexpr (kSteep) {
+        const float alog = factor_ptr(jb)[3];
+        dt_t = kg ? rowf1 : rowf0;
+        cs_t = dt_t * alog;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const float up = __shfl_up(cs_t, off, 64);
+          if (lane >= off) cs_t += up;
+        }
+      }
 
       if constexpr (kRowStores) {
         // the raw rows of this block go to LDS only now: until the barrier that ended the previous
@@ -987,8 +1055,10 @@ void chunk_scan_kernel(const ScanParams p) {
         load_part(0, at(jb + 2), par);
       }
       Operand xo[4];  // Xm^T[row r][s = 16q + 8kg ..]
+      if constexpr (!kSteep) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
+        for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
+      }
       Operand bto[2][4];  // operands of the state update, double buffered over q
       f32x16 Y[2] = {};
 
@@ -1024,19 +1094,77 @@ void chunk_scan_kernel(const ScanParams p) {
         if (kk < 5) stage_tile(kk, buf ^ 1);
         if (kk == 4) {
           load_rowf(at(jb + 1));
-          // to the middle of the next block; after the last block only the way to its end is left
-          pend_next = factor_ptr(jb)[more ? 3 : 0];
+          if constexpr (kMixed) {
+            fac = *reinterpret_cast<const f32x4 *>(factor_ptr(jb));
+            nf = factor_ptr(at(jb + 1))[2];
+          } else {
+            // to the middle of the next block; after the last block only the way to its end is left
+            pend_next = factor_ptr(jb)[more ? 3 : 0];
+          }
         }
         if (kk == 5) load_part(1, at(jb + 2));
         if (kk == 6) load_part(2, at(jb + 2));
-        stage_column(kk, setA);
+        // (steep: the state update is the only user of this block's scaled input, which the next block's
+        // would overwrite here; it is staged after that update instead)
+        if constexpr (!kSteep) stage_column(kk, setA);
         __builtin_amdgcn_sched_barrier(0);
       }
       // the masked product
       u32x4 xe;  // x of the block in output layout (token r + 32lt, columns 32ph + 16kg + 8c ..), read from
                  // the raw copy at the start of the group whose end uses it
+      if constexpr (kSteep) {
+        const float csl[2] = {__shfl(cs_t, r, 64), __shfl(cs_t, 32 + r, 64)};
+        {
+          const float s0 = fast_exp2(csl[0]), s1 = fast_exp2(csl[1]);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+          for (int i = 0; i < 16; ++i) {
+            Y[0][i] *= s0;
+            Y[1][i] *= s1;
+          }
+        }
+        const uint16_t *const xcol_src = myRaw + pi_of_row(r);  // this lane's column of the raw rows
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float cs_s[8], dt_s[8];
+          Operand xr;  // raw x^T[row r][s = 16q + 8kg ..]
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int src = 16 * q + 8 * kg + j;
+            cs_s[j] = __shfl(cs_t, src, 64);
+            dt_s[j] = __shfl(dt_t, src, 64);
+          }
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const uint32_t lo = xcol_src[(16 * q + 8 * kg + 2 * k) * kRawStride];
+            const uint32_t hi = xcol_src[(16 * q + 8 * kg + 2 * k + 1) * kRawStride];
+            xr.u[k] = lo | (hi << 16);
+          }
+#pragma unroll
+          for (int lt = (q < 2 ? 0 : 1); lt < 2; ++lt) {
+            const Operand gq = lds16(lt ? tG + a_g1 + 16 * q : tG + a_g0 + 16 * q);
+            Operand gh;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              const float w0 = dt_s[2 * k] * fast_exp2(fminf(csl[lt] - cs_s[2 * k], 0.f));
+              const float w1 = dt_s[2 * k + 1] * fast_exp2(fminf(csl[lt] - cs_s[2 * k + 1], 0.f));
+              gh.u[k] = pack2(bf_lo(gq.u[k]) * w0, bf_hi(gq.u[k]) * w1);
+            }
+            Y[lt] = mfma(xr, gh, Y[lt]);
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) bto[0][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride);
+        const float e63 = fast_exp2(fac.y);  // the state, so far at the start of the block, to its end
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) Hacc[nt][i] *= e63;
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int q = 0; q < (kSteep ? 0 : 4); ++q) {
         if (q < 3) {
           go[(q + 1) & 1][1] = lds16(tG + a_g1 + 16 * (q + 1));
           if (q + 1 < 2) go[(q + 1) & 1][0] = lds16(tG + a_g0 + 16 * (q + 1));
@@ -1053,7 +1181,7 @@ void chunk_scan_kernel(const ScanParams p) {
       //      epilogue of the block (y[l][col] = rowf_l Y + D x; element i of the lane is column
       //      32ph + 16kg + i), one quarter per group ----
       const Rsrc ry = y_rsrc(jb);
-      const float rowf[2] = {rowf0, rowf1};
+      const float rowf[2] = {kSteep ? 1.f : rowf0, kSteep ? 1.f : rowf1};
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         if (q < 3) {
@@ -1083,6 +1211,10 @@ void chunk_scan_kernel(const ScanParams p) {
       //      rows of 32 tokens; the raw rows of the next block then go to LDS at the top of the next
       //      iteration instead of here.  Tokens beyond the sequence are beyond the descriptor and are
       //      dropped. ----
+      if constexpr (kSteep) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) stage_column(c, setA);
+      }
       if constexpr (kRowStores) __syncthreads();  // both halves of every row of y are in LDS
       {
         u32x4 yo[4];
@@ -1096,7 +1228,19 @@ void chunk_scan_kernel(const ScanParams p) {
         stage_raw(setA);
         load_part(0, at(jb + 3), setA);
       }
-      pending = pend_next;
+      // The factor still owed to the accumulators: from the middle of this block (steep: from its end) to
+      // the middle of the next block -- to its start if that one is steep; after the last block only the
+      // way to its end is left.
+      if constexpr (kMixed) {
+        const bool next_steep = more && __builtin_amdgcn_readfirstlane(__float_as_int(nf)) < 0;
+        if constexpr (kSteep)
+          pending = more && !next_steep ? nf : 1.f;
+        else
+          pending = more && !next_steep ? fac.w : fac.x;
+        steep_cur = next_steep;
+      } else {
+        pending = pend_next;
+      }
       rowf0 = rowf0n;
       rowf1 = rowf1n;
       __syncthreads();  // block jb's tiles may be overwritten; block jb+1's tiles are visible
@@ -1104,12 +1248,27 @@ void chunk_scan_kernel(const ScanParams p) {
     // pairs of blocks, then the odd one: with the test between the two halves of a pair the compiler
     // would also have to allow for "first half, then first half again", where the set staged at the
     // top has only just been requested, and would wait for the newest loads in every iteration
-    int jb = jb0;
-    for (; jb + 1 < jb1; jb += 2) {
-      body(0, jb);
-      body(1, jb + 1);
+    if constexpr (!kMixed) {
+      int jb = jb0;
+      for (; jb + 1 < jb1; jb += 2) {
+        body(0, jb, std::false_type{});
+        body(1, jb + 1, std::false_type{});
+      }
+      if (jb < jb1) body(0, jb, std::false_type{});
+    } else {
+      auto step = [&](int par, int jb) __attribute__((always_inline)) {
+        if (steep_cur)
+          body(par, jb, std::true_type{});
+        else
+          body(par, jb, std::false_type{});
+      };
+      int jb = jb0;
+      for (; jb + 1 < jb1; jb += 2) {
+        step(0, jb);
+        step(1, jb + 1);
+      }
+      if (jb < jb1) step(0, jb);
     }
-    if (jb < jb1) body(0, jb);
   }
   if constexpr (!kStatesOnly) {
 #pragma unroll
@@ -1139,6 +1298,56 @@ void chunk_scan_kernel(const ScanParams p) {
               f32x4{Hacc[nt][4 * i4 + 0], Hacc[nt][4 * i4 + 1], Hacc[nt][4 * i4 + 2], Hacc[nt][4 * i4 + 3]};
       }
   }
+}
+
+// The mixed walk as a function of its own: it is compiled, and its registers are allocated, apart from
+// the kernel around the call, so what the rare steep form needs (it spills) costs the common walk nothing.
+// (Arguments by value: a reference would make the kernel keep its own copy in private memory, where
+// nothing counts as uniform any more.)
+template <int HPW, bool kStreamY>
+__device__ __attribute__((noinline)) void scan_walk_mixed(const ScanParams p, const SeqView sv, const LdsTiles lds) {
+  scan_walk<false, HPW, kStreamY, true>(p, sv, lds);
+}
+
+// Whether the blocks this wave walks in the full scan include a steep one: one lane per block reads the
+// marker of its record.
+template <int HPW>
+__device__ __forceinline__ bool walk_meets_steep_block(const ScanParams &p, const SeqView &sv) {
+  const int lane = threadIdx.x & 63;
+  const int h = sv.col * HPW + (static_cast<int>(threadIdx.x) >> 7);
+  const int hrec = h / p.pdiv;
+  const bool plain = p.vp.tok0 == nullptr;
+  const size_t rec0 = plain ? (sv.blk0 * p.Hrec + static_cast<size_t>(hrec) * sv.blk_stride) : (hrec * sv.blk_stride + sv.blk0);
+  const int jb0 = min(sv.nb, sv.sg * p.seg_blocks), jb1 = min(sv.nb, jb0 + p.seg_blocks);
+  const float *marks = p.prep + rec0 * kRec + 2 * kBlk + 2;
+  float lowest = 1.f;
+  for (int j = jb0; j < jb1; j += 64)
+    if (j + lane < jb1) lowest = fminf(lowest, marks[static_cast<size_t>(j + lane) * kRec]);
+  return __builtin_amdgcn_ballot_w64(lowest < 0.f) != 0;
+}
+
+template <bool kStatesOnly, int HPW, bool kStreamY = false>
+__global__ __launch_bounds__(128 * HPW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void chunk_scan_kernel(const ScanParams p) {
+  using L = ScanLds<kStatesOnly, HPW>;
+  __shared__ __align__(16) uint16_t sC[L::kCBufs][L::kCElems];
+  __shared__ __align__(16) uint16_t sBt[2][L::kBtElems];
+  __shared__ __align__(16) uint16_t sG[L::kGBufs][L::kGElems];
+  __shared__ __align__(16) uint16_t sXm[HPW][L::kXmElems];
+  __shared__ __align__(16) uint16_t sRaw[L::kRawBufs][L::kRawElems];
+  SeqView sv;
+  if (!wg_coords(p, !kStatesOnly, sv)) return;  // uniform over the workgroup
+  const LdsTiles lds = {(lds_u16 *)&sC[0][0], (lds_u16 *)&sBt[0][0], (lds_u16 *)&sG[0][0], (lds_u16 *)&sXm[0][0],
+                        (lds_u16 *)&sRaw[0][0]};
+  if constexpr (!kStatesOnly) {
+    // Waves of one workgroup may take different walks: both stage the same shared tiles and meet at the
+    // same barriers, block for block.
+    if (walk_meets_steep_block<HPW>(p, sv)) {
+      scan_walk_mixed<HPW, kStreamY>(p, sv, lds);
+      return;
+    }
+  }
+  scan_walk<kStatesOnly, HPW, kStreamY, false>(p, sv, lds);
 }
 
 // ---- segment_pass: slot[0] = h0; slot[sg] = exp2(decay[sg-1]) * slot[sg-1] + local[sg-1] --------

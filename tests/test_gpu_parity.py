@@ -7,7 +7,8 @@ import torch
 
 from oracle import ssd_oracle
 from paper_2603_09555_amd import inputs
-from parity import TOL, assert_close, to_np64
+import blocked_model
+from parity import TOL, assert_close, errors, to_np64
 
 pytestmark = pytest.mark.gpu
 
@@ -321,13 +322,16 @@ def test_mfma_prefill_matches_oracle(ssd, case, monkeypatch):
     else:
         monkeypatch.delenv("SSD_SEG_CHUNKS", raising=False)
     # T = 300: an initial state of realistic size (what a prefill of similar inputs leaves behind);
-    # T = 1000: a large N(0,1) one, far bigger than anything the inputs build up, whose outputs are
-    # sums of large cancelling terms -> judged by the componentwise bound (see parity.py)
-    h0, mag_y, mag_st = None, None, None
+    # T = 1000: a large N(0,1) one, far bigger than anything the inputs build up, whose early outputs are
+    # sums of large cancelling terms.  Both gates apply to every case.  For the large initial state the
+    # limit of the allclose gate is what the documented bf16 rounding of the state operand of the
+    # state -> output product costs on these very inputs, computed on the CPU by blocked_model.py (it is
+    # 2.05e-2 from that rounding alone, see test_blocked_model.py), plus 5 %; and the componentwise bound
+    # is gated in addition.
+    h0, mag_y, mag_st, lim = None, None, None, None
     if cfg.seqlen == 300:
         warm = inputs.make_prefill_inputs(cfg, seed=77)
         h0 = torch.from_numpy(oracle_prefill(warm)[1]).float()
-    inp, y, st = None, None, None
     if cfg.seqlen == 1000:
         h0 = inputs.make_state(cfg, seed=4)
     inp, y, st = run_prefill(ssd, cfg, seed=23, h0=h0)
@@ -335,9 +339,124 @@ def test_mfma_prefill_matches_oracle(ssd, case, monkeypatch):
     if cfg.seqlen == 1000:
         ab = {k: (v.abs() if k in ("x", "B", "C", "D") else v) for k, v in inp.items()}
         mag_y, mag_st = oracle_prefill(ab, h0=h0.abs())
-    e = assert_close(y, y_ref, 2e-2, "mfma y", mag=mag_y)
+        model_y, _ = blocked_model.prefill(inp, h0)
+        lim = max(2e-2, 1.05 * errors(model_y, y_ref)["worst_allclose"])
+        print("allclose limit from the CPU model of the bf16 roundings: %.4e" % lim, flush=True)
+    e = assert_close(y, y_ref, 2e-2, "mfma y", mag=mag_y, allclose_tol=lim)
     assert_close(st, st_ref, 2e-2, "mfma final state", mag=mag_st)
     print("errors", e, flush=True)
+
+
+@pytest.mark.parametrize("case", [(1, 1000, 4, 64, 128, 1, 128, 1), (1, 1000, 12, 64, 128, 1, 128, 3),
+                                  (2, 1500, 8, 64, 128, 2, 64, 4)], ids=lambda c: "x".join(map(str, c)))
+def test_mfma_prefill_continues_a_cached_prompt(ssd, case, monkeypatch):
+    """Several segments from the state a prefill of similar inputs leaves behind (section "The O(1) state
+    cache": later calls continue from the cache), under the plain gates."""
+    *dims, seg = case
+    cfg = cfg_of(*dims, "bf16")
+    monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+    warm = inputs.make_prefill_inputs(cfg, seed=78)
+    h0 = torch.from_numpy(oracle_prefill(warm)[1]).float()
+    inp, y, st = run_prefill(ssd, cfg, seed=24, h0=h0)
+    y_ref, st_ref = oracle_prefill(inp, h0=h0)
+    e = assert_close(y, y_ref, 2e-2, "continued y")
+    assert_close(st, st_ref, 2e-2, "continued final state")
+    print("errors", e, flush=True)
+
+
+# ---- steep decay: step sizes far beyond the benchmark's dt*|A| <= 1.6 ------------------------------------
+def _steep_inputs(cfg, kind, seed):
+    inp = inputs.make_prefill_inputs(cfg, seed=seed)
+    H = cfg.nheads
+    if kind == "uniform":
+        # dt*|A| per token = 0.5, 3, 6, 12, repeated over the heads: the decay across half a 64-token block
+        # is 2^23, 2^139, 2^277, 2^554
+        inp["dt"] = torch.full_like(inp["dt"], 0.5)
+        inp["A"] = torch.tensor([-1.0, -6.0, -12.0, -24.0] * (H // 4))
+    elif kind == "spikes":
+        # the benchmark's step sizes with one token in sixteen 300 times larger: blocks differ, heads differ
+        g = torch.Generator().manual_seed(seed + 1)
+        spike = torch.rand(inp["dt"].shape, generator=g) < 1.0 / 16.0
+        inp["dt"] = torch.where(spike, inp["dt"] * 300.0, inp["dt"])
+    elif kind == "scaled_A":
+        # the benchmark's step sizes (median 0.01, up to 0.1) against |A| up to 1200: dt*|A| of 3 and 12 at
+        # the median, blocks on either side of the threshold inside one head
+        inp["A"] = torch.tensor([-16.0, -300.0, -1200.0, -1.0] * (H // 4))
+    else:
+        raise ValueError(kind)
+    return inp
+
+
+STEEP_CASES = [
+    # Bt, T, H, P, N, G, L, forced chunks per segment, kind, with h0
+    (1, 300, 4, 64, 128, 1, 64, 0, "uniform", False),
+    (2, 1000, 8, 64, 128, 2, 128, 1, "uniform", True),     # several segments, two groups, carried state
+    (1, 1000, 4, 64, 128, 1, 128, 2, "spikes", True),
+    (1, 2048, 8, 64, 128, 1, 256, 0, "scaled_A", False),
+    (1, 700, 4, 128, 128, 1, 64, 1, "scaled_A", True),     # headdim 128: two slices share a head's records
+    (1, 500, 4, 64, 256, 1, 128, 2, "scaled_A", False),    # dstate 256: two state slices
+]
+
+
+@pytest.mark.parametrize("case", STEEP_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_mfma_prefill_with_steep_decay_matches_oracle(ssd, case, monkeypatch):
+    """Blocks whose decay across half a block leaves the range of the factorised mask take the
+    un-factorised form inside the same kernels (Eq. 3 holds for any dt and A): the result matches the
+    oracle like any other, nothing is clamped and nothing turns non-finite."""
+    *dims, seg, kind, with_h0 = case
+    cfg = cfg_of(*dims, "bf16")
+    sh = ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk,
+                        torch.bfloat16)
+    assert ssd.prefill_path(sh) == "mfma_bf16"
+    if seg:
+        monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+    else:
+        monkeypatch.delenv("SSD_SEG_CHUNKS", raising=False)
+    inp = _steep_inputs(cfg, kind, seed=61)
+    spans = blocked_model.block_half_spans(inp["dt"], inp["A"]).max(axis=-1)      # (Bt, H, blocks)
+    steep = spans > 96.0
+    print("steep case", case, "steep blocks per head", steep.sum(axis=(0, 2)).tolist(), "of", steep.shape[2],
+          "largest half-block exponent %.0f" % spans.max(), flush=True)
+    assert steep.any() and not steep.all()
+    h0 = None
+    if with_h0:
+        warm = inputs.make_prefill_inputs(cfg, seed=79)
+        h0 = torch.from_numpy(oracle_prefill(warm)[1]).float()
+    dev = {k: v.cuda() for k, v in inp.items()}
+    y, st = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk,
+                            h0=None if h0 is None else h0.cuda())
+    y2, st2 = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk,
+                              h0=None if h0 is None else h0.cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2) and torch.equal(st, st2)
+    y_ref, st_ref = oracle_prefill(inp, h0=h0)
+    e = assert_close(y, y_ref, 2e-2, "steep y")
+    assert_close(st, st_ref, 2e-2, "steep final state")
+    # head by head: a steep head's outputs must not hide behind the scale of a gentle one
+    yg = to_np64(y)
+    for h in range(cfg.nheads):
+        assert_close(yg[:, :, h], y_ref[:, :, h], 2e-2, "steep y, head %d" % h)
+        assert_close(to_np64(st)[:, h], st_ref[:, h], 2e-2, "steep state, head %d" % h)
+    print("errors", e, flush=True)
+
+
+def test_varlen_prefill_with_steep_decay_matches_oracle(ssd, monkeypatch):
+    monkeypatch.setenv("SSD_SEG_CHUNKS", "1")
+    lens = [130, 0, 700, 64, 5, 301]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cfg = cfg_of(1, int(cu[-1]), 8, 64, 128, 2, 64, "bf16")
+    inp = _steep_inputs(cfg, "scaled_A", seed=67)
+    pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
+    dev = {k: v.cuda() for k, v in pk.items()}
+    h0 = 0.1 * torch.randn((len(lens), 8, 64, 128), generator=torch.Generator().manual_seed(5))
+    print("steep packed batch", lens, flush=True)
+    y, st = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"],
+                                   torch.from_numpy(cu).cuda(), cfg.chunk, h0=h0.cuda())
+    torch.cuda.synchronize()
+    y_ref, st_ref = ssd_oracle.prefill_varlen(pk["x"], pk["dt"], pk["A"], pk["B"], pk["C"], pk["D"], cu, h0=h0)
+    for h in range(cfg.nheads):
+        assert_close(to_np64(y)[:, h], y_ref[:, h], 2e-2, "steep packed y, head %d" % h)
+        assert_close(to_np64(st)[:, h], st_ref[:, h], 2e-2, "steep packed state, head %d" % h)
 
 
 def test_mfma_and_generic_paths_agree(ssd, monkeypatch):
