@@ -60,7 +60,8 @@ typedef enum {
   SSD_ERR_UNSUPPORTED = -4, /* valid but not implemented (see each entry point) */
   SSD_ERR_WORKSPACE = -5,   /* workspace NULL, misaligned or smaller than required */
   SSD_ERR_HIP = -6,         /* a HIP launch reported an error */
-  SSD_ERR_ALIGN = -7        /* a tensor pointer is not 16-byte aligned */
+  SSD_ERR_ALIGN = -7,       /* a tensor pointer is not 16-byte aligned */
+  SSD_ERR_TOO_LARGE = -8    /* ssd_prefill_static: the shape needs more scratch than the library holds */
 } ssd_status;
 
 /* Plain data, filled by the caller; the library never keeps the pointer. */
@@ -131,6 +132,31 @@ SSD_API ssd_status ssd_prefill_dt(const ssd_shape *shape, const ssd_dt_transform
                           const void *B, const void *C, const float *D,
                           const float *h0, void *y, float *final_state,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * ssd_prefill for callers that cannot allocate device memory or pass a workspace
+ * along: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The scratch that ssd_prefill takes through its workspace argument
+ * is a buffer of SSD_STATIC_SCRATCH_BYTES that the library itself holds on every
+ * GPU it runs on, from the moment its code is loaded there until the process
+ * ends.  The call allocates and frees nothing (its first use on a device looks
+ * the buffer's address up, once).  Same arguments, results (bit for bit), errors
+ * and aliasing rules as ssd_prefill, plus
+ *     SSD_ERR_TOO_LARGE   ssd_prefill_workspace_bytes(shape) exceeds
+ *                         SSD_STATIC_SCRATCH_BYTES (nothing is enqueued);
+ *     SSD_ERR_HIP         the buffer's address could not be obtained.
+ * Every call on a GPU shares that GPU's buffer: calls that overlap in time on one
+ * GPU (different streams, different threads) race on it and must be serialised
+ * by the caller; calls on one stream are ordered by the stream.  Nothing in the
+ * buffer needs to start at zero, and nothing is kept there between calls.
+ * The device that is current when the call is made must be the one that holds
+ * the tensors (as for any launch on hip_stream).
+ */
+#define SSD_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+SSD_API ssd_status ssd_prefill_static(const ssd_shape *shape, const void *x, const float *dt,
+                              const float *A, const void *B, const void *C,
+                              const float *D, const float *h0, void *y,
+                              float *final_state, void *hip_stream);
 
 /*
  * Prefill of a packed, variable-length batch: `batch` independent sequences

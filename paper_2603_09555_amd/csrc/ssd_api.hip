@@ -3,6 +3,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <limits>
+#include <mutex>
 
 #include "ssd_internal.hpp"
 
@@ -111,6 +112,44 @@ ssd_status ssd_prefill(const ssd_shape *shape, const void *x, const float *dt, c
                        void *hip_stream) {
   return prefill_impl(shape, x, dt, A, B, C, D, h0, y, final_state, workspace, workspace_bytes_given,
                       hip_stream, nullptr);
+}
+
+namespace {
+// Scratch of ssd_prefill_static: one copy per GPU, part of the library's device image.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the address of a device's copy is looked up once,
+// with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[SSD_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+ssd_status static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SSD_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return SSD_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SSD_OK;
+}
+}  // namespace
+
+ssd_status ssd_prefill_static(const ssd_shape *shape, const void *x, const float *dt, const float *A,
+                              const void *B, const void *C, const float *D, const float *h0, void *y,
+                              float *final_state, void *hip_stream) {
+  Dims d;
+  const ssd_status st = make_dims(shape, false, &d);
+  if (st != SSD_OK) return st;
+  if (workspace_bytes(d) > SSD_STATIC_SCRATCH_BYTES) return SSD_ERR_TOO_LARGE;
+  if (!x || !dt || !A || !B || !C || !D || !y || !final_state) return SSD_ERR_NULL;  // before any HIP call
+  void *ws = nullptr;
+  const ssd_status sp = static_scratch(&ws);
+  if (sp != SSD_OK) return sp;
+  return prefill_impl(shape, x, dt, A, B, C, D, h0, y, final_state, ws, SSD_STATIC_SCRATCH_BYTES, hip_stream,
+                      nullptr);
 }
 
 ssd_status ssd_prefill_dt(const ssd_shape *shape, const ssd_dt_transform *dt_transform, const void *x,
@@ -352,6 +391,7 @@ const char *ssd_status_string(ssd_status status) {
     case SSD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SSD_ERR_HIP: return "HIP launch error";
     case SSD_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+    case SSD_ERR_TOO_LARGE: return "shape needs more scratch than the library's static buffer holds";
   }
   return "unknown status";
 }

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libssd_hip.so")
 SSD_F32, SSD_BF16 = 0, 1
 SSD_OK = 0
 
-EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
+EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_static", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
            "ssd_decode_steps_layers", "ssd_prefill_varlen_workspace_bytes", "ssd_prefill_varlen",
            "ssd_conv1d_prefill", "ssd_conv1d_step", "ssd_prefill_dt", "ssd_prefill_varlen_dt",
            "ssd_decode_step_layers_dt", "ssd_decode_steps_layers_dt", "ssd_peak_probe",
@@ -47,6 +47,9 @@ _lib.ssd_prefill_workspace_bytes.restype = _sz
 _lib.ssd_prefill_workspace_bytes.argtypes = [_sp]
 _lib.ssd_prefill.restype = ctypes.c_int
 _lib.ssd_prefill.argtypes = [_sp] + [_vp] * 10 + [_sz, _vp]
+_lib.ssd_prefill_static.restype = ctypes.c_int
+_lib.ssd_prefill_static.argtypes = [_sp] + [_vp] * 10
+STATIC_SCRATCH_BYTES = 32 << 20   # SSD_STATIC_SCRATCH_BYTES of include/ssd.h
 class ssd_dt_transform(ctypes.Structure):
     _fields_ = [("dt_bias", ctypes.c_void_p), ("dt_softplus", ctypes.c_int32), ("dt_min", ctypes.c_float),
                 ("dt_max", ctypes.c_float)]
@@ -189,6 +192,29 @@ def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, wor
         profile.extend((names[i].decode(), float(ms[i])) for i in range(n.value))
     if st != SSD_OK:
         raise SSDError(st, "ssd_prefill")
+    return y, final_state
+
+
+def ssd_prefill_static(x, dt, A, B, C, D, chunk, y, final_state, h0=None):
+    """``ssd_prefill_static`` of the C ABI: the prefill on the library's own scratch buffer.  The C call
+    allocates nothing; neither does this wrapper -- ``y`` and ``final_state`` must be given."""
+    Bt, T, H, P = x.shape
+    G, N = B.shape[2], B.shape[3]
+    shape = make_shape(Bt, T, H, P, N, G, chunk, x.dtype)
+    if B.dtype != x.dtype or C.dtype != x.dtype or y.dtype != x.dtype:
+        raise ValueError("x, B, C and y must share one dtype")
+    for t in (dt, A, D, h0, final_state):
+        if t is not None and t.dtype != torch.float32:
+            raise ValueError("dt, A, D, h0 and final_state must be fp32")
+    if tuple(dt.shape) != (Bt, T, H) or tuple(A.shape) != (H,) or tuple(D.shape) != (H,) \
+            or tuple(C.shape) != tuple(B.shape) or tuple(B.shape[:2]) != (Bt, T) or tuple(y.shape) != tuple(x.shape) \
+            or tuple(final_state.shape) != (Bt, H, P, N) or (h0 is not None and tuple(h0.shape) != (Bt, H, P, N)):
+        raise ValueError("inconsistent tensor shapes")
+    _check_dev(x, dt, A, B, C, D, h0, y, final_state)
+    st = _lib.ssd_prefill_static(ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(h0),
+                                 _ptr(y), _ptr(final_state), _stream_ptr())
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_prefill_static")
     return y, final_state
 
 

@@ -115,6 +115,27 @@ def test_prefill_rejects_before_any_hip_call(ssd):
     assert call(shape(ssd, batch=2 ** 30, seqlen=2 ** 30)) == -2
 
 
+def test_static_prefill_rejects_before_any_hip_call(ssd):
+    """The entry point for callers that cannot allocate: invalid shapes, shapes whose scratch exceeds the
+    library's static buffer and NULL tensors are refused on the host (no GPU needed to see it)."""
+    import torch
+    lib = ssd.raw()
+    one = ctypes.c_void_p(256)
+    ok = ssd.make_shape(1, 256, 4, 64, 128, 1, 64, torch.bfloat16)
+    assert ssd.prefill_workspace_bytes(ok) <= ssd.STATIC_SCRATCH_BYTES
+    args = [one] * 6 + [None, one, one, None]
+    assert lib.ssd_prefill_static(None, *args) == -1
+    bad = ssd.make_shape(1, 0, 4, 64, 128, 1, 64, torch.bfloat16)
+    assert lib.ssd_prefill_static(ctypes.byref(bad), *args) == -2
+    huge = ssd.make_shape(1, 16384, 80, 64, 128, 1, 256, torch.bfloat16)
+    assert ssd.prefill_workspace_bytes(huge) > ssd.STATIC_SCRATCH_BYTES
+    assert lib.ssd_prefill_static(ctypes.byref(huge), *args) == -8
+    assert lib.ssd_prefill_static(ctypes.byref(ok), None, *args[1:]) == -1
+    with open(os.path.join(ROOT, "include", "ssd.h")) as f:
+        m = re.search(r"#define SSD_STATIC_SCRATCH_BYTES \(\(size_t\)(\d+) << (\d+)\)", f.read())
+    assert m and int(m.group(1)) << int(m.group(2)) == ssd.STATIC_SCRATCH_BYTES
+
+
 def test_decode_rejects_before_any_hip_call(ssd):
     lib = ssd.raw()
     fake = ctypes.c_void_p(4096)
