@@ -28,7 +28,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # dense bf16 MFMA, MI355X
-PEAK_VALU_F32_TFLOPS = 157.3     # fp32 vector
+PEAK_VALU_F32_TFLOPS = 157.3     # fp32 vector, the published figure (counts packed fp32: 256 CUs x 4 SIMDs x 16
+                                 # lanes x 2 (packed) x 2 (fma) x 2.4 GHz); the peak every "alu" fraction here uses
+PEAK_VALU_F32_NON_PACKED = 78.6  # the same without packed instructions, which this build does not emit
 PEAK_HBM_GBS = 8000.0
 
 
@@ -77,13 +79,29 @@ def decode_flops(cfg, nlayers):
     return nlayers * cfg.batch * cfg.nheads * cfg.headdim * (5.0 * cfg.dstate + 3.0)
 
 
-# HBM bytes per launch of a kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
-# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a copy of known size gives on this chip; see
-# profiles/hbm_traffic_fetch_write_size.txt).  Measured values, not computed here: null for others.
-HBM_TRAFFIC_BYTES = {
-    ("c3_2p7b_long", "chunk_scan"): int((2 * 109647.3 + 166425.2) * 1024),
-    ("c3_2p7b_long", "segment_states"): int((2 * 85108.1 + 28185.8) * 1024),
-}
+# HBM bytes per launch of a kernel come from the committed summary of the rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of this file, profiles/hbm_traffic_fetch_write_size.txt: its "TRAFFIC <workload> <kernel>
+# fetch_kib=.. write_kib=.." lines, scaled by the factors a copy of known size gives on this chip
+# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; stated in the same file).  Nothing is typed in here; a kernel
+# without a line reports null.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_fetch_write_size.txt")
+FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
+
+
+def read_traffic(path=TRAFFIC_FILE):
+    """{(workload, kernel): HBM bytes per launch} from the TRAFFIC lines of the counter summary."""
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                w = line.split()
+                if len(w) == 5 and w[0] == "TRAFFIC" and w[3].startswith("fetch_kib=") and w[4].startswith("write_kib="):
+                    fetch, write = float(w[3].split("=")[1]), float(w[4].split("=")[1])
+                    out[(w[1], w[2])] = int((FETCH_SCALE * fetch + WRITE_SCALE * write) * 1024)
+    except OSError:
+        pass
+    return out
+
 
 # Which algorithmic FLOPs each kernel of a prefill call is responsible for.
 KERNEL_WORK = {
@@ -128,7 +146,7 @@ def main():
                  "--gpus %d is not supported, use --gpus 1" % args.gpus)
 
     import torch
-    from paper_2603_09555_amd import inputs, ssd
+    from paper_2603_09555_amd import inputs, measure, ssd
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
@@ -151,8 +169,12 @@ def main():
         ws = torch.empty((max(ssd.prefill_workspace_bytes(shape_of(cfg)), 256),), dtype=torch.uint8, device=dev)
 
         def step(profile=None):
-            ssd.ssd_prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], cfg.chunk, y=y,
-                            final_state=st, workspace=ws, profile=profile)
+            if profile is None:
+                ssd.ssd_prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], cfg.chunk, y=y,
+                                final_state=st, workspace=ws)
+            else:  # the measurement library's copy of the same call, an event after every kernel
+                profile.extend(measure.prefill_profile(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"],
+                                                       cfg.chunk, y, st, ws))
             if with_decode:
                 ssd.ssd_decode_step(st, nxt["x"], nxt["dt"], inp["A"], nxt["B"], nxt["C"], inp["D"], y=yd)
 
@@ -228,10 +250,10 @@ def main():
         pa = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).fill_(1)
         pb = torch.empty_like(pa)
         for kind in ("copy", "read", "write", "copy_nt", "read_nt", "write_nt"):
-            rate, ms = ssd.peak_probe(kind, pa, pb, reps=10)
+            rate, ms = measure.peak_probe(kind, pa, pb, reps=10)
             peaks["stream_%s_gbs" % kind] = round(rate / 1e9, 1)
         for label, iters in (("short", 300), ("long", 4000)):
-            rate, ms = ssd.peak_probe("mfma", pa, None, iters=iters, reps=3)
+            rate, ms = measure.peak_probe("mfma", pa, None, iters=iters, reps=3)
             peaks["mfma_bf16_tflops_%s" % label] = round(rate / 1e12, 1)
             peaks["mfma_%s_ms" % label] = round(ms, 3)
         log("[bench] measured peaks: %s" % peaks)
@@ -260,8 +282,18 @@ def main():
         bound, peak = "alu", PEAK_VALU_F32_TFLOPS
     achieved = dom_flops / kern[dom] / 1e9
     roofline = dict(bound=bound, kernel=dom, achieved=round(achieved, 3), peak=peak, unit="TFLOP/s",
-                    frac=round(achieved / peak, 5), traffic=HBM_TRAFFIC_BYTES.get((cfg.name, dom)),
+                    frac=round(achieved / peak, 5), traffic=read_traffic().get((cfg.name, dom)),
                     kernel_ms=round(kern[dom], 5), flops_per_launch=dom_flops)
+    # the whole prefill call (every kernel of it) beside its dominant kernel: the metric is the prefill
+    kern_total = sum(kern.values())
+    tot_c = sum(fl_c.values())
+    roofline["prefill"] = dict(
+        kernels_ms=round(kern_total, 5), tflops_causal=round(tot_c / kern_total / 1e9, 1),
+        frac_of_peak=round(tot_c / kern_total / 1e9 / peak, 5),
+        frac_of_attainable=round(tot_c / kern_total / 1e9 / min(peak, tot_c / prefill_bytes(cfg) * PEAK_HBM_GBS / 1e3), 5),
+        step_frac_of_peak=round(head["frac_of_peak"], 5), step_frac_of_attainable=round(head["frac_of_attainable"], 5),
+        cold_cache_step_frac_of_peak=round(head["cold_cache_tflops_causal"] / peak, 5),
+        note="kernels_ms: sum of the call's kernels by events; step_*: the timed step (prefill + one decode step)")
     if bound == "mfma" and dom == "chunk_scan":
         # what the kernel actually issues: 38 v_mfma_f32_32x32x16_bf16 per wave and 64-token block, two waves
         # per 64-column head slice (confirmed by SQ_INSTS_MFMA, profiles/prefill_c3_sq_counters.txt)
@@ -438,10 +470,10 @@ def main():
         conv["prefill"]["conv_then_ssd_prefill_us"] = round(pair_us, 2)
         log("[bench] conv1d prefill followed by ssd_prefill on its outputs: %.1f us" % pair_us)
         # the same pair with the other cache policy for y (the library chooses from the size of x; the
-        # environment variable overrides the choice per call)
+        # test-only knob overrides the choice)
         other = {}
         for pol in ("0", "1", "0", "1"):   # twice each, the better one kept: clocks drift over the legs of a run
-            os.environ["SSD_Y_STREAM"] = pol
+            ssd.set_knob("y_stream", int(pol))
             for _ in range(3):
                 pair()
             torch.cuda.synchronize()
@@ -451,7 +483,7 @@ def main():
             e1.record()
             torch.cuda.synchronize()
             other[pol] = min(other.get(pol, 1e30), round(e0.elapsed_time(e1) * 1e3 / args.steps, 2))
-        del os.environ["SSD_Y_STREAM"]
+        ssd.set_knob("y_stream", -1)
         conv["prefill"]["pair_us_y_stores_cached"] = other["0"]
         conv["prefill"]["pair_us_y_stores_non_temporal"] = other["1"]
         log("[bench] the pair with y stored through the caches %.1f us, non-temporally %.1f us" % (other["0"], other["1"]))
@@ -527,9 +559,9 @@ def main():
             log("[bench] decode %s: %.2f us/step, %.0f GB/s (%.1f%% of HBM peak)" %
                 (name, us, gbs, 100 * gbs / PEAK_HBM_GBS))
             # the other cache policy for the state (the library streams it past the caches when the states
-            # of a call exceed the memory-side cache; the environment variable overrides that per call)
+            # of a call exceed the memory-side cache; the test-only knob overrides that)
             for pol, key in (("0", "us_per_step_state_cached"), ("1", "us_per_step_state_non_temporal")):
-                os.environ["SSD_DECODE_STREAM"] = pol
+                ssd.set_knob("decode_stream", int(pol))
                 nshort = min(nsteps, 64)
                 for i in range(3):
                     ssd.ssd_decode_step_layers(state, xs[i], dts[i], A, Bs[i], Cs[i], D, y=yd)
@@ -540,7 +572,7 @@ def main():
                 e1.record()
                 torch.cuda.synchronize()
                 decode[name][key] = round(e0.elapsed_time(e1) * 1e3 / nshort, 3)
-            del os.environ["SSD_DECODE_STREAM"]
+            ssd.set_knob("decode_stream", -1)
             log("[bench] decode %s: state through the caches %.2f us/step, non-temporal %.2f us/step" %
                 (name, decode[name]["us_per_step_state_cached"], decode[name]["us_per_step_state_non_temporal"]))
             # the same stacked launches replayed from a HIP graph (the launch work done once), and all
@@ -587,7 +619,9 @@ def main():
                                 speedup_vs_stacked=round(us / us_fused, 2),
                                 bytes_per_step=int(fused_bytes), hbm_gbs=round(fused_bytes / us_fused / 1e3, 1),
                                 gflops=round(decode_flops(c, Ly) / us_fused / 1e3, 1),
-                                frac_of_fp32_valu_peak=round(decode_flops(c, Ly) / us_fused / 1e6 / PEAK_VALU_F32_TFLOPS, 4)))
+                                bound="alu", peak_tflops=PEAK_VALU_F32_TFLOPS,
+                                frac_of_fp32_valu_peak=round(decode_flops(c, Ly) / us_fused / 1e6 / PEAK_VALU_F32_TFLOPS, 4),
+                                frac_of_non_packed_fp32_peak=round(decode_flops(c, Ly) / us_fused / 1e6 / PEAK_VALU_F32_NON_PACKED, 4)))
             log("[bench] decode %s: graph replay %s us/step; %d steps per launch %.2f us/step (%.1fx)" %
                 (name, "-" if us_graph is None else "%.2f" % us_graph, nb, us_fused, us / us_fused))
             del ys_blk

@@ -1,0 +1,41 @@
+/*
+ * ssd_testing.h -- test-only entry points of libssd_hip.so.
+ *
+ * The library chooses by itself which kernel family runs a prefill, how a prompt is
+ * cut into segments and whether outputs and states stream past the caches.  Tests
+ * and tuning runs need to force those choices (to reach every code path at small
+ * sizes, to compare both cache policies bit for bit); these calls do that.  The
+ * settings are process-wide and not synchronised: set them from one thread while no
+ * call of the library is in flight, and reset them afterwards.  Nothing in the
+ * library reads the environment.  Workspace sizes (ssd_prefill_workspace_bytes,
+ * ssd_prefill_varlen_workspace_bytes) do not depend on any knob.
+ */
+#ifndef SSD_TESTING_H_
+#define SSD_TESTING_H_
+
+#include "ssd.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SSD_KNOB_FORCE_GENERIC = 0, /* 1: every prefill runs on the generic fp32 kernels; 0: default */
+  SSD_KNOB_SEG_CHUNKS = 1,    /* k > 0: k chunks per segment in the MFMA prefill; 0: library's choice */
+  SSD_KNOB_SEG_BLOCKS = 2,    /* k > 0: k 64-token blocks per segment (when SEG_CHUNKS is 0); 0: default */
+  SSD_KNOB_SEG_PARTS = 3,     /* k > 0: pieces per segment in the states-only pass, if k divides the
+                                 segment length and the state slots suffice; 0: default */
+  SSD_KNOB_Y_STREAM = 4,      /* 0 / 1: ordinary / non-temporal stores of y in the full scan; -1: default */
+  SSD_KNOB_DECODE_STREAM = 5  /* 0 / 1: ordinary / non-temporal accesses to the decode state; -1: default */
+} ssd_knob;
+
+/* Sets one knob.  Errors: SSD_ERR_SHAPE for an unknown knob. */
+SSD_API ssd_status ssd_testing_set_knob(int32_t knob, int32_t value);
+
+/* All knobs back to the library's own choices. */
+SSD_API void ssd_testing_reset_knobs(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSD_TESTING_H_ */

@@ -1,11 +1,18 @@
 // C ABI of the SSD library (declared in include/ssd.h): host-side validation and dispatch.
 // Every check runs before the first HIP call, so an invalid call enqueues nothing.
-#include <cstdlib>
 #include <cstring>
 #include <limits>
 #include <mutex>
 
 #include "ssd_internal.hpp"
+#include "ssd_testing.h"
+
+namespace ssd {
+Knobs &knobs() {
+  static Knobs k;
+  return k;
+}
+}  // namespace ssd
 
 namespace {
 
@@ -41,16 +48,17 @@ ssd_status make_dims(const ssd_shape *s, bool decode, Dims *out, bool packed = f
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-bool force_generic() {
-  const char *e = std::getenv("SSD_FORCE_GENERIC");
-  return e && e[0] == '1';
-}
+bool force_generic() { return ssd::knobs().force_generic != 0; }
 
 bool use_mfma(const Dims &d) { return !force_generic() && ssd::mfma_supported(d); }
 
-// The family that will run decides (SSD_FORCE_GENERIC must not change between the query and the call).
+// Enough for either kernel family that may run the shape, so that which one does (a test may force the
+// generic one between the query and the call) never invalidates a size the caller was given.
 size_t workspace_bytes(const Dims &d) {
-  return use_mfma(d) ? ssd::mfma_workspace_bytes(d) : ssd::generic_workspace_bytes(d);
+  const size_t generic = ssd::generic_workspace_bytes(d);
+  if (!ssd::mfma_supported(d)) return generic;
+  const size_t mfma = ssd::mfma_workspace_bytes(d);
+  return mfma > generic ? mfma : generic;
 }
 
 // Copies the caller's step-size map into the validated dimensions (nullptr: dt is used as given).
@@ -91,6 +99,15 @@ ssd_status prefill_impl(const ssd_shape *shape, const void *x, const float *dt, 
 }
 
 }  // namespace
+
+namespace ssd {
+ssd_status prefill_traced(const ssd_shape *shape, const void *x, const float *dt, const float *A, const void *B,
+                          const void *C, const float *D, const float *h0, void *y, float *final_state,
+                          void *workspace, size_t workspace_bytes_given, void *hip_stream, KernelTrace *trace) {
+  return prefill_impl(shape, x, dt, A, B, C, D, h0, y, final_state, workspace, workspace_bytes_given, hip_stream,
+                      trace);
+}
+}  // namespace ssd
 
 extern "C" {
 
@@ -161,36 +178,6 @@ ssd_status ssd_prefill_dt(const ssd_shape *shape, const ssd_dt_transform *dt_tra
                       nullptr, dt_transform);
 }
 
-ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, const float *dt, const float *A,
-                               const void *B, const void *C, const float *D, const float *h0, void *y,
-                               float *final_state, void *workspace, size_t workspace_bytes_given,
-                               void *hip_stream, int32_t max_kernels, float *kernel_ms,
-                               const char **kernel_names, int32_t *num_kernels) {
-  if (!kernel_ms || !kernel_names || !num_kernels || max_kernels < 1) return SSD_ERR_NULL;
-  *num_kernels = 0;
-  ssd::KernelTrace trace;
-  int made = 0;
-  for (; made <= ssd::KernelTrace::kMax; ++made)
-    if (hipEventCreate(&trace.ev[made]) != hipSuccess) break;
-  ssd_status st = SSD_ERR_HIP;
-  if (made == ssd::KernelTrace::kMax + 1) {
-    st = prefill_impl(shape, x, dt, A, B, C, D, h0, y, final_state, workspace, workspace_bytes_given,
-                      hip_stream, &trace);
-    if (st == SSD_OK) {
-      if (trace.n > 0 && hipEventSynchronize(trace.ev[trace.n]) != hipSuccess) st = SSD_ERR_HIP;
-      for (int i = 0; st == SSD_OK && i < trace.n && i < max_kernels; ++i) {
-        float ms = 0.f;
-        if (hipEventElapsedTime(&ms, trace.ev[i], trace.ev[i + 1]) != hipSuccess) st = SSD_ERR_HIP;
-        kernel_ms[i] = ms;
-        kernel_names[i] = trace.names[i];
-        *num_kernels = i + 1;
-      }
-    }
-  }
-  for (int i = 0; i < made; ++i) (void)hipEventDestroy(trace.ev[i]);
-  return st;
-}
-
 namespace {
 // The generic kernels take a packed batch while (sequences x heads) and the chunk capacity fit a grid axis.
 bool generic_varlen_ok(const Dims &d) {
@@ -203,8 +190,10 @@ bool use_mfma_varlen(const Dims &d) { return !force_generic() && ssd::mfma_varle
 size_t ssd_prefill_varlen_workspace_bytes(const ssd_shape *shape) {
   Dims d;
   if (make_dims(shape, false, &d, true) != SSD_OK) return 0;
-  if (use_mfma_varlen(d)) return ssd::mfma_varlen_workspace_bytes(d);
-  return generic_varlen_ok(d) ? ssd::generic_varlen_workspace_bytes(d) : 0;  // 0: neither family takes this shape
+  // enough for either family that may run it (see workspace_bytes); 0: neither family takes this shape
+  const size_t generic = generic_varlen_ok(d) ? ssd::generic_varlen_workspace_bytes(d) : 0;
+  const size_t mfma = ssd::mfma_varlen_supported(d) ? ssd::mfma_varlen_workspace_bytes(d) : 0;
+  return mfma > generic ? mfma : generic;
 }
 
 namespace {
@@ -369,17 +358,20 @@ ssd_status ssd_conv1d_step(int32_t batch, int32_t ksize, int32_t io_dtype, const
   return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
 }
 
-ssd_status ssd_peak_probe(int32_t kind, int32_t iters, int32_t reps, void *a, void *b, size_t bytes, float *ms,
-                          double *work, void *hip_stream) {
-  if (!ms || !work || !a) return SSD_ERR_NULL;
-  if (kind < 0 || kind > 6 || reps < 1 || reps > 100000) return SSD_ERR_SHAPE;
-  if (kind == 0 && (iters < 1 || bytes < static_cast<size_t>(2048) * 256 * sizeof(float))) return SSD_ERR_SHAPE;
-  if (kind != 0 && !b) return SSD_ERR_NULL;
-  if (kind != 0 && bytes < 16) return SSD_ERR_SHAPE;
-  if (!aligned16(a) || (b && !aligned16(b))) return SSD_ERR_ALIGN;
-  const hipError_t e = ssd::run_peak_probe(kind, iters, reps, a, b, bytes, ms, work, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
+ssd_status ssd_testing_set_knob(int32_t knob, int32_t value) {
+  ssd::Knobs &k = ssd::knobs();
+  switch (knob) {
+    case SSD_KNOB_FORCE_GENERIC: k.force_generic = value > 0 ? 1 : 0; return SSD_OK;
+    case SSD_KNOB_SEG_CHUNKS: k.seg_chunks = value > 0 ? value : 0; return SSD_OK;
+    case SSD_KNOB_SEG_BLOCKS: k.seg_blocks = value > 0 ? value : 0; return SSD_OK;
+    case SSD_KNOB_SEG_PARTS: k.seg_parts = value > 0 ? value : 0; return SSD_OK;
+    case SSD_KNOB_Y_STREAM: k.y_stream = value < 0 ? -1 : (value != 0); return SSD_OK;
+    case SSD_KNOB_DECODE_STREAM: k.decode_stream = value < 0 ? -1 : (value != 0); return SSD_OK;
+    default: return SSD_ERR_SHAPE;
+  }
 }
+
+void ssd_testing_reset_knobs(void) { ssd::knobs() = ssd::Knobs(); }
 
 const char *ssd_status_string(ssd_status status) {
   switch (status) {

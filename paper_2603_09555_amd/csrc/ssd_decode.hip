@@ -308,9 +308,9 @@ hipError_t launch_typed(int nlayers, const Dims &d, float *state, const void *x,
     while (npairs * split < 1024 && d.P / (2 * split) >= rows_per_pass && split < 8) split *= 2;
     return split;
   };
-  // the states of this call against the memory-side cache (see load_h4); SSD_DECODE_STREAM=0/1 overrides
+  // the states of this call against the memory-side cache (see load_h4); the decode_stream knob overrides
   bool stream_state = npairs * static_cast<size_t>(d.P) * d.N * sizeof(float) > (256ull << 20);
-  if (const char *e = std::getenv("SSD_DECODE_STREAM")) stream_state = std::atoi(e) != 0;
+  if (knobs().decode_stream >= 0) stream_state = knobs().decode_stream != 0;
 #define SSD_DECODE_CASE(LPR_)                                                                            \
   case LPR_:                                                                                             \
     if (stream_state)                                                                                    \

@@ -70,7 +70,7 @@ struct IoBf16 {
   }
 };
 
-// Optional per-kernel timing (used only by ssd_prefill_profile): an event is recorded on the
+// Optional per-kernel timing (used only by the measurement library): an event is recorded on the
 // launch stream after every kernel of a prefill call.
 struct KernelTrace {
   static constexpr int kMax = 8;
@@ -84,6 +84,18 @@ inline void trace_mark(KernelTrace *t, hipStream_t s, const char *name) {
     t->names[t->n++] = name;
   }
 }
+
+// Process-wide overrides of choices the library otherwise makes by itself; set only through the
+// test-only entry points of include/ssd_testing.h (nothing reads the environment).
+struct Knobs {
+  int force_generic = 0;   // 1: every prefill takes the generic fp32 kernels
+  int seg_chunks = 0;      // > 0: chunks per segment of the MFMA prefill
+  int seg_blocks = 0;      // > 0: 64-token blocks per segment (if seg_chunks is not set)
+  int seg_parts = 0;       // > 0: pieces per segment in the states-only pass
+  int y_stream = -1;       // 0 / 1: ordinary / non-temporal stores of y in the full scan
+  int decode_stream = -1;  // 0 / 1: ordinary / non-temporal accesses to the decode state
+};
+Knobs &knobs();
 
 // ---- launchers (each returns the first HIP error it sees) ----
 hipError_t launch_decode(int nlayers, const Dims &d, float *state, const void *x, const float *dt,
@@ -136,8 +148,10 @@ hipError_t launch_conv_prefill(int Bt, int T, int ksize, bool bf16, const void *
 hipError_t launch_conv_step(int Bt, int ksize, bool bf16, void *state, const void *u, const float *w, const float *bias,
                             void *const z[3], const int width[3], int act, hipStream_t stream);
 
-hipError_t run_peak_probe(int kind, int iters, int reps, void *a, void *b, size_t bytes, float *ms, double *work,
-                          hipStream_t stream);
+// ssd_prefill with an event recorded after every kernel (the measurement library's ssd_prefill_profile).
+ssd_status prefill_traced(const ssd_shape *shape, const void *x, const float *dt, const float *A, const void *B,
+                          const void *C, const float *D, const float *h0, void *y, float *final_state,
+                          void *workspace, size_t workspace_bytes_given, void *hip_stream, KernelTrace *trace);
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

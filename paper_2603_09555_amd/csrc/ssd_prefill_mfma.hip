@@ -45,7 +45,6 @@
 //   chunk_scan<false> per (batch, 4 heads, segment): everything above, from the entering state.
 // A segment is a whole number of 64-token blocks; with one segment only the first and the last kernel
 // run.
-#include <cstdlib>
 #include <type_traits>
 
 #include "ssd_internal.hpp"
@@ -1410,8 +1409,8 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
 // serial pass over segment states (traffic proportional to segments x sequences) and two launches.
 // The constants are a least-squares fit to 31 timed (shape, segment length) points of the three
 // bf16 benchmark shapes (residual 5 us rms).
-// SSD_SEG_CHUNKS=k forces k chunks per segment (tests), SSD_SEG_BLOCKS=k forces k blocks and
-// SSD_SEG_PARTS=k forces k pieces per segment in the states-only pass (tuning).
+// The test-only knobs (see Knobs) force chunks or blocks per segment, and pieces per segment in the
+// states-only pass.
 constexpr int kNumCUs = 256;
 double rounds_time(long wgs, int blocks, double t_idle, double t_busy) {
   double t = 0.0;
@@ -1460,14 +1459,8 @@ double states_cost(long groups, double seqs, int S, int seg_blocks, int max_slot
 int choose_seg_blocks(const Dims &d, int min_blocks, int max_slots, int max_parts) {
   const int chunk_blocks = d.L / kBlk;
   const int nblocks = (d.T + kBlk - 1) / kBlk;
-  if (const char *e = std::getenv("SSD_SEG_CHUNKS")) {
-    const int k = std::atoi(e);
-    if (k >= 1) return (k > d.Nc ? d.Nc : k) * chunk_blocks;
-  }
-  if (const char *e = std::getenv("SSD_SEG_BLOCKS")) {
-    const int k = std::atoi(e);
-    if (k >= min_blocks) return k;
-  }
+  if (const int k = knobs().seg_chunks; k >= 1) return (k > d.Nc ? d.Nc : k) * chunk_blocks;
+  if (const int k = knobs().seg_blocks; k >= min_blocks && k >= 1) return k;
   const int slices = d.H * (d.P / kP);
   const long groups = static_cast<long>(d.Bt) * (slices / kHeadsPerWg);
   const double seqs = static_cast<double>(d.Bt) * slices;
@@ -1577,10 +1570,10 @@ bool shape_ok(const Dims &d, unsigned long long tokens, unsigned long long nb) {
 // columns: x of 160 MiB, 7-14 % less time for the full kernel, 4-7 % for the pipeline; x of 180 MiB or
 // more, where x with the other operands no longer fits, 1-2 % slower; x below a quarter of the cache,
 // where x and y both fit, no difference, and the consumer of y is better off finding it cached.
-// SSD_Y_STREAM=0/1 overrides (tuning aid).
+// The y_stream knob overrides (tests, tuning).
 constexpr unsigned long long kMemCacheBytes = 256ull << 20;
 bool stream_y(const Dims &d, const NSlice &ns, bool two_passes, int rows) {
-  if (const char *e = std::getenv("SSD_Y_STREAM")) return std::atoi(e) != 0;
+  if (knobs().y_stream >= 0) return knobs().y_stream != 0;
   if (!two_passes || ns.width > kN) return false;  // no second read of x; later state slices re-read y to add to it
   const unsigned long long x_bytes = 2ull * rows * d.T * d.H * d.P;
   return 4 * x_bytes > kMemCacheBytes && 3 * x_bytes <= 2 * kMemCacheBytes;
@@ -1661,10 +1654,7 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
     const long groups = static_cast<long>(d.Bt) * (d.H * (d.P / kP) / kHeadsPerWg);
     const double seqs = static_cast<double>(d.Bt) * d.H * (d.P / kP);
     (void)states_cost(groups, seqs, S, seg_blocks, w.S_max, 8, &parts);
-    if (const char *e = std::getenv("SSD_SEG_PARTS")) {  // tuning aid, like SSD_SEG_BLOCKS
-      const int k = std::atoi(e);
-      if (k >= 1 && seg_blocks % k == 0 && (S - 1) * k + 1 <= w.S_max) parts = k;
-    }
+    if (const int k = knobs().seg_parts; k >= 1 && seg_blocks % k == 0 && (S - 1) * k + 1 <= w.S_max) parts = k;
   }
   p.parts = parts;
   p.part_blocks = seg_blocks / parts;

@@ -18,11 +18,12 @@ LIB_PATH = os.path.join(_HERE, "libssd_hip.so")
 SSD_F32, SSD_BF16 = 0, 1
 SSD_OK = 0
 
-EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_static", "ssd_prefill_profile", "ssd_decode_step", "ssd_decode_step_layers",
+EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_static", "ssd_decode_step", "ssd_decode_step_layers",
            "ssd_decode_steps_layers", "ssd_prefill_varlen_workspace_bytes", "ssd_prefill_varlen",
            "ssd_conv1d_prefill", "ssd_conv1d_step", "ssd_prefill_dt", "ssd_prefill_varlen_dt",
-           "ssd_decode_step_layers_dt", "ssd_decode_steps_layers_dt", "ssd_peak_probe",
-           "ssd_prefill_path", "ssd_status_string", "ssd_version"]
+           "ssd_decode_step_layers_dt", "ssd_decode_steps_layers_dt",
+           "ssd_prefill_path", "ssd_status_string", "ssd_version",
+           "ssd_testing_set_knob", "ssd_testing_reset_knobs"]
 
 
 class ssd_shape(ctypes.Structure):
@@ -57,12 +58,10 @@ class ssd_dt_transform(ctypes.Structure):
 
 _lib.ssd_prefill_dt.restype = ctypes.c_int
 _lib.ssd_prefill_dt.argtypes = [_sp, ctypes.POINTER(ssd_dt_transform)] + [_vp] * 10 + [_sz, _vp]
-_lib.ssd_peak_probe.restype = ctypes.c_int
-_lib.ssd_peak_probe.argtypes = [ctypes.c_int32] * 3 + [_vp, _vp, _sz, ctypes.POINTER(ctypes.c_float),
-                                ctypes.POINTER(ctypes.c_double), _vp]
-_lib.ssd_prefill_profile.restype = ctypes.c_int
-_lib.ssd_prefill_profile.argtypes = [_sp] + [_vp] * 10 + [_sz, _vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_float),
-                                     ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_int32)]
+_lib.ssd_testing_set_knob.restype = ctypes.c_int
+_lib.ssd_testing_set_knob.argtypes = [ctypes.c_int32, ctypes.c_int32]
+_lib.ssd_testing_reset_knobs.restype = None
+_lib.ssd_testing_reset_knobs.argtypes = []
 _lib.ssd_decode_step.restype = ctypes.c_int
 _lib.ssd_decode_step.argtypes = [_sp] + [_vp] * 9
 _lib.ssd_decode_step_layers.restype = ctypes.c_int
@@ -143,14 +142,12 @@ def _dt_transform(dt_bias, dt_softplus, dt_limit, bias_shape):
     return ssd_dt_transform(None if dt_bias is None else dt_bias.data_ptr(), int(bool(dt_softplus)), lo, hi)
 
 
-def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, workspace=None, profile=None,
+def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, workspace=None,
                 dt_bias=None, dt_softplus=False, dt_limit=None):
     """``ssd_prefill`` of the C ABI on torch device tensors.  Returns ``(y, final_state)``.
 
     ``x (Bt,T,H,P)``, ``B, C (Bt,T,G,N)`` in fp32 or bf16; ``dt (Bt,T,H)``, ``A, D (H)``,
     ``h0 (Bt,H,P,N)`` fp32.  Output and workspace tensors are allocated with torch unless given.
-    With ``profile`` a list, the call goes through ``ssd_prefill_profile`` (it waits for the
-    device) and ``(kernel name, milliseconds)`` pairs are appended to the list.
     With ``dt_bias (H)``, ``dt_softplus`` or ``dt_limit=(lo, hi)`` the call goes through
     ``ssd_prefill_dt``: ``dt`` is then the raw value and the kernels apply
     ``clamp(softplus(dt + dt_bias), lo, hi)`` as they read it.
@@ -179,17 +176,9 @@ def ssd_prefill(x, dt, A, B, C, D, chunk, h0=None, y=None, final_state=None, wor
             _ptr(final_state), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_ptr())
     xf = _dt_transform(dt_bias, dt_softplus, dt_limit, (H,))
     if xf is not None:
-        if profile is not None:
-            raise ValueError("profile and a dt transform cannot be combined")
         st = _lib.ssd_prefill_dt(args[0], ctypes.byref(xf), *args[1:])
-    elif profile is None:
-        st = _lib.ssd_prefill(*args)
     else:
-        ms = (ctypes.c_float * 8)()
-        names = (ctypes.c_char_p * 8)()
-        n = ctypes.c_int32(0)
-        st = _lib.ssd_prefill_profile(*args, 8, ms, names, ctypes.byref(n))
-        profile.extend((names[i].decode(), float(ms[i])) for i in range(n.value))
+        st = _lib.ssd_prefill(*args)
     if st != SSD_OK:
         raise SSDError(st, "ssd_prefill")
     return y, final_state
@@ -375,17 +364,16 @@ def ssd_conv1d_step(conv_state, u, weight, bias=None, split=None, activation="si
     return [o for o in outs if o is not None]
 
 
-def peak_probe(kind, a, b=None, iters=0, reps=1):
-    """``ssd_peak_probe``: returns ``(work per second, milliseconds per launch)`` -- flop/s for
-    ``kind="mfma"``, bytes/s for ``"copy"``, ``"read"``, ``"write"`` and their non-temporal forms
-    ``"copy_nt"``, ``"read_nt"``, ``"write_nt"``.  ``a``, ``b``: device tensors."""
-    k = {"mfma": 0, "copy": 1, "read": 2, "write": 3, "copy_nt": 4, "read_nt": 5, "write_nt": 6}[kind]
-    ms, work = ctypes.c_float(0), ctypes.c_double(0)
-    nbytes = a.numel() * a.element_size() if k in (0, 1, 2, 4, 5) else b.numel() * b.element_size()
-    _check_dev(a, b)
-    st = _lib.ssd_peak_probe(k, iters, reps, _ptr(a), _ptr(b), nbytes, ctypes.byref(ms), ctypes.byref(work),
-                             _stream_ptr())
+KNOBS = {"force_generic": 0, "seg_chunks": 1, "seg_blocks": 2, "seg_parts": 3, "y_stream": 4, "decode_stream": 5}
+
+
+def set_knob(name: str, value: int) -> None:
+    """``ssd_testing_set_knob`` (include/ssd_testing.h): force a choice the library otherwise makes itself.
+    Process-wide; for tests and tuning runs only."""
+    st = _lib.ssd_testing_set_knob(KNOBS[name], int(value))
     if st != SSD_OK:
-        raise SSDError(st, "ssd_peak_probe")
-    per = ms.value / reps
-    return work.value / (per * 1e-3), per
+        raise SSDError(st, "ssd_testing_set_knob")
+
+
+def reset_knobs() -> None:
+    _lib.ssd_testing_reset_knobs()

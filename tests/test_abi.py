@@ -17,19 +17,33 @@ def ssd():
     return binding
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "ssd.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"SSD_API\s+[\w\s\*]+?\b(ssd_\w+)\s*\(", text)))
+def declared_symbols(*headers):
+    names = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"SSD_API\s+[\w\s\*]+?\b(ssd_\w+)\s*\(", text))
+    return sorted(names)
+
+
+def exported_symbols(path):
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], check=True, capture_output=True, text=True).stdout
+    return sorted(l.split()[-1] for l in out.splitlines() if " T " in l and l.split()[-1].startswith("ssd_"))
 
 
 def test_header_symbols_are_exported(ssd):
-    names = declared_symbols()
+    """The product library exports exactly what ssd.h and the test-only ssd_testing.h declare -- none of it
+    creates events or waits -- and the measurement library adds exactly what ssd_measure.h declares."""
+    names = declared_symbols("ssd.h", "ssd_testing.h")
     assert len(names) >= 7, names
     assert sorted(ssd.EXPORTS) == names
-    lib = ctypes.CDLL(ssd.LIB_PATH)
-    for n in names:
-        assert hasattr(lib, n), "libssd_hip.so does not export %s" % n
+    assert exported_symbols(ssd.LIB_PATH) == names
+    assert "ssd_prefill_profile" not in names and "ssd_peak_probe" not in names
+    from paper_2603_09555_amd import measure
+    extra = declared_symbols("ssd_measure.h")
+    assert sorted(measure.EXPORTS) == extra == ["ssd_peak_probe", "ssd_prefill_profile"]
+    assert exported_symbols(measure.LIB_PATH) == sorted(names + extra)
 
 
 def test_header_is_plain_c_and_a_c_program_links(ssd, tmp_path):
@@ -136,6 +150,27 @@ def test_static_prefill_rejects_before_any_hip_call(ssd):
     assert m and int(m.group(1)) << int(m.group(2)) == ssd.STATIC_SCRATCH_BYTES
 
 
+def test_knobs_do_not_change_workspace_sizes(ssd):
+    """Forcing the generic kernel family changes which kernels run, never a size the caller was given."""
+    import torch
+    shapes = [ssd.make_shape(2, 1000, 8, 64, 128, 2, 128, torch.bfloat16), ssd.make_shape(1, 512, 4, 32, 16, 1, 64, torch.float32)]
+    try:
+        for sh in shapes:
+            ssd.reset_knobs()
+            a, av, path = ssd.prefill_workspace_bytes(sh), int(ssd.raw().ssd_prefill_varlen_workspace_bytes(ctypes.byref(sh))), ssd.prefill_path(sh)
+            ssd.set_knob("force_generic", 1)
+            assert ssd.prefill_path(sh) == "generic_f32"
+            assert ssd.prefill_workspace_bytes(sh) == a
+            assert int(ssd.raw().ssd_prefill_varlen_workspace_bytes(ctypes.byref(sh))) == av
+            ssd.set_knob("seg_chunks", 1)
+            assert ssd.prefill_workspace_bytes(sh) == a
+            ssd.reset_knobs()
+            assert ssd.prefill_path(sh) == path
+        assert ssd.raw().ssd_testing_set_knob(99, 1) == -2
+    finally:
+        ssd.reset_knobs()
+
+
 def test_decode_rejects_before_any_hip_call(ssd):
     lib = ssd.raw()
     fake = ctypes.c_void_p(4096)
@@ -227,7 +262,8 @@ def test_varlen_and_decode_dt_variants_reject_before_any_hip_call(ssd):
 
 
 def test_peak_probe_rejects_before_any_hip_call(ssd):
-    lib = ssd.raw()
+    from paper_2603_09555_amd import measure
+    lib = measure.raw()
     fake = ctypes.c_void_p(4096)
     ms, work = ctypes.c_float(0), ctypes.c_double(0)
 

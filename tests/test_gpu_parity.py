@@ -19,6 +19,15 @@ def ssd():
     return binding
 
 
+@pytest.fixture(autouse=True)
+def _library_choices_restored(ssd):
+    """Tests force segment lengths, kernel families and cache policies through the test-only knobs of the
+    library; every test starts from, and leaves behind, the library's own choices."""
+    ssd.reset_knobs()
+    yield
+    ssd.reset_knobs()
+
+
 def cfg_of(Bt, T, H, P, N, G, L, io):
     return inputs.SSDConfig("t", Bt, T, H, P, N, G, L, io)
 
@@ -311,16 +320,16 @@ MFMA_CASES = [
 
 
 @pytest.mark.parametrize("case", MFMA_CASES, ids=lambda c: "x".join(map(str, c)))
-def test_mfma_prefill_matches_oracle(ssd, case, monkeypatch):
+def test_mfma_prefill_matches_oracle(ssd, case):
     *dims, seg = case
     cfg = cfg_of(*dims, "bf16")
     sh = ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk,
                         torch.bfloat16)
     assert ssd.prefill_path(sh) == "mfma_bf16"
     if seg:
-        monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+        ssd.set_knob("seg_chunks", seg)
     else:
-        monkeypatch.delenv("SSD_SEG_CHUNKS", raising=False)
+        ssd.set_knob("seg_chunks", 0)
     # T = 300: an initial state of realistic size (what a prefill of similar inputs leaves behind);
     # T = 1000: a large N(0,1) one, far bigger than anything the inputs build up, whose early outputs are
     # sums of large cancelling terms.  Both gates apply to every case.  For the large initial state the
@@ -349,12 +358,12 @@ def test_mfma_prefill_matches_oracle(ssd, case, monkeypatch):
 
 @pytest.mark.parametrize("case", [(1, 1000, 4, 64, 128, 1, 128, 1), (1, 1000, 12, 64, 128, 1, 128, 3),
                                   (2, 1500, 8, 64, 128, 2, 64, 4)], ids=lambda c: "x".join(map(str, c)))
-def test_mfma_prefill_continues_a_cached_prompt(ssd, case, monkeypatch):
+def test_mfma_prefill_continues_a_cached_prompt(ssd, case):
     """Several segments from the state a prefill of similar inputs leaves behind (section "The O(1) state
     cache": later calls continue from the cache), under the plain gates."""
     *dims, seg = case
     cfg = cfg_of(*dims, "bf16")
-    monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+    ssd.set_knob("seg_chunks", seg)
     warm = inputs.make_prefill_inputs(cfg, seed=78)
     h0 = torch.from_numpy(oracle_prefill(warm)[1]).float()
     inp, y, st = run_prefill(ssd, cfg, seed=24, h0=h0)
@@ -399,7 +408,7 @@ STEEP_CASES = [
 
 
 @pytest.mark.parametrize("case", STEEP_CASES, ids=lambda c: "x".join(map(str, c)))
-def test_mfma_prefill_with_steep_decay_matches_oracle(ssd, case, monkeypatch):
+def test_mfma_prefill_with_steep_decay_matches_oracle(ssd, case):
     """Blocks whose decay across half a block leaves the range of the factorised mask take the
     un-factorised form inside the same kernels (Eq. 3 holds for any dt and A): the result matches the
     oracle like any other, nothing is clamped and nothing turns non-finite."""
@@ -409,9 +418,9 @@ def test_mfma_prefill_with_steep_decay_matches_oracle(ssd, case, monkeypatch):
                         torch.bfloat16)
     assert ssd.prefill_path(sh) == "mfma_bf16"
     if seg:
-        monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+        ssd.set_knob("seg_chunks", seg)
     else:
-        monkeypatch.delenv("SSD_SEG_CHUNKS", raising=False)
+        ssd.set_knob("seg_chunks", 0)
     inp = _steep_inputs(cfg, kind, seed=61)
     spans = blocked_model.block_half_spans(inp["dt"], inp["A"]).max(axis=-1)      # (Bt, H, blocks)
     steep = spans > 96.0
@@ -440,8 +449,8 @@ def test_mfma_prefill_with_steep_decay_matches_oracle(ssd, case, monkeypatch):
     print("errors", e, flush=True)
 
 
-def test_varlen_prefill_with_steep_decay_matches_oracle(ssd, monkeypatch):
-    monkeypatch.setenv("SSD_SEG_CHUNKS", "1")
+def test_varlen_prefill_with_steep_decay_matches_oracle(ssd):
+    ssd.set_knob("seg_chunks", 1)
     lens = [130, 0, 700, 64, 5, 301]
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     cfg = cfg_of(1, int(cu[-1]), 8, 64, 128, 2, 64, "bf16")
@@ -459,27 +468,27 @@ def test_varlen_prefill_with_steep_decay_matches_oracle(ssd, monkeypatch):
         assert_close(to_np64(st)[:, h], st_ref[:, h], 2e-2, "steep packed state, head %d" % h)
 
 
-def test_mfma_and_generic_paths_agree(ssd, monkeypatch):
+def test_mfma_and_generic_paths_agree(ssd):
     cfg = cfg_of(2, 700, 8, 64, 128, 2, 128, "bf16")
     inp, y, st = run_prefill(ssd, cfg, seed=29)
-    monkeypatch.setenv("SSD_FORCE_GENERIC", "1")
+    ssd.set_knob("force_generic", 1)
     _, yg, stg = run_prefill(ssd, cfg, seed=29)
-    monkeypatch.delenv("SSD_FORCE_GENERIC")
+    ssd.set_knob("force_generic", 0)
     assert_close(y, to_np64(yg), 2e-2, "mfma vs generic y")
     assert_close(st, to_np64(stg), 2e-2, "mfma vs generic state")
 
 
 @pytest.mark.parametrize("case", [(2, 1000, 8, 64, 128, 2, 128, 2), (1, 700, 4, 128, 128, 1, 64, 1)],
                          ids=lambda c: "x".join(map(str, c)))
-def test_cache_policy_of_the_y_stores_changes_no_bit(ssd, case, monkeypatch):
+def test_cache_policy_of_the_y_stores_changes_no_bit(ssd, case):
     """The full kernel writes y with ordinary or with non-temporal stores, chosen from the size of x;
     either way the result matches the oracle and the two agree bit for bit (plain and packed batches)."""
     *dims, seg = case
     cfg = cfg_of(*dims, "bf16")
-    monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+    ssd.set_knob("seg_chunks", seg)
     outs = {}
     for pol in ("0", "1"):
-        monkeypatch.setenv("SSD_Y_STREAM", pol)
+        ssd.set_knob("y_stream", int(pol))
         print("y store policy", pol, case, flush=True)
         inp, y, st = run_prefill(ssd, cfg, seed=31)
         dev = {k: v.cuda() for k, v in inp.items()}
@@ -490,7 +499,7 @@ def test_cache_policy_of_the_y_stores_changes_no_bit(ssd, case, monkeypatch):
                                          dev["D"], cu, cfg.chunk)
         torch.cuda.synchronize()
         outs[pol] = (y.clone(), st.clone(), yp.clone(), stp.clone())
-    monkeypatch.delenv("SSD_Y_STREAM")
+    ssd.set_knob("y_stream", -1)
     y_ref, st_ref = oracle_prefill(inp)
     assert_close(outs["1"][0], y_ref, 2e-2, "streamed y")
     assert_close(outs["1"][1], st_ref, 2e-2, "final state beside streamed y")
@@ -500,7 +509,7 @@ def test_cache_policy_of_the_y_stores_changes_no_bit(ssd, case, monkeypatch):
 
 
 @pytest.mark.parametrize("io", ["f32", "bf16"])
-def test_cache_policy_of_the_decode_state_changes_no_bit(ssd, io, monkeypatch):
+def test_cache_policy_of_the_decode_state_changes_no_bit(ssd, io):
     """The decode step streams the state past the caches when the states of the call exceed the memory-side
     cache; forced on and off on a small call, both match the oracle and agree bit for bit."""
     Ly, Bt, H, P, N, G = 3, 2, 8, 64, 128, 2
@@ -515,13 +524,13 @@ def test_cache_policy_of_the_decode_state_changes_no_bit(ssd, io, monkeypatch):
     C = (0.25 * torch.randn((Ly, Bt, G, N), generator=g)).to(iod)
     outs = {}
     for pol in ("0", "1"):
-        monkeypatch.setenv("SSD_DECODE_STREAM", pol)
+        ssd.set_knob("decode_stream", int(pol))
         print("decode state policy", pol, io, flush=True)
         sd = state.cuda().clone()
         y = ssd.ssd_decode_step_layers(sd, x.cuda(), dt.cuda(), A.cuda(), B.cuda(), C.cuda(), D.cuda())
         torch.cuda.synchronize()
         outs[pol] = (y, sd)
-    monkeypatch.delenv("SSD_DECODE_STREAM")
+    ssd.set_knob("decode_stream", -1)
     y_ref, st_ref = ssd_oracle.decode_step_layers(state, x, dt, A, B, C, D)
     assert_close(outs["1"][0], y_ref, TOL[io], "decode y, streamed state")
     assert_close(outs["1"][1], st_ref, 1e-5, "decode state, streamed")
@@ -561,14 +570,14 @@ VARLEN_CASES = [
 
 
 @pytest.mark.parametrize("case", VARLEN_CASES, ids=lambda c: "-".join(str(v) for v in c[1:]) + "-n%d" % len(c[0]))
-def test_varlen_prefill_matches_oracle(ssd, case, monkeypatch):
+def test_varlen_prefill_matches_oracle(ssd, case):
     lengths, H, G, L, seg_chunks, with_h0 = case
     H, P, N = (tuple(H) + (128,))[:3] if isinstance(H, tuple) else (H, 64, 128)
     lens = [v[0] if isinstance(v, tuple) else v for v in lengths]   # gaps are simply more sequences
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     T, nseq = int(cu[-1]), len(lens)
     if seg_chunks:
-        monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg_chunks))
+        ssd.set_knob("seg_chunks", seg_chunks)
     cfg = cfg_of(1, T, H, P, N, G, L, "bf16")
     inp = inputs.make_prefill_inputs(cfg, seed=31)
     pk = {k: (v[0] if k in ("x", "dt", "B", "C") else v) for k, v in inp.items()}
@@ -633,7 +642,7 @@ def test_varlen_leaves_unowned_tokens_alone_and_rejects_bad_boundaries(ssd, N):
     (2, 100, 4, 32, 16, 2, 32, "f32", True, True, (1e-3, 1e-1)),        # generic family
     (1, 65, 2, 16, 8, 1, 64, "bf16", True, False, None),                # bias only
 ], ids=lambda c: "x".join(str(v) for v in c))
-def test_prefill_with_fused_dt_transform(ssd, case, monkeypatch):
+def test_prefill_with_fused_dt_transform(ssd, case):
     Bt, T, H, P, N, G, L, io, with_bias, softplus, limit = case
     cfg = cfg_of(Bt, T, H, P, N, G, L, io)
     inp = inputs.make_prefill_inputs(cfg, seed=71)
@@ -752,7 +761,7 @@ def test_varlen_prefill_generic_family_matches_oracle(ssd, case):
     assert_close(st, st_ref, TOL[io], "generic varlen final states")
 
 
-def test_varlen_families_agree_and_bad_boundaries_are_a_no_op_on_both(ssd, monkeypatch):
+def test_varlen_families_agree_and_bad_boundaries_are_a_no_op_on_both(ssd):
     lens = [100, 0, 300, 65]
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     cfg = cfg_of(1, int(cu[-1]), 4, 64, 128, 1, 64, "bf16")
@@ -760,7 +769,7 @@ def test_varlen_families_agree_and_bad_boundaries_are_a_no_op_on_both(ssd, monke
     dev = {k: (v[0] if k in ("x", "dt", "B", "C") else v).cuda() for k, v in inp.items()}
     cud = torch.from_numpy(cu).cuda()
     y1, s1 = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cud, 64)
-    monkeypatch.setenv("SSD_FORCE_GENERIC", "1")
+    ssd.set_knob("force_generic", 1)
     y2, s2 = ssd.ssd_prefill_varlen(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cud, 64)
     torch.cuda.synchronize()
     assert_close(y1, to_np64(y2), 2e-2, "varlen: MFMA vs generic y")
@@ -817,25 +826,26 @@ def test_prefill_replayed_from_a_hip_graph(ssd):
 
 
 def test_peak_probes_run_and_the_copy_probe_copies(ssd):
+    from paper_2603_09555_amd import measure
     a = torch.arange(1 << 22, dtype=torch.int32, device="cuda")          # 16 MiB
     b = torch.zeros_like(a)
-    rate, ms = ssd.peak_probe("copy", a, b, reps=2)
+    rate, ms = measure.peak_probe("copy", a, b, reps=2)
     torch.cuda.synchronize()
     assert torch.equal(a, b) and rate > 1e11 and ms > 0
     odd = torch.arange(1000 * 4 + 4, dtype=torch.int32, device="cuda")    # not a multiple of the 32 KB slabs
     out = torch.zeros_like(odd)
-    ssd.peak_probe("copy", odd, out)
+    measure.peak_probe("copy", odd, out)
     torch.cuda.synchronize()
     assert torch.equal(odd, out)
     for kind in ("read", "write", "read_nt", "write_nt"):
-        rate, _ = ssd.peak_probe(kind, a, b, reps=2)
+        rate, _ = measure.peak_probe(kind, a, b, reps=2)
         assert rate > 1e11
     b.zero_()
-    ssd.peak_probe("copy_nt", a, b)
-    ssd.peak_probe("copy_nt", odd, out.zero_())
+    measure.peak_probe("copy_nt", a, b)
+    measure.peak_probe("copy_nt", odd, out.zero_())
     torch.cuda.synchronize()
     assert torch.equal(a, b) and torch.equal(odd, out)
-    rate, _ = ssd.peak_probe("mfma", a, None, iters=50, reps=2)
+    rate, _ = measure.peak_probe("mfma", a, None, iters=50, reps=2)
     assert rate > 1e13
 
 
@@ -869,12 +879,12 @@ def _random_cases(seed, n):
 
 @pytest.mark.parametrize("case", _random_cases(2024, 24), ids=lambda c: "%s-%dx%dx%dx%dx%d-%s-h0%d-seg%d" % (
     "+".join(map(str, c[0])), c[1], c[2], c[3], c[4], c[5], c[6], c[7], c[8]))
-def test_random_shapes_plain_and_packed(ssd, case, monkeypatch):
+def test_random_shapes_plain_and_packed(ssd, case):
     """Each random case runs packed (all sequences in one call) and plain (the longest sequence alone,
     batch 1): both against the oracle."""
     lens, H, P, N, G, L, io, with_h0, seg = case
     if seg:
-        monkeypatch.setenv("SSD_SEG_CHUNKS", str(seg))
+        ssd.set_knob("seg_chunks", seg)
     tol = TOL[io]
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     T, nseq = int(cu[-1]), len(lens)
