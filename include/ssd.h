@@ -316,8 +316,11 @@ SSD_API ssd_status ssd_conv1d_step(int32_t batch, int32_t ksize, int32_t io_dtyp
 
 /*
  * Name of the kernel family ssd_prefill would use for this shape:
- * "mfma_bf16" (MFMA contractions over LDS-staged tiles), "generic_f32"
- * (plain fp32 kernels, any shape), or "invalid".  Host-only.
+ * "mfma_bf16" (bf16 io: bf16 MFMA contractions over LDS-staged tiles, fp32
+ * accumulation), "mfma_f32" (fp32 io, headdim a multiple of 32, dstate a multiple
+ * of 8 up to 128: fp32 MFMA contractions, one launch, the workspace is not
+ * touched), "generic_f32" (plain fp32 vector kernels, any shape), or "invalid".
+ * Host-only.
  */
 SSD_API const char *ssd_prefill_path(const ssd_shape *shape);
 

@@ -15,7 +15,9 @@ extern "C" {
 
 /*
  * ssd_prefill (Alg. 1; see ssd.h) with a HIP event recorded on `hip_stream` after
- * every kernel of the call (the prefill of Alg. 1 is several kernels).  Unlike
+ * every kernel of the call (the prefill of Alg. 1 is several kernels).  The
+ * call is enqueued twice back to back and the second run is the timed one, so
+ * that no interval includes the host's enqueue latency.  Unlike
  * every other entry point it creates and destroys HIP events and WAITS for the
  * call to finish.  On return kernel_ms[i] (HOST array of max_kernels floats)
  * holds the duration in milliseconds of the i-th kernel, kernel_names[i] (HOST

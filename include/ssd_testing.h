@@ -26,7 +26,10 @@ typedef enum {
   SSD_KNOB_SEG_PARTS = 3,     /* k > 0: pieces per segment in the states-only pass, if k divides the
                                  segment length and the state slots suffice; 0: default */
   SSD_KNOB_Y_STREAM = 4,      /* 0 / 1: ordinary / non-temporal stores of y in the full scan; -1: default */
-  SSD_KNOB_DECODE_STREAM = 5  /* 0 / 1: ordinary / non-temporal accesses to the decode state; -1: default */
+  SSD_KNOB_DECODE_STREAM = 5, /* 0 / 1: ordinary / non-temporal accesses to the decode state; -1: default */
+  SSD_KNOB_FORCE_MFMA_F32 = 6 /* 1: fp32 io runs on the fp32 MFMA kernel whenever the shape is eligible (headdim
+                                 a multiple of 32, dstate a multiple of 8 up to 128), also where the library
+                                 expects the generic kernels to be faster; 0: default */
 } ssd_knob;
 
 /* Sets one knob.  Errors: SSD_ERR_SHAPE for an unknown knob. */

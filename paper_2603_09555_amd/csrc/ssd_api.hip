@@ -51,6 +51,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bool force_generic() { return ssd::knobs().force_generic != 0; }
 
 bool use_mfma(const Dims &d) { return !force_generic() && ssd::mfma_supported(d); }
+bool use_mfma_f32(const Dims &d) { return !force_generic() && ssd::mfma_f32_supported(d, ssd::knobs().force_mfma_f32 != 0); }
 
 // Enough for either kernel family that may run the shape, so that which one does (a test may force the
 // generic one between the query and the call) never invalidates a size the caller was given.
@@ -93,6 +94,8 @@ ssd_status prefill_impl(const ssd_shape *shape, const void *x, const float *dt, 
   const hipError_t e =
       use_mfma(d)
           ? ssd::launch_prefill_mfma(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace)
+      : use_mfma_f32(d)
+          ? ssd::launch_prefill_mfma_f32(d, x, dt, A, B, C, D, h0, y, final_state, stream, trace)
           : ssd::launch_prefill_generic(d, x, dt, A, B, C, D, h0, y, final_state, workspace, stream,
                                         trace);
   return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;
@@ -120,7 +123,7 @@ size_t ssd_prefill_workspace_bytes(const ssd_shape *shape) {
 const char *ssd_prefill_path(const ssd_shape *shape) {
   Dims d;
   if (make_dims(shape, false, &d) != SSD_OK) return "invalid";
-  return use_mfma(d) ? "mfma_bf16" : "generic_f32";
+  return use_mfma(d) ? "mfma_bf16" : use_mfma_f32(d) ? "mfma_f32" : "generic_f32";
 }
 
 ssd_status ssd_prefill(const ssd_shape *shape, const void *x, const float *dt, const float *A,
@@ -367,6 +370,7 @@ ssd_status ssd_testing_set_knob(int32_t knob, int32_t value) {
     case SSD_KNOB_SEG_PARTS: k.seg_parts = value > 0 ? value : 0; return SSD_OK;
     case SSD_KNOB_Y_STREAM: k.y_stream = value < 0 ? -1 : (value != 0); return SSD_OK;
     case SSD_KNOB_DECODE_STREAM: k.decode_stream = value < 0 ? -1 : (value != 0); return SSD_OK;
+    case SSD_KNOB_FORCE_MFMA_F32: k.force_mfma_f32 = value > 0 ? 1 : 0; return SSD_OK;
     default: return SSD_ERR_SHAPE;
   }
 }

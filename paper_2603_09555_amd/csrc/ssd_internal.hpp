@@ -94,6 +94,7 @@ struct Knobs {
   int seg_parts = 0;       // > 0: pieces per segment in the states-only pass
   int y_stream = -1;       // 0 / 1: ordinary / non-temporal stores of y in the full scan
   int decode_stream = -1;  // 0 / 1: ordinary / non-temporal accesses to the decode state
+  int force_mfma_f32 = 0;  // 1: fp32 io takes the fp32 MFMA kernel whenever the shape is eligible
 };
 Knobs &knobs();
 
@@ -118,6 +119,12 @@ hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, co
                                const void *B, const void *C, const float *D, const float *h0,
                                void *y, float *final_state, void *workspace, hipStream_t stream,
                                KernelTrace *trace = nullptr);
+
+// fp32 io on fp32 MFMA (one launch, no workspace); see ssd_prefill_mfma_f32.hip.
+bool mfma_f32_supported(const Dims &d, bool whenever_eligible);  // false: only where it is expected to win
+hipError_t launch_prefill_mfma_f32(const Dims &d, const void *x, const float *dt, const float *A, const void *B,
+                                   const void *C, const float *D, const float *h0, void *y, float *final_state,
+                                   hipStream_t stream, KernelTrace *trace = nullptr);
 
 // Device-side tables of a packed variable-length batch (all int32; see ssd_prefill_mfma.hip, "tables of a
 // variable-length call").  tok0 == nullptr: plain batch.

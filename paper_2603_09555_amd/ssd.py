@@ -364,7 +364,8 @@ def ssd_conv1d_step(conv_state, u, weight, bias=None, split=None, activation="si
     return [o for o in outs if o is not None]
 
 
-KNOBS = {"force_generic": 0, "seg_chunks": 1, "seg_blocks": 2, "seg_parts": 3, "y_stream": 4, "decode_stream": 5}
+KNOBS = {"force_generic": 0, "seg_chunks": 1, "seg_blocks": 2, "seg_parts": 3, "y_stream": 4, "decode_stream": 5,
+         "force_mfma_f32": 6}
 
 
 def set_knob(name: str, value: int) -> None:

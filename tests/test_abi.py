@@ -102,7 +102,7 @@ def test_workspace_query(ssd):
     # seqlen need not be a multiple of chunk, and chunk may exceed seqlen
     assert ssd.prefill_workspace_bytes(shape(ssd, seqlen=65)) > 0
     assert ssd.prefill_workspace_bytes(shape(ssd, seqlen=5, chunk=64)) > 0
-    assert ssd.prefill_path(shape(ssd)) in ("generic_f32", "mfma_bf16")
+    assert ssd.prefill_path(shape(ssd)) in ("generic_f32", "mfma_f32", "mfma_bf16")
 
 
 def test_prefill_rejects_before_any_hip_call(ssd):

@@ -373,6 +373,72 @@ def test_mfma_prefill_continues_a_cached_prompt(ssd, case):
     print("errors", e, flush=True)
 
 
+# ---- fp32 io on fp32 MFMA (headdim % 32 == 0, dstate % 8 == 0 up to 128) -----------------------------------
+F32_MFMA_CASES = [
+    # Bt, T, H, P, N, G, L, with h0
+    (1, 512, 4, 32, 16, 1, 64, False),      # configs[0]
+    (1, 700, 4, 64, 128, 2, 256, True),     # Mamba-2 head shape, ragged last block, carried state
+    (2, 2048, 8, 64, 128, 1, 256, False),   # 32 blocks per sequence
+    (2, 130, 6, 96, 72, 3, 64, True),       # three column slices per head, dstate 72: a padded third state tile
+    (1, 1, 2, 32, 8, 1, 16, True),          # a single token
+    (3, 65, 4, 32, 40, 2, 100, False),      # one block and one token; chunk neither a divisor nor a multiple of 64
+]
+
+
+@pytest.mark.parametrize("case", F32_MFMA_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_f32_mfma_prefill_matches_oracle(ssd, case):
+    *dims, with_h0 = case
+    cfg = cfg_of(*dims, "f32")
+    sh = ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk,
+                        torch.float32)
+    if cfg.seqlen == 512:
+        assert ssd.prefill_path(sh) == "mfma_f32"      # configs[0] takes it by the library's own choice
+    ssd.set_knob("force_mfma_f32", 1)                  # (few heads and many blocks would go to the generic kernels)
+    assert ssd.prefill_path(sh) == "mfma_f32"
+    h0 = inputs.make_state(cfg, seed=6, scale=0.3) if with_h0 else None
+    inp, y, st = run_prefill(ssd, cfg, seed=41, h0=h0)
+    _, y2, st2 = run_prefill(ssd, cfg, seed=41, h0=h0)
+    assert torch.equal(y, y2) and torch.equal(st, st2)
+    y_ref, st_ref = oracle_prefill(inp, h0=h0)
+    e = assert_close(y, y_ref, 1e-4, "fp32 mfma y")
+    assert_close(st, st_ref, 1e-4, "fp32 mfma final state")
+    print("errors", e, flush=True)
+    # the generic fp32 kernels on the same inputs: both families are held to the same tolerance
+    ssd.set_knob("force_generic", 1)
+    assert ssd.prefill_path(sh) == "generic_f32"
+    _, yg, stg = run_prefill(ssd, cfg, seed=41, h0=h0)
+    assert_close(yg, y_ref, 1e-4, "generic fp32 y")
+    assert_close(stg, st_ref, 1e-4, "generic fp32 final state")
+
+
+def test_f32_mfma_prefill_with_steep_decay_and_fused_dt(ssd):
+    """fp32 MFMA path at dt*|A| of 0.5 ... 12 per token (the mask is evaluated un-factorised, exponent never
+    positive, so no step size is special), and with the step-size activation applied as dt is read."""
+    cfg = cfg_of(2, 300, 4, 64, 128, 1, 64, "f32")
+    ssd.set_knob("force_mfma_f32", 1)
+    assert ssd.prefill_path(ssd.make_shape(2, 300, 4, 64, 128, 1, 64, torch.float32)) == "mfma_f32"
+    inp = _steep_inputs(cfg, "uniform", seed=43)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    y, st = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
+    torch.cuda.synchronize()
+    y_ref, st_ref = oracle_prefill(inp)
+    for h in range(cfg.nheads):
+        assert_close(to_np64(y)[:, :, h], y_ref[:, :, h], 1e-4, "steep fp32 y, head %d" % h)
+        assert_close(to_np64(st)[:, h], st_ref[:, h], 1e-4, "steep fp32 state, head %d" % h)
+    raw = inputs.make_prefill_inputs(cfg, seed=44)
+    g = torch.Generator().manual_seed(45)
+    dt_raw = torch.randn(raw["dt"].shape, generator=g) * 1.5 - 3.0
+    bias = torch.randn((cfg.nheads,), generator=g) * 0.5
+    dev = {k: v.cuda() for k, v in raw.items()}
+    y, st = ssd.ssd_prefill(dev["x"], dt_raw.cuda(), dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk,
+                            dt_bias=bias.cuda(), dt_softplus=True, dt_limit=(1e-3, 0.5))
+    torch.cuda.synchronize()
+    raw["dt"] = torch.from_numpy(ssd_oracle.dt_transform(dt_raw, bias, True, (1e-3, 0.5))).float()
+    y_ref, st_ref = oracle_prefill(raw)
+    assert_close(y, y_ref, 1e-4, "fp32 mfma y with fused dt")
+    assert_close(st, st_ref, 1e-4, "fp32 mfma state with fused dt")
+
+
 # ---- steep decay: step sizes far beyond the benchmark's dt*|A| <= 1.6 ------------------------------------
 def _steep_inputs(cfg, kind, seed):
     inp = inputs.make_prefill_inputs(cfg, seed=seed)
