@@ -177,8 +177,7 @@ SSD_API ssd_status ssd_prefill_static(const ssd_shape *shape, const void *x, con
  *   workspace         at least ssd_prefill_varlen_workspace_bytes() bytes, 256-byte aligned
  * Tokens outside every sequence are left untouched in y.
  * Shapes of the MFMA kernel family (bf16 io, headdim a multiple of 64, dstate a
- * multiple of 8 up to 512, chunk a multiple of 64, heads per group x headdim /
- * 64 a multiple of 4) run on it; every other shape and fp32 io run on the
+ * multiple of 8 up to 512) run on it; every other shape and fp32 io run on the
  * generic fp32 kernels, which need batch x nheads <= 65535 and
  * ceil(seqlen / chunk) + batch <= 65535 (else SSD_ERR_UNSUPPORTED, and
  * ssd_prefill_varlen_workspace_bytes returns 0).

@@ -1,6 +1,6 @@
 // MFMA prefill for the Mamba-2 head shape (headdim 64 or a multiple of it, dstate 128 -- other state
-// sizes are mapped onto it, see "state slices" at the launcher -- bf16 io, chunk % 64 == 0, heads per
-// group x (headdim / 64) a multiple of 4).  A head with headdim 64 k is
+// sizes are mapped onto it, see "state slices" at the launcher -- bf16 io; any chunk length, any number of
+// heads per group).  A head with headdim 64 k is
 // processed as k independent heads of 64 columns ("head" below means such a 64-column slice): its
 // columns never interact, x, y and the state are laid out exactly as those of k narrower heads, and
 // the slices share the head's decay records, A and D.
@@ -17,7 +17,8 @@
 // the first one scales output rows, and what remains of the mask -- the causal zero pattern --
 // is head independent and baked into G = tril(C B^T), computed once per group.  So the mask is
 // never materialised, costs no per-element work per head, and every exponent that is evaluated
-// is bounded by the decay of 32 tokens (clamped at 2^+-100, far beyond dt*|A| = 1.6 per token).
+// is bounded by the decay of 32 tokens; blocks where that leaves the fp32 range ("steep" blocks, far beyond
+// the benchmark's dt*|A| <= 1.6 per token) keep the mask un-factorised, see block_cumsum_block.
 // With Ht = exp(c31) * (state entering the block), per block and head:
 //     Y^T  = Ht C^T + Xm^T G^T            (state -> output, K = dstate; intra-block, K <= 64)
 //     y    = exp(cs_l - c31) o Y + D x     (epilogue)
@@ -469,6 +470,8 @@ struct ScanParams {
   float *seg_state;        // states-only: local end state of a segment -> the slot of the NEXT segment
   float *seg_decay;        // states-only: log2 of the segment's total decay, one per slot
   int T, H, G, hpg, NB, seg_blocks, S;  // H, hpg count 64-column slices
+  int cpg;                 // workgroups ("head groups of four") per B/C group: ceil(hpg / 4); the slots of the
+                           // last one beyond hpg repeat the group's last slice with every store suppressed
   // The states-only pass may cut every segment into `parts` pieces of `part_blocks` blocks (more,
   // shorter workgroups when the segments alone would leave most of the chip idle); the pass over
   // segment states then chains the pieces, and a sequence has `slots` state slots, of which segment
@@ -657,8 +660,13 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
   // pipe in the same phase (measured: 3 % on 8 x 4096 tokens x 48 heads, nothing lost elsewhere).
   if (wave >= 4) __builtin_amdgcn_s_setprio(1);
   const int col = sv.col, sg = sv.sg;
-  const int h = col * HPW + hw;
-  const int g = (col * HPW) / p.hpg;  // the heads of a workgroup share one group
+  // The heads of a workgroup share one B/C group.  A group whose number of (64-column) slices is not a
+  // multiple of four leaves slots of its last workgroup without a slice: those waves repeat the group's last
+  // slice -- they take part in the shared staging and the barriers like any other -- and write nothing.
+  const int g = col / p.cpg;
+  const int slot = (col % p.cpg) * HPW + hw;
+  const bool live = slot < p.hpg;
+  const int h = g * p.hpg + min(slot, p.hpg - 1);
   // workspace numbering: tiles (b, g, block), records (b, h, block), state slots (b, h, segment) for a
   // plain batch; (g, block), (h, block), (h, segment) with batch-wide block / segment numbers otherwise
   const bool plain = p.vp.tok0 == nullptr;
@@ -690,7 +698,7 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
   const Rsrc rs_prep = make_rsrc(prep_bh, static_cast<uint32_t>(sv.nb) * (kRec * 4));
   // descriptors of x, y and C start at the block and end at the sequence's last token
   auto x_rsrc = [&](int jb) { return make_rsrc(xb + static_cast<size_t>(jb) * kBlk * xrow, xbytes - static_cast<uint32_t>(jb) * kBlk * xrow); };
-  auto y_rsrc = [&](int jb) { return make_rsrc(yb + static_cast<size_t>(jb) * kBlk * xrow, xbytes - static_cast<uint32_t>(jb) * kBlk * xrow); };
+  auto y_rsrc = [&](int jb) { return make_rsrc(yb + static_cast<size_t>(jb) * kBlk * xrow, live ? xbytes - static_cast<uint32_t>(jb) * kBlk * xrow : 0u); };
   auto c_rsrc = [&](int jb) { return make_rsrc(cb + static_cast<size_t>(jb) * kBlk * crow, cbytes - static_cast<uint32_t>(jb) * kBlk * crow); };
   const uint32_t vt = static_cast<uint32_t>(tid) * 16;  // shared tiles: 16 bytes per thread, tid-major
   const uint32_t xcol = static_cast<uint32_t>(h) * (kP * 2) + 64 * ph;
@@ -1281,12 +1289,12 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
   int out_valid = kN;
   if (kStatesOnly) {
     out = p.seg_state + (slot0 + sg + 1) * (kP * kN) + static_cast<size_t>(pcol) * kN;
-    if (lane == 0 && ph == 0) p.seg_decay[slot0 + sg] = seg_total;
+    if (lane == 0 && ph == 0 && live) p.seg_decay[slot0 + sg] = seg_total;
   } else if (sg == sv.S - 1) {
     out = p.final_state + (bh * kP + pcol) * p.ns.width + p.ns.off;
     out_valid = p.ns.valid;
   }
-  if (out != nullptr) {
+  if (out != nullptr && live) {
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
@@ -1313,7 +1321,8 @@ __device__ __attribute__((noinline)) void scan_walk_mixed(const ScanParams p, co
 template <int HPW>
 __device__ __forceinline__ bool walk_meets_steep_block(const ScanParams &p, const SeqView &sv) {
   const int lane = threadIdx.x & 63;
-  const int h = sv.col * HPW + (static_cast<int>(threadIdx.x) >> 7);
+  const int slot = (sv.col % p.cpg) * HPW + (static_cast<int>(threadIdx.x) >> 7);
+  const int h = (sv.col / p.cpg) * p.hpg + min(slot, p.hpg - 1);
   const int hrec = h / p.pdiv;
   const bool plain = p.vp.tok0 == nullptr;
   const size_t rec0 = plain ? (sv.blk0 * p.Hrec + static_cast<size_t>(hrec) * sv.blk_stride) : (hrec * sv.blk_stride + sv.blk0);
@@ -1426,9 +1435,11 @@ double rounds_time(long wgs, int blocks, double t_idle, double t_busy) {
 // exceed what fills the chip several times over; and never more than fill the chip four times over
 // (at least 64), which keeps the workspace of a very long prompt small: the choice below would not
 // take more anyway.
+// Workgroups of four head slots per batch row and segment: every B/C group has ceil(slices per group / 4).
+int head_groups(const Dims &d) { return d.G * ((d.hpg * (d.P / kP) + kHeadsPerWg - 1) / kHeadsPerWg); }
 int max_segments(const Dims &d) {
   const int nblocks = (d.T + kBlk - 1) / kBlk;
-  const long groups = static_cast<long>(d.Bt) * (d.H * (d.P / kP) / kHeadsPerWg);
+  const long groups = static_cast<long>(d.Bt) * head_groups(d);
   long by_fill = (8L * kNumCUs + groups - 1) / groups;
   if (by_fill > 64) by_fill = 64;
   if (by_fill > nblocks) by_fill = nblocks;
@@ -1462,7 +1473,7 @@ int choose_seg_blocks(const Dims &d, int min_blocks, int max_slots, int max_part
   if (const int k = knobs().seg_chunks; k >= 1) return (k > d.Nc ? d.Nc : k) * chunk_blocks;
   if (const int k = knobs().seg_blocks; k >= min_blocks && k >= 1) return k;
   const int slices = d.H * (d.P / kP);
-  const long groups = static_cast<long>(d.Bt) * (slices / kHeadsPerWg);
+  const long groups = static_cast<long>(d.Bt) * head_groups(d);
   const double seqs = static_cast<double>(d.Bt) * slices;
   const int hi = nblocks > min_blocks ? nblocks : min_blocks;
   int best_blocks = hi;
@@ -1557,8 +1568,7 @@ Layout make_layout(const Dims &d, bool varlen) {
 bool shape_ok(const Dims &d, unsigned long long tokens, unsigned long long nb) {
   // one sequence of x, C and the per-head block records must be addressable with 32-bit byte offsets
   const unsigned long long lim = 0xFFFF0000ull;
-  return d.bf16 && d.P % kP == 0 && d.P <= 16 * kP && d.N % 8 == 0 && d.N <= 4 * kN && d.L % kBlk == 0 &&
-         (d.hpg * (d.P / kP)) % kHeadsPerWg == 0 && d.Bt <= 65535 && d.H <= 65535 &&
+  return d.bf16 && d.P % kP == 0 && d.P <= 16 * kP && d.N % 8 == 0 && d.N <= 4 * kN && d.Bt <= 65535 && d.H <= 65535 &&
          tokens * d.H * (static_cast<unsigned long long>(d.P) * 2) <= lim &&
          tokens * d.G * (static_cast<unsigned long long>(d.N > kN ? d.N : kN) * 2) <= lim &&
          nb * (kN * kBlk * 2) <= lim;
@@ -1644,6 +1654,7 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   p.Hrec = d.H;
   p.G = d.G;
   p.hpg = d.hpg * pdiv;
+  p.cpg = (p.hpg + kHeadsPerWg - 1) / kHeadsPerWg;
   p.NB = w.NB;
   p.seg_blocks = seg_blocks;
   p.S = S;
@@ -1651,7 +1662,7 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   // time of that pass plus the longer chain over state slots, among the divisors of the segment length
   int parts = 1;
   if (!varlen && S > 1) {
-    const long groups = static_cast<long>(d.Bt) * (d.H * (d.P / kP) / kHeadsPerWg);
+    const long groups = static_cast<long>(d.Bt) * head_groups(d);
     const double seqs = static_cast<double>(d.Bt) * d.H * (d.P / kP);
     (void)states_cost(groups, seqs, S, seg_blocks, w.S_max, 8, &parts);
     if (const int k = knobs().seg_parts; k >= 1 && seg_blocks % k == 0 && (S - 1) * k + 1 <= w.S_max) parts = k;
@@ -1663,8 +1674,8 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   if (varlen || S > 1) {
     // (a packed batch always takes this route: whether any sequence has more than one segment is
     // known on the device only; workgroups of last segments leave the states-only pass at once)
-    constexpr int kStatesHeads = 4;  // heads per workgroup of the states-only kernel (2 was measured: slower)
-    p.cols = Hs / kStatesHeads;
+    constexpr int kStatesHeads = kHeadsPerWg;  // heads per workgroup of the states-only kernel (2 was measured: slower)
+    p.cols = d.G * p.cpg;
     p.segs = (S - 1) * parts;
     p.total = p.cols * p.segs * d.Bt;
     if (varlen) p.total = p.cols * items;
@@ -1677,7 +1688,7 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
                        dim3(kThreads), 0, stream, seg_state, seg_decay, h0, p.slots, Hs, rows_bh, vp, ns);
     trace_mark(trace, stream, "segment_pass");
   }
-  p.cols = Hs / kHeadsPerWg;
+  p.cols = d.G * p.cpg;
   p.segs = S;
   p.total = p.cols * p.segs * d.Bt;
   if (varlen) p.total = p.cols * items;
@@ -1734,16 +1745,25 @@ void launch_varlen_tables(const int32_t *cu, int total, int blk_len, int seg_blo
                      seg_blocks, const_cast<int32_t *>(vp.blk_seq), const_cast<int32_t *>(vp.item_seq));
 }
 
+// The kernels work on 64-token blocks whatever the chunk length is (results do not depend on it); the chunk
+// only bounds the number of segments, for which it counts as the next multiple of 64.
+static Dims with_block_chunk(const Dims &d_in) {
+  Dims d = d_in;
+  d.L = (d.L + kBlk - 1) / kBlk * kBlk;
+  d.Nc = (d.T + d.L - 1) / d.L;
+  return d;
+}
+
 bool mfma_supported(const Dims &d) {
   return shape_ok(d, static_cast<unsigned long long>(d.T), (static_cast<unsigned long long>(d.T) + kBlk - 1) / kBlk);
 }
 
-size_t mfma_workspace_bytes(const Dims &d) { return make_layout(d, false).total; }
+size_t mfma_workspace_bytes(const Dims &d) { return make_layout(with_block_chunk(d), false).total; }
 
 hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, const float *A, const void *B,
                                const void *C, const float *D, const float *h0, void *y, float *final_state,
                                void *workspace, hipStream_t stream, KernelTrace *trace) {
-  return launch(d, nullptr, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);
+  return launch(with_block_chunk(d), nullptr, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);
 }
 
 // Packed variable-length batch: d.Bt sequences, d.T tokens in total, boundaries in the device array cu.
@@ -1752,13 +1772,13 @@ bool mfma_varlen_supported(const Dims &d) {
   return shape_ok(d, static_cast<unsigned long long>(d.T), nb) && nb <= 0x7fffffffull / 64;
 }
 
-size_t mfma_varlen_workspace_bytes(const Dims &d) { return make_layout(d, true).total; }
+size_t mfma_varlen_workspace_bytes(const Dims &d) { return make_layout(with_block_chunk(d), true).total; }
 
 hipError_t launch_prefill_mfma_varlen(const Dims &d, const int32_t *cu_seqlens, const void *x, const float *dt,
                                       const float *A, const void *B, const void *C, const float *D, const float *h0,
                                       void *y, float *final_state, void *workspace, hipStream_t stream,
                                       KernelTrace *trace) {
-  return launch(d, cu_seqlens, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);
+  return launch(with_block_chunk(d), cu_seqlens, x, dt, A, B, C, D, h0, y, final_state, workspace, stream, trace);
 }
 
 }  // namespace ssd

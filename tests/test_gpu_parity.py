@@ -316,6 +316,12 @@ MFMA_CASES = [
     (1, 1000, 8, 64, 256, 2, 128, 2),    # dstate 256: two state slices, outputs added
     (1, 500, 4, 64, 32, 1, 256, 0),      # dstate 32
     (2, 300, 4, 128, 192, 1, 64, 1),     # dstate 192 (one and a half slices), headdim 128
+    (1, 1000, 1, 64, 128, 1, 128, 2),    # a single head: three slots of its workgroup idle
+    (2, 513, 6, 64, 128, 2, 64, 2),      # three heads per group
+    (1, 700, 24, 64, 128, 8, 100, 0),    # 24 heads in 8 groups; a chunk length that is no multiple of 64
+    (2, 300, 5, 128, 128, 1, 37, 1),     # ten 64-column slices in one group: 2 idle slots; chunk 37
+    (1, 500, 7, 64, 64, 7, 200, 0),      # one head per group, dstate 64
+    (1, 600, 3, 64, 256, 1, 256, 2),     # three heads, two state slices
 ]
 
 
@@ -632,6 +638,8 @@ VARLEN_CASES = [
     ([130, 0, 700, 64], (4, 64, 64), 1, 64, 2, True),            # dstate 64 (heads, headdim, dstate)
     ([130, 0, 700, 64], (4, 64, 256), 1, 64, 2, False),          # dstate 256: two state slices, outputs added
     ([300, 5, 200], (4, 128, 192), 2, 128, 1, True),             # dstate 192, headdim 128, two groups
+    ([130, 0, 700, 64, 1], 6, 2, 100, 1, True),                  # three heads per group, chunk no multiple of 64
+    ([64, 65, 300], 1, 1, 50, 2, False),                         # a single head
 ]
 
 
@@ -662,8 +670,9 @@ def test_varlen_prefill_matches_oracle(ssd, case):
         a, b = int(cu[q]), int(cu[q + 1])
         if b == a:
             continue
-        yq, sq = ssd.ssd_prefill(dev["x"][None, a:b].contiguous(), dev["dt"][None, a:b].contiguous(), dev["A"],
-                                 dev["B"][None, a:b].contiguous(), dev["C"][None, a:b].contiguous(), dev["D"], L,
+        # (copies: a slice of a contiguous tensor is a view, and its pointer need not be 16-byte aligned)
+        yq, sq = ssd.ssd_prefill(dev["x"][None, a:b].clone(), dev["dt"][None, a:b].clone(), dev["A"],
+                                 dev["B"][None, a:b].clone(), dev["C"][None, a:b].clone(), dev["D"], L,
                                  h0=None if h0 is None else h0[q:q + 1].cuda())
         torch.cuda.synchronize()
         assert_close(y[a:b], to_np64(yq[0]), 2e-2, "varlen y vs single sequence %d" % q)
