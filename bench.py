@@ -114,6 +114,7 @@ KERNEL_WORK = {
     "block_prep": ("scores",),
     "segment_states": (),          # re-computation: carries no algorithmic FLOPs of its own
     "segment_pass": ("state_pass",),
+    "prefill_f32": ("scores", "intra", "states", "state_pass", "state_out", "skip"),   # fp32 MFMA: one kernel
     "chunk_scan": ("intra", "states", "state_out", "skip"),
 }
 
@@ -136,6 +137,8 @@ def main():
     ap.add_argument("--no-conv", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-configs", action="store_true")
+    ap.add_argument("--no-segment-model", action="store_true",
+                    help="skip the check of the library's segment-length choice on shapes it was not fitted to")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (counter calibration for "
@@ -158,7 +161,7 @@ def main():
         return ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups,
                               cfg.chunk, cfg.torch_io_dtype)
 
-    def time_prefill(cfg, steps, warmup, with_decode=True):
+    def time_prefill(cfg, steps, warmup, with_decode=True, profile=True):
         """Times `steps` whole steps; then the same number of profiled steps for per-kernel times."""
         inp = inputs.make_prefill_inputs(cfg, seed=0, device=dev)
         nxt = inputs.make_decode_inputs(cfg, 1, seed=0, device=dev)
@@ -187,7 +190,7 @@ def main():
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / steps
         kern = {}
-        for _ in range(steps):
+        for _ in range(steps if profile else 0):
             prof = []
             step(profile=prof)
             for name, kms in prof:
@@ -329,6 +332,40 @@ def main():
             sweeps[label] = dict(path=rep["path"], ms=round(ms, 5), tflops_causal=round(rep["tflops_causal"], 1),
                                  tflops_dense=round(rep["tflops_dense"], 1))
             log("[bench] sweep %s (%s): %.4f ms, %.1f TFLOP/s causal" % (label, rep["path"], ms, rep["tflops_causal"]))
+            torch.cuda.empty_cache()
+
+    # ---- the library's choice of segment length on shapes its cost model was not fitted to -------------
+    # (the model's constants come from the three bf16 benchmark shapes).  For each shape: the time with the
+    # library's own choice, and with forced lengths around it; a choice more than 10 % behind the best
+    # forced length is a miss.
+    segment_model = {}
+    if not args.no_segment_model and not args.no_extra_configs:
+        unseen = [("b2_t8192_h32", cfg.with_(batch=2, seqlen=8192, nheads=32)),
+                  ("b1_t32768_h16", cfg.with_(batch=1, seqlen=32768, nheads=16)),
+                  ("b4_t4096_h64", cfg.with_(batch=4, seqlen=4096, nheads=64)),
+                  ("b4_t2048_h128", cfg.with_(batch=4, seqlen=2048, nheads=128)),
+                  ("b1_t16384_h8", cfg.with_(batch=1, seqlen=16384, nheads=8)),
+                  ("b16_t1024_h48", cfg.with_(batch=16, seqlen=1024, nheads=48)),
+                  ("b1_t8192_h24_p128", cfg.with_(batch=1, seqlen=8192, nheads=24, headdim=128)),
+                  ("b3_t3000_h20", cfg.with_(batch=3, seqlen=3000, nheads=20))]
+        for label, c in unseen:
+            nblk = (c.seqlen + 63) // 64
+            ms0, _, _ = time_prefill(c, 10, 2, with_decode=False, profile=False)
+            forced = {}
+            for blocks in sorted({nblk, max(4, nblk // 2), max(4, nblk // 4), max(4, nblk // 8), max(4, nblk // 16), 8, 4}):
+                if blocks > nblk:
+                    continue
+                ssd.set_knob("seg_blocks", blocks)
+                forced[blocks], _, _ = time_prefill(c, 10, 2, with_decode=False, profile=False)
+            ssd.set_knob("seg_blocks", 0)
+            best = min(forced, key=forced.get)
+            segment_model[label] = dict(batch=c.batch, seqlen=c.seqlen, nheads=c.nheads, headdim=c.headdim,
+                                        chosen_ms=round(ms0, 5), best_forced_blocks=best,
+                                        best_forced_ms=round(forced[best], 5),
+                                        forced_ms={str(k): round(v, 5) for k, v in forced.items()},
+                                        behind_best=round(ms0 / forced[best] - 1.0, 4), miss=bool(ms0 > 1.10 * forced[best]))
+            log("[bench] segment model %s: chosen %.4f ms, best forced %d blocks %.4f ms (%+.1f %%)" %
+                (label, ms0, best, forced[best], 100 * (ms0 / forced[best] - 1)))
             torch.cuda.empty_cache()
 
     # ---- ragged batches and piecewise prompts (same token count and head shape as the headline) -----
@@ -707,7 +744,7 @@ def main():
                    "headdim": cfg.headdim, "dstate": cfg.dstate, "ngroups": cfg.ngroups, "chunk": cfg.chunk,
                    "step": "ssd_prefill + one ssd_decode_step", "flop_count": "algorithmic, causal-only"},
         "prefill": head, "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "other_configs": extra,
-        "varlen": varlen, "sweeps": sweeps, "conv": conv, "measured_peaks": peaks,
+        "varlen": varlen, "sweeps": sweeps, "segment_model": segment_model, "conv": conv, "measured_peaks": peaks,
     }
     print(json.dumps(out))
 
