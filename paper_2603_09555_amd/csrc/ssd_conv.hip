@@ -18,7 +18,7 @@ namespace ssd {
 namespace {
 
 constexpr int kConvThreads = 256;
-constexpr int kRunMin = 16, kRunMax = 64;  // tokens per thread in the prefill kernel: chosen per launch
+constexpr int kRunMin = 16, kRunMax = 192;  // tokens per thread in the prefill kernel: chosen per launch
 
 // SiLU v / (1 + exp(-v)) with the hardware exp2 and reciprocal (each within 1 ulp): the kernels are
 // streams, and an IEEE division per element would make them ALU bound.
@@ -216,10 +216,11 @@ __global__ __launch_bounds__(kConvThreads) void conv_step_kernel(void *__restric
 }
 
 // Tokens per thread: long runs amortise the k-1 rows a thread reads in front of its own and the
-// weights it loads, but the threads should also fill the chip a whole number of times (the kernel holds
-// five waves per SIMD): the length in [16, 64] with the least (rounds of waves) x (rows read per run).
-int choose_run(int T, size_t groups_total, int ksize) {
-  const double slots = 256.0 * 4 * 5 * 64;  // threads resident at once
+// weights it loads, but the threads should also fill the chip a whole number of times: the length in
+// [kRunMin, kRunMax] with the least (rounds of waves) x (rows read per run).  `blocks_per_cu` is what the
+// runtime reports for the kernel (its register count decides it).
+int choose_run(int T, size_t groups_total, int ksize, int blocks_per_cu) {
+  const double slots = 256.0 * blocks_per_cu * kConvThreads;  // threads resident at once
   int best = kRunMin;
   double best_cost = 0.0;
   for (int len = kRunMin; len <= kRunMax; ++len) {
@@ -234,13 +235,25 @@ int choose_run(int T, size_t groups_total, int ksize) {
   return best;
 }
 
+template <typename Io, int VEC, int K>
+int resident_blocks() {
+  static const int blocks = [] {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, conv_prefill_kernel<Io, VEC, K>, kConvThreads, 0) != hipSuccess ||
+        n < 1)
+      n = 4;
+    return n;
+  }();
+  return blocks;
+}
+
 template <typename Io, int K>
 hipError_t prefill_typed(int Bt, int T, int C, bool vec8, const void *u, const float *w, const float *bias,
                          const void *state_in, const ConvOut &out, void *state_out, int act, hipStream_t stream) {
   if constexpr (sizeof(typename Io::type) == 2) {
     if (vec8) {
       constexpr int kV = 4;
-      const int run_len = choose_run(T, static_cast<size_t>(Bt) * (C / kV), K);
+      const int run_len = choose_run(T, static_cast<size_t>(Bt) * (C / kV), K, resident_blocks<Io, kV, K>());
       const int runs = (T + run_len - 1) / run_len;
       const dim3 grid(static_cast<unsigned>((static_cast<size_t>(runs) * (C / kV) + kConvThreads - 1) / kConvThreads), 1, Bt);
       hipLaunchKernelGGL((conv_prefill_kernel<Io, kV, K>), grid, dim3(kConvThreads), 0, stream, u, w, bias, state_in,
@@ -249,7 +262,7 @@ hipError_t prefill_typed(int Bt, int T, int C, bool vec8, const void *u, const f
     }
   }
   {
-    const int run_len = choose_run(T, static_cast<size_t>(Bt) * C, K);
+    const int run_len = choose_run(T, static_cast<size_t>(Bt) * C, K, resident_blocks<Io, 1, K>());
     const int runs = (T + run_len - 1) / run_len;
     const dim3 grid(static_cast<unsigned>((static_cast<size_t>(runs) * C + kConvThreads - 1) / kConvThreads), 1, Bt);
     hipLaunchKernelGGL((conv_prefill_kernel<Io, 1, K>), grid, dim3(kConvThreads), 0, stream, u, w, bias, state_in, out,

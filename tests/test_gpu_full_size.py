@@ -53,6 +53,25 @@ def test_full_size_prefill_every_sequence(ssd, name):
     assert worst <= 2e-2, "worst per-sequence normalised error %.3e" % worst
 
 
+def test_full_size_conv_prefill_every_element(ssd):
+    """The convolution in front of the core at the long-prompt benchmark shape: 16384 tokens, the x | B | C
+    channels of the 2.7B configuration (5120 + 128 + 128), k = 4, SiLU, with a cache going in and out.
+    At this size a thread walks a long run of tokens, which the small cases never reach."""
+    T, split, k = 16384, (5120, 128, 128), 4
+    C = sum(split)
+    g = torch.Generator().manual_seed(71)
+    u = torch.randn((1, T, C), generator=g).bfloat16()
+    w = torch.randn((C, k), generator=g) * 0.5
+    b = torch.randn((C,), generator=g) * 0.1
+    st = torch.randn((1, C, k - 1), generator=g).bfloat16()
+    print("full-size conv", T, split, k, flush=True)
+    outs, new_st = ssd.ssd_conv1d_prefill(u.cuda(), w.cuda(), b.cuda(), st.cuda(), split=split, activation="silu")
+    torch.cuda.synchronize()
+    z_ref, st_ref = ssd_oracle.conv1d_prefill(u, w, b, st, "silu")
+    assert_close(torch.cat(outs, dim=2), z_ref, 2e-2, "conv z at 16384 x 5376")
+    assert np.array_equal(to_np64(new_st), st_ref)
+
+
 STEP_BLOCK = 128   # decode steps whose inputs are resident at a time
 
 
