@@ -29,6 +29,16 @@ __device__ __forceinline__ float dt_apply_biased(float v, float bias, const DtXf
 __device__ __forceinline__ float dt_apply(float v, int h, const DtXform &t) {
   return dt_apply_biased(v, t.bias != nullptr ? t.bias[h] : 0.f, t);
 }
+// The same map without a branch (hardware exp2 / log2, relative error about 2e-7), for code whose loads
+// must not wait at a join: softplus(v) = max(v, 0) + log(1 + exp(-|v|)).
+__device__ __forceinline__ float dt_apply_branchless(float v, float bias, const DtXform &t) {
+  v += bias;
+  const float e = __builtin_amdgcn_exp2f(-fabsf(v) * 1.4426950408889634f);
+  const float sp = fmaxf(v, 0.f) + 0.6931471805599453f * __builtin_amdgcn_logf(1.f + e);
+  v = t.softplus ? sp : v;
+  const float cl = fminf(fmaxf(v, t.lo), t.hi);
+  return t.hi > 0.f ? cl : v;
+}
 
 // Validated problem dimensions (host side).
 struct Dims {

@@ -233,37 +233,103 @@ __global__ __launch_bounds__(256) void varlen_fill_kernel(const int32_t *__restr
   }
 }
 
+// Buffer addressing: a 128-bit descriptor (base, size) in scalar registers plus a 32-bit byte offset
+// per lane.  The hardware checks the per-lane offset against the size: loads beyond it return zero
+// and stores beyond it are dropped, which is how the ragged last block is handled (a descriptor
+// that ends at the last token of the batch row) without clamps or branches.
+using Rsrc = __amdgpu_buffer_rsrc_t;
+__device__ __forceinline__ Rsrc make_rsrc(const void *base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, static_cast<int>(bytes), 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(Rsrc r, uint32_t voff, uint32_t soff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+}
+// kPolicy is the instruction's cache-policy field: 0 = default (write-back through L2 and the memory-side
+// cache), kStreamStore = sc0 | nt, a non-temporal store that does not displace what those caches hold.
+constexpr int kStreamStore = 3;
+template <int kPolicy = 0>
+__device__ __forceinline__ void buf_store16(Rsrc r, uint32_t voff, u32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, kPolicy);
+}
+
+// A 64-bit value that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ size_t uniform_size(size_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+  return (static_cast<size_t>(hi) << 32) | lo;
+}
+
 // ---- scores_bt: G = tril(C B^T) on the diagonal blocks, and B transposed ------------------------------
 // One workgroup per (block, group).  The block covers rows [row0, row0 + 64) of the (tokens, G, N)
 // arrays B and C, of which only rows below row_end belong to its sequence; its results go to tile
-// number `tile` of Gd (64 l x 64 s, bf16) and of Btr (128 n x 64 s, bf16).  sB: kBlk * (kN + 2)
-// elements of LDS.  ns: which columns of the dstate axis this launch works on (see NSlice); with a
-// slice that is not the whole axis, the slice of C is also copied, zero padded to 128 columns, to
-// Cpad (tokens, G, 128), from which the scan then reads it.
-__device__ __forceinline__ void scores_bt_block(uint16_t *sB, size_t row0, size_t row_end, size_t tile, int g,
-                                                const uint16_t *__restrict__ B, const uint16_t *__restrict__ C,
+// number `tile` of Gd (64 l x 64 s, bf16) and of Btr (128 n x 64 s, bf16).  ns: which columns of the
+// dstate axis this launch works on (see NSlice); with a slice that is not the whole axis, the slice of C
+// is also copied, zero padded to 128 columns, to Cpad (tokens, G, 128), from which the scan then reads it.
+// Both tiles are read once, 16 consecutive bytes per thread and whole rows per 16 threads (a lane per
+// row, which is what the MFMA operands want, would fetch every 128-byte line of the tiles four times,
+// 32 bytes at a time: measured four times slower with many groups), and go through LDS:
+//   sB  kBlk rows of kN + 2 elements: the odd dword stride makes the transposed read-back conflict free
+//   sC  kBlk rows of kN + 8 elements, read as operands with 16-byte reads; once the products are done
+//       it holds G on its way out (rows of kBlk + 8 elements), so that G too is stored in whole rows
+constexpr int kGtStride = kBlk + 8;
+constexpr int kSbElems = kBlk * (kN + 2), kScElems = kBlk * (kN + 8);
+__device__ __forceinline__ void scores_bt_block(uint16_t *sB, uint16_t *sC, size_t row0, size_t row_end, size_t tile,
+                                                int g, const uint16_t *__restrict__ B, const uint16_t *__restrict__ C,
                                                 uint16_t *__restrict__ Gd, uint16_t *__restrict__ Btr, int G,
                                                 const NSlice ns, uint16_t *__restrict__ Cpad) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ws = wave >> 1, wl = wave & 1;
   const int r = lane & 31, kg = lane >> 5;
 
-  // G^T tile (rows s, columns l): lane ends up with four consecutive s for its l.
-  const size_t srow = row0 + 32 * ws + r, lrow = row0 + 32 * wl + r;
-  const uint16_t *Bp = B + (srow * G + g) * ns.width + ns.off + 8 * kg;
-  const uint16_t *Cp = C + (lrow * G + g) * ns.width + ns.off + 8 * kg;
-  f32x16 acc = {};
+  // The block's rows of the group's slice of B and of C, addressed as row * row_bytes + 2 * column.  The
+  // descriptors end with the slice of the last row that belongs to the sequence, so later rows read as
+  // zero; a column beyond the slice is given an offset no descriptor covers.  No load sits behind a
+  // branch, so all of them are in flight together.
+  const uint32_t row_bytes = static_cast<uint32_t>(G) * ns.width * 2;
+  const uint32_t rows_here = row_end > row0 ? static_cast<uint32_t>(row_end - row0 < kBlk ? row_end - row0 : kBlk) : 0;
+  // (readfirstlane: 64-bit comparisons are vector instructions, and a descriptor with a part in vector
+  // registers is accessed through a loop over the lanes' values)
+  const uint32_t span = __builtin_amdgcn_readfirstlane(rows_here ? (rows_here - 1) * row_bytes + static_cast<uint32_t>(ns.valid) * 2 : 0);
+  const size_t first = (row0 * G + g) * ns.width + ns.off;
+  const Rsrc rB = make_rsrc(B + first, span), rC = make_rsrc(C + first, span);
+  constexpr uint32_t kNowhere = 0xFFFFFF00u;
+  constexpr int kPieces = kBlk * (kN / 8) / kThreads;
+  u32x4 vb[kPieces], vc[kPieces];
 #pragma unroll
-  for (int q = 0; q < kN / 16; ++q) {
-    Operand a, c;
-    a.q = mk4(0, 0, 0, 0);
-    c.q = mk4(0, 0, 0, 0);
-    const bool in_slice = 8 * kg + 16 * q < ns.valid;  // columns beyond the slice count as zero
-    if (srow < row_end && in_slice) a.q = *reinterpret_cast<const u32x4 *>(Bp + 16 * q);
-    if (lrow < row_end && in_slice) c.q = *reinterpret_cast<const u32x4 *>(Cp + 16 * q);
-    acc = mfma(a, c, acc);
+  for (int i = 0; i < kPieces; ++i) {
+    const int ch16 = threadIdx.x + i * kThreads, row = ch16 / (kN / 8), ch = ch16 % (kN / 8);
+    const uint32_t off = 8 * ch < ns.valid ? row * row_bytes + ch * 16 : kNowhere;  // columns beyond the slice: zero
+    vb[i] = buf_load16(rB, off, 0);
+    vc[i] = buf_load16(rC, off, 0);
   }
-  uint16_t *Gout = Gd + tile * kBlk * kBlk;
+#pragma unroll
+  for (int i = 0; i < kPieces; ++i) {
+    const int ch16 = threadIdx.x + i * kThreads, row = ch16 / (kN / 8), ch = ch16 % (kN / 8);
+    uint32_t *dst = reinterpret_cast<uint32_t *>(sB + row * (kN + 2) + 8 * ch);
+    dst[0] = vb[i].x;
+    dst[1] = vb[i].y;
+    dst[2] = vb[i].z;
+    dst[3] = vb[i].w;
+    *reinterpret_cast<u32x4 *>(sC + row * (kN + 8) + 8 * ch) = vc[i];
+    if (Cpad != nullptr && row0 + row < row_end)
+      *reinterpret_cast<u32x4 *>(Cpad + ((row0 + row) * G + g) * kN + 8 * ch) = vc[i];
+  }
+  __syncthreads();
+  // G^T tile (rows s, columns l): lane ends up with four consecutive s for its l.
+  f32x16 acc = {};
+  {
+    const uint32_t *bp = reinterpret_cast<const uint32_t *>(sB + (32 * ws + r) * (kN + 2) + 8 * kg);
+    const uint16_t *cp = sC + (32 * wl + r) * (kN + 8) + 8 * kg;
+#pragma unroll
+    for (int q = 0; q < kN / 16; ++q) {
+      Operand a, c;
+      a.q = mk4(bp[8 * q], bp[8 * q + 1], bp[8 * q + 2], bp[8 * q + 3]);
+      c.q = *reinterpret_cast<const u32x4 *>(cp + 16 * q);
+      acc = mfma(a, c, acc);
+    }
+  }
+  __syncthreads();  // every wave has read its operands: sC may take G
+  uint16_t *sGt = sC;
   const int l = 32 * wl + r;
 #pragma unroll
   for (int i4 = 0; i4 < 4; ++i4) {
@@ -271,30 +337,21 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, size_t row0, size_
     u32x2 v;  // causal zero pattern: keep s <= l
     v.x = pack2(s + 0 <= l ? acc[4 * i4 + 0] : 0.f, s + 1 <= l ? acc[4 * i4 + 1] : 0.f);
     v.y = pack2(s + 2 <= l ? acc[4 * i4 + 2] : 0.f, s + 3 <= l ? acc[4 * i4 + 3] : 0.f);
-    *reinterpret_cast<u32x2 *>(Gout + l * kBlk + s) = v;
-  }
-
-  // B^T: stage the block row-major, write it back n-major.
-  for (int c = threadIdx.x; c < kBlk * (kN / 8); c += kThreads) {
-    const int row = c / (kN / 8), ch = c % (kN / 8);
-    u32x4 v = mk4(0, 0, 0, 0);
-    const bool have = row0 + row < row_end && 8 * ch < ns.valid;
-    if (have) v = *reinterpret_cast<const u32x4 *>(B + ((row0 + row) * G + g) * ns.width + ns.off + 8 * ch);
-    if (Cpad != nullptr && row0 + row < row_end) {  // the slice of C, zero padded to 128 columns
-      u32x4 cv = mk4(0, 0, 0, 0);
-      if (have) cv = *reinterpret_cast<const u32x4 *>(C + ((row0 + row) * G + g) * ns.width + ns.off + 8 * ch);
-      *reinterpret_cast<u32x4 *>(Cpad + ((row0 + row) * G + g) * kN + 8 * ch) = cv;
-    }
-    uint32_t *dst = reinterpret_cast<uint32_t *>(sB + row * (kN + 2) + 8 * ch);
-    dst[0] = v.x;
-    dst[1] = v.y;
-    dst[2] = v.z;
-    dst[3] = v.w;
+    *reinterpret_cast<u32x2 *>(sGt + l * kGtStride + s) = v;
   }
   __syncthreads();
+  // G in whole rows; B^T: the staged block read back n-major
+  uint16_t *Gout = Gd + tile * kBlk * kBlk;
+#pragma unroll
+  for (int i = 0; i < kBlk * (kBlk / 8) / kThreads; ++i) {
+    const int ch16 = threadIdx.x + i * kThreads, row = ch16 / (kBlk / 8), piece = ch16 % (kBlk / 8);
+    *reinterpret_cast<u32x4 *>(Gout + row * kBlk + 8 * piece) =
+        *reinterpret_cast<const u32x4 *>(sGt + row * kGtStride + 8 * piece);
+  }
   uint16_t *Bout = Btr + tile * kN * kBlk;
-  for (int c = threadIdx.x; c < kN * (kBlk / 8); c += kThreads) {
-    const int n = c / (kBlk / 8), s0 = (c % (kBlk / 8)) * 8;
+#pragma unroll
+  for (int i = 0; i < kN * (kBlk / 8) / kThreads; ++i) {
+    const int c8 = threadIdx.x + i * kThreads, n = c8 / (kBlk / 8), s0 = (c8 % (kBlk / 8)) * 8;
     uint32_t w[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -338,30 +395,43 @@ __device__ __forceinline__ void block_cumsum_block(float (*tile)[kCumHeads + 1],
                                                    const float *__restrict__ A, float *__restrict__ prep, int H,
                                                    const DtXform dtx) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int i = threadIdx.x; i < kBlk * kCumHeads; i += kThreads) {
-    const int tok = i / kCumHeads, hh = i % kCumHeads;
-    float v = 0.f;
-    if (row0 + tok < row_end && h0 + hh < H) v = dt_apply(dt[(row0 + tok) * H + h0 + hh], h0 + hh, dtx);
-    tile[tok][hh] = v;
+  // dt of the block's 64 tokens and of the first 32 of the next block, 16 heads each: six values per
+  // thread, requested together (no load sits behind a branch).  The descriptor covers the rows from
+  // row0 to the end of the sequence, so later rows read as zero; a head beyond H is given an offset
+  // outside it.  Padding must end up as dt = 0 whatever the step-size map makes of a zero.
+  constexpr int kTileToks = kBlk + kBlk / 2, kLoads = kTileToks * kCumHeads / kThreads;
+  const size_t rows_left = row_end > row0 ? row_end - row0 : 0;
+  const Rsrc rdt = make_rsrc(dt + row0 * H, __builtin_amdgcn_readfirstlane(static_cast<uint32_t>((rows_left < kTileToks ? rows_left : kTileToks) * H * 4)));
+  constexpr int kPer = kCumHeads / (kThreads / 64);
+  float a_head[kPer];  // A of the wave's heads (see below), requested with everything else
+#pragma unroll
+  for (int k = 0; k < kPer; ++k) a_head[k] = A[min(h0 + wave + k * (kThreads / 64), H - 1)];
+  float raw[kLoads], bias[kLoads];
+#pragma unroll
+  for (int k = 0; k < kLoads; ++k) {
+    const int i = threadIdx.x + k * kThreads, tok = i / kCumHeads, hh = i % kCumHeads;
+    const bool head_ok = h0 + hh < H;
+    raw[k] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                           rdt, head_ok ? static_cast<uint32_t>(tok * H + h0 + hh) * 4u : 0xFFFFFF00u, 0, 0));
+    bias[k] = dtx.bias != nullptr ? dtx.bias[head_ok ? h0 + hh : H - 1] : 0.f;
   }
-  for (int i = threadIdx.x; i < (kBlk / 2) * kCumHeads; i += kThreads) {
-    const int tok = kBlk + i / kCumHeads, hh = i % kCumHeads;
-    float v = 0.f;
-    if (row0 + tok < row_end && h0 + hh < H) v = dt_apply(dt[(row0 + tok) * H + h0 + hh], h0 + hh, dtx);
-    tile[tok][hh] = v;
+#pragma unroll
+  for (int k = 0; k < kLoads; ++k) {
+    const int i = threadIdx.x + k * kThreads, tok = i / kCumHeads, hh = i % kCumHeads;
+    const bool there = static_cast<size_t>(tok) < rows_left && h0 + hh < H;
+    tile[tok][hh] = there ? dt_apply_branchless(raw[k], bias[k], dtx) : 0.f;
   }
   __syncthreads();
   // A wave takes the heads wave, wave + 4, wave + 8, wave + 12 of the group of 16.  Their prefix sums
   // are four independent chains of cross-lane steps, written side by side so that the latency of one
   // chain's step is covered by the steps of the others.
-  constexpr int kPer = kCumHeads / (kThreads / 64);
   float dtv[kPer], v[kPer], nx[kPer], ah[kPer];
   bool live[kPer];
 #pragma unroll
   for (int k = 0; k < kPer; ++k) {
     const int hh = wave + k * (kThreads / 64);
     live[k] = h0 + hh < H;
-    ah[k] = live[k] ? A[h0 + hh] * kLog2e : 0.f;
+    ah[k] = live[k] ? a_head[k] * kLog2e : 0.f;
     dtv[k] = tile[lane][hh];
     v[k] = dtv[k] * ah[k];
     // prefix sum at token 31 of the next block: the sum of its first 32 terms
@@ -423,36 +493,41 @@ __global__ __launch_bounds__(kThreads) void block_prep_kernel(const uint16_t *__
                                                               int NB, int n_scores, const VarPlan vp,
                                                               const NSlice ns, uint16_t *__restrict__ Cpad,
                                                               const DtXform dtx) {
-  __shared__ __align__(16) uint16_t sB[kBlk * (kN + 2)];
-  __shared__ float tile[kBlk + kBlk / 2][kCumHeads + 1];
+  // score workgroups: the B and C tiles; decay workgroups: the transposed dt (in the same memory)
+  __shared__ __align__(16) uint16_t sB[kSbElems];
+  __shared__ __align__(16) uint16_t sC[kScElems];
+  static_assert(sizeof(float) * (kBlk + kBlk / 2) * (kCumHeads + 1) <= sizeof(uint16_t) * kScElems, "dt tile fits");
+  float (*tile)[kCumHeads + 1] = reinterpret_cast<float (*)[kCumHeads + 1]>(sC);
   const int wg = blockIdx.x;
   const bool scores = wg < n_scores;
   const int i = scores ? wg : wg - n_scores;
-  const int jb = i % NB;  // block inside the batch row, or block of the packed batch
+  // Workgroups that read neighbouring pieces of the same rows of B and C (the groups of a block) or of dt
+  // (the sets of 16 heads of a block) have consecutive numbers, so that they run at about the same time.
+  const int hgroups = (H + kCumHeads - 1) / kCumHeads;
+  const int fan = scores ? G : hgroups;
+  const int part = i % fan;          // group, or set of 16 heads
+  const int jb = (i / fan) % NB;     // block inside the batch row, or block of the packed batch
+  const int b = i / (fan * NB);
   size_t row0, row_end;
   if (vp.tok0 != nullptr) {
     if (jb >= vp.blk0[vp.nseq]) return;
     const int q = vp.blk_seq[jb];
     row0 = static_cast<size_t>(vp.tok0[q]) + static_cast<size_t>(jb - vp.blk0[q]) * kBlk;
     row_end = static_cast<size_t>(vp.tok0[q]) + vp.len[q];
-  }
-  if (scores) {
-    const int bg = i / NB;
-    if (vp.tok0 == nullptr) {
-      row0 = static_cast<size_t>(bg / G) * T + static_cast<size_t>(jb) * kBlk;
-      row_end = static_cast<size_t>(bg / G) * T + T;
-    }
-    scores_bt_block(sB, row0, row_end, static_cast<size_t>(bg) * NB + jb, bg % G, B, C, Gd, Btr, G, ns, Cpad);
   } else {
-    const int hgroups = (H + kCumHeads - 1) / kCumHeads;
-    const int b = i / (NB * hgroups);
-    if (vp.tok0 == nullptr) {
-      row0 = static_cast<size_t>(b) * T + static_cast<size_t>(jb) * kBlk;
-      row_end = static_cast<size_t>(b) * T + T;
-    }
-    block_cumsum_block(tile, row0, row_end, ((i / NB) % hgroups) * kCumHeads, NB,
-                       static_cast<size_t>(b) * H * NB + jb, dt, A, prep, H, dtx);
+    row0 = static_cast<size_t>(b) * T + static_cast<size_t>(jb) * kBlk;
+    row_end = static_cast<size_t>(b) * T + T;
   }
+  // (the tables are read with vector loads: tell the compiler that the rows are the same for every lane,
+  // or every buffer descriptor built from them costs a loop over the lanes' values per access)
+  row0 = uniform_size(row0);
+  row_end = uniform_size(row_end);
+  if (scores)
+    scores_bt_block(sB, sC, row0, row_end, (static_cast<size_t>(b) * G + part) * NB + jb, part,
+                    B, C, Gd, Btr, G, ns, Cpad);
+  else
+    block_cumsum_block(tile, row0, row_end, part * kCumHeads, NB, static_cast<size_t>(b) * H * NB + jb, dt, A, prep, H,
+                       dtx);
 }
 
 // ---- chunk_scan / segment_states ----------------------------------------------------------------
@@ -563,25 +638,6 @@ __device__ __forceinline__ bool wg_coords_varlen(const ScanParams &p, bool last_
 constexpr int kHeadsPerWg = 4;
 constexpr int kScanThreads = 2 * 64 * kHeadsPerWg;  // two waves per head, one per half of headdim
 constexpr int kGStride = kBlk + 8;
-
-// Buffer addressing: a 128-bit descriptor (base, size) in scalar registers plus a 32-bit byte offset
-// per lane.  The hardware checks the per-lane offset against the size: loads beyond it return zero
-// and stores beyond it are dropped, which is how the ragged last block is handled (a descriptor
-// that ends at the last token of the batch row) without clamps or branches.
-using Rsrc = __amdgpu_buffer_rsrc_t;
-__device__ __forceinline__ Rsrc make_rsrc(const void *base, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, static_cast<int>(bytes), 0x00020000);
-}
-__device__ __forceinline__ u32x4 buf_load16(Rsrc r, uint32_t voff, uint32_t soff) {
-  return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
-}
-// kPolicy is the instruction's cache-policy field: 0 = default (write-back through L2 and the memory-side
-// cache), kStreamStore = sc0 | nt, a non-temporal store that does not displace what those caches hold.
-constexpr int kStreamStore = 3;
-template <int kPolicy = 0>
-__device__ __forceinline__ void buf_store16(Rsrc r, uint32_t voff, u32x4 v) {
-  __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, kPolicy);
-}
 
 // Waits until no vector memory operation of the wave is outstanding.  Used once, at the end of a
 // loop prologue: the compiler places its waits for the worst case over all paths into a loop, and the

@@ -84,16 +84,6 @@ __device__ __forceinline__ void buf_store1(Rsrc rs, uint32_t voff, float v) {
 }
 constexpr uint32_t kNowhere = 0xFFFFFF00u;  // an offset beyond any descriptor
 
-// softplus / clamp of DtXform without a branch (hardware exp2 / log2, relative error about 2e-7):
-// softplus(v) = max(v, 0) + log(1 + exp(-|v|)).
-__device__ __forceinline__ float dt_apply_branchless(float v, float bias, const DtXform &t) {
-  v += bias;
-  const float sp = fmaxf(v, 0.f) + 0.6931471805599453f * __builtin_amdgcn_logf(1.f + exp2_fast(-fabsf(v) * kLog2e));
-  v = t.softplus ? sp : v;
-  const float cl = fminf(fmaxf(v, t.lo), t.hi);
-  return t.hi > 0.f ? cl : v;
-}
-
 struct F32Params {
   const float *x, *dt, *A, *B, *C, *D, *h0;
   float *y, *final_state;
