@@ -874,35 +874,35 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
   // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][column of lane r] ----
   const int pcol = 32 * ph + pi_of_row(r);  // headdim column of this lane's state column
   f32x16 Hacc[4];
+  // Everything the prologue needs from memory -- D, the entering state, the first block factor and (below)
+  // the first block -- is requested before any of it is waited for: one trip to memory instead of one each.
   float Dh = kStatesOnly || p.D == nullptr ? 0.f : p.D[hrec];
-  // Pin the value as "arrived" before the loop: otherwise the wait for it is placed at its first use
-  // inside the loop, where it also waits for every younger load of every iteration.
-  asm volatile("" : "+v"(Dh));
-  const float *hp = nullptr;
-  int hp_valid = kN;  // state columns present at hp
-  if (!kStatesOnly) {
+  if constexpr (!kStatesOnly) {
     // A sequence of one segment starts from h0 itself (this workgroup reads it here and is the only
     // one to write final_state, so the two may share memory); with several segments every segment,
     // the first included, starts from the slot that the pass over segment states has filled.
+    // Rows of hrow floats of which hvalid columns exist; no state at all: an empty descriptor, whose
+    // loads return zero.
+    const float *hbase = nullptr;
+    uint32_t hrow = kN, hvalid = kN;
     if (sv.S > 1) {
-      hp = p.Hin + (slot0 + static_cast<size_t>(sg) * p.parts) * (kP * kN) + static_cast<size_t>(pcol) * kN;
+      hbase = p.Hin + (slot0 + static_cast<size_t>(sg) * p.parts) * (kP * kN);
     } else if (p.h0 != nullptr) {
-      hp = p.h0 + (bh * kP + pcol) * p.ns.width + p.ns.off;
-      hp_valid = p.ns.valid;
+      hbase = p.h0 + bh * kP * p.ns.width + p.ns.off;
+      hrow = static_cast<uint32_t>(p.ns.width);
+      hvalid = static_cast<uint32_t>(p.ns.valid);
     }
-  }
-  if (hp != nullptr) {
+    const Rsrc rs_h = make_rsrc(hbase != nullptr ? hbase : p.prep, hbase != nullptr ? ((kP - 1) * hrow + hvalid) * 4u : 0u);
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const int n0 = 32 * nt + 8 * i4 + 4 * kg;
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        if (n0 < hp_valid) v = *reinterpret_cast<const f32x4 *>(hp + n0);
-        Hacc[nt][4 * i4 + 0] = v.x;
-        Hacc[nt][4 * i4 + 1] = v.y;
-        Hacc[nt][4 * i4 + 2] = v.z;
-        Hacc[nt][4 * i4 + 3] = v.w;
+        const uint32_t n0 = 32 * nt + 8 * i4 + 4 * kg;
+        const u32x4 v = buf_load16(rs_h, n0 < hvalid ? (static_cast<uint32_t>(pcol) * hrow + n0) * 4u : 0xFFFFFF00u, 0);
+        Hacc[nt][4 * i4 + 0] = __uint_as_float(v.x);
+        Hacc[nt][4 * i4 + 1] = __uint_as_float(v.y);
+        Hacc[nt][4 * i4 + 2] = __uint_as_float(v.z);
+        Hacc[nt][4 * i4 + 3] = __uint_as_float(v.w);
       }
   } else {
 #pragma unroll
@@ -915,7 +915,6 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
   // block.  It is multiplied in eight elements at a time, right where those elements are converted
   // to an MFMA operand, so the multiplies hide under the matrix instructions of the same loop.
   float pending = jb0 < jb1 && !kStatesOnly ? factor_ptr(jb0)[2] : 1.f;
-  asm volatile("" : "+v"(pending));  // arrived before the loop (see Dh above)
   // A steep block (see block_cumsum_block) marks its record with a negative entry there; it starts from
   // the state as it is at the start of the block.  Uniform over the wave, kept in a scalar register.
   bool steep_cur = false;
@@ -969,6 +968,15 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
     //      with block k+3.  Two iterations are written out per loop trip so that the set index is a
     //      compile-time constant. ----
     auto at = [&](int j) { return min(j, jlast); };
+    auto load_factors = [&](int j) { return *reinterpret_cast<const f32x2 *>(factor_ptr(j)); };
+    // {middle -> end, log2 of the total decay} of the block to be staged next, fetched one iteration
+    // before it is used
+    f32x2 sf_stage = {1.f, 0.f};
+    if (jb0 < jb1) {  // the first block is requested together with the decays that are summed next
+      load_part(0, jb0, 0);
+      load_part(1, jb0);
+      sf_stage = load_factors(jb0);
+    }
     for (int j = jb0; j < jb1; j += 64) {  // the segment's total log2 decay: one lane per block
       float v = j + lane < jb1 ? factor_ptr(j + lane)[1] : 0.f;
 #pragma unroll
@@ -976,23 +984,16 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
       seg_total += v;
     }
     float rest = seg_total;  // log2 decay of the blocks after the one being staged
-    // {middle -> end, log2 of the total decay} of the block to be staged next, fetched one iteration
-    // before it is used
-    f32x2 sf_stage = {1.f, 0.f};
     float ws = 0.f;
     auto next_weight = [&]() __attribute__((always_inline)) {
       rest -= sf_stage.y;
       ws = sf_stage.x * fast_exp2(rest);
     };
-    auto load_factors = [&](int j) { return *reinterpret_cast<const f32x2 *>(factor_ptr(j)); };
     auto weigh = [&](int set) __attribute__((always_inline)) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) r_f[set][i] = __float_as_uint(__uint_as_float(r_f[set][i]) * ws);
     };
     if (jb0 < jb1) {
-      load_part(0, jb0, 0);
-      load_part(1, jb0);
-      sf_stage = load_factors(jb0);
       next_weight();
       weigh(0);
       sf_stage = load_factors(at(jb0 + 1));
@@ -1071,6 +1072,10 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
       load_rowf(jb0);
     }
     wait_all_loads();
+    // Pin the two as "arrived": otherwise the wait for them is placed at their first use inside the
+    // loop, where it also waits for every younger load of every iteration.
+    asm volatile("" : "+v"(Dh));
+    asm volatile("" : "+v"(pending));
     rowf0 = rowf0n;
     rowf1 = rowf1n;
     __syncthreads();
