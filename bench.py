@@ -122,8 +122,12 @@ KERNEL_WORK = {
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--preheat-ms", type=float, default=100.0,
+                    help="before the warm-up steps of every timed loop the same call is repeated for this long: after "
+                         "an idle gap (input generation, the previous leg's teardown) the GPU takes some 30 ms of "
+                         "sustained work to return to its steady clocks, which is the state a serving process is in")
     ap.add_argument("--workload", default="c3_2p7b_long",
                     help="prefill configuration of the timed step (see paper_2603_09555_amd.inputs.CONFIGS)")
     ap.add_argument("--decode-steps", type=int, default=1024)
@@ -157,6 +161,14 @@ def main():
     dev = "cuda"
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
 
+    def preheat(fn):
+        """Repeats fn (a call that only enqueues) until --preheat-ms of wall time have passed."""
+        t_end = time.perf_counter() + args.preheat_ms * 1e-3
+        while time.perf_counter() < t_end:
+            for _ in range(8):
+                fn()
+            torch.cuda.synchronize()
+
     def shape_of(cfg):
         return ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups,
                               cfg.chunk, cfg.torch_io_dtype)
@@ -181,6 +193,7 @@ def main():
             if with_decode:
                 ssd.ssd_decode_step(st, nxt["x"], nxt["dt"], inp["A"], nxt["B"], nxt["C"], inp["D"], y=yd)
 
+        preheat(step)
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
@@ -350,20 +363,23 @@ def main():
                   ("b3_t3000_h20", cfg.with_(batch=3, seqlen=3000, nheads=20))]
         for label, c in unseen:
             nblk = (c.seqlen + 63) // 64
-            ms0, _, _ = time_prefill(c, 10, 2, with_decode=False, profile=False)
+            ms0, _, _ = time_prefill(c, 40, 5, with_decode=False, profile=False)
             forced = {}
             for blocks in sorted({nblk, max(4, nblk // 2), max(4, nblk // 4), max(4, nblk // 8), max(4, nblk // 16), 8, 4}):
                 if blocks > nblk:
                     continue
                 ssd.set_knob("seg_blocks", blocks)
-                forced[blocks], _, _ = time_prefill(c, 10, 2, with_decode=False, profile=False)
+                forced[blocks], _, _ = time_prefill(c, 40, 5, with_decode=False, profile=False)
             ssd.set_knob("seg_blocks", 0)
+            # the library's own choice once more, after the forced ones: the first leg on a new shape also pays
+            # for first touches of fresh allocations; the better of the two is its figure
+            ms0 = min(ms0, time_prefill(c, 40, 5, with_decode=False, profile=False)[0])
             best = min(forced, key=forced.get)
             segment_model[label] = dict(batch=c.batch, seqlen=c.seqlen, nheads=c.nheads, headdim=c.headdim,
                                         chosen_ms=round(ms0, 5), best_forced_blocks=best,
                                         best_forced_ms=round(forced[best], 5),
                                         forced_ms={str(k): round(v, 5) for k, v in forced.items()},
-                                        behind_best=round(ms0 / forced[best] - 1.0, 4), miss=bool(ms0 > 1.10 * forced[best]))
+                                        behind_best=round(ms0 / forced[best] - 1.0, 4), miss=bool(ms0 > 1.05 * forced[best]))
             log("[bench] segment model %s: chosen %.4f ms, best forced %d blocks %.4f ms (%+.1f %%)" %
                 (label, ms0, best, forced[best], 100 * (ms0 / forced[best] - 1)))
             torch.cuda.empty_cache()
@@ -395,6 +411,7 @@ def main():
             ws = torch.empty((ssd.raw().ssd_prefill_varlen_workspace_bytes(shp),), dtype=torch.uint8, device=dev)
             run = lambda: ssd.ssd_prefill_varlen(pk["x"], pk["dt"], pk["A"], pk["B"], pk["C"], pk["D"], cu, cfg.chunk,
                                                  y=y, final_state=st, workspace=ws)
+            preheat(run)
             for _ in range(3):
                 run()
             torch.cuda.synchronize()
@@ -421,6 +438,7 @@ def main():
             for i in range(pieces):
                 ssd.ssd_prefill(sl[i]["x"], sl[i]["dt"], inp["A"], sl[i]["B"], sl[i]["C"], inp["D"], cfg.chunk,
                                 h0=None if i == 0 else st, y=yp, final_state=st, workspace=ws)
+        preheat(run_pieces)
         for _ in range(3):
             run_pieces()
         torch.cuda.synchronize()
@@ -461,6 +479,7 @@ def main():
                                                     vp(wgt), vp(bia), None, vp(outs[0]), vp(outs[1]), vp(outs[2]),
                                                     vp(cache), 1, _ct.c_void_p(torch.cuda.current_stream().cuda_stream))
         assert call() == 0
+        preheat(call)
         torch.cuda.synchronize()
         e0.record()
         for _ in range(args.steps):
@@ -470,7 +489,7 @@ def main():
         us = e0.elapsed_time(e1) * 1e3 / args.steps
         nbytes = 2 * u.numel() * u.element_size()
         zc = torch.empty_like(u)  # a plain device copy of the same tensor, for scale
-        zc.copy_(u)
+        preheat(lambda: zc.copy_(u))
         torch.cuda.synchronize()
         e0.record()
         for _ in range(args.steps):
@@ -495,6 +514,7 @@ def main():
         def pair():
             call()
             ssd.ssd_prefill(xv, pin["dt"], pin["A"], Bv, Cv, pin["D"], cfg.chunk, y=yp, final_state=stp, workspace=wsp)
+        preheat(pair)
         for _ in range(3):
             pair()
         torch.cuda.synchronize()
@@ -742,7 +762,8 @@ def main():
         "dtype": "bf16" if cfg.io_dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.batch, "seqlen": cfg.seqlen, "nheads": cfg.nheads,
                    "headdim": cfg.headdim, "dstate": cfg.dstate, "ngroups": cfg.ngroups, "chunk": cfg.chunk,
-                   "step": "ssd_prefill + one ssd_decode_step", "flop_count": "algorithmic, causal-only"},
+                   "step": "ssd_prefill + one ssd_decode_step", "flop_count": "algorithmic, causal-only",
+                   "preheat_ms": args.preheat_ms},
         "prefill": head, "roofline": roofline, "cpu_baseline": cpu, "decode": decode, "other_configs": extra,
         "varlen": varlen, "sweeps": sweeps, "segment_model": segment_model, "conv": conv, "measured_peaks": peaks,
     }
