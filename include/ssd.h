@@ -29,8 +29,14 @@
  *    accumulation are fp32 (section "Mapping SSD onto JAX primitives",
  *    precision rules).
  *  - Arguments are validated on the host before any HIP call; an invalid call
- *    returns a negative ssd_status and enqueues nothing.  Device data (the
- *    sign of A, dt) is not inspected.  No C++ exception crosses this boundary.
+ *    returns a negative ssd_status and enqueues nothing.  Device data is not
+ *    inspected; what it must satisfy is A <= 0 and dt >= 0 (after the optional
+ *    step-size map of the *_dt entry points), nothing else: there is no upper
+ *    bound on dt*|A|.  (The bf16 prefill factorises the decay mask of Eq. 3
+ *    around the middle of each 64-token block; a block of a head whose decay
+ *    across half the block exceeds 2^96 takes the un-factorised mask instead,
+ *    whose exponents are never positive, so any step size gives the result of
+ *    the recurrence.)  No C++ exception crosses this boundary.
  *  - Results do not depend on `chunk` beyond floating-point summation order.
  *    Runs are bitwise reproducible (no floating-point atomics).
  */

@@ -53,6 +53,39 @@ def test_full_size_prefill_every_sequence(ssd, name):
     assert worst <= 2e-2, "worst per-sequence normalised error %.3e" % worst
 
 
+SWEEP_SHAPES = {
+    # the head-shape / group / chunk-length variations of config 3 that the benchmark sweeps
+    "chunk_64": dict(chunk=64),
+    "chunk_1024": dict(chunk=1024),
+    "ngroups_4": dict(ngroups=4),
+    "ngroups_20": dict(ngroups=20),
+    "headdim_128": dict(nheads=40, headdim=128),
+    "dstate_64": dict(dstate=64),
+    "dstate_256": dict(dstate=256),
+}
+
+
+@pytest.mark.parametrize("name", list(SWEEP_SHAPES))
+def test_full_size_sweep_shapes_every_sequence(ssd, name):
+    """The shapes of the benchmark's sweeps at their full size, every sequence against the oracle."""
+    cfg = inputs.CONFIGS["c3_2p7b_long"].with_(name="c3_" + name, **SWEEP_SHAPES[name])
+    print("full-size sweep shape", cfg, flush=True)
+    inp = inputs.make_prefill_inputs(cfg, seed=1)
+    dev = {k: v.cuda() for k, v in inp.items()}
+    sh = ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk,
+                        cfg.torch_io_dtype)
+    assert ssd.prefill_path(sh) == "mfma_bf16"
+    y, st = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk)
+    torch.cuda.synchronize()
+    y_ref, st_ref = ssd_oracle.prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"])
+    e = assert_close(y, y_ref, 2e-2, "%s y" % name)
+    assert_close(st, st_ref, 2e-2, "%s final state" % name)
+    err = np.abs(to_np64(y) - y_ref).max(axis=(1, 3))
+    worst = float((err / np.abs(y_ref).max(axis=(1, 3))).max())
+    print("errors", e, "worst per-sequence normalised error %.3e" % worst, flush=True)
+    assert worst <= 2e-2
+
+
 def test_full_size_conv_prefill_every_element(ssd):
     """The convolution in front of the core at the long-prompt benchmark shape: 16384 tokens, the x | B | C
     channels of the 2.7B configuration (5120 + 128 + 128), k = 4, SiLU, with a cache going in and out.
