@@ -86,3 +86,27 @@ def test_conv_feeds_the_ssd_core(ssd):
     assert_close(st, st_ref, 2e-2, "ssd on conv output: state")
     z_ref, _ = ssd_oracle.conv1d_prefill(u, w, b, None)
     assert_close(torch.cat([zx, zB, zC], dim=2), z_ref, 2e-2, "conv z")
+
+
+def test_conv_prefill_replayed_from_a_graph_equals_eager(ssd):
+    """The convolution enqueues one kernel and nothing else (the run length per thread comes from a host-side
+    occupancy query, no device work), so it can be captured; replays equal the eager call bit for bit."""
+    Bt, T, split, k = 2, 3000, (512, 64, 64), 4
+    C = sum(split)
+    u, w, b, st = draw(Bt, T, C, k, "bf16", seed=64)
+    ud, wd, bd, sd = u.cuda(), w.cuda(), b.cuda(), st.cuda()
+    eager, eager_cache = ssd.ssd_conv1d_prefill(ud, wd, bd, sd, split=split, activation="silu")
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        outs, cache = ssd.ssd_conv1d_prefill(ud, wd, bd, sd, split=split, activation="silu")
+    for rep in range(3):
+        for o in outs:
+            o.zero_()
+        cache.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, e) for a, e in zip(outs, eager)), "replay %d" % rep
+        assert torch.equal(cache, eager_cache)
