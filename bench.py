@@ -272,6 +272,9 @@ def main():
             rate, ms = measure.peak_probe("mfma", pa, None, iters=iters, reps=3)
             peaks["mfma_bf16_tflops_%s" % label] = round(rate / 1e12, 1)
             peaks["mfma_%s_ms" % label] = round(ms, 3)
+        for kind, label in (("mfma_f32", "mfma_f32_32x32x2_tflops"), ("mfma_f32_16x16x4", "mfma_f32_16x16x4_tflops")):
+            rate, ms = measure.peak_probe(kind, pa, None, iters=1000, reps=3)
+            peaks[label] = round(rate / 1e12, 1)
         log("[bench] measured peaks: %s" % peaks)
         del pa, pb
         torch.cuda.empty_cache()

@@ -44,6 +44,8 @@ SSD_API ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, co
  *   kind 3   streaming write of `b` (a: any valid device pointer)
  *   kind 4..6  as 1..3 with non-temporal loads and stores (what the decode step
  *            uses for a state larger than the memory-side cache)
+ *   kind 7, 8  as 0 on the fp32 matrix instructions v_mfma_f32_32x32x2_f32 (what
+ *            the fp32 prefill kernel uses) and v_mfma_f32_16x16x4_f32
  * One warm-up launch, then `reps` launches back to back; *ms (HOST) = their
  * total time in milliseconds, *work (HOST) = flops (kind 0) or bytes moved
  * (read + written) of ONE launch.

@@ -51,10 +51,11 @@ ssd_status ssd_prefill_profile(const ssd_shape *shape, const void *x, const floa
 ssd_status ssd_peak_probe(int32_t kind, int32_t iters, int32_t reps, void *a, void *b, size_t bytes, float *ms,
                           double *work, void *hip_stream) {
   if (!ms || !work || !a) return SSD_ERR_NULL;
-  if (kind < 0 || kind > 6 || reps < 1 || reps > 100000) return SSD_ERR_SHAPE;
-  if (kind == 0 && (iters < 1 || bytes < static_cast<size_t>(2048) * 256 * sizeof(float))) return SSD_ERR_SHAPE;
-  if (kind != 0 && !b) return SSD_ERR_NULL;
-  if (kind != 0 && bytes < 16) return SSD_ERR_SHAPE;
+  if (kind < 0 || kind > 8 || reps < 1 || reps > 100000) return SSD_ERR_SHAPE;
+  const bool mfma = kind == 0 || kind >= 7;
+  if (mfma && (iters < 1 || bytes < static_cast<size_t>(2048) * 256 * sizeof(float))) return SSD_ERR_SHAPE;
+  if (!mfma && !b) return SSD_ERR_NULL;
+  if (!mfma && bytes < 16) return SSD_ERR_SHAPE;
   if ((reinterpret_cast<uintptr_t>(a) & 15u) || (b && (reinterpret_cast<uintptr_t>(b) & 15u))) return SSD_ERR_ALIGN;
   const hipError_t e = ssd::run_peak_probe(kind, iters, reps, a, b, bytes, ms, work, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SSD_OK : SSD_ERR_HIP;

@@ -35,6 +35,45 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(float *__restrict__ sink
   sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = s;
 }
 
+// The same loop on the fp32 matrix instructions: kShape 0 = v_mfma_f32_32x32x2_f32 (what the fp32 prefill
+// kernel is written on), 1 = v_mfma_f32_16x16x4_f32.  Eight accumulators per wave again.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+template <int kShape>
+__global__ __launch_bounds__(256) void mfma_f32_loop_kernel(float *__restrict__ sink, int iters) {
+  const float a = 0.001f * static_cast<float>(threadIdx.x & 7), b = 0.002f * static_cast<float>((threadIdx.x * 3) & 7);
+  float s = 0.f;
+  if constexpr (kShape == 0) {
+    f32x16_t acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s += acc[j][i];
+  } else {
+    f32x4_t acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[j][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s += acc[j][i];
+  }
+  sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = s;
+}
+
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 template <bool kNt>
 __device__ __forceinline__ uint4 ld16(const uint4 *p) {
@@ -94,7 +133,8 @@ __global__ __launch_bounds__(256) void stream_kernel(const uint4 *__restrict__ s
 
 }  // namespace
 
-// kind 0: MFMA loop (work = iters; buffer a: at least 2048 * 256 floats).  kinds 1..3: copy / read /
+// kind 0: MFMA loop (work = iters; buffer a: at least 2048 * 256 floats); kinds 7, 8: the same on the fp32 matrix
+// instructions 32x32x2 / 16x16x4.  kinds 1..3: copy / read /
 // write of `bytes` bytes (a = source, b = destination); kinds 4..6: the same, non-temporal.  Returns the elapsed milliseconds of `reps`
 // back-to-back launches in *ms and the work of ONE launch (flops or bytes moved) in *work.
 hipError_t run_peak_probe(int kind, int iters, int reps, void *a, void *b, size_t bytes, float *ms, double *work,
@@ -111,6 +151,10 @@ hipError_t run_peak_probe(int kind, int iters, int reps, void *a, void *b, size_
   auto once = [&]() {
     if (kind == 0)
       hipLaunchKernelGGL(mfma_loop_kernel, dim3(wgs), dim3(256), 0, stream, static_cast<float *>(a), iters);
+    else if (kind == 7)
+      hipLaunchKernelGGL(mfma_f32_loop_kernel<0>, dim3(wgs), dim3(256), 0, stream, static_cast<float *>(a), iters);
+    else if (kind == 8)
+      hipLaunchKernelGGL(mfma_f32_loop_kernel<1>, dim3(wgs), dim3(256), 0, stream, static_cast<float *>(a), iters);
     else if (kind <= 3)
       hipLaunchKernelGGL(stream_kernel<false>, dim3(wgs * 2), dim3(256), 0, stream, static_cast<const uint4 *>(a),
                          static_cast<uint4 *>(b), bytes / 16, kind - 1);
@@ -129,6 +173,10 @@ hipError_t run_peak_probe(int kind, int iters, int reps, void *a, void *b, size_
   (void)hipEventDestroy(e1);
   if (kind == 0)
     *work = static_cast<double>(wgs) * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
+  else if (kind == 7)
+    *work = static_cast<double>(wgs) * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 2);
+  else if (kind == 8)
+    *work = static_cast<double>(wgs) * 4.0 * iters * 8.0 * (2.0 * 16 * 16 * 4);
   else
     *work = static_cast<double>(bytes / 16 * 16) * (kind == 1 || kind == 4 ? 2.0 : 1.0);
   return e;

@@ -57,11 +57,12 @@ def prefill_profile(x, dt, A, B, C, D, chunk, y, final_state, workspace, h0=None
 
 def peak_probe(kind, a, b=None, iters=0, reps=1):
     """``ssd_peak_probe``: returns ``(work per second, milliseconds per launch)`` -- flop/s for
-    ``kind="mfma"``, bytes/s for ``"copy"``, ``"read"``, ``"write"`` and their non-temporal forms
+    ``kind="mfma"`` (bf16) and ``"mfma_f32"``, ``"mfma_f32_16x16x4"`` (the fp32 matrix instructions), bytes/s for ``"copy"``, ``"read"``, ``"write"`` and their non-temporal forms
     ``"copy_nt"``, ``"read_nt"``, ``"write_nt"``.  ``a``, ``b``: device tensors."""
-    k = {"mfma": 0, "copy": 1, "read": 2, "write": 3, "copy_nt": 4, "read_nt": 5, "write_nt": 6}[kind]
+    k = {"mfma": 0, "copy": 1, "read": 2, "write": 3, "copy_nt": 4, "read_nt": 5, "write_nt": 6,
+         "mfma_f32": 7, "mfma_f32_16x16x4": 8}[kind]
     ms, work = ctypes.c_float(0), ctypes.c_double(0)
-    nbytes = a.numel() * a.element_size() if k in (0, 1, 2, 4, 5) else b.numel() * b.element_size()
+    nbytes = a.numel() * a.element_size() if k in (0, 1, 2, 4, 5, 7, 8) else b.numel() * b.element_size()
     _ssd._check_dev(a, b)
     st = _lib.ssd_peak_probe(k, iters, reps, _ssd._ptr(a), _ssd._ptr(b), nbytes, ctypes.byref(ms),
                              ctypes.byref(work), _ssd._stream_ptr())
