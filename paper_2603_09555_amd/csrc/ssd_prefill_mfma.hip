@@ -687,6 +687,7 @@ struct ScanLds {
   static constexpr int kBtElems = kN * kBtStride;
   static constexpr int kGElems = kStatesOnly ? 8 : kGTile, kGBufs = kStatesOnly ? 1 : 2;
   static constexpr int kXmElems = kP * kXStride;
+  static constexpr int kXmBufs = kStatesOnly ? 2 : 1;  // the states-only pass reads the other wave's half: two copies
   static constexpr int kRawElems = kStatesOnly ? 8 : kBlk * kRawStride, kRawBufs = kStatesOnly ? 1 : 2 * HPW;
 };
 
@@ -820,12 +821,13 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
 
   // Registers -> LDS for the block in flight, in slices.  Slice c < 8 computes column c of the own
   // slice, Xm^T[row][s] = f_s x[s][col] (four tokens per 8-byte write).
-  auto stage_column = [&](int c, int set = 0) __attribute__((always_inline)) {
+  // (xbuf: which copy of Xm^T, for the states-only pass; the full kernel has one)
+  auto stage_column = [&](int c, int set = 0, int xbuf = 0) __attribute__((always_inline)) {
     const float f0 = __uint_as_float(r_f[set].x), f1 = __uint_as_float(r_f[set].y),
                 f2 = __uint_as_float(r_f[set].z), f3 = __uint_as_float(r_f[set].w);
     const int w = c >> 1;
     const uint32_t a0 = r_x[set][0][w], a1 = r_x[set][1][w], a2 = r_x[set][2][w], a3 = r_x[set][3][w];
-    uint16_t *dst = xm_dst + (8 * (c >> 2) + (c & 3)) * kXStride;
+    uint16_t *dst = xm_dst + xbuf * (HPW * L::kXmElems) + (8 * (c >> 2) + (c & 3)) * kXStride;
     if (c & 1)
       *reinterpret_cast<u32x2 *>(dst) =
           mk2(pack2(f0 * bf_hi(a0), f1 * bf_hi(a1)), pack2(f2 * bf_hi(a2), f3 * bf_hi(a3)));
@@ -1012,33 +1014,52 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
       const uint16_t *const tBt = sBt[buf];
       next_weight();                          // weight of block jb+1 from the factors fetched an iteration ago
       sf_stage = load_factors(at(jb + 2));    // for the next iteration
-      // all twenty operands of the block are requested up front (this kernel has the registers): with
-      // eight waves reading at once an LDS read takes a few hundred cycles to come back, far more than
-      // the four matrix instructions of one group cover
-      Operand xo[4], bto[4][4];
+      // This pass is bound by its LDS operand reads (without them it takes half the time), so its two
+      // waves per head split the state differently from the full kernel: wave `ph` owns state columns
+      // [64 ph, 64 ph + 64) for all 64 headdim columns -- two n tiles x two column tiles, 2 + 2 operand
+      // reads per group of four matrix instructions where four n tiles x one column tile need 4 + 1.
+      // (Staging is unchanged: wave `ph` stages headdim half `ph` of Xm^T; the other half comes from the
+      // head's other wave, through the barrier that every block has anyway -- and since that wave may
+      // already be staging the next block while this one still reads, Xm^T has two copies in this pass.)
+      Operand xo[4][2], bto[4][2];
+      const uint16_t *const headX = sXm[buf * HPW + hw];  // block jb's copy; the next block is staged into the other
+      auto request = [&](int q) __attribute__((always_inline)) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) xo[q] = lds16(myX + r * kXStride + 16 * q + 8 * kg);
+        for (int pt = 0; pt < 2; ++pt) xo[q][pt] = lds16(headX + (32 * pt + r) * kXStride + 16 * q + 8 * kg);
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+        for (int nt = 0; nt < 2; ++nt) bto[q][nt] = lds16(tBt + a_bt + 32 * (2 * ph + nt) * kBtStride + 16 * q);
+      };
+      // Hacc[2 pt + nt]: headdim columns 32 pt + pi(r), state columns 32 (2 ph + nt) + row of the element
+      auto multiply = [&](int q) __attribute__((always_inline)) {
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) bto[q][nt] = lds16(tBt + a_bt + 32 * nt * kBtStride + 16 * q);
+        for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt) Hacc[2 * pt + nt] = mfma(bto[q][nt], xo[q][pt], Hacc[2 * pt + nt]);
+      };
+      // The two waves of a SIMD (w and w + 4) take the two halves of an iteration in opposite order: while
+      // one reads its operands and keeps the matrix pipe busy, the other stages the next block on the vector
+      // ALU.  Both halves only need what the barrier at the end of the previous iteration has published
+      // (the matrix half reads LDS copy `buf`, the staging half writes copy `buf ^ 1`), so their order is
+      // free; with every wave in the same half at the same time the pipes would take turns idling.
+      auto matrix_half = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) request(q);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) multiply(q);
+      };
+      const bool matrix_first = wave < 4;
+      if (matrix_first) matrix_half();
       __builtin_amdgcn_sched_barrier(0);
-      // While the operands are on their way (the LDS serves the eight waves' 160 reads for roughly a
-      // thousand cycles, and nothing of this block can start before), the NEXT block is staged: that
-      // work needs registers only.  Then its registers are refilled (tile of block jb+2, x of block
-      // jb+3), and only then come the matrix instructions.
+      // the next block is staged, then its registers are refilled (tile of block jb+2, x of block jb+3)
       weigh(set);
 #pragma unroll
-      for (int c = 0; c < 8; ++c) stage_column(c, set);
+      for (int c = 0; c < 8; ++c) stage_column(c, set, buf ^ 1);
 #pragma unroll
       for (int k = 0; k < kBtPieces; ++k) *reinterpret_cast<u32x4 *>(&sBt[buf ^ 1][lds_bt[k]]) = r_bt[k];
       load_part(1, at(jb + 2));
       load_part(0, at(jb + 3), set);
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) Hacc[nt] = mfma(bto[q][nt], xo[q], Hacc[nt]);
+      if (!matrix_first) matrix_half();
       __syncthreads();
     };
     // pairs of blocks, then the odd one: with the test between the two halves of a pair the compiler
@@ -1348,9 +1369,22 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
   // ---- write the state out (canonical (p, n) layout, four consecutive n per 16-byte store) ----
   float *out = nullptr;
   int out_valid = kN;
-  if (kStatesOnly) {
-    out = p.seg_state + (slot0 + sg + 1) * (kP * kN) + static_cast<size_t>(pcol) * kN;
-    if (lane == 0 && ph == 0 && live) p.seg_decay[slot0 + sg] = seg_total;
+  if constexpr (kStatesOnly) {
+    // (this pass tiles the state differently, see its loop body: tile 2 pt + nt of wave ph)
+    if (live) {
+      float *slot = p.seg_state + (slot0 + sg + 1) * (kP * kN);
+#pragma unroll
+      for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const f32x16 &t = Hacc[2 * pt + nt];
+            *reinterpret_cast<f32x4 *>(slot + static_cast<size_t>(32 * pt + pi_of_row(r)) * kN + 32 * (2 * ph + nt) + 8 * i4 + 4 * kg) =
+                f32x4{t[4 * i4 + 0], t[4 * i4 + 1], t[4 * i4 + 2], t[4 * i4 + 3]};
+          }
+      if (lane == 0 && ph == 0) p.seg_decay[slot0 + sg] = seg_total;
+    }
   } else if (sg == sv.S - 1) {
     out = p.final_state + (bh * kP + pcol) * p.ns.width + p.ns.off;
     out_valid = p.ns.valid;
@@ -1402,7 +1436,7 @@ void chunk_scan_kernel(const ScanParams p) {
   __shared__ __align__(16) uint16_t sC[L::kCBufs][L::kCElems];
   __shared__ __align__(16) uint16_t sBt[2][L::kBtElems];
   __shared__ __align__(16) uint16_t sG[L::kGBufs][L::kGElems];
-  __shared__ __align__(16) uint16_t sXm[HPW][L::kXmElems];
+  __shared__ __align__(16) uint16_t sXm[L::kXmBufs * HPW][L::kXmElems];
   __shared__ __align__(16) uint16_t sRaw[L::kRawBufs][L::kRawElems];
   SeqView sv;
   if (!wg_coords(p, !kStatesOnly, sv)) return;  // uniform over the workgroup
