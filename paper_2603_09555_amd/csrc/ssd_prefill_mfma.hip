@@ -1367,38 +1367,68 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
   }
 
   // ---- write the state out (canonical (p, n) layout, four consecutive n per 16-byte store) ----
-  float *out = nullptr;
-  int out_valid = kN;
   if constexpr (kStatesOnly) {
     // (this pass tiles the state differently, see its loop body: tile 2 pt + nt of wave ph)
+    // In the accumulators a lane holds 16-byte pieces of 32 different state rows: stored as they are, every
+    // store instruction would touch 32 rows, 32 bytes each (measured: 5 us of the pass at 16384 tokens x 80
+    // heads, 6.6 of 17 at 2048 x 24).  The wave turns its tile through a private piece of LDS instead -- the
+    // tiles there are dead after the loop's last barrier -- half at a time (32 headdim columns x 64 state
+    // columns, rows padded by 16 bytes), and stores four whole 256-byte row segments per instruction.  One
+    // wave, one piece of LDS, in-order LDS operations: no barrier.
     if (live) {
+      constexpr int kTurnStride = 64 + 4;  // floats
+      static_assert(2 * HPW * 32 * kTurnStride * sizeof(float) <= L::kXmBufs * HPW * L::kXmElems * sizeof(uint16_t),
+                    "the waves' turning tiles fit where Xm^T was");
+      float *const turn = reinterpret_cast<float *>(&sXm[0][0]) + wave * (32 * kTurnStride);
       float *slot = p.seg_state + (slot0 + sg + 1) * (kP * kN);
 #pragma unroll
-      for (int pt = 0; pt < 2; ++pt)
+      for (int pt = 0; pt < 2; ++pt) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
           for (int i4 = 0; i4 < 4; ++i4) {
             const f32x16 &t = Hacc[2 * pt + nt];
-            *reinterpret_cast<f32x4 *>(slot + static_cast<size_t>(32 * pt + pi_of_row(r)) * kN + 32 * (2 * ph + nt) + 8 * i4 + 4 * kg) =
+            *reinterpret_cast<f32x4 *>(turn + pi_of_row(r) * kTurnStride + 32 * nt + 8 * i4 + 4 * kg) =
                 f32x4{t[4 * i4 + 0], t[4 * i4 + 1], t[4 * i4 + 2], t[4 * i4 + 3]};
           }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int row = 4 * k + (lane >> 4), piece = lane & 15;
+          *reinterpret_cast<f32x4 *>(slot + static_cast<size_t>(32 * pt + row) * kN + 64 * ph + 4 * piece) =
+              *reinterpret_cast<const f32x4 *>(turn + row * kTurnStride + 4 * piece);
+        }
+      }
       if (lane == 0 && ph == 0) p.seg_decay[slot0 + sg] = seg_total;
     }
-  } else if (sg == sv.S - 1) {
-    out = p.final_state + (bh * kP + pcol) * p.ns.width + p.ns.off;
-    out_valid = p.ns.valid;
-  }
-  if (out != nullptr && live) {
+  } else if (sg == sv.S - 1 && live) {
+    // The same turn for the final state of the full kernel (a wave owns 32 headdim columns x 128 state
+    // columns there: two halves of 64 state columns).  Waves 0-3 turn their tiles in what was the B^T
+    // buffers, waves 4-7 in the C buffers; every wave is past the loop's last barrier.
+    constexpr int kTurnStride = 64 + 4;  // floats
+    static_assert(4 * 32 * kTurnStride * sizeof(float) <= 2 * L::kBtElems * sizeof(uint16_t) &&
+                      4 * 32 * kTurnStride * sizeof(float) <= L::kCBufs * L::kCElems * sizeof(uint16_t),
+                  "four turning tiles fit in either buffer pair");
+    float *const turn = reinterpret_cast<float *>(wave < 4 ? &sBt[0][0] : &sC[0][0]) + (wave & 3) * (32 * kTurnStride);
+    float *const rows = p.final_state + (bh * kP + 32 * ph) * p.ns.width + p.ns.off;
+    const int valid = p.ns.valid;
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
+    for (int half = 0; half < 2; ++half) {
 #pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int n0 = 32 * nt + 8 * i4 + 4 * kg;
-        if (n0 < out_valid)
-          *reinterpret_cast<f32x4 *>(out + n0) =
-              f32x4{Hacc[nt][4 * i4 + 0], Hacc[nt][4 * i4 + 1], Hacc[nt][4 * i4 + 2], Hacc[nt][4 * i4 + 3]};
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+          const f32x16 &t = Hacc[2 * half + nt];
+          *reinterpret_cast<f32x4 *>(turn + pi_of_row(r) * kTurnStride + 32 * nt + 8 * i4 + 4 * kg) =
+              f32x4{t[4 * i4 + 0], t[4 * i4 + 1], t[4 * i4 + 2], t[4 * i4 + 3]};
+        }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int row = 4 * k + (lane >> 4), n0 = 64 * half + 4 * (lane & 15);
+        if (n0 < valid)
+          *reinterpret_cast<f32x4 *>(rows + static_cast<size_t>(row) * p.ns.width + n0) =
+              *reinterpret_cast<const f32x4 *>(turn + row * kTurnStride + 4 * (lane & 15));
       }
+    }
   }
 }
 
