@@ -873,9 +873,10 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
     }
   };
 
-  // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][column of lane r] ----
-  const int pcol = 32 * ph + pi_of_row(r);  // headdim column of this lane's state column
+  // ---- state slice: Hacc[nt][i] = Ht^T[n = 32nt + (i/4)*8 + 4kg + i%4][headdim column 32 ph + pi_of_row(r)] ----
   f32x16 Hacc[4];
+  u32x4 hraw[16];          // the entering state as loaded (full kernel)
+  bool has_state = false;  // uniform over the workgroup
   // Everything the prologue needs from memory -- D, the entering state, the first block factor and (below)
   // the first block -- is requested before any of it is waited for: one trip to memory instead of one each.
   float Dh = kStatesOnly || p.D == nullptr ? 0.f : p.D[hrec];
@@ -895,17 +896,15 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
       hvalid = static_cast<uint32_t>(p.ns.valid);
     }
     const Rsrc rs_h = make_rsrc(hbase != nullptr ? hbase : p.prep, hbase != nullptr ? ((kP - 1) * hrow + hvalid) * 4u : 0u);
+    // Requested in whole row segments (16 lanes x 16 bytes = 64 state columns of one headdim column, four
+    // columns per instruction); the accumulator layout -- 16-byte pieces of 32 different rows per lane --
+    // is reached through LDS below (turn_state), once the first block's loads are on their way as well.
+    has_state = hbase != nullptr;
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const uint32_t n0 = 32 * nt + 8 * i4 + 4 * kg;
-        const u32x4 v = buf_load16(rs_h, n0 < hvalid ? (static_cast<uint32_t>(pcol) * hrow + n0) * 4u : 0xFFFFFF00u, 0);
-        Hacc[nt][4 * i4 + 0] = __uint_as_float(v.x);
-        Hacc[nt][4 * i4 + 1] = __uint_as_float(v.y);
-        Hacc[nt][4 * i4 + 2] = __uint_as_float(v.z);
-        Hacc[nt][4 * i4 + 3] = __uint_as_float(v.w);
-      }
+    for (int k = 0; k < 16; ++k) {
+      const uint32_t row = 32 * ph + 4 * (k & 7) + (lane >> 4), n0 = 64 * (k >> 3) + 4 * (lane & 15);
+      hraw[k] = buf_load16(rs_h, n0 < hvalid ? (row * hrow + n0) * 4u : 0xFFFFFF00u, 0);
+    }
   } else {
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt)
@@ -1078,6 +1077,37 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
       // ---- prologue: block jb0 into LDS buffer 0; blocks jb0+1 and jb0+2 in flight ----
 #pragma unroll
       for (int part = 0; part < 3; ++part) load_part(part, jb0, 0);
+    }
+    // The entering state into the accumulators: every wave turns its 32 x 128 tile, half at a time, through
+    // a private piece of LDS (waves 0-3 in what will be the B^T buffers, waves 4-7 in the C buffers; rows of
+    // 64 state columns padded by 16 bytes).  The barrier hands those buffers over to the staging below.
+    if (has_state) {
+      constexpr int kTurnStride = 64 + 4;  // floats
+      float *const turn = reinterpret_cast<float *>(wave < 4 ? &sBt[0][0] : &sC[0][0]) + (wave & 3) * (32 * kTurnStride);
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          *reinterpret_cast<u32x4 *>(turn + (4 * k + (lane >> 4)) * kTurnStride + 4 * (lane & 15)) = hraw[8 * half + k];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(turn + pi_of_row(r) * kTurnStride + 32 * nt + 8 * i4 + 4 * kg);
+            Hacc[2 * half + nt][4 * i4 + 0] = v.x;
+            Hacc[2 * half + nt][4 * i4 + 1] = v.y;
+            Hacc[2 * half + nt][4 * i4 + 2] = v.z;
+            Hacc[2 * half + nt][4 * i4 + 3] = v.w;
+          }
+      }
+      __syncthreads();
+    } else {
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) Hacc[nt][i] = 0.f;
+    }
+    if (jb0 < jb1) {
 #pragma unroll
       for (int c = 0; c < 8; ++c) stage_column(c, 0);
 #pragma unroll
