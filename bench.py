@@ -212,7 +212,7 @@ def main():
         kern = {k: sum(v) / len(v) for k, v in kern.items()}
         return ms, kern, inp
 
-    def time_step_cold(cfg, reps=9):
+    def time_step_cold(cfg, reps=9, dirty=True):
         """The same step with the caches overwritten before every call (512 MiB of unrelated dirty data:
         twice the memory-side cache), timed per call with events; the median.  The back-to-back loop above
         finds part of x cached from the step before, as a layer finds the x its convolution just wrote;
@@ -226,7 +226,10 @@ def main():
         junk = torch.empty((512 << 20,), dtype=torch.uint8, device=dev)
         evs = []
         for i in range(reps + 2):
-            junk.fill_(i & 1)
+            if dirty:
+                junk.fill_(i & 1)       # the caches end up full of modified lines that must be written back
+            else:
+                junk.sum()              # read only: the caches end up full of unrelated clean lines
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             ssd.ssd_prefill(inp["x"], inp["dt"], inp["A"], inp["B"], inp["C"], inp["D"], cfg.chunk, y=y,
@@ -290,6 +293,9 @@ def main():
     head["cold_cache_tflops_causal"] = round(sum(prefill_flops(cfg, True).values()) / head["cold_cache_ms"] / 1e9, 1)
     log("[bench] %s with the caches overwritten before every step: %.3f ms/step, %.1f TFLOP/s" %
         (cfg.name, head["cold_cache_ms"], head["cold_cache_tflops_causal"]))
+    head["cold_clean_cache_ms"] = round(time_step_cold(cfg, dirty=False), 5)
+    log("[bench] %s with the caches filled with unrelated clean data before every step: %.3f ms/step" %
+        (cfg.name, head["cold_clean_cache_ms"]))
 
     # roofline of the dominant kernel of the step
     dom = max(kern, key=kern.get)
