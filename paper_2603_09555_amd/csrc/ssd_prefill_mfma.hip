@@ -247,6 +247,7 @@ __device__ __forceinline__ u32x4 buf_load16(Rsrc r, uint32_t voff, uint32_t soff
 // kPolicy is the instruction's cache-policy field: 0 = default (write-back through L2 and the memory-side
 // cache), kStreamStore = sc0 | nt, a non-temporal store that does not displace what those caches hold.
 constexpr int kStreamStore = 3;
+constexpr int kYPlain = 0, kYStream = 1, kYAdd = 2;
 template <int kPolicy = 0>
 __device__ __forceinline__ void buf_store16(Rsrc r, uint32_t voff, u32x4 v) {
   __builtin_amdgcn_raw_buffer_store_b128(v, r, voff, 0, kPolicy);
@@ -673,9 +674,10 @@ constexpr int kGTile = 32 * kGLowStride + 32 * kGStride;  // elements of a compa
 // HPW = heads per workgroup (two waves each).  Both kernels take four heads: the full kernel's LDS tiles
 // fill the CU; the states-only kernel could run two smaller workgroups per CU, but its grid then no
 // longer divides evenly over the CUs and the measured time was worse.
-// kStreamY: y leaves with non-temporal stores, so that writing it does not evict x, which the states-only
-// pass has just pulled into the memory-side cache, before this kernel reads it again (chosen per launch,
-// see stream_y()).
+// kYMode, how y leaves: kYPlain -- ordinary stores; kYStream -- non-temporal stores, so that writing y does not
+// evict x, which the states-only pass has just pulled into the memory-side cache, before this kernel reads it
+// again (chosen per launch, see stream_y()); kYAdd -- added to what y already holds (the later state slices
+// of a dstate above 128: the sum of the slices' outputs is formed where the last one is stored).
 // The LDS tiles of a scan workgroup, as pointers that keep their address space across a function call.
 typedef __attribute__((address_space(3))) uint16_t lds_u16;
 struct LdsTiles {
@@ -693,9 +695,9 @@ struct ScanLds {
 
 // The walk of one workgroup over its blocks.  kMixed: the walk may meet steep blocks (see
 // block_cumsum_block) and chooses the form block by block; otherwise every block has the common form.
-template <bool kStatesOnly, int HPW, bool kStreamY, bool kMixed>
+template <bool kStatesOnly, int HPW, int kYMode, bool kMixed>
 __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv, const LdsTiles lds) {
-  static_assert(!(kStatesOnly && kStreamY), "the states-only pass writes no y");
+  static_assert(!(kStatesOnly && kYMode != kYPlain), "the states-only pass writes no y");
   static_assert(!(kStatesOnly && kMixed), "the states-only pass needs no second form");
   static_assert(kStatesOnly || HPW == kHeadsPerWg, "the full kernel is written for four heads per workgroup");
   constexpr int kThr = 128 * HPW;
@@ -1334,14 +1336,26 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
 #pragma unroll
         for (int c = 0; c < 8; ++c) stage_column(c, setA);
       }
+      u32x4 yprev[4];  // kYAdd: what y holds so far, requested before the barrier
+      if constexpr (kYMode == kYAdd) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) yprev[k] = buf_load16(ry, vy + static_cast<uint32_t>(kRowStep * k) * xrow, 0);
+      }
       if constexpr (kRowStores) __syncthreads();  // both halves of every row of y are in LDS
       {
         u32x4 yo[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) yo[k] = *reinterpret_cast<const u32x4 *>(raw_dst_row + kRowStep * k * kRawStride);
+        if constexpr (kYMode == kYAdd) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+              yo[k][w] = pack2(bf_lo(yo[k][w]) + bf_lo(yprev[k][w]), bf_hi(yo[k][w]) + bf_hi(yprev[k][w]));
+        }
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-          buf_store16<kStreamY ? kStreamStore : 0>(ry, vy + static_cast<uint32_t>(kRowStep * k) * xrow, yo[k]);
+          buf_store16<kYMode == kYStream ? kStreamStore : 0>(ry, vy + static_cast<uint32_t>(kRowStep * k) * xrow, yo[k]);
       }
       if constexpr (!kRowStores) {
         stage_raw(setA);
@@ -1466,9 +1480,9 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
 // the kernel around the call, so what the rare steep form needs (it spills) costs the common walk nothing.
 // (Arguments by value: a reference would make the kernel keep its own copy in private memory, where
 // nothing counts as uniform any more.)
-template <int HPW, bool kStreamY>
+template <int HPW, int kYMode>
 __device__ __attribute__((noinline)) void scan_walk_mixed(const ScanParams p, const SeqView sv, const LdsTiles lds) {
-  scan_walk<false, HPW, kStreamY, true>(p, sv, lds);
+  scan_walk<false, HPW, kYMode, true>(p, sv, lds);
 }
 
 // Whether the blocks this wave walks in the full scan include a steep one: one lane per block reads the
@@ -1489,7 +1503,7 @@ __device__ __forceinline__ bool walk_meets_steep_block(const ScanParams &p, cons
   return __builtin_amdgcn_ballot_w64(lowest < 0.f) != 0;
 }
 
-template <bool kStatesOnly, int HPW, bool kStreamY = false>
+template <bool kStatesOnly, int HPW, int kYMode = kYPlain>
 __global__ __launch_bounds__(128 * HPW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void chunk_scan_kernel(const ScanParams p) {
   using L = ScanLds<kStatesOnly, HPW>;
@@ -1506,11 +1520,11 @@ void chunk_scan_kernel(const ScanParams p) {
     // Waves of one workgroup may take different walks: both stage the same shared tiles and meet at the
     // same barriers, block for block.
     if (walk_meets_steep_block<HPW>(p, sv)) {
-      scan_walk_mixed<HPW, kStreamY>(p, sv, lds);
+      scan_walk_mixed<HPW, kYMode>(p, sv, lds);
       return;
     }
   }
-  scan_walk<kStatesOnly, HPW, kStreamY, false>(p, sv, lds);
+  scan_walk<kStatesOnly, HPW, kYMode, false>(p, sv, lds);
 }
 
 // ---- segment_pass: slot[0] = h0; slot[sg] = exp2(decay[sg-1]) * slot[sg-1] + local[sg-1] --------
@@ -1649,28 +1663,6 @@ int choose_seg_blocks(const Dims &d, int min_blocks, int max_slots, int max_part
   return best_blocks;
 }
 
-// y += t over n 16-byte pieces of bf16 (sum in fp32, rounded once): adds the output of a later state
-// slice to the output so far.  For a packed batch only the tokens that belong to a sequence are touched:
-// the sequences lie back to back, so those are [tok0[0], tok0[nseq-1] + len[nseq-1]) of the tables
-// (empty when the boundaries were rejected); per_token = 16-byte pieces per token.
-__global__ __launch_bounds__(kThreads) void add_outputs_kernel(uint16_t *__restrict__ y, const uint16_t *__restrict__ t,
-                                                               size_t n, const int32_t *__restrict__ tok0,
-                                                               const int32_t *__restrict__ len, int nseq,
-                                                               size_t per_token) {
-  const size_t i = static_cast<size_t>(blockIdx.x) * kThreads + threadIdx.x;
-  if (i >= n) return;
-  if (tok0 != nullptr) {
-    const size_t begin = static_cast<size_t>(tok0[0]) * per_token;
-    const size_t end = (static_cast<size_t>(tok0[nseq - 1]) + len[nseq - 1]) * per_token;
-    if (i < begin || i >= end) return;
-  }
-  const u32x4 a = reinterpret_cast<const u32x4 *>(y)[i], b = reinterpret_cast<const u32x4 *>(t)[i];
-  u32x4 r;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) r[k] = pack2(bf_lo(a[k]) + bf_lo(b[k]), bf_hi(a[k]) + bf_hi(b[k]));
-  reinterpret_cast<u32x4 *>(y)[i] = r;
-}
-
 // Workspace.  Plain batch: rows = Bt sequences of NB blocks each.  Variable-length batch: one "row" whose
 // NB is the block capacity ceil(total / 64) + nseq (every sequence may end in a partial block), whose
 // segment list holds at most NB / (blocks per chunk) + nseq + 1 entries (a segment is at least a
@@ -1679,7 +1671,7 @@ __global__ __launch_bounds__(kThreads) void add_outputs_kernel(uint16_t *__restr
 // most min(that, 4 ceil(total / 64) / (blocks per chunk) + 4); then the int32 tables of VarPlan.
 struct Layout {
   int NB, S_max, items_max;
-  size_t off_G, off_Bt, off_prep, off_state, off_decay, off_tables, off_Cpad, off_ytmp, total;
+  size_t off_G, off_Bt, off_prep, off_state, off_decay, off_tables, off_Cpad, total;
 };
 
 Layout make_layout(const Dims &d, bool varlen) {
@@ -1709,13 +1701,10 @@ Layout make_layout(const Dims &d, bool varlen) {
   off += round_up(BHs * w.S_max * sizeof(float), 256);
   w.off_tables = off;
   if (varlen) off += round_up((5 * (static_cast<size_t>(nseq) + 1) + w.NB + w.items_max) * sizeof(int32_t), 256);
-  // dstate other than 128: a 128-column copy of the slice of C in work; more than one slice: the
-  // output of the later slices before it is added to y
+  // dstate other than 128: a 128-column copy of the slice of C in work
   const size_t tokens = static_cast<size_t>(rows) * d.T;
   w.off_Cpad = off;
   if (d.N != kN) off += round_up(tokens * d.G * kN * sizeof(uint16_t), 256);
-  w.off_ytmp = off;
-  if (d.N > kN) off += round_up(tokens * d.H * d.P * sizeof(uint16_t), 256);
   w.total = off;
   return w;
 }
@@ -1735,11 +1724,13 @@ bool shape_ok(const Dims &d, unsigned long long tokens, unsigned long long nb) {
 // columns: x of 160 MiB, 7-14 % less time for the full kernel, 4-7 % for the pipeline; x of 180 MiB or
 // more, where x with the other operands no longer fits, 1-2 % slower; x below a quarter of the cache,
 // where x and y both fit, no difference, and the consumer of y is better off finding it cached.
+// With a dstate above 128 the later state slices read y back to add to it, but they read x twice more: the
+// first slice streams y all the same (measured at dstate 256: 333 -> 307 us).
 // The y_stream knob overrides (tests, tuning).
 constexpr unsigned long long kMemCacheBytes = 256ull << 20;
 bool stream_y(const Dims &d, const NSlice &ns, bool two_passes, int rows) {
   if (knobs().y_stream >= 0) return knobs().y_stream != 0;
-  if (!two_passes || ns.width > kN) return false;  // no second read of x; later state slices re-read y to add to it
+  if (!two_passes) return false;  // no second read of x
   const unsigned long long x_bytes = 2ull * rows * d.T * d.H * d.P;
   return 4 * x_bytes > kMemCacheBytes && 3 * x_bytes <= 2 * kMemCacheBytes;
 }
@@ -1748,7 +1739,7 @@ bool stream_y(const Dims &d, const NSlice &ns, bool two_passes, int rows) {
 // One state slice ns (see NSlice): y and final_state columns of that slice are written.
 hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const void *x, const float *dt,
                         const float *A, const void *B, const void *C, const float *D, const float *h0, void *y,
-                        float *final_state, void *workspace, hipStream_t stream, KernelTrace *trace) {
+                        bool add_to_y, float *final_state, void *workspace, hipStream_t stream, KernelTrace *trace) {
   const bool varlen = cu != nullptr;
   const Layout w = make_layout(d, varlen);
   char *ws = static_cast<char *>(workspace);
@@ -1848,8 +1839,11 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   p.total = p.cols * p.segs * d.Bt;
   if (varlen) p.total = p.cols * items;
   p.per_xcd = (p.total + kXcds - 1) / kXcds;
-  if (stream_y(d, ns, varlen || S > 1, rows))
-    hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg, true>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0,
+  if (add_to_y)
+    hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg, kYAdd>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0,
+                       stream, p);
+  else if (stream_y(d, ns, varlen || S > 1, rows))
+    hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg, kYStream>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0,
                        stream, p);
   else
     hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0, stream,
@@ -1858,29 +1852,17 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   return hipGetLastError();
 }
 
-// All state slices: the first writes y (with the skip term D x), every later one goes to a scratch
-// output without the skip term and is added.
+// All state slices: the first writes y (with the skip term D x), every later one adds its output, without the
+// skip term, to y where it stores it (the sum is formed in fp32 from the bf16 values and rounded once more:
+// y carries up to 1.5 bf16 ulp with two slices instead of 0.5).
 hipError_t launch(const Dims &d, const int32_t *cu, const void *x, const float *dt, const float *A, const void *B,
                   const void *C, const float *D, const float *h0, void *y, float *final_state, void *workspace,
                   hipStream_t stream, KernelTrace *trace) {
-  const Layout w = make_layout(d, cu != nullptr);
   for (int off = 0; off < d.N; off += kN) {
     const NSlice ns = {d.N, off, d.N - off < kN ? d.N - off : kN};
-    void *out = off == 0 ? y : static_cast<char *>(workspace) + w.off_ytmp;
-    const hipError_t e = launch_slice(d, ns, cu, x, dt, A, B, C, off == 0 ? D : nullptr, h0, out, final_state,
+    const hipError_t e = launch_slice(d, ns, cu, x, dt, A, B, C, off == 0 ? D : nullptr, h0, y, off > 0, final_state,
                                       workspace, stream, off == 0 ? trace : nullptr);
     if (e != hipSuccess) return e;
-    if (off > 0) {
-      const size_t per_token = static_cast<size_t>(d.H) * d.P / 8;
-      const size_t pieces = static_cast<size_t>(cu != nullptr ? 1 : d.Bt) * d.T * per_token;
-      // (the tables of a packed batch: as laid out by launch_slice, which has just rebuilt them)
-      const int32_t *tok0 = cu != nullptr ? reinterpret_cast<const int32_t *>(static_cast<char *>(workspace) + w.off_tables)
-                                          : nullptr;
-      hipLaunchKernelGGL(add_outputs_kernel, dim3(static_cast<unsigned>((pieces + kThreads - 1) / kThreads)),
-                         dim3(kThreads), 0, stream, static_cast<uint16_t *>(y),
-                         reinterpret_cast<const uint16_t *>(out), pieces, tok0,
-                         tok0 != nullptr ? tok0 + (d.Bt + 1) : nullptr, d.Bt, per_token);
-    }
   }
   return hipGetLastError();
 }
