@@ -1768,12 +1768,15 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
     if (items > w.items_max) items = w.items_max;
     S = 0;  // per sequence, from the tables
     vp = VarPlan{tok0, len, blk0, item0, slot0, blk_seq, item_seq, d.Bt, w.NB, w.S_max};
-    launch_varlen_tables(cu, d.T, kBlk, seg_blocks, items, vp, stream);
-    trace_mark(trace, stream, "varlen_tables");
+    if (!add_to_y) {  // (a later state slice finds the tables of the first)
+      launch_varlen_tables(cu, d.T, kBlk, seg_blocks, items, vp, stream);
+      trace_mark(trace, stream, "varlen_tables");
+    }
   }
 
   const int n_scores = w.NB * rows * d.G;
-  const int n_cumsum = w.NB * ((d.H + kCumHeads - 1) / kCumHeads) * rows;
+  // (the decay records depend on dt and A alone: the first state slice has left them in the workspace)
+  const int n_cumsum = add_to_y ? 0 : w.NB * ((d.H + kCumHeads - 1) / kCumHeads) * rows;
   hipLaunchKernelGGL(block_prep_kernel, dim3(n_scores + n_cumsum), dim3(kThreads), 0, stream,
                      static_cast<const uint16_t *>(B), static_cast<const uint16_t *>(C), Gd, Btr, dt, A, prep,
                      d.T, d.H, d.G, w.NB, n_scores, vp, ns, Cpad, d.dtx);
