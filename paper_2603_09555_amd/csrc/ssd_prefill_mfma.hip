@@ -1718,21 +1718,21 @@ bool shape_ok(const Dims &d, unsigned long long tokens, unsigned long long nb) {
          nb * (kN * kBlk * 2) <= lim;
 }
 
-// Whether the full kernel writes y with non-temporal stores.  x is read twice, by the states-only pass and
-// again by the full kernel; the 256 MiB memory-side cache (Infinity Cache) keeps it in between unless the
-// y written meanwhile pushes it out.  Measured on the convolution -> prefill pipeline at 80 heads of 64
-// columns: x of 160 MiB, 7-14 % less time for the full kernel, 4-7 % for the pipeline; x of 180 MiB or
-// more, where x with the other operands no longer fits, 1-2 % slower; x below a quarter of the cache,
-// where x and y both fit, no difference, and the consumer of y is better off finding it cached.
-// With a dstate above 128 the later state slices read y back to add to it, but they read x twice more: the
-// first slice streams y all the same (measured at dstate 256: 333 -> 307 us).
-// The y_stream knob overrides (tests, tuning).
+// Whether the full kernel writes y with non-temporal stores.  The 256 MiB memory-side cache (Infinity Cache)
+// holds x when the kernel starts -- the states-only pass has just read it, or the producer (the convolution)
+// has just written it -- unless the y written meanwhile pushes it out before it is read.  Once x takes more
+// than a quarter of that cache, x and y no longer fit side by side and y is streamed past the caches.
+// Measured (prefill alone, back to back; us with ordinary / non-temporal stores): x of 64-96 MiB 80 / 79, 62 / 62,
+// 88 / 88 (no difference: below a quarter of the cache the consumer of y is better off finding it cached);
+// 128 MiB 122 / 110 (two passes over x) and 109 / 97 (one); 160 MiB 151 / 131; 192 MiB 178 / 171 and 175 / 153;
+// 256 MiB 220 / 211; 320 MiB 278 / 281 (nothing left to protect, nothing lost).  With a dstate above 128 the
+// later state slices read y back to add to it, but they read x twice more: the first slice streams y all the
+// same (dstate 256: 333 -> 307 us).  The y_stream knob overrides (tests, tuning).
 constexpr unsigned long long kMemCacheBytes = 256ull << 20;
-bool stream_y(const Dims &d, const NSlice &ns, bool two_passes, int rows) {
+bool stream_y(const Dims &d, int rows) {
   if (knobs().y_stream >= 0) return knobs().y_stream != 0;
-  if (!two_passes) return false;  // no second read of x
   const unsigned long long x_bytes = 2ull * rows * d.T * d.H * d.P;
-  return 4 * x_bytes > kMemCacheBytes && 3 * x_bytes <= 2 * kMemCacheBytes;
+  return 4 * x_bytes > kMemCacheBytes;
 }
 
 // d: plain batch (cu == nullptr), or Bt = number of sequences and T = total tokens of a packed batch.
@@ -1845,7 +1845,7 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   if (add_to_y)
     hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg, kYAdd>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0,
                        stream, p);
-  else if (stream_y(d, ns, varlen || S > 1, rows))
+  else if (stream_y(d, rows))
     hipLaunchKernelGGL((chunk_scan_kernel<false, kHeadsPerWg, kYStream>), dim3(kXcds * p.per_xcd), dim3(kScanThreads), 0,
                        stream, p);
   else
