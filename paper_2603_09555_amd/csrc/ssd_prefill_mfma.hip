@@ -268,12 +268,18 @@ __device__ __forceinline__ size_t uniform_size(size_t v) {
 // is also copied, zero padded to 128 columns, to Cpad (tokens, G, 128), from which the scan then reads it.
 // Both tiles are read once, 16 consecutive bytes per thread and whole rows per 16 threads (a lane per
 // row, which is what the MFMA operands want, would fetch every 128-byte line of the tiles four times,
-// 32 bytes at a time: measured four times slower with many groups), and go through LDS:
+// 32 bytes at a time: measured four times slower with many groups), and go through LDS -- B whole, C one
+// half of the dstate axis (64 columns) at a time, from the registers that hold the whole tile: the
+// workgroup's LDS is what limits how many of these short, latency-bound workgroups a CU holds (six this
+// way; four with both tiles whole, which put the launch through two rounds at the benchmark shapes).
 //   sB  kBlk rows of kN + 2 elements: the odd dword stride makes the transposed read-back conflict free
-//   sC  kBlk rows of kN + 8 elements, read as operands with 16-byte reads; once the products are done
+//   sC  kBlk rows of 64 + 8 elements, read as operands with 16-byte reads; once the products are done
 //       it holds G on its way out (rows of kBlk + 8 elements), so that G too is stored in whole rows
+constexpr int kHalfN = kN / 2;
+constexpr int kSbStride = kN + 2, kScStride = kHalfN + 8;
 constexpr int kGtStride = kBlk + 8;
-constexpr int kSbElems = kBlk * (kN + 2), kScElems = kBlk * (kN + 8);
+constexpr int kSbElems = kBlk * kSbStride, kScElems = kBlk * kScStride;
+static_assert(kBlk * kGtStride <= kScElems, "G fits where the half tile of C was");
 __device__ __forceinline__ void scores_bt_block(uint16_t *sB, uint16_t *sC, size_t row0, size_t row_end, size_t tile,
                                                 int g, const uint16_t *__restrict__ B, const uint16_t *__restrict__ C,
                                                 uint16_t *__restrict__ Gd, uint16_t *__restrict__ Btr, int G,
@@ -295,39 +301,66 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, uint16_t *sC, size
   const Rsrc rB = make_rsrc(B + first, span), rC = make_rsrc(C + first, span);
   constexpr uint32_t kNowhere = 0xFFFFFF00u;
   constexpr int kPieces = kBlk * (kN / 8) / kThreads;
+  // thread -> 16-byte piece `ch` of the rows row_first + 16 i
+  const int ch = threadIdx.x % (kN / 8), row_first = threadIdx.x / (kN / 8);
+  static_assert(kThreads % (kN / 8) == 0, "a thread keeps its piece of the row over its rows");
+  constexpr int kRowStep = kThreads / (kN / 8);
   u32x4 vb[kPieces], vc[kPieces];
 #pragma unroll
   for (int i = 0; i < kPieces; ++i) {
-    const int ch16 = threadIdx.x + i * kThreads, row = ch16 / (kN / 8), ch = ch16 % (kN / 8);
+    const int row = row_first + i * kRowStep;
     const uint32_t off = 8 * ch < ns.valid ? row * row_bytes + ch * 16 : kNowhere;  // columns beyond the slice: zero
     vb[i] = buf_load16(rB, off, 0);
     vc[i] = buf_load16(rC, off, 0);
   }
+  if (Cpad != nullptr) {
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i) {
+      const int row = row_first + i * kRowStep;
+      if (row0 + row < row_end) *reinterpret_cast<u32x4 *>(Cpad + ((row0 + row) * G + g) * kN + 8 * ch) = vc[i];
+    }
+  }
 #pragma unroll
   for (int i = 0; i < kPieces; ++i) {
-    const int ch16 = threadIdx.x + i * kThreads, row = ch16 / (kN / 8), ch = ch16 % (kN / 8);
-    uint32_t *dst = reinterpret_cast<uint32_t *>(sB + row * (kN + 2) + 8 * ch);
+    uint32_t *dst = reinterpret_cast<uint32_t *>(sB + (row_first + i * kRowStep) * kSbStride + 8 * ch);
     dst[0] = vb[i].x;
     dst[1] = vb[i].y;
     dst[2] = vb[i].z;
     dst[3] = vb[i].w;
-    *reinterpret_cast<u32x4 *>(sC + row * (kN + 8) + 8 * ch) = vc[i];
-    if (Cpad != nullptr && row0 + row < row_end)
-      *reinterpret_cast<u32x4 *>(Cpad + ((row0 + row) * G + g) * kN + 8 * ch) = vc[i];
   }
-  __syncthreads();
   // G^T tile (rows s, columns l): lane ends up with four consecutive s for its l.
   f32x16 acc = {};
-  {
-    const uint32_t *bp = reinterpret_cast<const uint32_t *>(sB + (32 * ws + r) * (kN + 2) + 8 * kg);
-    const uint16_t *cp = sC + (32 * wl + r) * (kN + 8) + 8 * kg;
 #pragma unroll
-    for (int q = 0; q < kN / 16; ++q) {
+  for (int half = 0; half < 2; ++half) {
+    if (half) __syncthreads();  // the first half's operands have been read
+    if (ch / (kHalfN / 8) == half) {
+#pragma unroll
+      for (int i = 0; i < kPieces; ++i)
+        *reinterpret_cast<u32x4 *>(sC + (row_first + i * kRowStep) * kScStride + 8 * (ch % (kHalfN / 8))) = vc[i];
+    }
+    __syncthreads();
+    const uint32_t *bp = reinterpret_cast<const uint32_t *>(sB + (32 * ws + r) * kSbStride + kHalfN * half + 8 * kg);
+    const uint16_t *cp = sC + (32 * wl + r) * kScStride + 8 * kg;
+#pragma unroll
+    for (int q = 0; q < kHalfN / 16; ++q) {
       Operand a, c;
       a.q = mk4(bp[8 * q], bp[8 * q + 1], bp[8 * q + 2], bp[8 * q + 3]);
       c.q = *reinterpret_cast<const u32x4 *>(cp + 16 * q);
       acc = mfma(a, c, acc);
     }
+  }
+  // B^T: the staged block read back n-major
+  uint16_t *Bout = Btr + tile * kN * kBlk;
+#pragma unroll
+  for (int i = 0; i < kN * (kBlk / 8) / kThreads; ++i) {
+    const int c8 = threadIdx.x + i * kThreads, n = c8 / (kBlk / 8), s0 = (c8 % (kBlk / 8)) * 8;
+    uint32_t w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t lo = sB[(s0 + 2 * k) * kSbStride + n], hi = sB[(s0 + 2 * k + 1) * kSbStride + n];
+      w[k] = lo | (hi << 16);
+    }
+    *reinterpret_cast<u32x4 *>(Bout + n * kBlk + s0) = mk4(w[0], w[1], w[2], w[3]);
   }
   __syncthreads();  // every wave has read its operands: sC may take G
   uint16_t *sGt = sC;
@@ -341,25 +374,13 @@ __device__ __forceinline__ void scores_bt_block(uint16_t *sB, uint16_t *sC, size
     *reinterpret_cast<u32x2 *>(sGt + l * kGtStride + s) = v;
   }
   __syncthreads();
-  // G in whole rows; B^T: the staged block read back n-major
+  // G in whole rows
   uint16_t *Gout = Gd + tile * kBlk * kBlk;
 #pragma unroll
   for (int i = 0; i < kBlk * (kBlk / 8) / kThreads; ++i) {
     const int ch16 = threadIdx.x + i * kThreads, row = ch16 / (kBlk / 8), piece = ch16 % (kBlk / 8);
     *reinterpret_cast<u32x4 *>(Gout + row * kBlk + 8 * piece) =
         *reinterpret_cast<const u32x4 *>(sGt + row * kGtStride + 8 * piece);
-  }
-  uint16_t *Bout = Btr + tile * kN * kBlk;
-#pragma unroll
-  for (int i = 0; i < kN * (kBlk / 8) / kThreads; ++i) {
-    const int c8 = threadIdx.x + i * kThreads, n = c8 / (kBlk / 8), s0 = (c8 % (kBlk / 8)) * 8;
-    uint32_t w[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const uint32_t lo = sB[(s0 + 2 * k) * (kN + 2) + n], hi = sB[(s0 + 2 * k + 1) * (kN + 2) + n];
-      w[k] = lo | (hi << 16);
-    }
-    *reinterpret_cast<u32x4 *>(Bout + n * kBlk + s0) = mk4(w[0], w[1], w[2], w[3]);
   }
 }
 
@@ -975,10 +996,20 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
     // {middle -> end, log2 of the total decay} of the block to be staged next, fetched one iteration
     // before it is used
     f32x2 sf_stage = {1.f, 0.f};
-    if (jb0 < jb1) {  // the first block is requested together with the decays that are summed next
+    // The first TWO blocks are requested at once, together with the decays that are summed next: the second
+    // block's B^T pieces land in registers of their own until the first block's have gone to LDS, so the
+    // prologue costs one trip to memory, not two.
+    f32x2 sf_second = {1.f, 0.f};
+    u32x4 r_bt_second[kBtPieces];
+    if (jb0 < jb1) {
       load_part(0, jb0, 0);
       load_part(1, jb0);
+      load_part(0, at(jb0 + 1), 1);
+#pragma unroll
+      for (int k = 0; k < kBtPieces; ++k)
+        r_bt_second[k] = buf_load16(rs_bt, vt, at(jb0 + 1) * (kN * kBlk * 2) + k * (kThr * 16));
       sf_stage = load_factors(jb0);
+      sf_second = load_factors(at(jb0 + 1));
     }
     for (int j = jb0; j < jb1; j += 64) {  // the segment's total log2 decay: one lane per block
       float v = j + lane < jb1 ? factor_ptr(j + lane)[1] : 0.f;
@@ -999,16 +1030,16 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
     if (jb0 < jb1) {
       next_weight();
       weigh(0);
-      sf_stage = load_factors(at(jb0 + 1));
+      sf_stage = sf_second;
 #pragma unroll
       for (int c = 0; c < 8; ++c) stage_column(c, 0);
 #pragma unroll
       for (int k = 0; k < kBtPieces; ++k) *reinterpret_cast<u32x4 *>(&sBt[0][lds_bt[k]]) = r_bt[k];
-      load_part(0, at(jb0 + 1), 1);
-      load_part(1, at(jb0 + 1));
+#pragma unroll
+      for (int k = 0; k < kBtPieces; ++k) r_bt[k] = r_bt_second[k];
+      wait_all_loads();  // (everything so far is needed by now: nothing is lost)
       load_part(0, at(jb0 + 2), 0);
     }
-    wait_all_loads();
     __syncthreads();
     auto body = [&](int par, int jb) __attribute__((always_inline)) {
       const int buf = par, set = par ^ 1;  // block jb sits in LDS buffer `par`; block jb+1 in register set par^1
@@ -1590,7 +1621,7 @@ __global__ __launch_bounds__(kThreads) void segment_pass_kernel(float *__restric
 // The test-only knobs (see Knobs) force chunks or blocks per segment, and pieces per segment in the
 // states-only pass.
 constexpr int kNumCUs = 256;
-double rounds_time(long wgs, int blocks, double t_idle, double t_busy) {
+double rounds_time(long wgs, double blocks, double t_idle, double t_busy) {
   double t = 0.0;
   for (long left = wgs; left > 0; left -= kNumCUs) {
     const double n = static_cast<double>(left < kNumCUs ? left : kNumCUs);
@@ -1636,6 +1667,7 @@ double states_cost(long groups, double seqs, int S, int seg_blocks, int max_slot
 }
 
 // min_blocks: the shortest segment allowed (packed batches size their tables for whole chunks).
+constexpr double kColdXBytes = 144.0 * 1024 * 1024;  // x above this does not survive in the memory-side cache
 int choose_seg_blocks(const Dims &d, int min_blocks, int max_slots, int max_parts) {
   const int chunk_blocks = d.L / kBlk;
   const int nblocks = (d.T + kBlk - 1) / kBlk;
@@ -1648,10 +1680,18 @@ int choose_seg_blocks(const Dims &d, int min_blocks, int max_slots, int max_part
   int best_blocks = hi;
   double best = 0.0;
   bool have = false;
+  // The states pass leaves the x it has read -- every segment but the last of each sequence -- in the
+  // memory-side cache, where the full scan finds it again; the last segment's x comes from HBM if the
+  // tensor is too large to have stayed there from whoever wrote it, at a measured 1.25 times the per-block
+  // time.  Segments somewhat longer than the count needs, leaving a shorter last one, even that out (8 x
+  // 4096 tokens x 48 heads: 168 us with 32 + 32 blocks, 161 with 36 + 28).
+  const double x_bytes = static_cast<double>(d.Bt) * d.T * d.H * d.P * 2.0;
+  const double cold = x_bytes > kColdXBytes ? 1.25 : 1.0;
   for (int cand = min_blocks; cand <= hi; ++cand) {
     const long segs = (nblocks + cand - 1) / cand;
-    if (cand > min_blocks && (nblocks + cand - 2) / (cand - 1) == segs) continue;  // same count, longer segments
-    double cost = rounds_time(groups * segs, cand, 2.57, 3.35);
+    const double last = static_cast<double>(nblocks - (segs - 1) * cand);
+    const double walk = segs > 1 && cold * last > cand ? cold * last : cand;  // the longest walk, in warm blocks
+    double cost = rounds_time(groups * segs, walk, 2.57, 3.35);
     int parts;
     if (segs > 1) cost += states_cost(groups, seqs, static_cast<int>(segs), cand, max_slots, max_parts, &parts) + 3.1 + 7.0;
     if (!have || cost < best) {
