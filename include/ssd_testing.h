@@ -27,9 +27,11 @@ typedef enum {
                                  segment length and the state slots suffice; 0: default */
   SSD_KNOB_Y_STREAM = 4,      /* 0 / 1: ordinary / non-temporal stores of y in the full scan; -1: default */
   SSD_KNOB_DECODE_STREAM = 5, /* 0 / 1: ordinary / non-temporal accesses to the decode state; -1: default */
-  SSD_KNOB_FORCE_MFMA_F32 = 6 /* 1: fp32 io runs on the fp32 MFMA kernel whenever the shape is eligible (headdim
+  SSD_KNOB_FORCE_MFMA_F32 = 6, /* 1: fp32 io runs on the fp32 MFMA kernel whenever the shape is eligible (headdim
                                  a multiple of 32, dstate a multiple of 8 up to 128), also where the library
                                  expects the generic kernels to be faster; 0: default */
+  SSD_KNOB_F32_SEGMENTS = 7    /* k > 0: the fp32 MFMA kernel cuts every sequence into k time segments (at most
+                                 one per 64-token block); 0: library's choice */
 } ssd_knob;
 
 /* Sets one knob.  Errors: SSD_ERR_SHAPE for an unknown knob. */

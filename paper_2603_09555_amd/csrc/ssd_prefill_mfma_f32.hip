@@ -6,8 +6,13 @@
 // One kernel, one launch, no workspace.  A workgroup of four waves owns (batch row, head, 32 columns of
 // headdim) and walks the sequence in 64-token blocks with its 32 x dstate slice of the state carried in
 // MFMA accumulators: the inter-chunk state pass (Alg. 1, "Inter-chunk scan") happens in registers and
-// the result does not depend on the chunk argument.  Per block, with cs_l the block-relative inclusive
-// prefix sum of dt*A and S the state entering the block:
+// the result does not depend on the chunk argument.
+// When that leaves most of the chip idle, the sequence is also cut into time segments, one workgroup
+// each: a workgroup walks from the first block of the sequence, but up to its own segment it only updates
+// the state (no scores, no output, the update shared by all four waves: a fraction of a block's time), then
+// computes the outputs of its segment.  The states are recomputed rather than handed over, so there is still one launch, no workspace
+// and no waiting on another workgroup; the last segment's workgroup writes the final state.
+// Per block, with cs_l the block-relative inclusive prefix sum of dt*A and S the state entering the block:
 //   scores      G[l][s] = C_l . B_s for s <= l                     three 32 x 32 tiles, K = dstate   (waves 0-2)
 //   mask        GM[l][s] = G[l][s] * dt_s * exp(cs_l - cs_s)      in registers, on the accumulators; the
 //               exponent is never positive, so any step size is exact; to LDS as the next operand
@@ -88,6 +93,7 @@ struct F32Params {
   const float *x, *dt, *A, *B, *C, *D, *h0;
   float *y, *final_state;
   int T, H, P, N, G, hpg;
+  int tseg;  // time segments per sequence (>= 1), each a workgroup of its own
   DtXform dtx;
 };
 
@@ -112,11 +118,17 @@ __global__ __launch_bounds__(kF32Threads) void prefill_f32_kernel(const F32Param
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 31, kk = lane >> 5;
   const int slices = p.P / kCols;
-  const int ps = blockIdx.x % slices;
-  const int h = (blockIdx.x / slices) % p.H;
-  const int b = blockIdx.x / (slices * p.H);
+  const int seg = blockIdx.x % p.tseg, owner = blockIdx.x / p.tseg;
+  const int ps = owner % slices;
+  const int h = (owner / slices) % p.H;
+  const int b = owner / (slices * p.H);
   const int g = h / p.hpg;
   const int nblocks = (p.T + kTok - 1) / kTok;
+  // this workgroup's blocks: the state alone up to out0, everything from out0 to walk_end
+  const int seg_len = (nblocks + p.tseg - 1) / p.tseg;
+  const int out0 = min(nblocks, seg * seg_len), walk_end = min(nblocks, out0 + seg_len);
+  const bool last_seg = walk_end == nblocks && (out0 < walk_end || seg == 0);  // writes the final state
+  if (out0 >= walk_end && !last_seg) return;  // more segments than blocks (uniform over the workgroup)
   const size_t tok0 = static_cast<size_t>(b) * p.T;
   const float alog = p.A[h] * kLog2e;
   const float Dh = p.D[h];
@@ -141,12 +153,23 @@ __global__ __launch_bounds__(kF32Threads) void prefill_f32_kernel(const F32Param
   f32x4 r_c[kVecN], r_b[kVecN], r_x[2];
   float r_dt = 0.f;
   // thread -> (token row, 16-byte piece) of the C / B tiles and of the x tile, tid-major
-  uint32_t v_bc[kVecN], v_x[2];
+  // (B is also written transposed, n-major: there the 16 lanes of a quarter wave take 16 consecutive token
+  // rows of one piece, so that their scalar writes fall into 16 consecutive banks -- with the row-major
+  // assignment of C they would share four)
+  auto b_piece = [&](int k, int &row, int &n0) {
+    const int c = tid + kF32Threads * k;
+    row = 16 * ((c >> 4) / (N32 / 4)) + (c & 15);
+    n0 = 4 * ((c >> 4) % (N32 / 4));
+  };
+  uint32_t v_bc[kVecN], v_b[kVecN], v_x[2];
 #pragma unroll
   for (int k = 0; k < kVecN; ++k) {
     const int c = tid + kF32Threads * k;
     const int row = c / (N32 / 4), n0 = 4 * (c % (N32 / 4));
     v_bc[k] = n0 < p.N ? static_cast<uint32_t>(row) * brow + 4 * n0 : kNowhere;  // dstate is a multiple of 8
+    int rb, nb;
+    b_piece(k, rb, nb);
+    v_b[k] = nb < p.N ? static_cast<uint32_t>(rb) * brow + 4 * nb : kNowhere;
   }
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
@@ -154,12 +177,14 @@ __global__ __launch_bounds__(kF32Threads) void prefill_f32_kernel(const F32Param
     v_x[k] = static_cast<uint32_t>(c >> 3) * xrow + 16 * (c & 7);
   }
   const uint32_t v_dt = static_cast<uint32_t>(lane) * drow;  // every wave fetches the block's 64 step sizes; wave 0 uses them
-  auto load_block = [&](int jb) __attribute__((always_inline)) {
+  // (with_c, uniform: a block of which only the state is wanted needs no C -- its loads are pointed beyond the
+  // descriptor, where they cost nothing, rather than put behind a branch)
+  auto load_block = [&](int jb, bool with_c = true) __attribute__((always_inline)) {
     const Rsrc rc = rsrc_at(Cb, brow, boff, jb), rb = rsrc_at(Bb, brow, boff, jb);
 #pragma unroll
     for (int k = 0; k < kVecN; ++k) {
-      r_c[k] = buf_load4(rc, v_bc[k]);
-      r_b[k] = buf_load4(rb, v_bc[k]);
+      r_c[k] = buf_load4(rc, with_c ? v_bc[k] : kNowhere);
+      r_b[k] = buf_load4(rb, v_b[k]);
     }
     const Rsrc rx = rsrc_at(xb, xrow, xoff, jb);
 #pragma unroll
@@ -167,15 +192,20 @@ __global__ __launch_bounds__(kF32Threads) void prefill_f32_kernel(const F32Param
     r_dt = buf_load1(rsrc_at(dtb, drow, static_cast<uint32_t>(h) * 4, jb), v_dt);
   };
   // registers -> LDS tiles; wave 0 also turns dt into the block's decay bookkeeping
-  auto stage_block = [&](int jb_staged) __attribute__((always_inline)) {
+  // (full, uniform: the row-major C and B tiles serve the scores only)
+  auto stage_block = [&](int jb_staged, bool full = true) __attribute__((always_inline)) {
 #pragma unroll
     for (int k = 0; k < kVecN; ++k) {
       const int c = tid + kF32Threads * k;
       const int row = c / (N32 / 4), n0 = 4 * (c % (N32 / 4));
-      *reinterpret_cast<f32x4 *>(&sC[row * kRowN + n0]) = r_c[k];
-      *reinterpret_cast<f32x4 *>(&sB[row * kRowN + n0]) = r_b[k];
+      int rb, nb;
+      b_piece(k, rb, nb);
+      if (full) {
+        *reinterpret_cast<f32x4 *>(&sC[row * kRowN + n0]) = r_c[k];
+        *reinterpret_cast<f32x4 *>(&sB[rb * kRowN + nb]) = r_b[k];
+      }
 #pragma unroll
-      for (int j = 0; j < 4; ++j) sBT[(n0 + j) * kRowT + row] = r_b[k][j];
+      for (int j = 0; j < 4; ++j) sBT[(nb + j) * kRowT + rb] = r_b[k][j];
     }
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
@@ -199,6 +229,10 @@ __global__ __launch_bounds__(kF32Threads) void prefill_f32_kernel(const F32Param
   // ---- the state: waves 2 and 3 carry it in accumulators, tile nt = wave - 2 (+ 2); D[i = col][j = n] ----
   constexpr int kTilesPerWave = (NT + 1) / 2;
   f32x16 Sacc[kTilesPerWave];
+#pragma unroll
+  for (int k = 0; k < kTilesPerWave; ++k)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) Sacc[k][e] = 0.f;
   auto state_tile = [&](int k) { return (wave - 2) + 2 * k; };  // meaningful for waves 2, 3
   if (wave >= 2) {
 #pragma unroll
@@ -221,12 +255,76 @@ __global__ __launch_bounds__(kF32Threads) void prefill_f32_kernel(const F32Param
       }
   };
 
-  if (nblocks > 0) load_block(0);
-  for (int jb = 0; jb < nblocks; ++jb) {
+  if (walk_end > 0) load_block(0, out0 == 0);
+  if (out0 > 0) {
+    // ---- the blocks before the segment: the state alone.  All four waves share the update -- wave w takes
+    //      tokens 16 w .. 16 w + 15 of every block, for every state tile -- in accumulators of their own, which
+    //      are summed once, at the end (the update is linear in the state); the initial state rides in the
+    //      accumulators of the wave that owns the tile afterwards. ----
+    f32x16 Spart[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const bool mine = wave == 2 + (nt & 1);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) Spart[nt][e] = mine ? Sacc[nt >> 1][e] : 0.f;
+    }
+    for (int jb = 0; jb < out0; ++jb) {
+      __syncthreads();  // the previous block's readers are done with every tile
+      stage_block(jb, false);
+      load_block(jb + 1, jb + 1 == out0);  // (out0 < walk_end: block jb + 1 exists)
+      __syncthreads();
+      const float e63 = sEl[kTok - 1];
+      const float *ap = &sXT[r * kRowT + 4 * kk];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) Spart[nt][e] *= e63;
+      }
+#pragma unroll
+      for (int mm = 0; mm < 2; ++mm) {
+        const int m = 2 * wave + mm;
+        f32x4 a = ld4(ap + 8 * m);
+        const f32x4 w = ld4(&sW[8 * m + 4 * kk]);
+        a = f32x4{a.x * w.x, a.y * w.y, a.z * w.z, a.w * w.w};
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) Spart[nt] = mfma_group(a, ld4(&sBT[(32 * nt + r) * kRowT + 4 * kk + 8 * m]), Spart[nt]);
+      }
+    }
+    // the sum, tile by tile, through what will be the masked-score tile: three waves put, the owner adds
+    static_assert(3 * 1024 <= kTok * kRowT, "three partial tiles fit in the masked-score tile");
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int owner_wave = 2 + (nt & 1);
+      __syncthreads();
+      if (wave != owner_wave) {
+        float *dst = &sGM[(wave - (wave > owner_wave)) * 1024 + 4 * lane];
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4)
+          *reinterpret_cast<f32x4 *>(dst + 256 * e4) = f32x4{Spart[nt][4 * e4], Spart[nt][4 * e4 + 1], Spart[nt][4 * e4 + 2], Spart[nt][4 * e4 + 3]};
+      }
+      __syncthreads();
+      if (wave == owner_wave) {
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+          f32x4 sum = f32x4{Spart[nt][4 * e4], Spart[nt][4 * e4 + 1], Spart[nt][4 * e4 + 2], Spart[nt][4 * e4 + 3]};
+#pragma unroll
+          for (int q = 0; q < 3; ++q) {
+            const f32x4 v = ld4(&sGM[q * 1024 + 256 * e4 + 4 * lane]);
+            sum = f32x4{sum.x + v.x, sum.y + v.y, sum.z + v.z, sum.w + v.w};
+          }
+          Sacc[nt >> 1][4 * e4] = sum.x;
+          Sacc[nt >> 1][4 * e4 + 1] = sum.y;
+          Sacc[nt >> 1][4 * e4 + 2] = sum.z;
+          Sacc[nt >> 1][4 * e4 + 3] = sum.w;
+        }
+      }
+    }
+  }
+  for (int jb = out0; jb < walk_end; ++jb) {
     __syncthreads();  // the previous block's readers are done with every tile
     stage_block(jb);
     if (wave >= 2) put_state();
-    load_block(min(jb + 1, nblocks - 1));  // (after the last block: a harmless repeat, no branch)
+    load_block(min(jb + 1, walk_end - 1));  // (after the last block: a harmless repeat, no branch)
     __syncthreads();
 
     // ---- scores and mask: wave w < 3 owns tile (lt, st) = (0,0), (1,0), (1,1) ----
@@ -324,7 +422,7 @@ __global__ __launch_bounds__(kF32Threads) void prefill_f32_kernel(const F32Param
   }
 
   // ---- final state (Alg. 1, "Store") ----
-  if (wave >= 2) {
+  if (wave >= 2 && last_seg) {
 #pragma unroll
     for (int k = 0; k < kTilesPerWave; ++k) {
       const int n = 32 * state_tile(k) + r;
@@ -341,9 +439,35 @@ __global__ __launch_bounds__(kF32Threads) void prefill_f32_kernel(const F32Param
 
 }  // namespace
 
+// Time per block of a workgroup (microseconds on MI355X; fits to a handful of timings): a full block, and a
+// block of which only the state update runs.  nt = 32-column tiles of the state.
+double f32_block_us(int nt) { return 1.7 + 1.39 * nt; }
+double f32_state_block_us(int nt) { return 0.29 + 0.47 * nt; }
+// Time segments per sequence, and the modelled time of the walk that results.  More segments shorten the
+// stretch of full blocks of the longest walk -- the last segment's, which first carries the state over
+// everything before it -- as long as the workgroups still run side by side (one round of 256).
+int f32_time_segments(const Dims &d, double *walk_us) {
+  const unsigned long long wgs = static_cast<unsigned long long>(d.Bt) * d.H * (d.P / kCols);
+  const int nblocks = (d.T + kTok - 1) / kTok, nt = (d.N + 31) / 32;
+  const double rounds = static_cast<double>((wgs + 255) / 256);
+  int best = 1;
+  double best_us = rounds * nblocks * f32_block_us(nt);
+  const int forced = knobs().f32_segments;
+  for (int s = 2; s <= nblocks && s <= 64 && (forced > 0 || wgs * s <= 256); ++s) {
+    const int len = (nblocks + s - 1) / s;
+    const double us = static_cast<double>((wgs * s + 255) / 256) * ((nblocks - len) * f32_state_block_us(nt) + len * f32_block_us(nt));
+    if (forced > 0 ? s <= forced : us < best_us) {
+      best = s;
+      best_us = us;
+    }
+  }
+  if (walk_us != nullptr) *walk_us = best_us;
+  return best;
+}
+
 // Shapes the kernel takes, and among them those it is expected to win on.  It walks a sequence block by block
-// with one workgroup per (batch row, head, 32 columns), so its time is (rounds of 256 workgroups) x (blocks) x
-// (time per block, which grows with the number of state tiles); the generic fp32 kernels are chunk-parallel
+// with one workgroup per (batch row, head, 32 columns, time segment), so its time is (rounds of 256
+// workgroups) x (the longest walk, see above); the generic fp32 kernels are chunk-parallel
 // over the whole chip, cost four launches and then time proportional to the work.  A long sequence with few
 // heads is theirs.  Both estimates are fits to a handful of timings on MI355X (microseconds); where they are
 // within a tenth of each other the MFMA kernel is taken.
@@ -351,13 +475,13 @@ bool mfma_f32_supported(const Dims &d, bool whenever_eligible) {
   const unsigned long long wgs = static_cast<unsigned long long>(d.Bt) * d.H * (d.P / kCols);
   // one batch row of x and of B / C must be addressable with 32-bit byte offsets
   const unsigned long long lim = 0xFFFF0000ull, t = static_cast<unsigned long long>(d.T);
-  if (d.bf16 || d.P % kCols != 0 || d.N % 8 != 0 || d.N > 128 || wgs > 0x7fffffffull || t * d.H * d.P * 4 > lim ||
+  if (d.bf16 || d.P % kCols != 0 || d.N % 8 != 0 || d.N > 128 || wgs > 0x7fffffffull / 64 || t * d.H * d.P * 4 > lim ||
       t * d.G * d.N * 4 > lim)
     return false;
   if (whenever_eligible) return true;
-  const double nblocks = static_cast<double>((d.T + kTok - 1) / kTok), nt = static_cast<double>((d.N + 31) / 32);
-  const double rounds = static_cast<double>((wgs + 255) / 256);
-  const double mfma_us = 8.0 + rounds * nblocks * (1.4 + 1.8 * nt);
+  double walk_us;
+  f32_time_segments(d, &walk_us);
+  const double mfma_us = 8.0 + walk_us;
   const double token_heads = static_cast<double>(d.Bt) * d.T * d.H;
   const double generic_us = 33.0 + token_heads * (0.9 + 0.0005 * d.P * d.N) * 1e-3;
   return mfma_us <= 1.1 * generic_us;
@@ -383,7 +507,8 @@ hipError_t launch_prefill_mfma_f32(const Dims &d, const void *x, const float *dt
   p.G = d.G;
   p.hpg = d.hpg;
   p.dtx = d.dtx;
-  const dim3 grid(static_cast<unsigned>(d.Bt) * d.H * (d.P / kCols)), block(kF32Threads);
+  p.tseg = f32_time_segments(d, nullptr);
+  const dim3 grid(static_cast<unsigned>(d.Bt) * d.H * (d.P / kCols) * p.tseg), block(kF32Threads);
   const int nt = (d.N + 31) / 32;
   switch (nt) {
     case 1: hipLaunchKernelGGL(prefill_f32_kernel<1>, grid, block, 0, stream, p); break;

@@ -417,6 +417,28 @@ def test_f32_mfma_prefill_matches_oracle(ssd, case):
     assert_close(stg, st_ref, 1e-4, "generic fp32 final state")
 
 
+@pytest.mark.parametrize("nseg", [2, 3, 5, 64])
+@pytest.mark.parametrize("case", [(1, 700, 4, 64, 128, 2, 256, True), (2, 130, 6, 96, 72, 3, 64, True),
+                                  (1, 512, 4, 32, 16, 1, 64, False), (3, 65, 4, 32, 40, 2, 100, False)],
+                         ids=lambda c: "x".join(map(str, c)))
+def test_f32_mfma_time_segments(ssd, case, nseg):
+    """The fp32 MFMA kernel with every sequence cut into time segments (one workgroup each, the state up to
+    the segment recomputed -- by all four waves, in partial sums -- not handed over): the oracle's results
+    within the fp32 tolerance, the same on a second run.  More segments than blocks (64 here) leave the
+    surplus workgroups without work."""
+    *dims, with_h0 = case
+    cfg = cfg_of(*dims, "f32")
+    ssd.set_knob("force_mfma_f32", 1)
+    h0 = inputs.make_state(cfg, seed=6, scale=0.3) if with_h0 else None
+    ssd.set_knob("f32_segments", nseg)
+    inp, y, st = run_prefill(ssd, cfg, seed=47, h0=h0)
+    _, y2, st2 = run_prefill(ssd, cfg, seed=47, h0=h0)
+    assert torch.equal(y, y2) and torch.equal(st, st2)
+    y_ref, st_ref = oracle_prefill(inp, h0=h0)
+    assert_close(y, y_ref, 1e-4, "fp32 mfma y, %d time segments" % nseg)
+    assert_close(st, st_ref, 1e-4, "fp32 mfma final state, %d time segments" % nseg)
+
+
 def test_f32_mfma_prefill_with_steep_decay_and_fused_dt(ssd):
     """fp32 MFMA path at dt*|A| of 0.5 ... 12 per token (the mask is evaluated un-factorised, exponent never
     positive, so no step size is special), and with the step-size activation applied as dt is read."""
