@@ -30,8 +30,12 @@ typedef enum {
   SSD_KNOB_FORCE_MFMA_F32 = 6, /* 1: fp32 io runs on the fp32 MFMA kernel whenever the shape is eligible (headdim
                                  a multiple of 32, dstate a multiple of 8 up to 128), also where the library
                                  expects the generic kernels to be faster; 0: default */
-  SSD_KNOB_F32_SEGMENTS = 7    /* k > 0: the fp32 MFMA kernel cuts every sequence into k time segments (at most
+  SSD_KNOB_F32_SEGMENTS = 7,   /* k > 0: the fp32 MFMA kernel cuts every sequence into k time segments (at most
                                  one per 64-token block); 0: library's choice */
+  SSD_KNOB_FOLD_MAX_SLOTS = 8  /* k >= 0: a plain batch whose chain over segment-state slots, (segments - 1) x
+                                 pieces, is at most k long runs no separate pass over those states -- every
+                                 segment of the full scan sums the slots before it as it loads them; 0: never.
+                                 Default 3.  Reset with ssd_testing_reset_knobs */
 } ssd_knob;
 
 /* Sets one knob.  Errors: SSD_ERR_SHAPE for an unknown knob. */

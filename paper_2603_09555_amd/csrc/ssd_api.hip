@@ -372,6 +372,7 @@ ssd_status ssd_testing_set_knob(int32_t knob, int32_t value) {
     case SSD_KNOB_DECODE_STREAM: k.decode_stream = value < 0 ? -1 : (value != 0); return SSD_OK;
     case SSD_KNOB_FORCE_MFMA_F32: k.force_mfma_f32 = value > 0 ? 1 : 0; return SSD_OK;
     case SSD_KNOB_F32_SEGMENTS: k.f32_segments = value > 0 ? value : 0; return SSD_OK;
+    case SSD_KNOB_FOLD_MAX_SLOTS: k.fold_max_slots = value > 0 ? value : 0; return SSD_OK;
     default: return SSD_ERR_SHAPE;
   }
 }

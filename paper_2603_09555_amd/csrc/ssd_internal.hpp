@@ -106,6 +106,7 @@ struct Knobs {
   int decode_stream = -1;  // 0 / 1: ordinary / non-temporal accesses to the decode state
   int force_mfma_f32 = 0;  // 1: fp32 io takes the fp32 MFMA kernel whenever the shape is eligible
   int f32_segments = 0;    // > 0: time segments per sequence in the fp32 MFMA kernel
+  int fold_max_slots = 3;  // most state slots a segment sums by itself instead of a pass over segment states (0: never)
 };
 Knobs &knobs();
 

@@ -574,6 +574,10 @@ struct ScanParams {
   // segment states then chains the pieces, and a sequence has `slots` state slots, of which segment
   // sg of the full scan starts from slot sg * parts.  Plain batches only; parts = 1 otherwise.
   int parts, part_blocks, slots;
+  // fold != 0 (plain batches of few segments): no pass over segment states has run.  The first segment
+  // starts from h0 itself; segment sg sums the local end states of the pieces before it (slots 1 .. sg
+  // parts) and h0, each times the decay of the pieces after it, as it loads them.
+  int fold;
   int pdiv, Hrec;          // slices per head (headdim / 64); heads (owners of decay records, A, D)
   NSlice ns;               // columns of h0 / final_state (rows of ns.width floats) this launch works on
   int cols, segs, total, per_xcd;  // workgroup mapping, see wg_coords
@@ -911,7 +915,7 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
     // loads return zero.
     const float *hbase = nullptr;
     uint32_t hrow = kN, hvalid = kN;
-    if (sv.S > 1) {
+    if (sv.S > 1 && !(p.fold && sg == 0)) {
       hbase = p.Hin + (slot0 + static_cast<size_t>(sg) * p.parts) * (kP * kN);
     } else if (p.h0 != nullptr) {
       hbase = p.h0 + bh * kP * p.ns.width + p.ns.off;
@@ -1132,6 +1136,42 @@ __device__ __forceinline__ void scan_walk(const ScanParams &p, const SeqView &sv
             Hacc[2 * half + nt][4 * i4 + 2] = v.z;
             Hacc[2 * half + nt][4 * i4 + 3] = v.w;
           }
+      }
+      if (p.fold && sg >= 1) {
+        // What was loaded is the local end state of the piece that ends where this segment begins; the
+        // earlier pieces' (slots sg parts - 1 .. 1) and h0 follow, one at a time through the same registers,
+        // each weighted by the decay of everything after it.  (Uniform over the workgroup.)
+        float log2_decay = 0.f;
+        for (int k = sg * p.parts - 1; k >= 0; --k) {
+          log2_decay += p.seg_decay[slot0 + k];
+          if (k == 0 && p.h0 == nullptr) break;
+          const float *base = k > 0 ? p.Hin + (slot0 + k) * (kP * kN) : p.h0 + bh * kP * p.ns.width + p.ns.off;
+          const uint32_t trow = k > 0 ? kN : static_cast<uint32_t>(p.ns.width);
+          const uint32_t tvalid = k > 0 ? kN : static_cast<uint32_t>(p.ns.valid);
+          const Rsrc rs_t = make_rsrc(base, ((kP - 1) * trow + tvalid) * 4u);
+          const float wgt = fast_exp2(log2_decay);
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const uint32_t row = 32 * ph + 4 * (i & 7) + (lane >> 4), n0 = 64 * (i >> 3) + 4 * (lane & 15);
+            hraw[i] = buf_load16(rs_t, n0 < tvalid ? (row * trow + n0) * 4u : 0xFFFFFF00u, 0);
+          }
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+              *reinterpret_cast<u32x4 *>(turn + (4 * i + (lane >> 4)) * kTurnStride + 4 * (lane & 15)) = hraw[8 * half + i];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+              for (int i4 = 0; i4 < 4; ++i4) {
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(turn + pi_of_row(r) * kTurnStride + 32 * nt + 8 * i4 + 4 * kg);
+                Hacc[2 * half + nt][4 * i4 + 0] += wgt * v.x;
+                Hacc[2 * half + nt][4 * i4 + 1] += wgt * v.y;
+                Hacc[2 * half + nt][4 * i4 + 2] += wgt * v.z;
+                Hacc[2 * half + nt][4 * i4 + 3] += wgt * v.w;
+              }
+          }
+        }
       }
       __syncthreads();
     } else {
@@ -1693,7 +1733,13 @@ int choose_seg_blocks(const Dims &d, int min_blocks, int max_slots, int max_part
     const double walk = segs > 1 && cold * last > cand ? cold * last : cand;  // the longest walk, in warm blocks
     double cost = rounds_time(groups * segs, walk, 2.57, 3.35);
     int parts;
-    if (segs > 1) cost += states_cost(groups, seqs, static_cast<int>(segs), cand, max_slots, max_parts, &parts) + 3.1 + 7.0;
+    if (segs > 1) {
+      cost += states_cost(groups, seqs, static_cast<int>(segs), cand, max_slots, max_parts, &parts) + 3.1 + 7.0;
+      // a short chain over state slots is summed by the full scan itself (see ScanParams::fold): no pass over
+      // segment states and its launch, one more trip to memory per slot beyond the first instead (the net
+      // saving measured on six shapes of 24 to 384 sequences: 2 to 11 us)
+      if ((segs - 1) * parts <= knobs().fold_max_slots) cost -= 1.5 + 0.025 * seqs;
+    }
     if (!have || cost < best) {
       have = true;
       best = cost;
@@ -1860,6 +1906,15 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   p.part_blocks = seg_blocks / parts;
   p.slots = (S - 1) * parts + 1;
   p.vp = vp;
+  // Two segments: the chain over state slots is a sum of `parts` terms (and h0), which the second segment's
+  // workgroups form as they load their state -- one launch and one round trip of every state through memory
+  // less (8 x 4096 tokens x 48 heads: 162 -> 150 us).  Not when h0 and final_state share memory: the second
+  // segment might store the final state before the first has read h0.
+  const size_t state_bytes = static_cast<size_t>(d.Bt) * d.H * d.P * ns.width * sizeof(float);
+  const bool h0_aliases = h0 != nullptr && final_state != nullptr &&
+                          reinterpret_cast<const char *>(h0) < reinterpret_cast<const char *>(final_state) + state_bytes &&
+                          reinterpret_cast<const char *>(final_state) < reinterpret_cast<const char *>(h0) + state_bytes;
+  p.fold = !varlen && S >= 2 && (S - 1) * parts <= knobs().fold_max_slots && !h0_aliases ? 1 : 0;
   if (varlen || S > 1) {
     // (a packed batch always takes this route: whether any sequence has more than one segment is
     // known on the device only; workgroups of last segments leave the states-only pass at once)
@@ -1876,9 +1931,10 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
                        stream, p);
     trace_mark(trace, stream, "segment_states");
     const int rows_bh = d.Bt * Hs;  // a packed batch may have many one-segment sequences: rows are looped over
-    hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), rows_bh > (varlen ? 2048 : 65535) ? (varlen ? 2048 : 65535) : rows_bh),
-                       dim3(kThreads), 0, stream, seg_state, seg_decay, h0, p.slots, Hs, rows_bh, vp, ns);
-    trace_mark(trace, stream, "segment_pass");
+    if (!p.fold)
+      hipLaunchKernelGGL(segment_pass_kernel, dim3(kP * kN / (4 * kThreads), rows_bh > (varlen ? 2048 : 65535) ? (varlen ? 2048 : 65535) : rows_bh),
+                         dim3(kThreads), 0, stream, seg_state, seg_decay, h0, p.slots, Hs, rows_bh, vp, ns);
+    if (!p.fold) trace_mark(trace, stream, "segment_pass");
   }
   p.cols = d.G * p.cpg;
   p.segs = S;

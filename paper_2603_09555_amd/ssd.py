@@ -365,7 +365,7 @@ def ssd_conv1d_step(conv_state, u, weight, bias=None, split=None, activation="si
 
 
 KNOBS = {"force_generic": 0, "seg_chunks": 1, "seg_blocks": 2, "seg_parts": 3, "y_stream": 4, "decode_stream": 5,
-         "force_mfma_f32": 6, "f32_segments": 7}
+         "force_mfma_f32": 6, "f32_segments": 7, "fold_max_slots": 8}
 
 
 def set_knob(name: str, value: int) -> None:

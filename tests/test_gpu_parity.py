@@ -379,6 +379,46 @@ def test_mfma_prefill_continues_a_cached_prompt(ssd, case):
     print("errors", e, flush=True)
 
 
+@pytest.mark.parametrize("with_h0", [False, True], ids=["zero", "h0"])
+@pytest.mark.parametrize("parts", [1, 2, 4])
+@pytest.mark.parametrize("case", [(2, 1024, 8, 64, 128, 1, 256, 8), (1, 1000, 4, 128, 256, 2, 128, 10),
+                                  (3, 777, 12, 64, 64, 3, 64, 8), (2, 1300, 8, 64, 128, 1, 64, 4)],
+                         ids=lambda c: "x".join(map(str, c)))
+def test_mfma_prefill_segment_states_folded(ssd, case, parts, with_h0):
+    """A prompt cut into few segments runs no pass over segment states: every later segment's workgroups sum
+    the local end states of the pieces before them (and the decayed h0) as they load them.  Checked against
+    the oracle with two segments (one, two and four pieces; a ragged last block; two state slices at dstate
+    256; a carried state) and, with the limit raised, six segments of up to four pieces (a chain of 20
+    slots); against the separate pass on the same inputs; and with h0 and final_state in the same memory,
+    where the library must fall back to the separate pass."""
+    *dims, seg_blocks = case
+    cfg = cfg_of(*dims, "bf16")
+    ssd.set_knob("seg_blocks", seg_blocks)
+    ssd.set_knob("seg_parts", parts)
+    ssd.set_knob("fold_max_slots", 64)
+    h0 = None
+    if with_h0:  # an initial state of realistic size: what a prefill of similar inputs leaves behind
+        h0 = torch.from_numpy(oracle_prefill(inputs.make_prefill_inputs(cfg, seed=79))[1]).float()
+    inp, y, st = run_prefill(ssd, cfg, seed=52, h0=h0)
+    y_ref, st_ref = oracle_prefill(inp, h0=h0)
+    e = assert_close(y, y_ref, 2e-2, "folded y")
+    assert_close(st, st_ref, 2e-2, "folded final state")
+    print("errors", e, flush=True)
+    ssd.set_knob("fold_max_slots", 0)
+    _, y2, st2 = run_prefill(ssd, cfg, seed=52, h0=h0)
+    assert_close(y2, y_ref, 2e-2, "separate pass y")
+    assert_close(st2, st_ref, 2e-2, "separate pass final state")
+    ssd.set_knob("fold_max_slots", 64)
+    if with_h0:
+        dev = {k: v.cuda() for k, v in inp.items()}
+        shared = h0.cuda().clone()
+        y3, st3 = ssd.ssd_prefill(dev["x"], dev["dt"], dev["A"], dev["B"], dev["C"], dev["D"], cfg.chunk, h0=shared,
+                                  final_state=shared)
+        torch.cuda.synchronize()
+        assert st3.data_ptr() == shared.data_ptr()
+        assert torch.equal(y3, y2) and torch.equal(st3, st2)   # the separate pass ran: the same bits
+
+
 # ---- fp32 io on fp32 MFMA (headdim % 32 == 0, dstate % 8 == 0 up to 128) -----------------------------------
 F32_MFMA_CASES = [
     # Bt, T, H, P, N, G, L, with h0
