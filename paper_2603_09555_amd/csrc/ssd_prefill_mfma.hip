@@ -45,7 +45,7 @@
 //   segment_pass   sequential pass over segment end states -> state entering each segment.
 //   chunk_scan<false> per (batch, 4 heads, segment): everything above, from the entering state.
 // A segment is a whole number of 64-token blocks; with one segment only the first and the last kernel
-// run.
+// run, and with few segments segment_pass does not: the last kernel sums the few states itself.
 #include <type_traits>
 
 #include "ssd_internal.hpp"
