@@ -44,6 +44,17 @@ SSD_API ssd_status ssd_testing_set_knob(int32_t knob, int32_t value);
 /* All knobs back to the library's own choices. */
 SSD_API void ssd_testing_reset_knobs(void);
 
+/* How ssd_prefill would run a shape under the current knobs (host arithmetic only: no GPU call, nothing
+ * launched).  plan[0]: kernel family, 0 generic fp32 kernels, 1 bf16 MFMA, 2 fp32 MFMA.  For the bf16
+ * MFMA family (per state slice of 128 columns): plan[1] 64-token blocks per segment, plan[2] segments
+ * per sequence, plan[3] pieces per segment in the states-only pass, plan[4] 1 if the full scan sums the
+ * chain over segment states itself and no separate pass runs (h0_aliases_final_state != 0: as for a call
+ * whose h0 and final_state share memory, which rules that out).  For the fp32 MFMA family: plan[5] time
+ * segments per sequence.  The other entries are zero.
+ * Errors: SSD_ERR_NULL; the shape errors of ssd_prefill. */
+SSD_API ssd_status ssd_testing_prefill_plan(const ssd_shape *shape, int32_t h0_aliases_final_state,
+                                            int32_t plan[8]);
+
 #ifdef __cplusplus
 }
 #endif

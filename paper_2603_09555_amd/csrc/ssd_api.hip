@@ -126,6 +126,25 @@ const char *ssd_prefill_path(const ssd_shape *shape) {
   return use_mfma(d) ? "mfma_bf16" : use_mfma_f32(d) ? "mfma_f32" : "generic_f32";
 }
 
+ssd_status ssd_testing_prefill_plan(const ssd_shape *shape, int32_t h0_aliases_final_state, int32_t plan[8]) {
+  Dims d;
+  if (shape == nullptr || plan == nullptr) return SSD_ERR_NULL;
+  if (const ssd_status st = make_dims(shape, false, &d); st != SSD_OK) return st;
+  for (int i = 0; i < 8; ++i) plan[i] = 0;
+  if (use_mfma(d)) {
+    const ssd::SlicePlan pl = ssd::mfma_plan(d, h0_aliases_final_state != 0);
+    plan[0] = 1;
+    plan[1] = pl.seg_blocks;
+    plan[2] = pl.segments;
+    plan[3] = pl.parts;
+    plan[4] = pl.fold;
+  } else if (use_mfma_f32(d)) {
+    plan[0] = 2;
+    plan[5] = ssd::mfma_f32_time_segments(d);
+  }
+  return SSD_OK;
+}
+
 ssd_status ssd_prefill(const ssd_shape *shape, const void *x, const float *dt, const float *A,
                        const void *B, const void *C, const float *D, const float *h0, void *y,
                        float *final_state, void *workspace, size_t workspace_bytes_given,

@@ -125,6 +125,12 @@ hipError_t launch_prefill_generic(const Dims &d, const void *x, const float *dt,
                                   void *y, float *final_state, void *workspace, hipStream_t stream,
                                   KernelTrace *trace = nullptr);
 
+// How the bf16 MFMA prefill cuts a call up (for the launcher and for the test-only plan query).
+struct SlicePlan {
+  int seg_blocks, segments, parts, fold;
+};
+SlicePlan mfma_plan(const Dims &d, bool h0_aliases_final_state);
+int mfma_f32_time_segments(const Dims &d);
 bool mfma_supported(const Dims &d);
 size_t mfma_workspace_bytes(const Dims &d);
 hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, const float *A,

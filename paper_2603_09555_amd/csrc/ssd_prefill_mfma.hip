@@ -1823,6 +1823,35 @@ bool stream_y(const Dims &d, int rows) {
 
 // d: plain batch (cu == nullptr), or Bt = number of sequences and T = total tokens of a packed batch.
 // One state slice ns (see NSlice): y and final_state columns of that slice are written.
+// How a call is cut up: blocks per segment, segments per sequence (0 for a packed batch, where the
+// device-side tables hold them per sequence), pieces per segment of the states-only pass, and whether the
+// full scan sums the chain over state slots itself (ScanParams::fold).
+SlicePlan plan_slice(const Dims &d, bool varlen, bool h0_aliases_final_state) {
+  const Layout w = make_layout(d, varlen);
+  Dims one = d;  // the segment length of a packed batch is chosen as for one sequence of all its tokens
+  if (varlen) one.Bt = 1;
+  SlicePlan pl;
+  // shortest segment: a chunk for a packed batch; what the state slots allow for a plain one
+  pl.seg_blocks = choose_seg_blocks(one, varlen ? d.L / kBlk : (w.NB + w.S_max - 1) / w.S_max, w.S_max, varlen ? 1 : 8);
+  if (!varlen && (w.NB + pl.seg_blocks - 1) / pl.seg_blocks > w.S_max) pl.seg_blocks = (w.NB + w.S_max - 1) / w.S_max;
+  pl.segments = varlen ? 0 : (w.NB + pl.seg_blocks - 1) / pl.seg_blocks;
+  // pieces per segment for the states-only pass (see ScanParams): the split with the least modelled
+  // time of that pass plus the longer chain over state slots, among the divisors of the segment length
+  pl.parts = 1;
+  if (!varlen && pl.segments > 1) {
+    const long groups = static_cast<long>(d.Bt) * head_groups(d);
+    const double seqs = static_cast<double>(d.Bt) * d.H * (d.P / kP);
+    (void)states_cost(groups, seqs, pl.segments, pl.seg_blocks, w.S_max, 8, &pl.parts);
+    if (const int k = knobs().seg_parts; k >= 1 && pl.seg_blocks % k == 0 && (pl.segments - 1) * k + 1 <= w.S_max) pl.parts = k;
+  }
+  // A short chain over state slots is a sum of few terms (and h0), which the later segments' workgroups form
+  // as they load their state -- one launch and one round trip of every state through memory less (8 x 4096
+  // tokens x 48 heads: 162 -> 152 us).  Not when h0 and final_state share memory: the last segment might
+  // store the final state before the first has read h0.
+  pl.fold = !varlen && pl.segments >= 2 && (pl.segments - 1) * pl.parts <= knobs().fold_max_slots && !h0_aliases_final_state ? 1 : 0;
+  return pl;
+}
+
 hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const void *x, const float *dt,
                         const float *A, const void *B, const void *C, const float *D, const float *h0, void *y,
                         bool add_to_y, float *final_state, void *workspace, hipStream_t stream, KernelTrace *trace) {
@@ -1836,11 +1865,12 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   float *seg_decay = reinterpret_cast<float *>(ws + w.off_decay);
   uint16_t *Cpad = d.N != kN ? reinterpret_cast<uint16_t *>(ws + w.off_Cpad) : nullptr;
   const int rows = varlen ? 1 : d.Bt;
-  Dims one = d;  // the segment length of a packed batch is chosen as for one sequence of all its tokens
-  if (varlen) one.Bt = 1;
-  // shortest segment: a chunk for a packed batch; what the state slots allow for a plain one
-  int seg_blocks = choose_seg_blocks(one, varlen ? d.L / kBlk : (w.NB + w.S_max - 1) / w.S_max, w.S_max, varlen ? 1 : 8);
-  if (!varlen && (w.NB + seg_blocks - 1) / seg_blocks > w.S_max) seg_blocks = (w.NB + w.S_max - 1) / w.S_max;
+  const size_t state_bytes = static_cast<size_t>(d.Bt) * d.H * d.P * ns.width * sizeof(float);
+  const bool h0_aliases = h0 != nullptr && final_state != nullptr &&
+                          reinterpret_cast<const char *>(h0) < reinterpret_cast<const char *>(final_state) + state_bytes &&
+                          reinterpret_cast<const char *>(final_state) < reinterpret_cast<const char *>(h0) + state_bytes;
+  const SlicePlan pl = plan_slice(d, varlen, h0_aliases);
+  const int seg_blocks = pl.seg_blocks;
 
   VarPlan vp = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, 0};
   int S = (w.NB + seg_blocks - 1) / seg_blocks;  // plain batch: segments per sequence
@@ -1893,28 +1923,12 @@ hipError_t launch_slice(const Dims &d, const NSlice ns, const int32_t *cu, const
   p.NB = w.NB;
   p.seg_blocks = seg_blocks;
   p.S = S;
-  // pieces per segment for the states-only pass (see ScanParams): the split with the least modelled
-  // time of that pass plus the longer chain over state slots, among the divisors of the segment length
-  int parts = 1;
-  if (!varlen && S > 1) {
-    const long groups = static_cast<long>(d.Bt) * head_groups(d);
-    const double seqs = static_cast<double>(d.Bt) * d.H * (d.P / kP);
-    (void)states_cost(groups, seqs, S, seg_blocks, w.S_max, 8, &parts);
-    if (const int k = knobs().seg_parts; k >= 1 && seg_blocks % k == 0 && (S - 1) * k + 1 <= w.S_max) parts = k;
-  }
+  const int parts = pl.parts;
   p.parts = parts;
   p.part_blocks = seg_blocks / parts;
   p.slots = (S - 1) * parts + 1;
   p.vp = vp;
-  // Two segments: the chain over state slots is a sum of `parts` terms (and h0), which the second segment's
-  // workgroups form as they load their state -- one launch and one round trip of every state through memory
-  // less (8 x 4096 tokens x 48 heads: 162 -> 150 us).  Not when h0 and final_state share memory: the second
-  // segment might store the final state before the first has read h0.
-  const size_t state_bytes = static_cast<size_t>(d.Bt) * d.H * d.P * ns.width * sizeof(float);
-  const bool h0_aliases = h0 != nullptr && final_state != nullptr &&
-                          reinterpret_cast<const char *>(h0) < reinterpret_cast<const char *>(final_state) + state_bytes &&
-                          reinterpret_cast<const char *>(final_state) < reinterpret_cast<const char *>(h0) + state_bytes;
-  p.fold = !varlen && S >= 2 && (S - 1) * parts <= knobs().fold_max_slots && !h0_aliases ? 1 : 0;
+  p.fold = pl.fold;
   if (varlen || S > 1) {
     // (a packed batch always takes this route: whether any sequence has more than one segment is
     // known on the device only; workgroups of last segments leave the states-only pass at once)
@@ -1998,6 +2012,10 @@ bool mfma_supported(const Dims &d) {
 }
 
 size_t mfma_workspace_bytes(const Dims &d) { return make_layout(with_block_chunk(d), false).total; }
+
+SlicePlan mfma_plan(const Dims &d, bool h0_aliases_final_state) {
+  return plan_slice(with_block_chunk(d), false, h0_aliases_final_state);
+}
 
 hipError_t launch_prefill_mfma(const Dims &d, const void *x, const float *dt, const float *A, const void *B,
                                const void *C, const float *D, const float *h0, void *y, float *final_state,

@@ -487,6 +487,8 @@ bool mfma_f32_supported(const Dims &d, bool whenever_eligible) {
   return mfma_us <= 1.1 * generic_us;
 }
 
+int mfma_f32_time_segments(const Dims &d) { return f32_time_segments(d, nullptr); }
+
 hipError_t launch_prefill_mfma_f32(const Dims &d, const void *x, const float *dt, const float *A, const void *B,
                                    const void *C, const float *D, const float *h0, void *y, float *final_state,
                                    hipStream_t stream, KernelTrace *trace) {

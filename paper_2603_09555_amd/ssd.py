@@ -23,7 +23,7 @@ EXPORTS = ["ssd_prefill_workspace_bytes", "ssd_prefill", "ssd_prefill_static", "
            "ssd_conv1d_prefill", "ssd_conv1d_step", "ssd_prefill_dt", "ssd_prefill_varlen_dt",
            "ssd_decode_step_layers_dt", "ssd_decode_steps_layers_dt",
            "ssd_prefill_path", "ssd_status_string", "ssd_version",
-           "ssd_testing_set_knob", "ssd_testing_reset_knobs"]
+           "ssd_testing_set_knob", "ssd_testing_reset_knobs", "ssd_testing_prefill_plan"]
 
 
 class ssd_shape(ctypes.Structure):
@@ -62,6 +62,8 @@ _lib.ssd_testing_set_knob.restype = ctypes.c_int
 _lib.ssd_testing_set_knob.argtypes = [ctypes.c_int32, ctypes.c_int32]
 _lib.ssd_testing_reset_knobs.restype = None
 _lib.ssd_testing_reset_knobs.argtypes = []
+_lib.ssd_testing_prefill_plan.restype = ctypes.c_int
+_lib.ssd_testing_prefill_plan.argtypes = [ctypes.POINTER(ssd_shape), ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
 _lib.ssd_decode_step.restype = ctypes.c_int
 _lib.ssd_decode_step.argtypes = [_sp] + [_vp] * 9
 _lib.ssd_decode_step_layers.restype = ctypes.c_int
@@ -378,3 +380,14 @@ def set_knob(name: str, value: int) -> None:
 
 def reset_knobs() -> None:
     _lib.ssd_testing_reset_knobs()
+
+
+def prefill_plan(shape, h0_aliases_final_state: bool = False) -> dict:
+    """``ssd_testing_prefill_plan`` (include/ssd_testing.h): how ``ssd_prefill`` would run ``shape`` under the
+    current knobs, as a dict.  Host arithmetic only."""
+    out = (ctypes.c_int32 * 8)()
+    st = _lib.ssd_testing_prefill_plan(ctypes.byref(shape), int(bool(h0_aliases_final_state)), out)
+    if st != SSD_OK:
+        raise SSDError(st, "ssd_testing_prefill_plan")
+    return dict(path=("generic_f32", "mfma_bf16", "mfma_f32")[out[0]], seg_blocks=out[1], segments=out[2], parts=out[3],
+                fold=bool(out[4]), f32_segments=out[5])

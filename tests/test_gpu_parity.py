@@ -396,6 +396,11 @@ def test_mfma_prefill_segment_states_folded(ssd, case, parts, with_h0):
     ssd.set_knob("seg_blocks", seg_blocks)
     ssd.set_knob("seg_parts", parts)
     ssd.set_knob("fold_max_slots", 64)
+    sh = ssd.make_shape(cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk,
+                        torch.bfloat16)
+    plan = ssd.prefill_plan(sh)
+    assert plan["fold"] and plan["seg_blocks"] == seg_blocks and plan["segments"] >= 2, plan
+    assert not ssd.prefill_plan(sh, h0_aliases_final_state=True)["fold"]
     h0 = None
     if with_h0:  # an initial state of realistic size: what a prefill of similar inputs leaves behind
         h0 = torch.from_numpy(oracle_prefill(inputs.make_prefill_inputs(cfg, seed=79))[1]).float()
@@ -405,6 +410,7 @@ def test_mfma_prefill_segment_states_folded(ssd, case, parts, with_h0):
     assert_close(st, st_ref, 2e-2, "folded final state")
     print("errors", e, flush=True)
     ssd.set_knob("fold_max_slots", 0)
+    assert not ssd.prefill_plan(sh)["fold"]
     _, y2, st2 = run_prefill(ssd, cfg, seed=52, h0=h0)
     assert_close(y2, y_ref, 2e-2, "separate pass y")
     assert_close(st2, st_ref, 2e-2, "separate pass final state")
